@@ -1,0 +1,262 @@
+"""Seeded synthetic inputs (CSR graphs, edge values, dense feature matrices).
+
+Inputs only: nothing here computes any part of SpMM.  The CPU oracle and the GPU
+library are both fed from this module and share nothing else.
+
+The five workloads below stand in for the paper's data (the citation graphs of
+Table IV, the random graphs of Section V-B, the SNAP size/skew range of Section
+V-A); the real dataset files are not used anywhere.
+"""
+from __future__ import annotations
+
+import ctypes
+import hashlib
+import os
+import subprocess
+from dataclasses import dataclass, field
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "graphgen.cpp")
+_LIB = os.path.join(_HERE, "libgraphgen.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile graphgen.cpp into libgraphgen.so (g++, OpenMP)."""
+    if force or not os.path.exists(_LIB):
+        cmd = ["g++", "-O3", "-fopenmp", "-shared", "-fPIC", "-std=c++17", "-o", _LIB, _SRC]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    L = ctypes.CDLL(_LIB)
+    i64, f64, u64, vp, ci = ctypes.c_int64, ctypes.c_double, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_int
+    L.gg_csr_rows.restype = i64; L.gg_csr_rows.argtypes = [vp]
+    L.gg_csr_cols.restype = i64; L.gg_csr_cols.argtypes = [vp]
+    L.gg_csr_nnz.restype = i64; L.gg_csr_nnz.argtypes = [vp]
+    L.gg_csr_copy.restype = None; L.gg_csr_copy.argtypes = [vp, vp, vp]
+    L.gg_csr_free.restype = None; L.gg_csr_free.argtypes = [vp]
+    L.gg_chung_lu_symmetric.restype = vp
+    L.gg_chung_lu_symmetric.argtypes = [i64, f64, f64, i64, ci, u64]
+    L.gg_chung_lu_directed.restype = vp
+    L.gg_chung_lu_directed.argtypes = [i64, f64, f64, f64, i64, f64, u64]
+    L.gg_rmat.restype = vp
+    L.gg_rmat.argtypes = [i64, ci, f64, f64, f64, i64, f64, u64]
+    L.gg_vals_sym_norm.restype = None; L.gg_vals_sym_norm.argtypes = [i64, vp, vp, vp]
+    for name in ("gg_fill_uniform_01", "gg_fill_uniform_pm1", "gg_fill_normal"):
+        fn = getattr(L, name)
+        fn.restype = None
+        fn.argtypes = [i64, u64, u64, vp]
+    L.gg_max_threads.restype = ci
+    L.gg_set_threads.restype = None; L.gg_set_threads.argtypes = [ci]
+    _lib = L
+    return L
+
+
+def set_threads(n: int) -> None:
+    _load().gg_set_threads(int(n))
+
+
+def _take(handle):
+    L = _load()
+    if not handle:
+        raise ValueError("graphgen: invalid generator arguments")
+    try:
+        M, K, nnz = L.gg_csr_rows(handle), L.gg_csr_cols(handle), L.gg_csr_nnz(handle)
+        rowptr = np.empty(M + 1, dtype=np.int32)
+        colind = np.empty(nnz, dtype=np.int32)
+        L.gg_csr_copy(handle, rowptr.ctypes.data, colind.ctypes.data)
+    finally:
+        L.gg_csr_free(handle)
+    return int(M), int(K), rowptr, colind
+
+
+def chung_lu_symmetric(M, edges, seed, gamma=2.5, max_over_mean=40.0, exact=False):
+    return _take(_load().gg_chung_lu_symmetric(M, gamma, max_over_mean, edges, int(exact), seed))
+
+
+def chung_lu_directed(M, edges, seed, gamma=2.5, max_over_mean_out=70.0, max_over_mean_in=70.0,
+                      empty_frac=0.0):
+    return _take(_load().gg_chung_lu_directed(M, gamma, max_over_mean_out, max_over_mean_in,
+                                              edges, empty_frac, seed))
+
+
+def rmat(M, scale, draws, seed, a=0.57, b=0.19, c=0.19, extra_empty_frac=0.0):
+    return _take(_load().gg_rmat(M, scale, a, b, c, draws, extra_empty_frac, seed))
+
+
+def vals_sym_norm(rowptr, colind):
+    vals = np.empty(colind.shape[0], dtype=np.float32)
+    _load().gg_vals_sym_norm(rowptr.shape[0] - 1, rowptr.ctypes.data, colind.ctypes.data,
+                             vals.ctypes.data)
+    return vals
+
+
+def _fill(name, shape, seed, stream):
+    out = np.empty(shape, dtype=np.float32)
+    getattr(_load(), name)(out.size, seed, stream, out.ctypes.data)
+    return out
+
+
+def uniform_01(shape, seed, stream=0):
+    """fp32 uniform on (0, 1]."""
+    return _fill("gg_fill_uniform_01", shape, seed, stream)
+
+
+def uniform_pm1(shape, seed, stream=0):
+    """fp32 uniform on (-1, 1), never exactly zero."""
+    return _fill("gg_fill_uniform_pm1", shape, seed, stream)
+
+
+def normal(shape, seed, stream=0):
+    """fp32 standard normal, never exactly zero."""
+    return _fill("gg_fill_normal", shape, seed, stream)
+
+
+# --------------------------------------------------------------------------
+# The five workloads
+# --------------------------------------------------------------------------
+@dataclass
+class Workload:
+    name: str
+    M: int
+    K: int
+    rowptr: np.ndarray
+    colind: np.ndarray
+    vals: np.ndarray | None
+    seed: int
+    b_kind: str                       # "uniform_pm1" | "normal"
+    widths: tuple                     # feature widths N this workload is run at
+    ops: tuple                        # reduce ops this workload is run with
+    meta: dict = field(default_factory=dict)
+
+    @property
+    def nnz(self) -> int:
+        return int(self.colind.shape[0])
+
+    def B(self, N: int) -> np.ndarray:
+        fill = uniform_pm1 if self.b_kind == "uniform_pm1" else normal
+        return fill((self.K, N), self.seed, stream=N)
+
+    def describe(self) -> dict:
+        lens = np.diff(self.rowptr)
+        h = hashlib.blake2b(digest_size=8)
+        h.update(self.rowptr.tobytes()); h.update(self.colind.tobytes())
+        return {"name": self.name, "M": self.M, "K": self.K, "nnz": self.nnz,
+                "max_row": int(lens.max()) if self.M else 0,
+                "mean_row": float(lens.mean()) if self.M else 0.0,
+                "empty_rows": float((lens == 0).mean()) if self.M else 0.0,
+                "csr_hash": h.hexdigest(), **self.meta}
+
+
+WORKLOAD_NAMES = ("tiny_citation", "width_sweep", "general_ops", "large_dense_degree", "skew_narrow")
+
+# number of Chung-Lu candidate pairs for "large_dense_degree": hub-hub pairs repeat
+# and are merged, so more than 114.6M/2 candidates are needed to land near 114.6M nnz
+_LARGE_CANDIDATES = 58_170_000
+
+
+def workload(which, scale: float = 1.0) -> Workload:
+    """Build workload `which` (index 0..4 or a name from WORKLOAD_NAMES).
+
+    `scale` < 1 shrinks M and the edge budget proportionally (used by CPU tests
+    and by quick parity runs); scale == 1 is the full size.
+    """
+    idx = WORKLOAD_NAMES.index(which) if isinstance(which, str) else int(which)
+    name = WORKLOAD_NAMES[idx]
+    s = float(scale)
+    if idx == 0:
+        M = max(8, int(round(2708 * s)))
+        e = max(4, int(round(5278 * s)))
+        M, K, rp, ci = chung_lu_symmetric(M, e, seed=0, max_over_mean=40.0, exact=True)
+        return Workload(name, M, K, rp, ci, vals_sym_norm(rp, ci), 0, "uniform_pm1", (16,), ("sum",))
+    if idx == 1:
+        M = max(8, int(round(19717 * s)))
+        e = max(4, int(round(44324 * s)))
+        M, K, rp, ci = chung_lu_symmetric(M, e, seed=1, max_over_mean=40.0, exact=True)
+        return Workload(name, M, K, rp, ci, uniform_01(ci.shape[0], 1), 1, "uniform_pm1",
+                        (32, 64, 128, 256, 512), ("sum",))
+    if idx == 2:
+        M = max(8, int(round(169343 * s)))
+        e = int(round(2_402_500 * s))
+        M, K, rp, ci = chung_lu_directed(M, e, seed=2, empty_frac=0.03)
+        return Workload(name, M, K, rp, ci, np.ones(ci.shape[0], dtype=np.float32), 2, "normal",
+                        (128,), ("sum", "mean", "max", "min"))
+    if idx == 3:
+        M = max(8, int(round(232965 * s)))
+        e = int(round(_LARGE_CANDIDATES * s))
+        # M and the candidate budget shrink together, so the mean degree stays near 492
+        M, K, rp, ci = chung_lu_symmetric(M, e, seed=3, max_over_mean=40.6, exact=False)
+        return Workload(name, M, K, rp, ci, vals_sym_norm(rp, ci), 3, "uniform_pm1", (64,),
+                        ("sum", "max"))
+    if idx == 4:
+        M = max(8, int(round(1_000_000 * s)))
+        sc = max(3, int(np.ceil(np.log2(M))))
+        draws = int(round(16_000_000 * s))
+        M, K, rp, ci = rmat(M, sc, draws, seed=4)
+        empty = float((np.diff(rp) == 0).mean())
+        if empty < 0.05:  # top up to 5 % empty rows only when R-MAT left fewer on its own
+            M, K, rp, ci = rmat(M, sc, draws, seed=4, extra_empty_frac=0.05 - empty)
+        return Workload(name, M, K, rp, ci, uniform_01(ci.shape[0], 4), 4, "uniform_pm1", (8, 32),
+                        ("sum", "mean"), {"rmat_scale": sc})
+    raise ValueError(which)
+
+
+# --------------------------------------------------------------------------
+# Small random CSR matrices for unit tests (numpy's seeded PCG64)
+# --------------------------------------------------------------------------
+def random_csr(M, K, mean_len, seed, empty_frac=0.0, duplicates=False, sort_cols=True,
+               long_rows=(), val_kind="uniform"):
+    """Random CSR with geometric-ish row lengths.
+
+    long_rows: iterable of (row, length) forcing specific long rows.
+    duplicates=True draws columns with replacement (repeated column indices stay as
+    separate stored entries); sort_cols=False leaves the columns in draw order.
+    """
+    rng = np.random.default_rng(seed)
+    lens = rng.geometric(1.0 / max(mean_len, 1.0), size=M).astype(np.int64) if M else np.zeros(0, np.int64)
+    if not duplicates:
+        lens = np.minimum(lens, K)
+    if empty_frac > 0 and M:
+        lens[rng.random(M) < empty_frac] = 0
+    for r, ln in long_rows:
+        lens[r] = ln if duplicates else min(ln, K)
+    if K == 0:
+        lens[:] = 0
+    rowptr = np.zeros(M + 1, dtype=np.int64)
+    np.cumsum(lens, out=rowptr[1:])
+    nnz = int(rowptr[-1])
+    colind = np.empty(nnz, dtype=np.int32)
+    for i in range(M):
+        n = int(lens[i])
+        if n == 0:
+            continue
+        if duplicates:
+            c = rng.integers(0, K, size=n)
+        elif n * 4 > K:
+            c = rng.permutation(K)[:n]
+        else:
+            c = np.unique(rng.integers(0, K, size=2 * n + 8))
+            while c.shape[0] < n:
+                c = np.unique(np.concatenate([c, rng.integers(0, K, size=2 * n + 8)]))
+            c = rng.permutation(c)[:n]
+        colind[rowptr[i]:rowptr[i + 1]] = np.sort(c) if sort_cols else c
+    if val_kind == "uniform":
+        vals = (rng.random(nnz) * 2.0 - 1.0).astype(np.float32)
+    elif val_kind == "ones":
+        vals = np.ones(nnz, dtype=np.float32)
+    else:
+        raise ValueError(val_kind)
+    return rowptr.astype(np.int32), colind, vals
+
+
+def random_dense(K, N, seed):
+    rng = np.random.default_rng(seed + 0x5EED)
+    return (rng.random((K, N)) * 2.0 - 1.0).astype(np.float32)

@@ -1,0 +1,105 @@
+"""Python face of the CPU oracle (spmm_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: the product path never imports this package.  Only
+tests, the smoke check and the benchmark's cpu_baseline leg may use it.  It
+imports nothing from the GPU package and shares no code with it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "spmm_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+OPS = {"sum": 0, "mean": 1, "max": 2, "min": 3}
+
+
+def build(force: bool = False, src: str = _SRC, lib: str = _LIB) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP over rows; no fast-math)."""
+    if force or not os.path.exists(lib):
+        subprocess.run(["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC", "-o", lib, src,
+                        "-lm"], check=True)
+    return lib
+
+
+def _bind(path):
+    L = ctypes.CDLL(path)
+    i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+    L.spmm_oracle.restype = ci
+    L.spmm_oracle.argtypes = [i64, i64, i64, vp, vp, vp, vp, ci, vp, i64, vp, vp, ci]
+    L.spmm_oracle_max_threads.restype = ci
+    return L
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = _bind(build())
+    return _lib
+
+
+def max_threads() -> int:
+    return int(_load().spmm_oracle_max_threads())
+
+
+def spmm(rowptr, colind, vals, B, op, rows=None, threads=0, _lib_override=None):
+    """Reference result of C = A (x) B for CSR A.
+
+    Returns (Cref, Sabs), both float64, shape (M, N) or (len(rows), N) when a row
+    subset is given.  `vals` may be None (all stored values are 1).
+    """
+    L = _lib_override or _load()
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int32)
+    colind = np.ascontiguousarray(colind, dtype=np.int32)
+    B = np.ascontiguousarray(B, dtype=np.float32)
+    if vals is not None:
+        vals = np.ascontiguousarray(vals, dtype=np.float32)
+        assert vals.shape[0] == colind.shape[0]
+    M = rowptr.shape[0] - 1
+    K, N = B.shape
+    assert int(rowptr[-1]) == colind.shape[0]
+    if colind.size:
+        assert colind.min() >= 0 and colind.max() < K
+    if rows is not None:
+        rows = np.ascontiguousarray(rows, dtype=np.int64)
+        count = rows.shape[0]
+        assert count == 0 or (rows.min() >= 0 and rows.max() < M)
+    else:
+        count = M
+    Cref = np.empty((count, N), dtype=np.float64)
+    Sabs = np.empty((count, N), dtype=np.float64)
+    rc = L.spmm_oracle(M, K, N, rowptr.ctypes.data, colind.ctypes.data,
+                       vals.ctypes.data if vals is not None else None, B.ctypes.data,
+                       OPS[op] if isinstance(op, str) else int(op),
+                       rows.ctypes.data if rows is not None else None, count,
+                       Cref.ctypes.data, Sabs.ctypes.data, int(threads))
+    if rc != 0:
+        raise ValueError("spmm_oracle: bad argument")
+    return Cref, Sabs
+
+
+def compare(op, C, Cref, Sabs):
+    """Check a fp32 result against the oracle.
+
+    sum / mean: |C - Cref| <= 1e-5 * Sabs + 1e-6 element-wise.
+    max / min : bit-for-bit equal to Cref rounded once to fp32.
+    Returns (ok, worst) where worst is the largest error/bound ratio (sum, mean)
+    or the number of mismatching elements (max, min).
+    """
+    C = np.asarray(C)
+    assert C.dtype == np.float32 and C.shape == Cref.shape
+    if op in ("sum", "mean"):
+        err = np.abs(C.astype(np.float64) - Cref)
+        bound = 1e-5 * Sabs + 1e-6
+        ok = bool(np.all(err <= bound)) and bool(np.all(np.isfinite(C)))
+        worst = float((err / bound).max()) if err.size else 0.0
+        return ok, worst
+    want = Cref.astype(np.float32)
+    bad = int(np.count_nonzero(C.view(np.uint32) != want.view(np.uint32)))
+    return bad == 0, bad

@@ -1,0 +1,104 @@
+/*
+ * CPU oracle for CSR SpMM and the SpMM-like reductions (sum, mean, max, min).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the
+ * GPU library is checked against; the product never calls it.  It shares no
+ * code with the GPU path.  Only tests, the smoke check and the benchmark's
+ * cpu_baseline leg may use it.
+ *
+ * What it computes is the plain definition of the result (Algorithm 1 of the
+ * paper, with the walk-through of Section III-A): for every output row i and
+ * column j, walk the stored entries p of row i in storage order, form
+ * vals[p] * B[colind[p], j], and fold the products with the reduction.  The
+ * SpMM-like generalisation (Eq. 1, Section IV-A) swaps the initial value and
+ * the fold, nothing else: the multiply stays for every op.
+ *
+ * Readings where the paper is silent (also listed in the design notes):
+ *   - mean divides by the number of STORED entries of the row;
+ *   - an empty row yields 0 for every op;
+ *   - max/min on signed zeros follow IEEE-754 maximum/minimum (+0 > -0);
+ *   - columns need not be sorted or unique: repeated columns are separate terms;
+ *   - vals == NULL means every stored value is 1.
+ *
+ * Arithmetic: every product of two fp32 numbers is formed in double (exact:
+ * 24 x 24 significant bits fit in 53) and the fold runs in double.  Besides the
+ * result, the oracle returns Sabs = sum_p |vals[p] * B[colind[p], j]| (divided
+ * by the row length for mean), the scale of the fp32 error bound.
+ *
+ * Pins (tests/test_oracle_pins.py): brute-force dense products and explicit
+ * per-entry loops on tiny inputs, the identity matrix, an all-ones B, closed
+ * forms, scipy's CSR product in float64, a hand-worked example, and a set of
+ * planted single-token mistakes that the pins must all reject.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <omp.h>
+
+enum { OP_SUM = 0, OP_MEAN = 1, OP_MAX = 2, OP_MIN = 3 };
+
+/* IEEE-754 maximum / minimum on non-NaN doubles, +0 ordered above -0. */
+static double fold_max(double acc, double x) {
+  if (x > acc) return x;
+  if (x == acc && !signbit(x)) return x;
+  return acc;
+}
+static double fold_min(double acc, double x) {
+  if (x < acc) return x;
+  if (x == acc && signbit(x)) return x;
+  return acc;
+}
+
+/* One output row: out_c[0..N) and out_s[0..N) for row i of A. */
+static void oracle_row(int64_t i, int64_t N, const int32_t* rowptr, const int32_t* colind,
+                       const float* vals, const float* B, int op, double* out_c, double* out_s) {
+  const int64_t row_start = rowptr[i];
+  const int64_t row_end = rowptr[i + 1];
+  const int64_t len = row_end - row_start;
+  for (int64_t j = 0; j < N; ++j) {
+    if (len == 0) {
+      out_c[j] = 0.0;
+      out_s[j] = 0.0;
+      continue;
+    }
+    double result = (op == OP_MAX) ? -INFINITY : (op == OP_MIN) ? INFINITY : 0.0;
+    double sabs = 0.0;
+    for (int64_t ptr = row_start; ptr < row_end; ++ptr) {
+      const int64_t k = colind[ptr];
+      const double a = vals ? (double)vals[ptr] : 1.0;
+      const double x = a * (double)B[k * N + j];
+      if (op == OP_MAX) result = fold_max(result, x);
+      else if (op == OP_MIN) result = fold_min(result, x);
+      else result += x;
+      sabs += fabs(x);
+    }
+    if (op == OP_MEAN) {
+      result /= (double)len;
+      sabs /= (double)len;
+    }
+    out_c[j] = result;
+    out_s[j] = sabs;
+  }
+}
+
+/*
+ * rows == NULL : all M rows; Cref and Sabs are M x N row-major.
+ * rows != NULL : only the nrows listed rows, in list order; outputs are nrows x N.
+ * threads <= 0 : use OpenMP's default.  Returns 0, or -1 on a bad argument.
+ */
+int spmm_oracle(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colind,
+                const float* vals, const float* B, int op, const int64_t* rows, int64_t nrows,
+                double* Cref, double* Sabs, int threads) {
+  if (M < 0 || K < 0 || N < 0 || op < OP_SUM || op > OP_MIN) return -1;
+  if (!rowptr || !Cref || !Sabs) return -1;
+  const int64_t count = rows ? nrows : M;
+  const int nt = threads > 0 ? threads : omp_get_max_threads();
+#pragma omp parallel for schedule(dynamic, 256) num_threads(nt)
+  for (int64_t r = 0; r < count; ++r) {
+    const int64_t i = rows ? rows[r] : r;
+    oracle_row(i, N, rowptr, colind, vals, B, op, Cref + r * N, Sabs + r * N);
+  }
+  return 0;
+}
+
+int spmm_oracle_max_threads(void) { return omp_get_max_threads(); }

@@ -1,0 +1,96 @@
+"""Seeded input generator: determinism, structure and the stated workload shapes (CPU only)."""
+import numpy as np
+import pytest
+
+import graphgen
+
+
+def _check_csr(M, K, rp, ci, symmetric=False, no_self_loops=False):
+    assert rp.dtype == np.int32 and ci.dtype == np.int32
+    assert rp.shape == (M + 1,) and rp[0] == 0 and rp[-1] == ci.shape[0]
+    lens = np.diff(rp)
+    assert (lens >= 0).all()
+    assert ci.size == 0 or (ci.min() >= 0 and ci.max() < K)
+    rows = np.repeat(np.arange(M, dtype=np.int64), lens)
+    keys = rows * K + ci
+    assert (np.diff(keys) > 0).all(), "columns must be sorted and unique inside every row"
+    if no_self_loops:
+        assert (rows != ci).all()
+    if symmetric:
+        assert np.array_equal(np.sort(ci.astype(np.int64) * K + rows), keys)
+
+
+def test_tiny_and_sweep_have_exact_sizes():
+    w0 = graphgen.workload(0)
+    assert (w0.M, w0.K, w0.nnz) == (2708, 2708, 10556)
+    _check_csr(w0.M, w0.K, w0.rowptr, w0.colind, symmetric=True, no_self_loops=True)
+    d = np.diff(w0.rowptr).astype(np.float64)
+    i, j = np.repeat(np.arange(w0.M), np.diff(w0.rowptr)), w0.colind
+    np.testing.assert_allclose(w0.vals, 1.0 / np.sqrt(d[i] * d[j]), rtol=1e-6)
+    w1 = graphgen.workload(1)
+    assert (w1.M, w1.nnz) == (19717, 88648)
+    _check_csr(w1.M, w1.K, w1.rowptr, w1.colind, symmetric=True, no_self_loops=True)
+    assert w1.vals.min() > 0 and w1.vals.max() <= 1
+    assert w1.widths == (32, 64, 128, 256, 512)
+
+
+def test_general_ops_workload_shape():
+    w = graphgen.workload(2)
+    assert w.M == 169343 and abs(w.nnz - 2.33e6) < 0.02e6
+    _check_csr(w.M, w.K, w.rowptr, w.colind, no_self_loops=True)
+    lens = np.diff(w.rowptr)
+    assert 0.03 <= (lens == 0).mean() < 0.04
+    assert lens.max() > 20 * lens.mean()            # power-law skew
+    assert (w.vals == 1).all()
+    B = w.B(128)
+    assert B.shape == (w.K, 128) and abs(B.mean()) < 0.01 and abs(B.std() - 1) < 0.01
+    assert (B != 0).all()
+
+
+def test_scaled_large_and_skew_workloads():
+    w = graphgen.workload(3, 0.01)
+    _check_csr(w.M, w.K, w.rowptr, w.colind, symmetric=True, no_self_loops=True)
+    assert np.diff(w.rowptr).mean() > 100
+    w = graphgen.workload(4, 0.01)
+    _check_csr(w.M, w.K, w.rowptr, w.colind)
+    lens = np.diff(w.rowptr)
+    assert (lens == 0).mean() >= 0.05
+    assert lens.max() > 50 * lens.mean()
+    # hub rows sit at low ids (rows are not permuted)
+    assert lens[: w.M // 16].sum() > lens[-(w.M // 16):].sum() * 10
+
+
+def test_same_seed_same_graph_any_thread_count():
+    a = graphgen.workload(2, 0.05)
+    graphgen.set_threads(1)
+    try:
+        b = graphgen.workload(2, 0.05)
+        r1 = graphgen.rmat(5000, 13, 40000, seed=9)
+        u1 = graphgen.uniform_pm1((1000, 7), 5, stream=7)
+    finally:
+        graphgen.set_threads(8)
+    assert np.array_equal(a.rowptr, b.rowptr) and np.array_equal(a.colind, b.colind)
+    r8 = graphgen.rmat(5000, 13, 40000, seed=9)
+    assert np.array_equal(r1[2], r8[2]) and np.array_equal(r1[3], r8[3])
+    assert np.array_equal(u1, graphgen.uniform_pm1((1000, 7), 5, stream=7))
+    other = graphgen.rmat(5000, 13, 40000, seed=10)
+    assert not np.array_equal(r1[3][:1000], other[3][:1000])
+
+
+def test_value_fillers():
+    u = graphgen.uniform_pm1((4096, 16), 3)
+    assert u.min() > -1 and u.max() < 1 and (u != 0).all() and abs(u.mean()) < 0.02
+    p = graphgen.uniform_01(100000, 3)
+    assert p.min() > 0 and p.max() <= 1 and abs(p.mean() - 0.5) < 0.01
+    n = graphgen.normal((100000,), 3)
+    assert abs(n.mean()) < 0.02 and abs(n.std() - 1) < 0.02
+
+
+@pytest.mark.parametrize("kw", [dict(duplicates=True, sort_cols=False), dict(empty_frac=0.5),
+                                dict(long_rows=((3, 500),))])
+def test_random_csr_is_valid(kw):
+    rp, ci, v = graphgen.random_csr(50, 700, 5.0, 1, **kw)
+    assert rp[0] == 0 and rp[-1] == ci.shape[0] == v.shape[0]
+    assert (np.diff(rp) >= 0).all() and ci.min() >= 0 and ci.max() < 700
+    if "long_rows" in kw:
+        assert rp[4] - rp[3] == 500
