@@ -1,0 +1,130 @@
+/*
+ * gespmm.h - C ABI of the MI355X (gfx950) CSR SpMM / SpMM-like library.
+ *
+ * The operation (paper: Algorithm 1 and Section III-A for the plain result,
+ * Eq. 1 and Section IV-A for the general reduce):
+ *
+ *     C[i, j] = reduce over the stored entries p of row i of  vals[p] * B[colind[p], j]
+ *
+ * with A (M x K) in plain CSR exactly as the caller holds it (Section III-A:
+ * rowptr / colind / vals; no preprocessing, no format conversion, no state kept
+ * between calls), B (K x N) and C (M x N) dense, row-major, fp32 (Section V-C).
+ * reduce is sum, mean, max or min; an empty row gives 0 for every op; mean
+ * divides by the number of stored entries of the row.
+ *
+ * All data pointers are DEVICE pointers on the current HIP device.  The caller
+ * owns every buffer.  The library allocates no device memory, frees nothing,
+ * and never synchronises (except gespmm_csr_simple, see below): all work is
+ * enqueued on the given stream.  Inputs are only read.  C is fully overwritten
+ * and need not be initialised; C must not overlap any input.
+ *
+ * Every function returns a gespmm_status_t (0 = success) unless stated.
+ * Argument errors are detected on the host before any HIP call is made.
+ * Device-side contents (colind range, rowptr monotonicity) are NOT validated:
+ * violating them is undefined behaviour.
+ */
+#ifndef GESPMM_H
+#define GESPMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { GESPMM_SUM = 0, GESPMM_MEAN = 1, GESPMM_MAX = 2, GESPMM_MIN = 3 } gespmm_op_t;
+
+typedef enum {
+  GESPMM_OK = 0,
+  GESPMM_ERR_BAD_ARG = 1,   /* negative size, unknown op, nnz inconsistent       */
+  GESPMM_ERR_NULL = 2,      /* a required pointer is NULL                         */
+  GESPMM_ERR_TOO_LARGE = 3, /* M, K or nnz does not fit the 32-bit index arrays   */
+  GESPMM_ERR_HIP = 4        /* a HIP call (launch, event, copy) reported an error */
+} gespmm_status_t;
+
+/*
+ * The SpMM / SpMM-like operation (Algorithm 1; Eq. 1; Section IV-A).
+ *
+ *   M, K, N   matrix sizes, >= 0.  M < 2^31 - 1, K < 2^31.
+ *   nnz       number of stored entries, 0 <= nnz < 2^31; must equal rowptr[M].
+ *   rowptr    device, int32[M+1], rowptr[0] == 0, non-decreasing, rowptr[M] == nnz.
+ *   colind    device, int32[nnz], 0 <= colind[p] < K, any order inside a row,
+ *             repeated columns allowed (each stored entry is its own term).
+ *   vals      device, fp32[nnz], or NULL meaning every stored value is 1.0f.
+ *   B         device, fp32[K*N], row-major, leading dimension N.
+ *   C         device, fp32[M*N], row-major, leading dimension N; overwritten.
+ *   op        gespmm_op_t.
+ *   stream    a hipStream_t passed as void* (NULL = the default stream).
+ *
+ * 16-byte aligned B and C with N a multiple of 4 take the vectorised kernels;
+ * anything else takes the scalar kernels.  M == 0 or N == 0 returns at once;
+ * nnz == 0 fills C with zeros.  sum and mean are accurate to fp32 rounding in an
+ * unspecified summation order (rows that are split across wavefronts are
+ * combined with fp32 atomic adds, so the last bits can differ from run to run);
+ * max and min are exact and bit-reproducible.
+ * Errors: GESPMM_ERR_NULL (rowptr, B or C NULL; colind NULL with nnz > 0),
+ * GESPMM_ERR_BAD_ARG, GESPMM_ERR_TOO_LARGE, GESPMM_ERR_HIP (launch failure).
+ */
+int gespmm_csr(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+               const int32_t* colind, const float* vals, const float* B, float* C, int op,
+               void* stream);
+
+/*
+ * Same operation for callers that do not track nnz: reads rowptr[M] from the
+ * device with one 4-byte copy and waits for it (this call DOES synchronise the
+ * stream once), then behaves as gespmm_csr.
+ */
+int gespmm_csr_simple(int64_t M, int64_t K, int64_t N, const int32_t* rowptr,
+                      const int32_t* colind, const float* vals, const float* B, float* C, int op,
+                      void* stream);
+
+/*
+ * The kernel selection of Section IV-A ("GE-SpMM for different matrix sizes"),
+ * redone for 64-lane wavefronts: pure host function, touches no device.
+ * Fills the launch shape gespmm_csr would use for these sizes.
+ */
+typedef struct {
+  int32_t vec;            /* floats per lane per load: 4 (vectorised) or 1 (scalar)      */
+  int32_t lanes_per_row;  /* G: lanes that cover one column block of a sparse row         */
+  int32_t tiles_per_lane; /* T: column tiles each lane accumulates (row loaded once)      */
+  int32_t slots;          /* 64 / G: non-zeros of a row consumed per wavefront step       */
+  int32_t chunk_nnz;      /* S: stored entries assigned to one wavefront                  */
+  int32_t col_blocks;     /* grid.y: ceil(N / (vec * G * T))                              */
+  int64_t chunks;         /* ceil(nnz / S)                                                */
+  int64_t grid_x;         /* workgroups along x of the main kernel                        */
+  int32_t block_threads;  /* threads per workgroup                                        */
+  int32_t xcd_remap;      /* 1: consecutive chunks are kept on one XCD                    */
+} gespmm_plan_t;
+
+int gespmm_plan(int64_t M, int64_t N, int64_t nnz, int aligned16, gespmm_plan_t* out);
+
+/*
+ * Tuning override for tests and benchmarks (process-wide, not thread-safe):
+ * lanes_per_row in {1,2,4,...,64}, tiles_per_lane in {1,2,4}, xcd_remap in {0,1};
+ * -1 restores the automatic choice for that field.  Returns GESPMM_ERR_BAD_ARG
+ * for a value that has no kernel.
+ */
+int gespmm_set_tuning(int lanes_per_row, int tiles_per_lane, int xcd_remap);
+
+/*
+ * Per-kernel timing for the benchmark.  gespmm_profile_begin creates `capacity`
+ * event pairs; while profiling is on, each gespmm_csr call brackets its main
+ * kernel with one pair on the call's stream (calls beyond capacity are not
+ * bracketed).  gespmm_profile_end waits for the recorded events, returns the
+ * summed main-kernel time in milliseconds and the number of bracketed launches,
+ * and destroys the events.  Not thread-safe.
+ */
+int gespmm_profile_begin(int capacity);
+int gespmm_profile_end(double* main_kernel_ms_sum, int* launches);
+
+/* Static text for a status code (never NULL). */
+const char* gespmm_status_string(int status);
+
+/* Library version, major * 100 + minor. */
+int gespmm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GESPMM_H */

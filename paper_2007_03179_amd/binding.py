@@ -1,0 +1,144 @@
+"""ctypes binding of libgespmm.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/gespmm.h).  Tensors
+are torch CUDA tensors used purely as device memory; the stream is torch's current
+stream unless one is given.  Nothing is computed on this side, and there is no
+fallback: a missing library is an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgespmm.so")
+
+OPS = {"sum": 0, "mean": 1, "max": 2, "min": 3}
+GESPMM_OK = 0
+
+
+class GespmmError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"gespmm status {status}: {text}")
+        self.status = status
+
+
+class gespmm_plan_t(ctypes.Structure):
+    _fields_ = [("vec", ctypes.c_int32), ("lanes_per_row", ctypes.c_int32),
+                ("tiles_per_lane", ctypes.c_int32), ("slots", ctypes.c_int32),
+                ("chunk_nnz", ctypes.c_int32), ("col_blocks", ctypes.c_int32),
+                ("chunks", ctypes.c_int64), ("grid_x", ctypes.c_int64),
+                ("block_threads", ctypes.c_int32), ("xcd_remap", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library (built by build.py; raises if it is not there)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                "(or paper_2007_03179_amd/build.py) first; there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+        L.gespmm_csr.restype = ci
+        L.gespmm_csr.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, ci, vp]
+        L.gespmm_csr_simple.restype = ci
+        L.gespmm_csr_simple.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, ci, vp]
+        L.gespmm_plan.restype = ci
+        L.gespmm_plan.argtypes = [i64, i64, i64, ci, ctypes.POINTER(gespmm_plan_t)]
+        L.gespmm_set_tuning.restype = ci
+        L.gespmm_set_tuning.argtypes = [ci, ci, ci]
+        L.gespmm_profile_begin.restype = ci
+        L.gespmm_profile_begin.argtypes = [ci]
+        L.gespmm_profile_end.restype = ci
+        L.gespmm_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
+        L.gespmm_status_string.restype = ctypes.c_char_p
+        L.gespmm_status_string.argtypes = [ci]
+        L.gespmm_version.restype = ci
+        _lib = L
+    return _lib
+
+
+def gespmm_status_string(status: int) -> str:
+    return lib().gespmm_status_string(int(status)).decode()
+
+
+def gespmm_version() -> int:
+    return int(lib().gespmm_version())
+
+
+def _check(status):
+    if status != GESPMM_OK:
+        raise GespmmError(status, gespmm_status_string(status))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check_tensors(rowptr, colind, vals, B, C):
+    import torch
+    assert rowptr.is_cuda and rowptr.dtype == torch.int32 and rowptr.is_contiguous()
+    assert colind.is_cuda and colind.dtype == torch.int32 and colind.is_contiguous()
+    assert vals is None or (vals.is_cuda and vals.dtype == torch.float32 and vals.is_contiguous()
+                            and vals.numel() == colind.numel())
+    assert B.is_cuda and B.dtype == torch.float32 and B.is_contiguous() and B.dim() == 2
+    assert C.is_cuda and C.dtype == torch.float32 and C.is_contiguous() and C.dim() == 2
+    assert C.shape == (rowptr.numel() - 1, B.shape[1])
+
+
+def gespmm_csr(rowptr, colind, vals, B, op, C=None, stream=None):
+    """C = A (x) B on the GPU; returns C (allocated here when not given)."""
+    import torch
+    M, (K, N) = rowptr.numel() - 1, B.shape
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.float32, device=B.device)
+    _check_tensors(rowptr, colind, vals, B, C)
+    code = OPS[op] if isinstance(op, str) else int(op)
+    _check(lib().gespmm_csr(M, K, N, colind.numel(), _ptr(rowptr), _ptr(colind), _ptr(vals),
+                            _ptr(B), _ptr(C), code, _stream(stream)))
+    return C
+
+
+def gespmm_csr_simple(rowptr, colind, vals, B, op, C=None, stream=None):
+    """Same as gespmm_csr, but the library reads nnz from rowptr[M] (one stream sync)."""
+    import torch
+    M, (K, N) = rowptr.numel() - 1, B.shape
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.float32, device=B.device)
+    _check_tensors(rowptr, colind, vals, B, C)
+    code = OPS[op] if isinstance(op, str) else int(op)
+    _check(lib().gespmm_csr_simple(M, K, N, _ptr(rowptr), _ptr(colind), _ptr(vals), _ptr(B),
+                                   _ptr(C), code, _stream(stream)))
+    return C
+
+
+def gespmm_plan(M, N, nnz, aligned16=True) -> dict:
+    p = gespmm_plan_t()
+    _check(lib().gespmm_plan(M, N, nnz, int(bool(aligned16)), ctypes.byref(p)))
+    return {name: int(getattr(p, name)) for name, _ in p._fields_}
+
+
+def gespmm_set_tuning(lanes_per_row=-1, tiles_per_lane=-1, xcd_remap=-1):
+    _check(lib().gespmm_set_tuning(int(lanes_per_row), int(tiles_per_lane), int(xcd_remap)))
+
+
+def gespmm_profile_begin(capacity: int):
+    _check(lib().gespmm_profile_begin(int(capacity)))
+
+
+def gespmm_profile_end():
+    """Returns (summed main-kernel milliseconds, number of bracketed launches)."""
+    ms, n = ctypes.c_double(0.0), ctypes.c_int(0)
+    _check(lib().gespmm_profile_end(ctypes.byref(ms), ctypes.byref(n)))
+    return float(ms.value), int(n.value)

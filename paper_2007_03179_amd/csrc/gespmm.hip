@@ -1,0 +1,523 @@
+// CSR SpMM / SpMM-like kernels for gfx950 (MI355X) and their C ABI.
+//
+// Result computed (paper: Algorithm 1, Section III-A; general reduce: Eq. 1, Section IV-A):
+//     C[i, j] = reduce_p  vals[p] * B[colind[p], j],   p over the stored entries of row i.
+//
+// How the work is laid out (what is kept from the paper and what is not):
+//  * The paper gives one thread block to each sparse row (Algorithms 2 and 3).  Here the
+//    unit of work is a CHUNK of S consecutive stored entries, one per 64-lane wavefront,
+//    so every wavefront has the same amount of gather work whatever the row lengths are.
+//    A row that crosses a chunk border is finished with atomics (add, or integer
+//    max/min on the ordered bit pattern of the float); rows inside one chunk are
+//    written with plain stores by exactly one wavefront.
+//  * Kept from Coalesced Row Caching (Section III-B): a wavefront first pulls its chunk
+//    of (colind, val) with fully coalesced loads into LDS, then every lane reads the
+//    entries it needs from LDS (broadcast reads), so sparse data crosses HBM once.
+//  * Kept from Coarse-grained Warp Merging (Section III-C): one lane owns T column tiles
+//    of 4 floats (one 16-byte load each), so the sparse chunk is read once for
+//    4*G*T output columns and several independent B loads are in flight per lane.
+//  * New for 64 lanes: the wavefront is cut into 64/G slots of G lanes.  The G lanes of
+//    a slot cover the column block; the slots take different stored entries of the same
+//    row in the same step, and their partial results are folded with cross-lane
+//    exchanges at the end of the row.
+//  * A first small kernel zero-fills empty rows and writes the reduce identity into the
+//    rows that will be finished with atomics.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstring>
+#include <vector>
+
+#include "gespmm.h"
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlock = kWave * kWavesPerBlock;
+constexpr int kChunkLoads = 4;                  // UA: coalesced loads per lane that fill a chunk
+constexpr int kChunk = kChunkLoads * kWave;     // S: stored entries per wavefront
+constexpr int kChunkShift = 8;                  // log2(kChunk)
+static_assert((1 << kChunkShift) == kChunk, "chunk size must match its shift");
+constexpr int kXcds = 8;
+constexpr int kLoadsInFlight = 4;               // 16-byte gathers a lane issues before it waits
+
+enum Fold { kAdd = 0, kMax = 1, kMin = 2 };
+
+struct KernelArgs {
+  int32_t M;
+  int32_t N;
+  int32_t nnz;
+  int32_t is_mean;
+  int64_t chunks;
+  int64_t chunk_blocks;   // grid.x
+  int32_t xcd_remap;
+  const int32_t* rowptr;
+  const int32_t* colind;
+  const float* vals;
+  const float* B;
+  float* C;
+};
+
+// ------------------------------------------------------------------ vectors --
+template <int V> struct Vec;
+template <> struct Vec<4> {
+  float v[4];
+  __device__ static Vec load(const float* p) {
+    const float4 t = *reinterpret_cast<const float4*>(p);
+    return Vec{{t.x, t.y, t.z, t.w}};
+  }
+  __device__ void store(float* p) const { *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]); }
+};
+template <> struct Vec<1> {
+  float v[1];
+  __device__ static Vec load(const float* p) { return Vec{{*p}}; }
+  __device__ void store(float* p) const { *p = v[0]; }
+};
+
+template <int F> __device__ __forceinline__ float fold_identity() {
+  return F == kAdd ? 0.0f : (F == kMax ? -__builtin_inff() : __builtin_inff());
+}
+template <int F> __device__ __forceinline__ float fold(float acc, float a, float b) {
+  if (F == kAdd) return __builtin_fmaf(a, b, acc);
+  const float x = a * b;                     // one correctly rounded fp32 product, then compare
+  return F == kMax ? __builtin_fmaxf(acc, x) : __builtin_fminf(acc, x);
+}
+template <int F> __device__ __forceinline__ float fold2(float x, float y) {
+  return F == kAdd ? x + y : (F == kMax ? __builtin_fmaxf(x, y) : __builtin_fminf(x, y));
+}
+
+// Combine a partial result into C[ptr] when several wavefronts share the row.
+// max/min use integer atomics on the float's bit pattern: for non-negative floats the
+// signed-int order equals the float order, for negative floats the unsigned order is
+// the reverse of the float order; -0 < +0 comes out as IEEE maximum/minimum want it.
+template <int F> __device__ __forceinline__ void atomic_fold(float* ptr, float x) {
+  if (F == kAdd) {
+    __hip_atomic_fetch_add(ptr, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  } else {
+    const int bits = __float_as_int(x);
+    if (F == kMax) {
+      if (bits >= 0) __hip_atomic_fetch_max(reinterpret_cast<int*>(ptr), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      else __hip_atomic_fetch_min(reinterpret_cast<unsigned*>(ptr), (unsigned)bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+      if (bits >= 0) __hip_atomic_fetch_min(reinterpret_cast<int*>(ptr), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      else __hip_atomic_fetch_max(reinterpret_cast<unsigned*>(ptr), (unsigned)bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
+// Workgroup id -> logical block id such that each XCD (workgroups are dealt to the 8
+// XCDs round-robin) walks one contiguous range of chunks: a row split over several
+// chunks then meets its atomics in one L2, and neighbouring rows of C stay together.
+__device__ __forceinline__ int64_t logical_block(int64_t b, int64_t nb, int remap) {
+  if (!remap) return b;
+  const int64_t xcd = b % kXcds, within = b / kXcds;
+  const int64_t q = nb / kXcds, r = nb % kXcds;
+  return xcd * q + (xcd < r ? xcd : r) + within;
+}
+
+// ------------------------------------------------------------- init kernel --
+// One lane per row: empty rows get zeros; rows whose entries lie in more than one chunk
+// get the reduce identity (they are completed by atomics in the main kernel).
+template <int V>
+__global__ void __launch_bounds__(kBlock) init_rows(int32_t M, int32_t N, const int32_t* __restrict__ rowptr,
+                                                   float* __restrict__ C, float identity) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t base = ((int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)) * kWave;
+  if (base >= M) return;
+  const int64_t r = base + lane;
+  int flag = 0;
+  if (r < M) {
+    const int s = rowptr[r], e = rowptr[r + 1];
+    if (s == e) flag = 1;
+    else if ((s >> kChunkShift) != ((e - 1) >> kChunkShift)) flag = 2;
+  }
+  unsigned long long todo = __ballot(flag != 0);
+  while (todo) {
+    const int i = __builtin_ctzll(todo);
+    todo &= todo - 1;
+    const float value = __builtin_amdgcn_readlane(flag, i) == 1 ? 0.0f : identity;
+    float* row = C + (base + i) * (int64_t)N;
+    Vec<V> out;
+#pragma unroll
+    for (int x = 0; x < V; ++x) out.v[x] = value;
+    for (int c = lane * V; c < N; c += kWave * V) out.store(row + c);
+  }
+}
+
+// ------------------------------------------------------------- main kernel --
+// F: fold; V: floats per lane per load; G: lanes per slot; T: column tiles per lane.
+template <int F, int V, int G, int T>
+__global__ void __launch_bounds__(kBlock) spmm_chunks(const KernelArgs a) {
+  constexpr int NS = kWave / G;                 // slots: entries of one row taken per step
+  constexpr int U = kLoadsInFlight / T > 0 ? kLoadsInFlight / T : 1;   // steps per pass
+  __shared__ int2 s_ka[kWavesPerBlock][kChunk];
+
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x >> 6;
+  const int slot = lane / G;
+  const int g = lane % G;
+
+  const int64_t chunk = logical_block(blockIdx.x, a.chunk_blocks, a.xcd_remap) * kWavesPerBlock + wave;
+  if (chunk >= a.chunks) return;                // whole wavefront leaves; no block barrier is used
+  const int cs = (int)(chunk << kChunkShift);   // first stored entry of this chunk (< 2^31)
+  const int cnt = (a.nnz - cs) < kChunk ? (a.nnz - cs) : kChunk;
+  const int ce = cs + cnt;
+  int2* ka = s_ka[wave];
+
+  // (1) coalesced load of the chunk's (colind, val) into this wavefront's LDS slice; all
+  //     loads are issued before the first LDS write (indices past the end repeat the last
+  //     entry, whose copies are never consumed)
+  {
+    int k[kChunkLoads];
+    float v[kChunkLoads];
+#pragma unroll
+    for (int u = 0; u < kChunkLoads; ++u) {
+      const int idx = u * kWave + lane;
+      k[u] = a.colind[cs + (idx < cnt ? idx : cnt - 1)];
+    }
+    if (a.vals) {
+#pragma unroll
+      for (int u = 0; u < kChunkLoads; ++u) {
+        const int idx = u * kWave + lane;
+        v[u] = a.vals[cs + (idx < cnt ? idx : cnt - 1)];
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < kChunkLoads; ++u) v[u] = 1.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < kChunkLoads; ++u) ka[u * kWave + lane] = make_int2(k[u], __float_as_int(v[u]));
+  }
+
+  // (2) first row of the chunk: the last r with rowptr[r] <= cs, found by a 64-way search
+  int lo = 0, hi = a.M;                          // rowptr[lo] <= cs < rowptr[hi]
+  while (hi - lo > 1) {
+    const int64_t step = ((int64_t)(hi - lo) + kWave - 1) / kWave;
+    int64_t probe = lo + (int64_t)(lane + 1) * step;
+    if (probe > hi) probe = hi;
+    const int below = __builtin_popcountll(__ballot(a.rowptr[probe] <= cs));   // probes are monotone
+    const int64_t nlo = lo + below * step;       // below <= 63 because rowptr[hi] > cs
+    int64_t nhi = nlo + step;
+    if (nhi > hi) nhi = hi;
+    lo = (int)nlo;
+    hi = (int)nhi;
+  }
+
+  // column tiles of this lane (loads use a clamped column so they are never masked)
+  const int colbase = blockIdx.y * (V * G * T);
+  int col[T];
+  int colc[T];
+#pragma unroll
+  for (int t = 0; t < T; ++t) {
+    col[t] = colbase + (t * G + g) * V;
+    colc[t] = col[t] < a.N ? col[t] : a.N - V;
+  }
+
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+  // (3) walk the rows that have entries in [cs, ce), 64 row bounds at a time
+  for (int64_t rbase = lo;; rbase += kWave) {
+    int64_t rr = rbase + lane;
+    if (rr > a.M) rr = a.M;
+    const int my_s = a.rowptr[rr];
+    const int my_e = a.rowptr[rr < a.M ? rr + 1 : a.M];
+    unsigned long long todo = __ballot(rbase + lane < a.M && my_e > my_s && my_s < ce);
+    while (todo) {
+      const int i = __builtin_ctzll(todo);
+      todo &= todo - 1;
+      const int s = __builtin_amdgcn_readlane(my_s, i);
+      const int e = __builtin_amdgcn_readlane(my_e, i);
+      const int ps = (s > cs ? s : cs) - cs;    // segment of the row inside the chunk, local offsets
+      const int pe = (e < ce ? e : ce) - cs;
+      const bool whole = s >= cs && e <= ce;
+
+      Vec<V> acc[T];
+#pragma unroll
+      for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int x = 0; x < V; ++x) acc[t].v[x] = fold_identity<F>();
+
+      // U steps per pass, all gathers issued before the first use.  A step past the end of
+      // the segment re-reads the segment's last entry: harmless for max/min (idempotent),
+      // and given weight 0 for the sum.
+      for (int base = ps; base < pe; base += U * NS) {
+        int2 e2[U];
+        Vec<V> b[U][T];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int q = base + u * NS + slot;
+          e2[u] = ka[q < pe ? q : pe - 1];
+          if (F == kAdd && q >= pe) e2[u].y = 0;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const float* brow = a.B + (int64_t)e2[u].x * a.N;
+#pragma unroll
+          for (int t = 0; t < T; ++t) b[u][t] = Vec<V>::load(brow + colc[t]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+          for (int t = 0; t < T; ++t)
+#pragma unroll
+            for (int x = 0; x < V; ++x) acc[t].v[x] = fold<F>(acc[t].v[x], __int_as_float(e2[u].y), b[u][t].v[x]);
+      }
+
+      // fold the slots together (every slot ends with the total)
+#pragma unroll
+      for (int off = G; off < kWave; off <<= 1)
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+#pragma unroll
+          for (int x = 0; x < V; ++x) acc[t].v[x] = fold2<F>(acc[t].v[x], __shfl_xor(acc[t].v[x], off, kWave));
+
+      if (slot == 0) {
+        float* crow = a.C + (rbase + i) * (int64_t)a.N;
+        const float len = (float)(e - s);
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+          if (col[t] < a.N) {
+            if (whole) {
+              if (a.is_mean) {
+#pragma unroll
+                for (int x = 0; x < V; ++x) acc[t].v[x] = acc[t].v[x] / len;
+              }
+              acc[t].store(crow + col[t]);
+            } else {
+              const float w = a.is_mean ? 1.0f / len : 1.0f;
+#pragma unroll
+              for (int x = 0; x < V; ++x) atomic_fold<F>(crow + col[t] + x, F == kAdd ? acc[t].v[x] * w : acc[t].v[x]);
+            }
+          }
+        }
+      }
+    }
+    // the next batch of rows is needed only if it still starts inside the chunk
+    const int next_start = __builtin_amdgcn_readlane(my_e, kWave - 1);
+    if (rbase + kWave >= a.M || next_start >= ce) break;
+  }
+}
+
+// --------------------------------------------------------------- host side --
+using MainKernel = void (*)(const KernelArgs);
+
+template <int F, int V>
+MainKernel pick_gt(int G, int T) {
+#define GESPMM_CASE(GG, TT) if (G == GG && T == TT) return spmm_chunks<F, V, GG, TT>;
+  GESPMM_CASE(1, 1) GESPMM_CASE(2, 1) GESPMM_CASE(4, 1) GESPMM_CASE(8, 1)
+  GESPMM_CASE(16, 1) GESPMM_CASE(32, 1) GESPMM_CASE(64, 1)
+  GESPMM_CASE(1, 2) GESPMM_CASE(2, 2) GESPMM_CASE(4, 2) GESPMM_CASE(8, 2)
+  GESPMM_CASE(16, 2) GESPMM_CASE(32, 2) GESPMM_CASE(64, 2)
+  GESPMM_CASE(8, 4) GESPMM_CASE(16, 4) GESPMM_CASE(32, 4) GESPMM_CASE(64, 4)
+#undef GESPMM_CASE
+  return nullptr;
+}
+
+MainKernel pick_kernel(int fold, int vec, int G, int T) {
+  if (vec == 4) {
+    if (fold == kAdd) return pick_gt<kAdd, 4>(G, T);
+    if (fold == kMax) return pick_gt<kMax, 4>(G, T);
+    return pick_gt<kMin, 4>(G, T);
+  }
+  if (fold == kAdd) return pick_gt<kAdd, 1>(G, T);
+  if (fold == kMax) return pick_gt<kMax, 1>(G, T);
+  return pick_gt<kMin, 1>(G, T);
+}
+
+bool has_kernel(int G, int T) {
+  return pick_gt<kAdd, 4>(G, T) != nullptr;
+}
+
+int next_pow2(int64_t x) {
+  int p = 1;
+  while (p < x && p < 64) p <<= 1;
+  return p;
+}
+
+// process-wide tuning overrides (-1 = automatic)
+int g_force_g = -1, g_force_t = -1, g_force_remap = -1;
+
+void make_plan(int64_t M, int64_t N, int64_t nnz, bool aligned16, gespmm_plan_t* p) {
+  (void)M;
+  const int vec = (aligned16 && N > 0 && N % 4 == 0) ? 4 : 1;
+  const int64_t ncv = N > 0 ? (N + vec - 1) / vec : 1;     // vector columns to cover
+  // widest slot that is still <= 16 lanes for wide N, so several entries of a row are in
+  // flight per step; two tiles per lane from 32 vector columns up (sparse chunk read once)
+  int G = next_pow2(ncv), T = 1;
+  if (G > 16) { G /= 2; T = 2; }
+  if (ncv > 64 && G * T < 128) { G = 64; T = 2; }
+  if (g_force_g > 0) G = g_force_g;
+  if (g_force_t > 0) T = g_force_t;
+  p->vec = vec;
+  p->lanes_per_row = G;
+  p->tiles_per_lane = T;
+  p->slots = kWave / G;
+  p->chunk_nnz = kChunk;
+  p->col_blocks = (int32_t)((ncv + (int64_t)G * T - 1) / ((int64_t)G * T));
+  p->chunks = (nnz + kChunk - 1) / kChunk;
+  p->grid_x = (p->chunks + kWavesPerBlock - 1) / kWavesPerBlock;
+  p->block_threads = kBlock;
+  p->xcd_remap = g_force_remap >= 0 ? g_force_remap : 1;
+}
+
+// profiling state
+std::vector<hipEvent_t> g_ev_start, g_ev_stop;
+int g_ev_used = 0;
+bool g_profiling = false;
+
+int validate(int64_t M, int64_t K, int64_t N, int64_t nnz, const void* rowptr, const void* colind,
+             const void* B, const void* C, int op) {
+  if (M < 0 || K < 0 || N < 0 || nnz < 0) return GESPMM_ERR_BAD_ARG;
+  if (op < GESPMM_SUM || op > GESPMM_MIN) return GESPMM_ERR_BAD_ARG;
+  if (M >= INT32_MAX || K > INT32_MAX || nnz > INT32_MAX - kChunk || N > INT32_MAX / 8) return GESPMM_ERR_TOO_LARGE;
+  if (nnz > 0 && (M == 0 || K == 0)) return GESPMM_ERR_BAD_ARG;
+  if (M == 0 || N == 0) return GESPMM_OK;
+  if (!rowptr || !C) return GESPMM_ERR_NULL;
+  if (nnz > 0 && (!colind || !B)) return GESPMM_ERR_NULL;
+  return GESPMM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gespmm_plan(int64_t M, int64_t N, int64_t nnz, int aligned16, gespmm_plan_t* out) {
+  if (!out) return GESPMM_ERR_NULL;
+  if (M < 0 || N < 0 || nnz < 0) return GESPMM_ERR_BAD_ARG;
+  make_plan(M, N, nnz, aligned16 != 0, out);
+  return GESPMM_OK;
+}
+
+int gespmm_set_tuning(int lanes_per_row, int tiles_per_lane, int xcd_remap) {
+  const int G = lanes_per_row, T = tiles_per_lane;
+  if (G > 0 && (G > kWave || (G & (G - 1)) != 0)) return GESPMM_ERR_BAD_ARG;
+  if (T > 0 && T != 1 && T != 2 && T != 4) return GESPMM_ERR_BAD_ARG;
+  if (G > 0 && T > 0 && !has_kernel(G, T)) return GESPMM_ERR_BAD_ARG;
+  if (xcd_remap > 1) return GESPMM_ERR_BAD_ARG;
+  g_force_g = G > 0 ? G : -1;
+  g_force_t = T > 0 ? T : -1;
+  g_force_remap = xcd_remap >= 0 ? xcd_remap : -1;
+  return GESPMM_OK;
+}
+
+int gespmm_csr(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+               const int32_t* colind, const float* vals, const float* B, float* C, int op,
+               void* stream_) {
+  const int st = validate(M, K, N, nnz, rowptr, colind, B, C, op);
+  if (st != GESPMM_OK || M == 0 || N == 0) return st;
+  hipStream_t stream = (hipStream_t)stream_;
+
+  const bool aligned16 = (((uintptr_t)B | (uintptr_t)C) & 15u) == 0;
+  gespmm_plan_t plan;
+  make_plan(M, N, nnz, aligned16, &plan);
+  const int fold = op == GESPMM_MAX ? kMax : (op == GESPMM_MIN ? kMin : kAdd);
+  MainKernel kernel = pick_kernel(fold, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
+  if (!kernel) return GESPMM_ERR_BAD_ARG;
+
+  // (a) empty rows -> 0, rows shared by several chunks -> reduce identity
+  float identity = 0.0f;
+  if (fold == kMax) identity = -__builtin_inff();
+  if (fold == kMin) identity = __builtin_inff();
+  const unsigned init_blocks = (unsigned)((M + kBlock - 1) / kBlock);
+  if (plan.vec == 4)
+    hipLaunchKernelGGL(init_rows<4>, dim3(init_blocks), dim3(kBlock), 0, stream, (int32_t)M, (int32_t)N, rowptr, C, identity);
+  else
+    hipLaunchKernelGGL(init_rows<1>, dim3(init_blocks), dim3(kBlock), 0, stream, (int32_t)M, (int32_t)N, rowptr, C, identity);
+  if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
+  if (nnz == 0) return GESPMM_OK;
+
+  // (b) the chunks
+  KernelArgs a;
+  a.M = (int32_t)M;
+  a.N = (int32_t)N;
+  a.nnz = (int32_t)nnz;
+  a.is_mean = op == GESPMM_MEAN;
+  a.chunks = plan.chunks;
+  a.chunk_blocks = plan.grid_x;
+  a.xcd_remap = plan.xcd_remap;
+  a.rowptr = rowptr;
+  a.colind = colind;
+  a.vals = vals;
+  a.B = B;
+  a.C = C;
+  const bool timed = g_profiling && g_ev_used < (int)g_ev_start.size();
+  if (timed && hipEventRecord(g_ev_start[g_ev_used], stream) != hipSuccess) return GESPMM_ERR_HIP;
+  hipLaunchKernelGGL(kernel, dim3((unsigned)plan.grid_x, (unsigned)plan.col_blocks), dim3(kBlock), 0, stream, a);
+  if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
+  if (timed) {
+    if (hipEventRecord(g_ev_stop[g_ev_used], stream) != hipSuccess) return GESPMM_ERR_HIP;
+    ++g_ev_used;
+  }
+  return GESPMM_OK;
+}
+
+int gespmm_csr_simple(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colind,
+                      const float* vals, const float* B, float* C, int op, void* stream_) {
+  if (M < 0 || K < 0 || N < 0) return GESPMM_ERR_BAD_ARG;
+  if (M >= INT32_MAX) return GESPMM_ERR_TOO_LARGE;
+  if (M == 0 || N == 0) return validate(M, K, N, 0, rowptr, colind, B, C, op);
+  if (!rowptr) return GESPMM_ERR_NULL;
+  hipStream_t stream = (hipStream_t)stream_;
+  int32_t nnz = 0;
+  if (hipMemcpyAsync(&nnz, rowptr + M, sizeof(nnz), hipMemcpyDeviceToHost, stream) != hipSuccess) return GESPMM_ERR_HIP;
+  if (hipStreamSynchronize(stream) != hipSuccess) return GESPMM_ERR_HIP;
+  return gespmm_csr(M, K, N, nnz, rowptr, colind, vals, B, C, op, stream_);
+}
+
+int gespmm_profile_begin(int capacity) {
+  if (capacity <= 0 || g_profiling) return GESPMM_ERR_BAD_ARG;
+  g_ev_start.assign(capacity, nullptr);
+  g_ev_stop.assign(capacity, nullptr);
+  for (int i = 0; i < capacity; ++i) {
+    if (hipEventCreate(&g_ev_start[i]) != hipSuccess || hipEventCreate(&g_ev_stop[i]) != hipSuccess) {
+      g_ev_start.clear();
+      g_ev_stop.clear();
+      return GESPMM_ERR_HIP;
+    }
+  }
+  g_ev_used = 0;
+  g_profiling = true;
+  return GESPMM_OK;
+}
+
+int gespmm_profile_end(double* main_kernel_ms_sum, int* launches) {
+  if (!g_profiling) return GESPMM_ERR_BAD_ARG;
+  g_profiling = false;
+  double total = 0.0;
+  int status = GESPMM_OK;
+  for (int i = 0; i < g_ev_used; ++i) {
+    float ms = 0.0f;
+    if (hipEventSynchronize(g_ev_stop[i]) != hipSuccess ||
+        hipEventElapsedTime(&ms, g_ev_start[i], g_ev_stop[i]) != hipSuccess)
+      status = GESPMM_ERR_HIP;
+    total += ms;
+  }
+  for (size_t i = 0; i < g_ev_start.size(); ++i) {
+    (void)hipEventDestroy(g_ev_start[i]);
+    (void)hipEventDestroy(g_ev_stop[i]);
+  }
+  if (main_kernel_ms_sum) *main_kernel_ms_sum = total;
+  if (launches) *launches = g_ev_used;
+  g_ev_start.clear();
+  g_ev_stop.clear();
+  g_ev_used = 0;
+  return status;
+}
+
+const char* gespmm_status_string(int status) {
+  switch (status) {
+    case GESPMM_OK: return "ok";
+    case GESPMM_ERR_BAD_ARG: return "bad argument (negative size, unknown op, or no kernel for the forced tuning)";
+    case GESPMM_ERR_NULL: return "a required pointer is NULL";
+    case GESPMM_ERR_TOO_LARGE: return "M, K or nnz does not fit 32-bit indices";
+    case GESPMM_ERR_HIP: return "a HIP call failed";
+    default: return "unknown status";
+  }
+}
+
+int gespmm_version(void) { return 100; }
+
+}  // extern "C"

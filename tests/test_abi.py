@@ -1,0 +1,99 @@
+"""The C-ABI library without a GPU: it loads, exports what the header declares,
+rejects bad arguments on the host, and plans launches sensibly (CPU only)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2007_03179_amd as gs
+from paper_2007_03179_amd import build as hip_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "gespmm.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    hip_build.build(force=False)
+    return gs.lib()
+
+
+def _declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(gespmm_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = _declared_functions()
+    assert {"gespmm_csr", "gespmm_csr_simple", "gespmm_plan", "gespmm_set_tuning",
+            "gespmm_profile_begin", "gespmm_profile_end", "gespmm_status_string",
+            "gespmm_version"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_version_and_status_strings(L):
+    assert gs.gespmm_version() >= 100
+    seen = {gs.gespmm_status_string(s) for s in range(0, 5)}
+    assert len(seen) == 5 and all(seen)
+    assert "unknown" in gs.gespmm_status_string(99)
+
+
+def test_argument_errors_come_before_any_device_work(L):
+    p = ctypes.c_void_p(0x1000)      # never dereferenced on the host
+    call = L.gespmm_csr
+    assert call(-1, 4, 4, 0, p, p, p, p, p, 0, None) == 1
+    assert call(4, 4, 4, -3, p, p, p, p, p, 0, None) == 1
+    assert call(4, 4, 4, 8, p, p, p, p, p, 7, None) == 1          # unknown op
+    assert call(4, 4, 4, 8, p, p, p, p, p, -1, None) == 1
+    assert call(0, 4, 4, 8, p, p, p, p, p, 0, None) == 1          # entries without rows
+    assert call(4, 4, 4, 8, None, p, p, p, p, 0, None) == 2       # rowptr NULL
+    assert call(4, 4, 4, 8, p, None, p, p, p, 0, None) == 2       # colind NULL with nnz > 0
+    assert call(4, 4, 4, 8, p, p, p, None, p, 0, None) == 2       # B NULL
+    assert call(4, 4, 4, 8, p, p, p, p, None, 0, None) == 2       # C NULL
+    assert call(2**31, 4, 4, 8, p, p, p, p, p, 0, None) == 3
+    assert call(4, 2**31 + 1, 4, 8, p, p, p, p, p, 0, None) == 3
+    assert call(4, 4, 4, 2**31, p, p, p, p, p, 0, None) == 3
+    # nothing to do: success without touching a device
+    assert call(0, 4, 4, 0, p, p, p, p, p, 0, None) == 0
+    assert call(4, 4, 0, 8, p, p, p, p, p, 0, None) == 0
+    assert L.gespmm_csr_simple(-1, 4, 4, p, p, p, p, p, 0, None) == 1
+    assert L.gespmm_csr_simple(4, 4, 4, None, p, p, p, p, 0, None) == 2
+    assert L.gespmm_csr_simple(0, 4, 4, p, p, p, p, p, 0, None) == 0
+    assert L.gespmm_plan(4, 4, 4, 1, None) == 2
+    assert L.gespmm_profile_end(None, None) == 1                  # not profiling
+
+
+@pytest.mark.parametrize("N,G,T,blocks", [(8, 2, 1, 1), (16, 4, 1, 1), (32, 8, 1, 1), (64, 16, 1, 1),
+                                          (128, 16, 2, 1), (256, 32, 2, 1), (512, 64, 2, 1),
+                                          (1024, 64, 2, 2), (4, 1, 1, 1), (100, 16, 2, 1)])
+def test_plan_covers_all_columns_vectorised(N, G, T, blocks):
+    p = gs.gespmm_plan(1000, N, 10_000)
+    assert p["vec"] == 4 and (p["lanes_per_row"], p["tiles_per_lane"], p["col_blocks"]) == (G, T, blocks)
+    assert p["vec"] * G * T * blocks >= N and p["slots"] * G == 64
+    assert p["chunks"] == -(-10_000 // p["chunk_nnz"])
+    assert p["grid_x"] * (p["block_threads"] // 64) >= p["chunks"]
+
+
+@pytest.mark.parametrize("N,aligned", [(1, True), (3, True), (7, False), (33, True), (100, False), (64, False)])
+def test_plan_scalar_path(N, aligned):
+    p = gs.gespmm_plan(10, N, 50, aligned16=aligned)
+    assert p["vec"] == (4 if (aligned and N % 4 == 0) else 1)
+    assert p["vec"] * p["lanes_per_row"] * p["tiles_per_lane"] * p["col_blocks"] >= N
+
+
+def test_tuning_override_is_validated():
+    with pytest.raises(gs.GespmmError):
+        gs.gespmm_set_tuning(3, -1, -1)
+    with pytest.raises(gs.GespmmError):
+        gs.gespmm_set_tuning(-1, 3, -1)
+    with pytest.raises(gs.GespmmError):
+        gs.gespmm_set_tuning(2, 4, -1)        # no such kernel
+    try:
+        gs.gespmm_set_tuning(32, 1, 0)
+        p = gs.gespmm_plan(1000, 64, 10_000)
+        assert (p["lanes_per_row"], p["tiles_per_lane"], p["xcd_remap"], p["col_blocks"]) == (32, 1, 0, 1)
+    finally:
+        gs.gespmm_set_tuning(-1, -1, -1)
+    assert gs.gespmm_plan(1000, 64, 10_000)["lanes_per_row"] == 16

@@ -1,0 +1,264 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+sum / mean: |C - Cref| <= 1e-5 * Sabs + 1e-6 per element (Sabs = sum |a||b|, divided by the
+row length for mean); max / min: bit-for-bit equal to the oracle rounded once to fp32.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import graphgen
+import oracle
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+OPS = ("sum", "mean", "max", "min")
+KERNEL_SHAPES = [(1, 1), (2, 1), (4, 1), (8, 1), (16, 1), (32, 1), (64, 1),
+                 (1, 2), (2, 2), (4, 2), (8, 2), (16, 2), (32, 2), (64, 2),
+                 (8, 4), (16, 4), (32, 4), (64, 4)]
+
+
+@pytest.fixture(scope="module")
+def gs():
+    import paper_2007_03179_amd as gs
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    gs.lib()                                   # raises if the HIP library was not built
+    yield gs
+    gs.gespmm_set_tuning(-1, -1, -1)
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def dev(x):
+    return None if x is None else torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def check(gs, rowptr, colind, vals, B, op, rows=None, label="", entry="gespmm_csr", dB=None, dA=None):
+    """Run one call on the GPU and compare with the oracle (all rows, or the sampled rows)."""
+    say(f"  case {label} op={op} M={len(rowptr) - 1} K={B.shape[0]} N={B.shape[1]} nnz={len(colind)}")
+    d_rp, d_ci, d_v = dA if dA is not None else (dev(rowptr), dev(colind), dev(vals))
+    d_B = dB if dB is not None else dev(B)
+    C = getattr(gs, entry)(d_rp, d_ci, d_v, d_B, op)
+    torch.cuda.synchronize()
+    C = C.cpu().numpy()
+    Cref, Sabs = oracle.spmm(rowptr, colind, vals, B, op, rows=rows)
+    got = C if rows is None else C[rows]
+    ok, worst = oracle.compare(op, got, Cref, Sabs)
+    assert ok, f"{label} {op}: worst={worst}"
+    return C
+
+
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("N", [1, 3, 4, 7, 8, 16, 32, 33, 64, 100, 128, 256, 512, 520])
+def test_widths_all_ops(gs, N):
+    # several chunks, ragged tails, empty rows, one row spanning ~12 chunks, M != K
+    rp, ci, v = graphgen.random_csr(700, 500, 9.0, 100 + N, empty_frac=0.1, long_rows=((350, 3000),),
+                                    duplicates=True)
+    B = graphgen.random_dense(500, N, N)
+    for op in OPS:
+        check(gs, rp, ci, v, B, op, label=f"widths N={N}")
+
+
+def test_unsorted_duplicate_columns_and_null_vals(gs):
+    rp, ci, v = graphgen.random_csr(400, 300, 12.0, 7, empty_frac=0.2, duplicates=True, sort_cols=False)
+    B = graphgen.random_dense(300, 32, 7)
+    for op in OPS:
+        check(gs, rp, ci, v, B, op, label="unsorted+dups")
+        check(gs, rp, ci, None, B, op, label="vals=NULL")
+
+
+def test_degenerate_shapes(gs):
+    B = graphgen.random_dense(5, 8, 1)
+    # all rows empty (nnz == 0): C must be all zeros for every op
+    rp = np.zeros(4, dtype=np.int32)
+    ci = np.zeros(0, dtype=np.int32)
+    v = np.zeros(0, dtype=np.float32)
+    for op in OPS:
+        C = check(gs, rp, ci, v, B, op, label="nnz=0")
+        assert not C.any()
+    # one row, one entry
+    rp, ci, v = np.array([0, 1], np.int32), np.array([4], np.int32), np.array([-2.5], np.float32)
+    for op in OPS:
+        check(gs, rp, ci, v, B, op, label="1x1")
+    # leading and trailing empty rows around a single dense row longer than several chunks
+    n = 1000
+    rp = np.array([0, 0, 0, n, n, n], dtype=np.int32)
+    rng = np.random.default_rng(3)
+    ci = rng.integers(0, 5, size=n).astype(np.int32)
+    v = (rng.random(n) - 0.5).astype(np.float32)
+    for op in OPS:
+        check(gs, rp, ci, v, B, op, label="empty-around-long")
+    # a chunk border that falls exactly on a row border (256 entries per chunk)
+    rp = np.array([0, 256, 512, 700], dtype=np.int32)
+    ci = rng.integers(0, 5, size=700).astype(np.int32)
+    v = (rng.random(700) - 0.5).astype(np.float32)
+    for op in OPS:
+        check(gs, rp, ci, v, B, op, label="row-border==chunk-border")
+    # many more rows than entries: long runs of empty rows inside and after the last chunk
+    rp, ci, v = graphgen.random_csr(5000, 64, 1.0, 17, empty_frac=0.97)
+    B = graphgen.random_dense(64, 16, 17)
+    for op in OPS:
+        check(gs, rp, ci, v, B, op, label="mostly-empty")
+
+
+def test_signed_zero_rule_on_gpu(gs):
+    # +0 must win max and lose min, whichever comes first and wherever the row is split
+    for n in (2, 600):
+        ci = np.tile(np.array([0, 1], dtype=np.int32), n // 2)
+        rp = np.array([0, n, 2 * n], dtype=np.int32)
+        ci = np.concatenate([ci, ci[::-1]]).astype(np.int32)
+        v = np.ones(2 * n, dtype=np.float32)
+        B = np.array([[-0.0] * 4, [0.0] * 4], dtype=np.float32)
+        hi = check(gs, rp, ci, v, B, "max", label=f"signed-zero n={n}")
+        lo = check(gs, rp, ci, v, B, "min", label=f"signed-zero n={n}")
+        assert not np.signbit(hi).any() and np.signbit(lo).all()
+
+
+def test_closed_form_long_row(gs):
+    # one row of 100000 ones against B[k, j] = k * (j + 1): 391 chunks combined by atomics
+    n, N = 100_000, 8
+    rp = np.array([0, n, n], dtype=np.int32)
+    ci = np.arange(n, dtype=np.int32)
+    B = (np.arange(n, dtype=np.float64)[:, None] * (np.arange(N) + 1.0)[None, :]).astype(np.float32)
+    for op in OPS:
+        C = check(gs, rp, ci, None, B, op, label="closed-form")
+        if op == "max":
+            assert np.array_equal(C[0], (n - 1) * (np.arange(N) + 1.0).astype(np.float32))
+        if op == "min":
+            assert not C[0].any()
+        assert not C[1].any()
+
+
+@pytest.mark.parametrize("vec_n", [(4, 72), (1, 37)])
+def test_every_kernel_shape(gs, vec_n):
+    vec, N = vec_n
+    rp, ci, v = graphgen.random_csr(300, 260, 7.0, 55, empty_frac=0.1, long_rows=((11, 900), (12, 300)))
+    B = graphgen.random_dense(260, N, 55)
+    dA, dB = (dev(rp), dev(ci), dev(v)), dev(B)
+    try:
+        for G, T in KERNEL_SHAPES:
+            for remap in (0, 1):
+                gs.gespmm_set_tuning(G, T, remap)
+                plan = gs.gespmm_plan(300, N, len(ci))
+                assert plan["vec"] == vec and plan["lanes_per_row"] == G and plan["tiles_per_lane"] == T
+                for op in ("sum", "mean", "max", "min"):
+                    check(gs, rp, ci, v, B, op, label=f"G={G} T={T} remap={remap}", dA=dA, dB=dB)
+    finally:
+        gs.gespmm_set_tuning(-1, -1, -1)
+
+
+def test_unaligned_buffers_take_scalar_path(gs):
+    rp, ci, v = graphgen.random_csr(200, 150, 8.0, 9)
+    B = graphgen.random_dense(150, 64, 9)
+    d_rp, d_ci, d_v = dev(rp), dev(ci), dev(v)
+    raw = torch.empty(150 * 64 + 1, dtype=torch.float32, device="cuda")
+    d_B = raw[1:].view(150, 64)
+    d_B.copy_(torch.from_numpy(B))
+    assert d_B.data_ptr() % 16 != 0
+    for op in OPS:
+        say(f"  case unaligned op={op}")
+        C = gs.gespmm_csr(d_rp, d_ci, d_v, d_B, op)
+        torch.cuda.synchronize()
+        ok, worst = oracle.compare(op, C.cpu().numpy(), *oracle.spmm(rp, ci, v, B, op))
+        assert ok, worst
+
+
+def test_simple_entry_point_and_side_stream(gs):
+    rp, ci, v = graphgen.random_csr(500, 400, 10.0, 21, empty_frac=0.05, long_rows=((0, 2000),))
+    B = graphgen.random_dense(400, 64, 21)
+    for op in OPS:
+        check(gs, rp, ci, v, B, op, label="simple", entry="gespmm_csr_simple")
+    d_rp, d_ci, d_v, d_B = dev(rp), dev(ci), dev(v), dev(B)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    say("  case side-stream")
+    with torch.cuda.stream(side):
+        C = gs.gespmm_csr(d_rp, d_ci, d_v, d_B, "sum", stream=side)
+    side.synchronize()
+    ok, worst = oracle.compare("sum", C.cpu().numpy(), *oracle.spmm(rp, ci, v, B, "sum"))
+    assert ok, worst
+
+
+def test_results_do_not_depend_on_what_C_held(gs):
+    rp, ci, v = graphgen.random_csr(300, 200, 5.0, 33, empty_frac=0.3, long_rows=((5, 800),))
+    B = graphgen.random_dense(200, 16, 33)
+    d = dev(rp), dev(ci), dev(v), dev(B)
+    for op in OPS:
+        say(f"  case dirty-C op={op}")
+        C = torch.full((300, 16), float("nan"), dtype=torch.float32, device="cuda")
+        for fill in (float("nan"), 1e30, -1e30):
+            C.fill_(fill)
+            gs.gespmm_csr(*d, op, C=C)
+            torch.cuda.synchronize()
+            ok, worst = oracle.compare(op, C.cpu().numpy(), *oracle.spmm(rp, ci, v, B, op))
+            assert ok, (op, fill, worst)
+
+
+def test_profile_brackets_main_kernel(gs):
+    rp, ci, v = graphgen.random_csr(2000, 2000, 20.0, 2)
+    d = dev(rp), dev(ci), dev(v), dev(graphgen.random_dense(2000, 64, 2))
+    gs.gespmm_profile_begin(3)
+    for _ in range(5):
+        gs.gespmm_csr(*d, "sum")
+    ms, n = gs.gespmm_profile_end()
+    assert n == 3 and 0 < ms < 1000
+
+
+# ------------------------------------------------------------ the workloads --
+@pytest.mark.parametrize("which", [0, 1, 2])
+def test_workload_full_size_every_element(gs, which):
+    w = graphgen.workload(which)
+    say(" ", w.describe())
+    dA = dev(w.rowptr), dev(w.colind), dev(w.vals)
+    for N in w.widths:
+        B = w.B(N)
+        dB = dev(B)
+        for op in w.ops:
+            check(gs, w.rowptr, w.colind, w.vals, B, op, label=w.name, dA=dA, dB=dB)
+        if which == 2:   # the unweighted graph is also run with vals == NULL
+            check(gs, w.rowptr, w.colind, None, B, "sum", label=w.name + " vals=NULL",
+                  dA=(dA[0], dA[1], None), dB=dB)
+
+
+def _sample_rows(rowptr, count, seed):
+    lens = np.diff(rowptr)
+    rng = np.random.default_rng(seed)
+    longest = np.argsort(lens)[-24:]
+    empties = np.flatnonzero(lens == 0)[:8]
+    rand = rng.integers(0, len(lens), size=count)
+    edges = np.array([0, 1, len(lens) - 2, len(lens) - 1])
+    return np.unique(np.concatenate([longest, empties, rand, edges])).astype(np.int64)
+
+
+@pytest.mark.parametrize("which", [3, 4])
+def test_workload_full_size_sampled_rows_and_properties(gs, which):
+    w = graphgen.workload(which)
+    say(" ", w.describe())
+    dA = dev(w.rowptr), dev(w.colind), dev(w.vals)
+    rows = _sample_rows(w.rowptr, 3000, which)
+    lens = np.diff(w.rowptr).astype(np.float64)[:, None]
+    for N in w.widths:
+        B = w.B(N)
+        dB = dev(B)
+        out = {}
+        for op in w.ops:
+            out[op] = check(gs, w.rowptr, w.colind, w.vals, B, op, rows=rows, label=w.name, dA=dA, dB=dB)
+            assert np.isfinite(out[op]).all()
+            assert not out[op][lens[:, 0] == 0].any()            # every empty row is exactly zero
+        # column independence: the left half computed alone must equal the left half of the
+        # full run (bit-for-bit for max; sum within twice the bound, checked on the samples)
+        half = N // 2
+        Bh = np.ascontiguousarray(B[:, :half])
+        for op in w.ops:
+            Ch = check(gs, w.rowptr, w.colind, w.vals, Bh, op, rows=rows, label=w.name + " half-width", dA=dA)
+            if op in ("max", "min"):
+                assert np.array_equal(Ch.view(np.uint32), out[op][:, :half].view(np.uint32))
+        if "mean" in out:                                        # mean * len == sum
+            _, Sabs = oracle.spmm(w.rowptr, w.colind, w.vals, B, "sum", rows=rows)
+            err = np.abs(out["mean"][rows].astype(np.float64) * lens[rows] - out["sum"][rows])
+            assert (err <= 2e-5 * Sabs + 2e-6 * np.maximum(lens[rows], 1)).all()
