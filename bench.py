@@ -2,12 +2,14 @@
 """Benchmark of the CSR SpMM / SpMM-like hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--width N] [--op OP]
+    python bench.py --sweep            # every workload / width / op, table on stderr
+    python bench.py --copy-gib 1       # also launch the calibration copy kernel (for --pmc runs)
 
 One "step" is one whole gespmm_csr call (row-initialisation kernel + chunk kernel) on a
-seeded synthetic workload that is already resident in HBM.  Prints ONE JSON line:
-throughput as the paper computes it (2 * nnz * N / time, Section V-A), the byte-model
-bandwidth of the dominant kernel against the HBM peak ("roofline"), and the CPU oracle
-timed on this box's host cores ("cpu_baseline").
+seeded synthetic workload that is already resident in HBM.  Prints ONE JSON line on
+stdout: throughput as the paper computes it (2 * nnz * N / time, Section V-A), the
+byte-model bandwidth of the dominant kernel against the HBM peak ("roofline"), and the
+CPU oracle timed on this box's host cores ("cpu_baseline").
 """
 from __future__ import annotations
 
@@ -23,8 +25,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 
-# HBM bytes per launch of the chunk kernel measured with rocprofv3 --pmc (FETCH_SIZE and
-# WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None = not measured.
+# HBM bytes per launch of the chunk kernel, measured with rocprofv3 --pmc (one FETCH_SIZE
+# run and one WRITE_SIZE run, each scaled by the calibration copy kernel of known size;
+# the summaries are under profiles/).  Key: "<workload>/N<width>/<op>".  Missing = null.
 MEASURED_TRAFFIC_BYTES = {}
 
 
@@ -39,8 +42,8 @@ def compulsory_bytes(M, K, N, nnz, has_vals=True):
     return 4 * (M + 1) + 4 * nnz + (4 * nnz if has_vals else 0) + 4 * K * N + 4 * M * N
 
 
-def cpu_baseline(w, B, op, budget_s=10.0, max_passes=5):
-    """The oracle as it stands, all rows of the same workload, repeated until ~budget_s."""
+def cpu_baseline(w, B, op, budget_s=12.0, max_passes=60):
+    """The oracle as it stands, all rows of the same workload, repeated for ~budget_s."""
     import oracle
     times = []
     t_all = time.perf_counter()
@@ -51,8 +54,64 @@ def cpu_baseline(w, B, op, budget_s=10.0, max_passes=5):
     mean = sum(times) / len(times)
     return {"value": 2.0 * w.nnz * B.shape[1] / mean / 1e9, "unit": "GFLOP/s",
             "cores": oracle.max_threads(), "kind": "oracle",
-            "sample": f"all {w.M} rows of the same workload, {len(times)} full pass(es), "
+            "sample": f"all {w.M} rows of the same workload, {len(times)} full passes, "
                       f"mean {mean:.3f} s per pass"}
+
+
+class DeviceCase:
+    """One workload at one width, resident on the GPU."""
+
+    def __init__(self, w, N, torch, dev):
+        self.w, self.N = w, N
+        self.B_host = w.B(N)
+        self.rp = torch.from_numpy(w.rowptr).to(dev)
+        self.ci = torch.from_numpy(w.colind).to(dev)
+        self.v = torch.from_numpy(w.vals).to(dev)
+        self.B = torch.from_numpy(self.B_host).to(dev)
+        self.C = torch.empty((w.M, N), dtype=torch.float32, device=dev)
+
+    def time(self, gs, torch, op, steps, warmup):
+        stream = torch.cuda.current_stream()
+        for _ in range(warmup):
+            gs.gespmm_csr(self.rp, self.ci, self.v, self.B, op, C=self.C, stream=stream)
+        torch.cuda.synchronize()
+        gs.gespmm_profile_begin(steps)
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            gs.gespmm_csr(self.rp, self.ci, self.v, self.B, op, C=self.C, stream=stream)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        main_ms_sum, launches = gs.gespmm_profile_end()
+        w, N = self.w, self.N
+        ms = (t1 - t0) * 1e3 / steps
+        main_ms = main_ms_sum / max(launches, 1)
+        mb = model_bytes(w.M, N, w.nnz)
+        return {"workload": w.name, "N": N, "op": op, "ms_per_step": ms, "main_kernel_ms": main_ms,
+                "launches_timed": launches, "gflops": 2.0 * w.nnz * N / (ms * 1e-3) / 1e9,
+                "model_bytes": mb, "model_GBps_step": mb / (ms * 1e-3) / 1e9,
+                "model_GBps_kernel": mb / (main_ms * 1e-3) / 1e9,
+                "compulsory_bytes": compulsory_bytes(w.M, w.K, N, w.nnz)}
+
+
+def sweep(args, gs, torch, graphgen, dev):
+    """Every workload / width / op of the five configurations; table on stderr."""
+    rows = []
+    for name in graphgen.WORKLOAD_NAMES:
+        w = graphgen.workload(name, args.scale)
+        print(f"# {w.describe()}", file=sys.stderr, flush=True)
+        for N in w.widths:
+            case = DeviceCase(w, N, torch, dev)
+            for op in w.ops:
+                steps = args.steps if w.nnz * N > 5e8 else max(args.steps, 200)
+                r = case.time(gs, torch, op, steps, args.warmup)
+                rows.append(r)
+                print(f"{r['workload']:20s} N={N:4d} {op:5s} step {r['ms_per_step']*1e3:9.1f} us  kernel "
+                      f"{r['main_kernel_ms']*1e3:9.1f} us  {r['gflops']:8.1f} GFLOP/s  model "
+                      f"{r['model_GBps_step']:8.1f} GB/s ({r['model_GBps_step']/HBM_PEAK_GBPS*100:5.1f}% of HBM peak)",
+                      file=sys.stderr, flush=True)
+            del case
+            torch.cuda.empty_cache()
+    return rows
 
 
 def main():
@@ -65,6 +124,11 @@ def main():
     ap.add_argument("--op", default="sum")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--sweep", action="store_true", help="also time every workload/width/op")
+    ap.add_argument("--sweep-out", default="", help="write the sweep rows to this JSON file")
+    ap.add_argument("--copy-gib", type=float, default=0.0,
+                    help="launch the calibration copy kernel once on this many GiB (traffic-counter yardstick)")
+    ap.add_argument("--tuning", default="", help="G,T,remap override (each -1 = automatic)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -77,57 +141,58 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     gs.lib()
+    dev = torch.device("cuda:0")
+    if args.tuning:
+        gs.gespmm_set_tuning(*[int(x) for x in args.tuning.split(",")])
+
+    if args.copy_gib > 0:
+        n = int(args.copy_gib * (1 << 30)) // 16 * 4
+        src = torch.ones(n, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        gs.gespmm_calibration_copy(src, dst)
+        torch.cuda.synchronize()
+        print(f"# calibration copy: {n * 4} bytes read, {n * 4} bytes written", file=sys.stderr)
+        del src, dst
+
+    sweep_rows = sweep(args, gs, torch, graphgen, dev) if args.sweep else None
+    if sweep_rows is not None and args.sweep_out:
+        with open(args.sweep_out, "w") as f:
+            json.dump(sweep_rows, f, indent=1)
+
     w = graphgen.workload(args.workload, args.scale)
     N = args.width or w.widths[0]
     op = args.op
-    B = w.B(N)
-    dev = torch.device("cuda:0")
-    d_rp, d_ci = torch.from_numpy(w.rowptr).to(dev), torch.from_numpy(w.colind).to(dev)
-    d_v, d_B = torch.from_numpy(w.vals).to(dev), torch.from_numpy(B).to(dev)
-    C = torch.empty((w.M, N), dtype=torch.float32, device=dev)
-    stream = torch.cuda.current_stream()
-
-    for _ in range(args.warmup):
-        gs.gespmm_csr(d_rp, d_ci, d_v, d_B, op, C=C, stream=stream)
-    torch.cuda.synchronize()
-    gs.gespmm_profile_begin(args.steps)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        gs.gespmm_csr(d_rp, d_ci, d_v, d_B, op, C=C, stream=stream)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    main_ms_sum, launches = gs.gespmm_profile_end()
-
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    flops = 2.0 * w.nnz * N
-    mbytes = model_bytes(w.M, N, w.nnz)
-    main_ms = main_ms_sum / max(launches, 1)
-    achieved = mbytes / (main_ms * 1e-3) / 1e9
+    case = DeviceCase(w, N, torch, dev)
+    r = case.time(gs, torch, op, args.steps, args.warmup)
     plan = gs.gespmm_plan(w.M, N, w.nnz)
-    key = f"{w.name}/N{N}/{op}"
+    desc = w.describe()
+    achieved = r["model_GBps_kernel"]
     out = {
         "metric": "fp32 CSR SpMM GFLOP/s (2*nnz*N) and achieved HBM GB/s vs peak, 1 MI355X",
-        "value": flops / (ms_per_step * 1e-3) / 1e9,
-        "unit": "GFLOP/s",
+        "value": r["gflops"], "unit": "GFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": r["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: M=K={w.M}, nnz={w.nnz}, N={N}, reduce={op}, seed={w.seed}",
-                   "csr_hash": w.describe()["csr_hash"], "max_row": int(w.describe()["max_row"]),
+                   "csr_hash": desc["csr_hash"], "max_row": desc["max_row"],
                    "kernel": f"spmm_chunks vec={plan['vec']} G={plan['lanes_per_row']} "
                              f"T={plan['tiles_per_lane']} S={plan['chunk_nnz']}"},
-        "model_GBps_whole_step": mbytes / (ms_per_step * 1e-3) / 1e9,
-        "frac_of_hbm_peak_whole_step": mbytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-        "compulsory_bytes": compulsory_bytes(w.M, w.K, N, w.nnz),
+        "model_GBps_whole_step": r["model_GBps_step"],
+        "frac_of_hbm_peak_whole_step": r["model_GBps_step"] / HBM_PEAK_GBPS,
+        "compulsory_bytes": r["compulsory_bytes"],
         "roofline": {"bound": "hbm", "kernel": "spmm_chunks", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(key),
-                     "algorithmic_bytes_per_launch": mbytes, "avg_launch_ms": main_ms,
-                     "launches_timed": launches},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(f"{w.name}/N{N}/{op}"),
+                     "algorithmic_bytes_per_launch": r["model_bytes"],
+                     "avg_launch_ms": r["main_kernel_ms"], "launches_timed": r["launches_timed"]},
     }
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(w, B, op)
+        out["cpu_baseline"] = cpu_baseline(w, case.B_host, op)
+    if sweep_rows is not None:
+        out["sweep"] = [{k: row[k] for k in ("workload", "N", "op", "ms_per_step", "gflops", "model_GBps_step")}
+                        for row in sweep_rows]
     print(json.dumps(out), flush=True)
 
 

@@ -95,17 +95,21 @@ typedef struct {
   int64_t grid_x;         /* workgroups along x of the main kernel                        */
   int32_t block_threads;  /* threads per workgroup                                        */
   int32_t xcd_remap;      /* 1: consecutive chunks are kept on one XCD                    */
+  int32_t short_len;      /* row segments up to this length are handled one per slot      */
+  int32_t lds_bytes;      /* dynamic LDS per workgroup                                    */
 } gespmm_plan_t;
 
 int gespmm_plan(int64_t M, int64_t N, int64_t nnz, int aligned16, gespmm_plan_t* out);
 
 /*
  * Tuning override for tests and benchmarks (process-wide, not thread-safe):
- * lanes_per_row in {1,2,4,...,64}, tiles_per_lane in {1,2,4}, xcd_remap in {0,1};
- * -1 restores the automatic choice for that field.  Returns GESPMM_ERR_BAD_ARG
- * for a value that has no kernel.
+ * lanes_per_row in {1,2,4,...,64}, tiles_per_lane in {1,2,4}, xcd_remap in {0,1},
+ * chunk_nnz a power of two in [64, 1024], short_len in [0, 1024] (0 = every row is
+ * handled by all slots together); -1 restores the automatic choice for that field.
+ * Returns GESPMM_ERR_BAD_ARG for a value that has no kernel.
  */
-int gespmm_set_tuning(int lanes_per_row, int tiles_per_lane, int xcd_remap);
+int gespmm_set_tuning(int lanes_per_row, int tiles_per_lane, int xcd_remap, int chunk_nnz,
+                      int short_len);
 
 /*
  * Per-kernel timing for the benchmark.  gespmm_profile_begin creates `capacity`
@@ -117,6 +121,14 @@ int gespmm_set_tuning(int lanes_per_row, int tiles_per_lane, int xcd_remap);
  */
 int gespmm_profile_begin(int capacity);
 int gespmm_profile_end(double* main_kernel_ms_sum, int* launches);
+
+/*
+ * Measurement helper, not part of the method: copies `bytes` (a multiple of 16, both
+ * pointers 16-byte aligned, device memory, non-overlapping) from src to dst with a plain
+ * copy kernel on `stream`.  It reads `bytes` and writes `bytes` of HBM and nothing else,
+ * which makes it the yardstick for scaling hardware traffic counters.
+ */
+int gespmm_calibration_copy(const void* src, void* dst, int64_t bytes, void* stream);
 
 /* Static text for a status code (never NULL). */
 const char* gespmm_status_string(int status);

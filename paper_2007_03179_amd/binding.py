@@ -28,7 +28,8 @@ class gespmm_plan_t(ctypes.Structure):
                 ("tiles_per_lane", ctypes.c_int32), ("slots", ctypes.c_int32),
                 ("chunk_nnz", ctypes.c_int32), ("col_blocks", ctypes.c_int32),
                 ("chunks", ctypes.c_int64), ("grid_x", ctypes.c_int64),
-                ("block_threads", ctypes.c_int32), ("xcd_remap", ctypes.c_int32)]
+                ("block_threads", ctypes.c_int32), ("xcd_remap", ctypes.c_int32),
+                ("short_len", ctypes.c_int32), ("lds_bytes", ctypes.c_int32)]
 
 
 _lib = None
@@ -51,11 +52,13 @@ def lib():
         L.gespmm_plan.restype = ci
         L.gespmm_plan.argtypes = [i64, i64, i64, ci, ctypes.POINTER(gespmm_plan_t)]
         L.gespmm_set_tuning.restype = ci
-        L.gespmm_set_tuning.argtypes = [ci, ci, ci]
+        L.gespmm_set_tuning.argtypes = [ci, ci, ci, ci, ci]
         L.gespmm_profile_begin.restype = ci
         L.gespmm_profile_begin.argtypes = [ci]
         L.gespmm_profile_end.restype = ci
         L.gespmm_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
+        L.gespmm_calibration_copy.restype = ci
+        L.gespmm_calibration_copy.argtypes = [vp, vp, i64, vp]
         L.gespmm_status_string.restype = ctypes.c_char_p
         L.gespmm_status_string.argtypes = [ci]
         L.gespmm_version.restype = ci
@@ -129,8 +132,17 @@ def gespmm_plan(M, N, nnz, aligned16=True) -> dict:
     return {name: int(getattr(p, name)) for name, _ in p._fields_}
 
 
-def gespmm_set_tuning(lanes_per_row=-1, tiles_per_lane=-1, xcd_remap=-1):
-    _check(lib().gespmm_set_tuning(int(lanes_per_row), int(tiles_per_lane), int(xcd_remap)))
+def gespmm_set_tuning(lanes_per_row=-1, tiles_per_lane=-1, xcd_remap=-1, chunk_nnz=-1, short_len=-1):
+    _check(lib().gespmm_set_tuning(int(lanes_per_row), int(tiles_per_lane), int(xcd_remap),
+                                   int(chunk_nnz), int(short_len)))
+
+
+def gespmm_calibration_copy(src, dst, stream=None):
+    """dst <- src with the library's plain copy kernel (same-size contiguous CUDA tensors)."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes and src.is_contiguous() and dst.is_contiguous()
+    _check(lib().gespmm_calibration_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)))
+    return dst
 
 
 def gespmm_profile_begin(capacity: int):

@@ -16,10 +16,11 @@
 //  * Kept from Coarse-grained Warp Merging (Section III-C): one lane owns T column tiles
 //    of 4 floats (one 16-byte load each), so the sparse chunk is read once for
 //    4*G*T output columns and several independent B loads are in flight per lane.
-//  * New for 64 lanes: the wavefront is cut into 64/G slots of G lanes.  The G lanes of
-//    a slot cover the column block; the slots take different stored entries of the same
-//    row in the same step, and their partial results are folded with cross-lane
-//    exchanges at the end of the row.
+//  * New for 64 lanes: the wavefront is cut into 64/G slots of G lanes; the G lanes of a
+//    slot cover the column block.  Short row segments are handled one per slot, 64/G
+//    rows at a time (no cross-lane traffic at all); long segments are handled by all
+//    slots together, each slot taking every (64/G)-th entry, and the slot partials are
+//    folded with cross-lane exchanges at the end of the row.
 //  * A first small kernel zero-fills empty rows and writes the reduce identity into the
 //    rows that will be finished with atomics.
 #include <hip/hip_runtime.h>
@@ -35,10 +36,7 @@ namespace {
 constexpr int kWave = 64;
 constexpr int kWavesPerBlock = 4;
 constexpr int kBlock = kWave * kWavesPerBlock;
-constexpr int kChunkLoads = 4;                  // UA: coalesced loads per lane that fill a chunk
-constexpr int kChunk = kChunkLoads * kWave;     // S: stored entries per wavefront
-constexpr int kChunkShift = 8;                  // log2(kChunk)
-static_assert((1 << kChunkShift) == kChunk, "chunk size must match its shift");
+constexpr int kMaxChunkShift = 10;              // chunks hold 64 .. 1024 stored entries
 constexpr int kXcds = 8;
 constexpr int kLoadsInFlight = 4;               // 16-byte gathers a lane issues before it waits
 
@@ -52,6 +50,8 @@ struct KernelArgs {
   int64_t chunks;
   int64_t chunk_blocks;   // grid.x
   int32_t xcd_remap;
+  int32_t chunk_shift;    // log2(S), S = stored entries per wavefront
+  int32_t short_len;      // row segments up to this length are handled one per slot
   const int32_t* rowptr;
   const int32_t* colind;
   const float* vals;
@@ -121,7 +121,7 @@ __device__ __forceinline__ int64_t logical_block(int64_t b, int64_t nb, int rema
 // get the reduce identity (they are completed by atomics in the main kernel).
 template <int V>
 __global__ void __launch_bounds__(kBlock) init_rows(int32_t M, int32_t N, const int32_t* __restrict__ rowptr,
-                                                   float* __restrict__ C, float identity) {
+                                                   float* __restrict__ C, float identity, int chunk_shift) {
   const int lane = threadIdx.x & (kWave - 1);
   const int64_t base = ((int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)) * kWave;
   if (base >= M) return;
@@ -130,7 +130,7 @@ __global__ void __launch_bounds__(kBlock) init_rows(int32_t M, int32_t N, const 
   if (r < M) {
     const int s = rowptr[r], e = rowptr[r + 1];
     if (s == e) flag = 1;
-    else if ((s >> kChunkShift) != ((e - 1) >> kChunkShift)) flag = 2;
+    else if ((s >> chunk_shift) != ((e - 1) >> chunk_shift)) flag = 2;
   }
   unsigned long long todo = __ballot(flag != 0);
   while (todo) {
@@ -145,49 +145,123 @@ __global__ void __launch_bounds__(kBlock) init_rows(int32_t M, int32_t N, const 
   }
 }
 
+// ------------------------------------------------------- calibration copy --
+// Plain 16-byte-per-lane copy of a known size: the yardstick that hardware traffic
+// counters (FETCH_SIZE / WRITE_SIZE) are scaled by.
+__global__ void __launch_bounds__(kBlock) copy_f4(const float4* __restrict__ src, float4* __restrict__ dst, int64_t n4) {
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += stride) dst[i] = src[i];
+}
+
 // ------------------------------------------------------------- main kernel --
 // F: fold; V: floats per lane per load; G: lanes per slot; T: column tiles per lane.
+//
+// One pass over `U` entries of one row segment for the column tiles of this lane.
+// `first` is the LDS index of the lane's first entry of the pass, `stride` the distance
+// to its next one, `left` how many of the U entries exist (<= 0: none).  An entry that
+// does not exist re-reads the previous one: harmless for max/min (idempotent) and given
+// weight 0 for the sum, so the pass is straight-line code with all gathers issued first.
+template <int F, int V, int T, int U>
+__device__ __forceinline__ void gather_pass(Vec<V> (&acc)[T], const int2* ka, int first, int stride, int left,
+                                            const float* __restrict__ B, int N, const int (&colc)[T]) {
+  int2 e2[U];
+  Vec<V> b[U][T];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int uu = u < left ? u : (left > 0 ? left - 1 : 0);
+    e2[u] = ka[first + uu * stride];
+    if (F == kAdd && u >= left) e2[u].y = 0;
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const float* brow = B + (int64_t)e2[u].x * N;
+#pragma unroll
+    for (int t = 0; t < T; ++t) b[u][t] = Vec<V>::load(brow + colc[t]);
+  }
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+#pragma unroll
+      for (int x = 0; x < V; ++x) acc[t].v[x] = fold<F>(acc[t].v[x], __int_as_float(e2[u].y), b[u][t].v[x]);
+}
+
+// Write one finished row segment: plain store when the whole row lay in this chunk,
+// atomics otherwise (the row was preset to the identity by init_rows).
+template <int F, int V, int T>
+__device__ __forceinline__ void emit(Vec<V> (&acc)[T], float* crow, const int (&col)[T], int N, bool whole,
+                                     int row_len, int is_mean) {
+  const float len = (float)row_len;
+#pragma unroll
+  for (int t = 0; t < T; ++t) {
+    if (col[t] < N) {
+      if (whole) {
+        if (is_mean) {
+#pragma unroll
+          for (int x = 0; x < V; ++x) acc[t].v[x] = acc[t].v[x] / len;
+        }
+        acc[t].store(crow + col[t]);
+      } else {
+        const float w = is_mean ? 1.0f / len : 1.0f;
+#pragma unroll
+        for (int x = 0; x < V; ++x) atomic_fold<F>(crow + col[t] + x, F == kAdd ? acc[t].v[x] * w : acc[t].v[x]);
+      }
+    }
+  }
+}
+
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 template <int F, int V, int G, int T>
 __global__ void __launch_bounds__(kBlock) spmm_chunks(const KernelArgs a) {
-  constexpr int NS = kWave / G;                 // slots: entries of one row taken per step
-  constexpr int U = kLoadsInFlight / T > 0 ? kLoadsInFlight / T : 1;   // steps per pass
-  __shared__ int2 s_ka[kWavesPerBlock][kChunk];
+  constexpr int NS = kWave / G;                 // slots
+  constexpr int U = kLoadsInFlight / T > 0 ? kLoadsInFlight / T : 1;   // entries per lane per pass
+  extern __shared__ int2 s_dyn[];               // per wavefront: S entries (colind, val) + 64 row descriptors
 
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x >> 6;
   const int slot = lane / G;
   const int g = lane % G;
+  const int S = 1 << a.chunk_shift;
 
   const int64_t chunk = logical_block(blockIdx.x, a.chunk_blocks, a.xcd_remap) * kWavesPerBlock + wave;
   if (chunk >= a.chunks) return;                // whole wavefront leaves; no block barrier is used
-  const int cs = (int)(chunk << kChunkShift);   // first stored entry of this chunk (< 2^31)
-  const int cnt = (a.nnz - cs) < kChunk ? (a.nnz - cs) : kChunk;
+  const int cs = (int)(chunk << a.chunk_shift); // first stored entry of this chunk (< 2^31)
+  const int cnt = (a.nnz - cs) < S ? (a.nnz - cs) : S;
   const int ce = cs + cnt;
-  int2* ka = s_ka[wave];
+  int2* ka = s_dyn + wave * (S + kWave);
+  int2* short_rows = ka + S;
 
-  // (1) coalesced load of the chunk's (colind, val) into this wavefront's LDS slice; all
-  //     loads are issued before the first LDS write (indices past the end repeat the last
-  //     entry, whose copies are never consumed)
-  {
-    int k[kChunkLoads];
-    float v[kChunkLoads];
+  // (1) coalesced load of the chunk's (colind, val) into this wavefront's LDS slice, four
+  //     loads of each array in flight at a time (indices past the end repeat the last
+  //     entry; those copies are never consumed)
+  for (int u0 = 0; u0 < cnt; u0 += 4 * kWave) {
+    int k[4];
+    float v[4];
 #pragma unroll
-    for (int u = 0; u < kChunkLoads; ++u) {
-      const int idx = u * kWave + lane;
+    for (int u = 0; u < 4; ++u) {
+      const int idx = u0 + u * kWave + lane;
       k[u] = a.colind[cs + (idx < cnt ? idx : cnt - 1)];
     }
     if (a.vals) {
 #pragma unroll
-      for (int u = 0; u < kChunkLoads; ++u) {
-        const int idx = u * kWave + lane;
+      for (int u = 0; u < 4; ++u) {
+        const int idx = u0 + u * kWave + lane;
         v[u] = a.vals[cs + (idx < cnt ? idx : cnt - 1)];
       }
     } else {
 #pragma unroll
-      for (int u = 0; u < kChunkLoads; ++u) v[u] = 1.0f;
+      for (int u = 0; u < 4; ++u) v[u] = 1.0f;
     }
 #pragma unroll
-    for (int u = 0; u < kChunkLoads; ++u) ka[u * kWave + lane] = make_int2(k[u], __float_as_int(v[u]));
+    for (int u = 0; u < 4; ++u) {
+      const int idx = u0 + u * kWave + lane;
+      if (idx < S) ka[idx] = make_int2(k[u], __float_as_int(v[u]));
+    }
   }
 
   // (2) first row of the chunk: the last r with rowptr[r] <= cs, found by a 64-way search
@@ -214,85 +288,75 @@ __global__ void __launch_bounds__(kBlock) spmm_chunks(const KernelArgs a) {
     colc[t] = col[t] < a.N ? col[t] : a.N - V;
   }
 
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  wave_lds_fence();
 
-  // (3) walk the rows that have entries in [cs, ce), 64 row bounds at a time
+  // (3) walk the rows that have entries in [cs, ce), 64 row bounds at a time (lane <-> row)
   for (int64_t rbase = lo;; rbase += kWave) {
     int64_t rr = rbase + lane;
     if (rr > a.M) rr = a.M;
     const int my_s = a.rowptr[rr];
     const int my_e = a.rowptr[rr < a.M ? rr + 1 : a.M];
-    unsigned long long todo = __ballot(rbase + lane < a.M && my_e > my_s && my_s < ce);
+    const bool valid = rbase + lane < a.M && my_e > my_s && my_s < ce;
+    const int my_ps = (my_s > cs ? my_s : cs) - cs;     // the row's segment inside the chunk,
+    const int my_pe = (my_e < ce ? my_e : ce) - cs;     // as offsets into the LDS slice
+    const bool my_whole = my_s >= cs && my_e <= ce;
+    const bool is_short = NS > 1 && valid && (my_pe - my_ps) <= a.short_len;
+
+    // (3a) short segments: one per slot, 64/G rows at a time, no cross-lane exchange
+    if (NS > 1) {
+      const unsigned long long smask = __ballot(is_short);
+      const int nshort = __builtin_popcountll(smask);
+      if (nshort > 0) {
+        const int rank = __builtin_amdgcn_mbcnt_hi((unsigned)(smask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)smask, 0u));
+        if (is_short)   // lane | offset << 6 | length << 18 | whole << 30 ; full row length
+          short_rows[rank] = make_int2(lane | (my_ps << 6) | ((my_pe - my_ps) << 18) | ((int)my_whole << 30), my_e - my_s);
+        wave_lds_fence();
+        for (int t0 = 0; t0 < nshort; t0 += NS) {
+          const bool have = t0 + slot < nshort;
+          const int2 d = short_rows[have ? t0 + slot : nshort - 1];
+          const int r_ps = (d.x >> 6) & 4095;
+          const int r_len = have ? (d.x >> 18) & 4095 : 0;
+          Vec<V> acc[T];
+#pragma unroll
+          for (int t = 0; t < T; ++t)
+#pragma unroll
+            for (int x = 0; x < V; ++x) acc[t].v[x] = fold_identity<F>();
+          for (int it = 0; __ballot(it < r_len) != 0ull; it += U)
+            gather_pass<F, V, T, U>(acc, ka, r_ps + (it < r_len ? it : 0), 1, r_len - it, a.B, a.N, colc);
+          if (have)
+            emit<F, V, T>(acc, a.C + (rbase + (d.x & 63)) * (int64_t)a.N, col, a.N, (d.x >> 30) & 1, d.y, a.is_mean);
+        }
+        wave_lds_fence();
+      }
+    }
+
+    // (3b) long segments: all slots work on one row, slot s takes entries s, s+NS, ...
+    unsigned long long todo = __ballot(valid && !is_short);
     while (todo) {
       const int i = __builtin_ctzll(todo);
       todo &= todo - 1;
-      const int s = __builtin_amdgcn_readlane(my_s, i);
-      const int e = __builtin_amdgcn_readlane(my_e, i);
-      const int ps = (s > cs ? s : cs) - cs;    // segment of the row inside the chunk, local offsets
-      const int pe = (e < ce ? e : ce) - cs;
-      const bool whole = s >= cs && e <= ce;
-
+      const int ps = __builtin_amdgcn_readlane(my_ps, i);
+      const int pe = __builtin_amdgcn_readlane(my_pe, i);
       Vec<V> acc[T];
 #pragma unroll
       for (int t = 0; t < T; ++t)
 #pragma unroll
         for (int x = 0; x < V; ++x) acc[t].v[x] = fold_identity<F>();
-
-      // U steps per pass, all gathers issued before the first use.  A step past the end of
-      // the segment re-reads the segment's last entry: harmless for max/min (idempotent),
-      // and given weight 0 for the sum.
       for (int base = ps; base < pe; base += U * NS) {
-        int2 e2[U];
-        Vec<V> b[U][T];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const int q = base + u * NS + slot;
-          e2[u] = ka[q < pe ? q : pe - 1];
-          if (F == kAdd && q >= pe) e2[u].y = 0;
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const float* brow = a.B + (int64_t)e2[u].x * a.N;
-#pragma unroll
-          for (int t = 0; t < T; ++t) b[u][t] = Vec<V>::load(brow + colc[t]);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-          for (int t = 0; t < T; ++t)
-#pragma unroll
-            for (int x = 0; x < V; ++x) acc[t].v[x] = fold<F>(acc[t].v[x], __int_as_float(e2[u].y), b[u][t].v[x]);
+        const int first = base + slot;
+        const int left = (pe - first + NS - 1) / NS;       // entries first, first+NS, ... below pe
+        gather_pass<F, V, T, U>(acc, ka, left > 0 ? first : pe - 1, NS, left, a.B, a.N, colc);
       }
-
-      // fold the slots together (every slot ends with the total)
 #pragma unroll
       for (int off = G; off < kWave; off <<= 1)
 #pragma unroll
         for (int t = 0; t < T; ++t)
 #pragma unroll
           for (int x = 0; x < V; ++x) acc[t].v[x] = fold2<F>(acc[t].v[x], __shfl_xor(acc[t].v[x], off, kWave));
-
       if (slot == 0) {
-        float* crow = a.C + (rbase + i) * (int64_t)a.N;
-        const float len = (float)(e - s);
-#pragma unroll
-        for (int t = 0; t < T; ++t) {
-          if (col[t] < a.N) {
-            if (whole) {
-              if (a.is_mean) {
-#pragma unroll
-                for (int x = 0; x < V; ++x) acc[t].v[x] = acc[t].v[x] / len;
-              }
-              acc[t].store(crow + col[t]);
-            } else {
-              const float w = a.is_mean ? 1.0f / len : 1.0f;
-#pragma unroll
-              for (int x = 0; x < V; ++x) atomic_fold<F>(crow + col[t] + x, F == kAdd ? acc[t].v[x] * w : acc[t].v[x]);
-            }
-          }
-        }
+        const int s = __builtin_amdgcn_readlane(my_s, i);
+        const int e = __builtin_amdgcn_readlane(my_e, i);
+        emit<F, V, T>(acc, a.C + (rbase + i) * (int64_t)a.N, col, a.N, s >= cs && e <= ce, e - s, a.is_mean);
       }
     }
     // the next batch of rows is needed only if it still starts inside the chunk
@@ -309,8 +373,7 @@ MainKernel pick_gt(int G, int T) {
 #define GESPMM_CASE(GG, TT) if (G == GG && T == TT) return spmm_chunks<F, V, GG, TT>;
   GESPMM_CASE(1, 1) GESPMM_CASE(2, 1) GESPMM_CASE(4, 1) GESPMM_CASE(8, 1)
   GESPMM_CASE(16, 1) GESPMM_CASE(32, 1) GESPMM_CASE(64, 1)
-  GESPMM_CASE(1, 2) GESPMM_CASE(2, 2) GESPMM_CASE(4, 2) GESPMM_CASE(8, 2)
-  GESPMM_CASE(16, 2) GESPMM_CASE(32, 2) GESPMM_CASE(64, 2)
+  GESPMM_CASE(4, 2) GESPMM_CASE(8, 2) GESPMM_CASE(16, 2) GESPMM_CASE(32, 2) GESPMM_CASE(64, 2)
   GESPMM_CASE(8, 4) GESPMM_CASE(16, 4) GESPMM_CASE(32, 4) GESPMM_CASE(64, 4)
 #undef GESPMM_CASE
   return nullptr;
@@ -338,7 +401,11 @@ int next_pow2(int64_t x) {
 }
 
 // process-wide tuning overrides (-1 = automatic)
-int g_force_g = -1, g_force_t = -1, g_force_remap = -1;
+int g_force_g = -1, g_force_t = -1, g_force_remap = -1, g_force_shift = -1, g_force_short = -1;
+
+// Waves the chip holds at full occupancy (256 CUs x 4 SIMDs x 8): a problem with fewer
+// chunks than this gets smaller chunks, so that its rows are spread over more wavefronts.
+constexpr int64_t kResidentWaves = 8192;
 
 void make_plan(int64_t M, int64_t N, int64_t nnz, bool aligned16, gespmm_plan_t* p) {
   (void)M;
@@ -351,16 +418,24 @@ void make_plan(int64_t M, int64_t N, int64_t nnz, bool aligned16, gespmm_plan_t*
   if (ncv > 64 && G * T < 128) { G = 64; T = 2; }
   if (g_force_g > 0) G = g_force_g;
   if (g_force_t > 0) T = g_force_t;
+  // chunk size: about the same gathered bytes per wavefront for every width (64 KiB),
+  // halved while the problem has too few chunks to fill the chip
+  int shift = 8;
+  while (shift < kMaxChunkShift && ((int64_t)vec * G * T << shift) < 16384) ++shift;
+  while (shift > 6 && ((nnz + (1ll << shift) - 1) >> shift) < kResidentWaves) --shift;
+  if (g_force_shift >= 6) shift = g_force_shift;
   p->vec = vec;
   p->lanes_per_row = G;
   p->tiles_per_lane = T;
   p->slots = kWave / G;
-  p->chunk_nnz = kChunk;
+  p->chunk_nnz = 1 << shift;
   p->col_blocks = (int32_t)((ncv + (int64_t)G * T - 1) / ((int64_t)G * T));
-  p->chunks = (nnz + kChunk - 1) / kChunk;
+  p->chunks = (nnz + p->chunk_nnz - 1) >> shift;
   p->grid_x = (p->chunks + kWavesPerBlock - 1) / kWavesPerBlock;
   p->block_threads = kBlock;
   p->xcd_remap = g_force_remap >= 0 ? g_force_remap : 1;
+  p->short_len = g_force_short >= 0 ? g_force_short : 2 * p->slots;
+  p->lds_bytes = (int32_t)(kWavesPerBlock * (p->chunk_nnz + kWave) * sizeof(int2));
 }
 
 // profiling state
@@ -372,7 +447,7 @@ int validate(int64_t M, int64_t K, int64_t N, int64_t nnz, const void* rowptr, c
              const void* B, const void* C, int op) {
   if (M < 0 || K < 0 || N < 0 || nnz < 0) return GESPMM_ERR_BAD_ARG;
   if (op < GESPMM_SUM || op > GESPMM_MIN) return GESPMM_ERR_BAD_ARG;
-  if (M >= INT32_MAX || K > INT32_MAX || nnz > INT32_MAX - kChunk || N > INT32_MAX / 8) return GESPMM_ERR_TOO_LARGE;
+  if (M >= INT32_MAX || K > INT32_MAX || nnz > INT32_MAX - (1 << kMaxChunkShift) || N > INT32_MAX / 8) return GESPMM_ERR_TOO_LARGE;
   if (nnz > 0 && (M == 0 || K == 0)) return GESPMM_ERR_BAD_ARG;
   if (M == 0 || N == 0) return GESPMM_OK;
   if (!rowptr || !C) return GESPMM_ERR_NULL;
@@ -391,15 +466,24 @@ int gespmm_plan(int64_t M, int64_t N, int64_t nnz, int aligned16, gespmm_plan_t*
   return GESPMM_OK;
 }
 
-int gespmm_set_tuning(int lanes_per_row, int tiles_per_lane, int xcd_remap) {
+int gespmm_set_tuning(int lanes_per_row, int tiles_per_lane, int xcd_remap, int chunk_nnz, int short_len) {
   const int G = lanes_per_row, T = tiles_per_lane;
   if (G > 0 && (G > kWave || (G & (G - 1)) != 0)) return GESPMM_ERR_BAD_ARG;
   if (T > 0 && T != 1 && T != 2 && T != 4) return GESPMM_ERR_BAD_ARG;
   if (G > 0 && T > 0 && !has_kernel(G, T)) return GESPMM_ERR_BAD_ARG;
   if (xcd_remap > 1) return GESPMM_ERR_BAD_ARG;
+  int shift = -1;
+  if (chunk_nnz > 0) {
+    for (int sh = 6; sh <= kMaxChunkShift; ++sh)
+      if (chunk_nnz == (1 << sh)) shift = sh;
+    if (shift < 0) return GESPMM_ERR_BAD_ARG;
+  }
+  if (short_len > (1 << kMaxChunkShift)) return GESPMM_ERR_BAD_ARG;
   g_force_g = G > 0 ? G : -1;
   g_force_t = T > 0 ? T : -1;
   g_force_remap = xcd_remap >= 0 ? xcd_remap : -1;
+  g_force_shift = shift;
+  g_force_short = short_len >= 0 ? short_len : -1;
   return GESPMM_OK;
 }
 
@@ -421,11 +505,13 @@ int gespmm_csr(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowp
   float identity = 0.0f;
   if (fold == kMax) identity = -__builtin_inff();
   if (fold == kMin) identity = __builtin_inff();
+  int shift = 0;
+  while ((1 << shift) < plan.chunk_nnz) ++shift;
   const unsigned init_blocks = (unsigned)((M + kBlock - 1) / kBlock);
   if (plan.vec == 4)
-    hipLaunchKernelGGL(init_rows<4>, dim3(init_blocks), dim3(kBlock), 0, stream, (int32_t)M, (int32_t)N, rowptr, C, identity);
+    hipLaunchKernelGGL(init_rows<4>, dim3(init_blocks), dim3(kBlock), 0, stream, (int32_t)M, (int32_t)N, rowptr, C, identity, shift);
   else
-    hipLaunchKernelGGL(init_rows<1>, dim3(init_blocks), dim3(kBlock), 0, stream, (int32_t)M, (int32_t)N, rowptr, C, identity);
+    hipLaunchKernelGGL(init_rows<1>, dim3(init_blocks), dim3(kBlock), 0, stream, (int32_t)M, (int32_t)N, rowptr, C, identity, shift);
   if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
   if (nnz == 0) return GESPMM_OK;
 
@@ -438,6 +524,8 @@ int gespmm_csr(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowp
   a.chunks = plan.chunks;
   a.chunk_blocks = plan.grid_x;
   a.xcd_remap = plan.xcd_remap;
+  a.chunk_shift = shift;
+  a.short_len = plan.short_len;
   a.rowptr = rowptr;
   a.colind = colind;
   a.vals = vals;
@@ -445,7 +533,7 @@ int gespmm_csr(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowp
   a.C = C;
   const bool timed = g_profiling && g_ev_used < (int)g_ev_start.size();
   if (timed && hipEventRecord(g_ev_start[g_ev_used], stream) != hipSuccess) return GESPMM_ERR_HIP;
-  hipLaunchKernelGGL(kernel, dim3((unsigned)plan.grid_x, (unsigned)plan.col_blocks), dim3(kBlock), 0, stream, a);
+  hipLaunchKernelGGL(kernel, dim3((unsigned)plan.grid_x, (unsigned)plan.col_blocks), dim3(kBlock), (size_t)plan.lds_bytes, stream, a);
   if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
   if (timed) {
     if (hipEventRecord(g_ev_stop[g_ev_used], stream) != hipSuccess) return GESPMM_ERR_HIP;
@@ -505,6 +593,19 @@ int gespmm_profile_end(double* main_kernel_ms_sum, int* launches) {
   g_ev_stop.clear();
   g_ev_used = 0;
   return status;
+}
+
+int gespmm_calibration_copy(const void* src, void* dst, int64_t bytes, void* stream_) {
+  if (bytes < 0 || bytes % 16 != 0) return GESPMM_ERR_BAD_ARG;
+  if (bytes == 0) return GESPMM_OK;
+  if (!src || !dst) return GESPMM_ERR_NULL;
+  if ((((uintptr_t)src | (uintptr_t)dst) & 15u) != 0) return GESPMM_ERR_BAD_ARG;
+  const int64_t n4 = bytes / 16;
+  int64_t blocks = (n4 + kBlock - 1) / kBlock;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  hipLaunchKernelGGL(copy_f4, dim3((unsigned)blocks), dim3(kBlock), 0, (hipStream_t)stream_,
+                     (const float4*)src, (float4*)dst, n4);
+  return hipGetLastError() == hipSuccess ? GESPMM_OK : GESPMM_ERR_HIP;
 }
 
 const char* gespmm_status_string(int status) {

@@ -28,6 +28,7 @@ def test_every_declared_symbol_is_exported(L):
     names = _declared_functions()
     assert {"gespmm_csr", "gespmm_csr_simple", "gespmm_plan", "gespmm_set_tuning",
             "gespmm_profile_begin", "gespmm_profile_end", "gespmm_status_string",
+            "gespmm_calibration_copy",
             "gespmm_version"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
@@ -63,6 +64,10 @@ def test_argument_errors_come_before_any_device_work(L):
     assert L.gespmm_csr_simple(0, 4, 4, p, p, p, p, p, 0, None) == 0
     assert L.gespmm_plan(4, 4, 4, 1, None) == 2
     assert L.gespmm_profile_end(None, None) == 1                  # not profiling
+    assert L.gespmm_calibration_copy(p, p, 24, None) == 1         # not a multiple of 16
+    assert L.gespmm_calibration_copy(None, p, 32, None) == 2
+    assert L.gespmm_calibration_copy(p, ctypes.c_void_p(0x1004), 32, None) == 1
+    assert L.gespmm_calibration_copy(p, p, 0, None) == 0
 
 
 @pytest.mark.parametrize("N,G,T,blocks", [(8, 2, 1, 1), (16, 4, 1, 1), (32, 8, 1, 1), (64, 16, 1, 1),
@@ -94,6 +99,25 @@ def test_tuning_override_is_validated():
         gs.gespmm_set_tuning(32, 1, 0)
         p = gs.gespmm_plan(1000, 64, 10_000)
         assert (p["lanes_per_row"], p["tiles_per_lane"], p["xcd_remap"], p["col_blocks"]) == (32, 1, 0, 1)
+        gs.gespmm_set_tuning(chunk_nnz=1024, short_len=5)
+        p = gs.gespmm_plan(1000, 64, 10_000)
+        assert (p["lanes_per_row"], p["chunk_nnz"], p["short_len"], p["chunks"]) == (16, 1024, 5, 10)
+        assert p["lds_bytes"] == 4 * (1024 + 64) * 8
+        for bad in (dict(chunk_nnz=100), dict(chunk_nnz=2048), dict(chunk_nnz=32), dict(short_len=5000)):
+            with pytest.raises(gs.GespmmError):
+                gs.gespmm_set_tuning(**bad)
     finally:
-        gs.gespmm_set_tuning(-1, -1, -1)
+        gs.gespmm_set_tuning()
     assert gs.gespmm_plan(1000, 64, 10_000)["lanes_per_row"] == 16
+
+
+def test_chunk_size_follows_width_and_problem_size():
+    # big problems: about the same gathered bytes per wavefront whatever the width
+    big = 100_000_000
+    assert [gs.gespmm_plan(10**6, N, big)["chunk_nnz"] for N in (8, 16, 32, 64, 128, 512)] == \
+        [1024, 1024, 512, 256, 256, 256]
+    # small problems: smaller chunks, so the rows spread over more wavefronts
+    assert gs.gespmm_plan(19717, 512, 88_648)["chunk_nnz"] == 64
+    assert gs.gespmm_plan(2708, 16, 10_556)["chunk_nnz"] == 64
+    p = gs.gespmm_plan(169_343, 128, 2_330_033)
+    assert p["chunk_nnz"] == 256 and p["short_len"] == 2 * p["slots"]

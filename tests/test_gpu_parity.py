@@ -16,8 +16,10 @@ pytestmark = pytest.mark.gpu
 
 OPS = ("sum", "mean", "max", "min")
 KERNEL_SHAPES = [(1, 1), (2, 1), (4, 1), (8, 1), (16, 1), (32, 1), (64, 1),
-                 (1, 2), (2, 2), (4, 2), (8, 2), (16, 2), (32, 2), (64, 2),
+                 (4, 2), (8, 2), (16, 2), (32, 2), (64, 2),
                  (8, 4), (16, 4), (32, 4), (64, 4)]
+# (xcd_remap, chunk_nnz, short_len): smallest and largest chunks, slot-per-row mode off / default / always
+LAUNCH_VARIANTS = [(0, 64, 0), (1, 256, -1), (1, 1024, 1024), (0, 128, 3)]
 
 
 @pytest.fixture(scope="module")
@@ -26,7 +28,7 @@ def gs():
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     gs.lib()                                   # raises if the HIP library was not built
     yield gs
-    gs.gespmm_set_tuning(-1, -1, -1)
+    gs.gespmm_set_tuning()
 
 
 def say(*a):
@@ -142,14 +144,16 @@ def test_every_kernel_shape(gs, vec_n):
     dA, dB = (dev(rp), dev(ci), dev(v)), dev(B)
     try:
         for G, T in KERNEL_SHAPES:
-            for remap in (0, 1):
-                gs.gespmm_set_tuning(G, T, remap)
+            for remap, chunk, short in LAUNCH_VARIANTS:
+                gs.gespmm_set_tuning(G, T, remap, chunk, short)
                 plan = gs.gespmm_plan(300, N, len(ci))
                 assert plan["vec"] == vec and plan["lanes_per_row"] == G and plan["tiles_per_lane"] == T
+                assert plan["chunk_nnz"] == chunk and plan["xcd_remap"] == remap
                 for op in ("sum", "mean", "max", "min"):
-                    check(gs, rp, ci, v, B, op, label=f"G={G} T={T} remap={remap}", dA=dA, dB=dB)
+                    check(gs, rp, ci, v, B, op, label=f"G={G} T={T} remap={remap} S={chunk} short={short}",
+                          dA=dA, dB=dB)
     finally:
-        gs.gespmm_set_tuning(-1, -1, -1)
+        gs.gespmm_set_tuning()
 
 
 def test_unaligned_buffers_take_scalar_path(gs):
