@@ -97,8 +97,6 @@ typedef struct {
   int32_t xcd_remap;      /* 1: consecutive chunks are kept on one XCD                    */
   int32_t short_len;      /* row segments up to this length are handled one per slot      */
   int32_t lds_bytes;      /* dynamic LDS per workgroup                                    */
-  int32_t chunks_per_wave;/* consecutive chunks one wavefront walks                       */
-  int32_t staged;         /* 1: the chunk's products are parked in LDS before the folds   */
 } gespmm_plan_t;
 
 int gespmm_plan(int64_t M, int64_t N, int64_t nnz, int aligned16, gespmm_plan_t* out);
@@ -106,14 +104,12 @@ int gespmm_plan(int64_t M, int64_t N, int64_t nnz, int aligned16, gespmm_plan_t*
 /*
  * Tuning override for tests and benchmarks (process-wide, not thread-safe):
  * lanes_per_row in {1,2,4,...,64}, tiles_per_lane in {1,2,4}, xcd_remap in {0,1},
- * chunk_nnz a power of two in [16, 1024] (lowered if the staged products would not fit
- * LDS), short_len in [0, 1024] (0 = every row is handled by all slots together),
- * chunks_per_wave in [1, 64], staged in {0,1} (honoured only where a staged kernel
- * exists: vectorised, tiles_per_lane 1, lanes_per_row <= 16); -1 restores the automatic
- * choice for that field.  Returns GESPMM_ERR_BAD_ARG for a value that has no kernel.
+ * chunk_nnz a power of two in [16, 1024], short_len in [0, 1024] (0 = every row is
+ * handled by all slots together); -1 restores the automatic choice for that field.
+ * Returns GESPMM_ERR_BAD_ARG for a value that has no kernel.
  */
 int gespmm_set_tuning(int lanes_per_row, int tiles_per_lane, int xcd_remap, int chunk_nnz,
-                      int short_len, int chunks_per_wave, int staged);
+                      int short_len);
 
 /*
  * Per-kernel timing for the benchmark.  gespmm_profile_begin creates `capacity`

@@ -29,8 +29,7 @@ class gespmm_plan_t(ctypes.Structure):
                 ("chunk_nnz", ctypes.c_int32), ("col_blocks", ctypes.c_int32),
                 ("chunks", ctypes.c_int64), ("grid_x", ctypes.c_int64),
                 ("block_threads", ctypes.c_int32), ("xcd_remap", ctypes.c_int32),
-                ("short_len", ctypes.c_int32), ("lds_bytes", ctypes.c_int32),
-                ("chunks_per_wave", ctypes.c_int32), ("staged", ctypes.c_int32)]
+                ("short_len", ctypes.c_int32), ("lds_bytes", ctypes.c_int32)]
 
 
 _lib = None
@@ -53,7 +52,7 @@ def lib():
         L.gespmm_plan.restype = ci
         L.gespmm_plan.argtypes = [i64, i64, i64, ci, ctypes.POINTER(gespmm_plan_t)]
         L.gespmm_set_tuning.restype = ci
-        L.gespmm_set_tuning.argtypes = [ci, ci, ci, ci, ci, ci, ci]
+        L.gespmm_set_tuning.argtypes = [ci, ci, ci, ci, ci]
         L.gespmm_profile_begin.restype = ci
         L.gespmm_profile_begin.argtypes = [ci]
         L.gespmm_profile_end.restype = ci
@@ -133,10 +132,9 @@ def gespmm_plan(M, N, nnz, aligned16=True) -> dict:
     return {name: int(getattr(p, name)) for name, _ in p._fields_}
 
 
-def gespmm_set_tuning(lanes_per_row=-1, tiles_per_lane=-1, xcd_remap=-1, chunk_nnz=-1, short_len=-1,
-                      chunks_per_wave=-1, staged=-1):
+def gespmm_set_tuning(lanes_per_row=-1, tiles_per_lane=-1, xcd_remap=-1, chunk_nnz=-1, short_len=-1):
     _check(lib().gespmm_set_tuning(int(lanes_per_row), int(tiles_per_lane), int(xcd_remap),
-                                   int(chunk_nnz), int(short_len), int(chunks_per_wave), int(staged)))
+                                   int(chunk_nnz), int(short_len)))
 
 
 def gespmm_calibration_copy(src, dst, stream=None):

@@ -55,7 +55,6 @@ struct KernelArgs {
   int32_t xcd_remap;
   int32_t chunk_shift;    // log2(S), S = stored entries per wavefront
   int32_t short_len;      // row segments up to this length are handled one per slot
-  int32_t chunks_per_wave;  // consecutive chunks one wavefront walks
   const int32_t* rowptr;
   const int32_t* colind;
   const float* vals;
@@ -229,39 +228,11 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Same pass when the products a * B[k, :] of the whole chunk already sit in LDS (X, one
-// block of G*T float4 per entry): an entry that does not exist reads the neutral block
-// at index `neutral`, which holds the reduce identity.
-template <int F, int G, int T, int U>
-__device__ __forceinline__ void staged_pass(Vec<4> (&acc)[T], const float4* X, int first, int stride, int left,
-                                            int neutral, int g) {
-  float4 x[U][T];
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int idx = u < left ? first + u * stride : neutral;
-#pragma unroll
-    for (int t = 0; t < T; ++t) x[u][t] = X[(idx * T + t) * G + g];
-  }
-#pragma unroll
-  for (int u = 0; u < U; ++u)
-#pragma unroll
-    for (int t = 0; t < T; ++t) {
-      acc[t].v[0] = fold2<F>(acc[t].v[0], x[u][t].x);
-      acc[t].v[1] = fold2<F>(acc[t].v[1], x[u][t].y);
-      acc[t].v[2] = fold2<F>(acc[t].v[2], x[u][t].z);
-      acc[t].v[3] = fold2<F>(acc[t].v[3], x[u][t].w);
-    }
-}
-
-// STAGED (narrow rows of B, vectorised only): the wavefront first gathers the B rows of
-// its whole chunk with every lane busy, whatever the row lengths, multiplies, and parks
-// the products in LDS; the per-row folds then read LDS instead of waiting on HBM.
-template <int F, int V, int G, int T, bool STAGED>
+template <int F, int V, int G, int T>
 __global__ void __launch_bounds__(kBlock) spmm_chunks(const KernelArgs a) {
-  static_assert(!STAGED || V == 4, "the staged kernel is vectorised");
   constexpr int NS = kWave / G;                 // slots
-  constexpr int U = STAGED ? 4 : (loads_in_flight(G) / T > 0 ? loads_in_flight(G) / T : 1);   // entries per lane per pass
-  extern __shared__ int2 s_dyn[];               // per wavefront: S x (colind, val) | 64 row descriptors | products
+  constexpr int U = loads_in_flight(G) / T > 0 ? loads_in_flight(G) / T : 1;   // entries per lane per pass
+  extern __shared__ int2 s_dyn[];               // per wavefront: S entries (colind, val) + 64 row descriptors
 
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x >> 6;
@@ -269,17 +240,55 @@ __global__ void __launch_bounds__(kBlock) spmm_chunks(const KernelArgs a) {
   const int g = lane % G;
   const int S = 1 << a.chunk_shift;
 
-  // this wavefront's run of consecutive chunks
-  const int64_t wave_id = logical_block(blockIdx.x, a.chunk_blocks, a.xcd_remap) * kWavesPerBlock + wave;
-  const int64_t chunk0 = wave_id * a.chunks_per_wave;
-  if (chunk0 >= a.chunks) return;               // whole wavefront leaves; no block barrier is used
-  const int nchunks = (int)(a.chunks - chunk0 < a.chunks_per_wave ? a.chunks - chunk0 : a.chunks_per_wave);
-
-  const int wave_lds = S + kWave + (STAGED ? 2 * G * T * (S + 1) : 0);   // in int2 units
-  int2* ka = s_dyn + wave * wave_lds;
+  const int64_t chunk = logical_block(blockIdx.x, a.chunk_blocks, a.xcd_remap) * kWavesPerBlock + wave;
+  if (chunk >= a.chunks) return;                // whole wavefront leaves; no block barrier is used
+  const int cs = (int)(chunk << a.chunk_shift); // first stored entry of this chunk (< 2^31)
+  const int cnt = (a.nnz - cs) < S ? (a.nnz - cs) : S;
+  const int ce = cs + cnt;
+  int2* ka = s_dyn + wave * (S + kWave);
   int2* short_rows = ka + S;
-  float4* X = reinterpret_cast<float4*>(short_rows + kWave);
-  (void)X;
+
+  // (1) coalesced load of the chunk's (colind, val) into this wavefront's LDS slice, four
+  //     loads of each array in flight at a time (indices past the end repeat the last
+  //     entry; those copies are never consumed)
+  for (int u0 = 0; u0 < cnt; u0 += 4 * kWave) {
+    int k[4];
+    float v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int idx = u0 + u * kWave + lane;
+      k[u] = a.colind[cs + (idx < cnt ? idx : cnt - 1)];
+    }
+    if (a.vals) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int idx = u0 + u * kWave + lane;
+        v[u] = a.vals[cs + (idx < cnt ? idx : cnt - 1)];
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = 1.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int idx = u0 + u * kWave + lane;
+      if (idx < S) ka[idx] = make_int2(k[u], __float_as_int(v[u]));
+    }
+  }
+
+  // (2) first row of the chunk: the last r with rowptr[r] <= cs, found by a 64-way search
+  int lo = 0, hi = a.M;                          // rowptr[lo] <= cs < rowptr[hi]
+  while (hi - lo > 1) {
+    const int64_t step = ((int64_t)(hi - lo) + kWave - 1) / kWave;
+    int64_t probe = lo + (int64_t)(lane + 1) * step;
+    if (probe > hi) probe = hi;
+    const int below = __builtin_popcountll(__ballot(a.rowptr[probe] <= cs));   // probes are monotone
+    const int64_t nlo = lo + below * step;       // below <= 63 because rowptr[hi] > cs
+    int64_t nhi = nlo + step;
+    if (nhi > hi) nhi = hi;
+    lo = (int)nlo;
+    hi = (int)nhi;
+  }
 
   // column tiles of this lane (loads use a clamped column so they are never masked)
   const int colbase = blockIdx.y * (V * G * T);
@@ -290,187 +299,81 @@ __global__ void __launch_bounds__(kBlock) spmm_chunks(const KernelArgs a) {
     col[t] = colbase + (t * G + g) * V;
     colc[t] = col[t] < a.N ? col[t] : a.N - V;
   }
-  if (STAGED && slot == 0) {
-#pragma unroll
-    for (int t = 0; t < T; ++t)
-      X[(S * T + t) * G + g] = make_float4(fold_identity<F>(), fold_identity<F>(), fold_identity<F>(), fold_identity<F>());
-  }
 
-  // first row of the first chunk: the last r with rowptr[r] <= cs, found by a 64-way search
-  int lo = 0, hi = a.M;                          // rowptr[lo] <= cs < rowptr[hi]
-  {
-    const int cs0 = (int)(chunk0 << a.chunk_shift);
-    while (hi - lo > 1) {
-      const int64_t step = ((int64_t)(hi - lo) + kWave - 1) / kWave;
-      int64_t probe = lo + (int64_t)(lane + 1) * step;
-      if (probe > hi) probe = hi;
-      const int below = __builtin_popcountll(__ballot(a.rowptr[probe] <= cs0));   // probes are monotone
-      const int64_t nlo = lo + below * step;     // below <= 63 because rowptr[hi] > cs0
-      int64_t nhi = nlo + step;
-      if (nhi > hi) nhi = hi;
-      lo = (int)nlo;
-      hi = (int)nhi;
-    }
-  }
+  wave_lds_fence();
 
-  // the current batch of 64 row bounds (lane <-> row); it is kept across chunk borders
-  int64_t rbase = lo;
-  int my_s, my_e;
-  {
-    const int64_t rr = rbase + lane < a.M ? rbase + lane : a.M;
-    my_s = a.rowptr[rr];
-    my_e = a.rowptr[rr < a.M ? rr + 1 : a.M];
-  }
+  // (3) walk the rows that have entries in [cs, ce), 64 row bounds at a time (lane <-> row)
+  for (int64_t rbase = lo;; rbase += kWave) {
+    int64_t rr = rbase + lane;
+    if (rr > a.M) rr = a.M;
+    const int my_s = a.rowptr[rr];
+    const int my_e = a.rowptr[rr < a.M ? rr + 1 : a.M];
+    const bool valid = rbase + lane < a.M && my_e > my_s && my_s < ce;
+    const int my_ps = (my_s > cs ? my_s : cs) - cs;     // the row's segment inside the chunk,
+    const int my_pe = (my_e < ce ? my_e : ce) - cs;     // as offsets into the LDS slice
+    const bool my_whole = my_s >= cs && my_e <= ce;
+    const bool is_short = NS > 1 && valid && (my_pe - my_ps) <= a.short_len;
 
-  for (int c = 0; c < nchunks; ++c) {
-    const int cs = (int)((chunk0 + c) << a.chunk_shift);   // first stored entry of this chunk (< 2^31)
-    const int cnt = (a.nnz - cs) < S ? (a.nnz - cs) : S;
-    const int ce = cs + cnt;
-
-    // (1) coalesced load of the chunk's (colind, val) into this wavefront's LDS slice, four
-    //     loads of each array in flight at a time (indices past the end repeat the last
-    //     entry; those copies are never consumed)
-    wave_lds_fence();
-    for (int u0 = 0; u0 < cnt; u0 += 4 * kWave) {
-      int k[4];
-      float v[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int idx = u0 + u * kWave + lane;
-        k[u] = a.colind[cs + (idx < cnt ? idx : cnt - 1)];
-      }
-      if (a.vals) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int idx = u0 + u * kWave + lane;
-          v[u] = a.vals[cs + (idx < cnt ? idx : cnt - 1)];
-        }
-      } else {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = 1.0f;
-      }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int idx = u0 + u * kWave + lane;
-        if (idx < S) ka[idx] = make_int2(k[u], __float_as_int(v[u]));
-      }
-    }
-    wave_lds_fence();
-
-    // (2) staged only: gather every entry's B row, multiply, park the products in LDS
-    if (STAGED) {
-      constexpr int UA = 8 / T > 0 ? 8 / T : 1;
-      for (int base = 0; base < cnt; base += NS * UA) {
-        int2 e2[UA];
-        Vec<V> b[UA][T];
-#pragma unroll
-        for (int u = 0; u < UA; ++u) {
-          const int q = base + u * NS + slot;
-          e2[u] = ka[q < cnt ? q : cnt - 1];
-        }
-#pragma unroll
-        for (int u = 0; u < UA; ++u) {
-          const float* brow = a.B + (int64_t)e2[u].x * a.N;
-#pragma unroll
-          for (int t = 0; t < T; ++t) b[u][t] = Vec<V>::load(brow + colc[t]);
-        }
-#pragma unroll
-        for (int u = 0; u < UA; ++u) {
-          const int q = base + u * NS + slot;
-          const float w = __int_as_float(e2[u].y);
-          if (q < cnt) {
-#pragma unroll
-            for (int t = 0; t < T; ++t)
-              X[(q * T + t) * G + g] = make_float4(w * b[u][t].v[0], w * b[u][t].v[V > 1 ? 1 : 0],
-                                                   w * b[u][t].v[V > 2 ? 2 : 0], w * b[u][t].v[V > 3 ? 3 : 0]);
-          }
-        }
-      }
-      wave_lds_fence();
-    }
-
-    // (3) walk the rows that have entries in [cs, ce)
-    for (;;) {
-      const bool valid = rbase + lane < a.M && my_e > my_s && my_s < ce && my_e > cs;
-      const int my_ps = (my_s > cs ? my_s : cs) - cs;     // the row's segment inside the chunk,
-      const int my_pe = (my_e < ce ? my_e : ce) - cs;     // as offsets into the LDS slice
-      const bool my_whole = my_s >= cs && my_e <= ce;
-      const bool is_short = NS > 1 && valid && (my_pe - my_ps) <= a.short_len;
-
-      // (3a) short segments: one per slot, 64/G rows at a time, no cross-lane exchange
-      if (NS > 1) {
-        const unsigned long long smask = __ballot(is_short);
-        const int nshort = __builtin_popcountll(smask);
-        if (nshort > 0) {
-          const int rank = __builtin_amdgcn_mbcnt_hi((unsigned)(smask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)smask, 0u));
-          if (is_short)   // lane | offset << 6 | length << 18 | whole << 30 ; full row length
-            short_rows[rank] = make_int2(lane | (my_ps << 6) | ((my_pe - my_ps) << 18) | ((int)my_whole << 30), my_e - my_s);
-          wave_lds_fence();
-          for (int t0 = 0; t0 < nshort; t0 += NS) {
-            const bool have = t0 + slot < nshort;
-            const int2 d = short_rows[have ? t0 + slot : nshort - 1];
-            const int r_ps = (d.x >> 6) & 4095;
-            const int r_len = have ? (d.x >> 18) & 4095 : 0;
-            Vec<V> acc[T];
-#pragma unroll
-            for (int t = 0; t < T; ++t)
-#pragma unroll
-              for (int x = 0; x < V; ++x) acc[t].v[x] = fold_identity<F>();
-            for (int it = 0; __ballot(it < r_len) != 0ull; it += U) {
-              if constexpr (STAGED)
-                staged_pass<F, G, T, U>(acc, X, r_ps + it, 1, r_len - it, S, g);
-              else
-                gather_pass<F, V, T, U>(acc, ka, r_ps + (it < r_len ? it : 0), 1, r_len - it, a.B, a.N, colc);
-            }
-            if (have)
-              emit<F, V, T>(acc, a.C + (rbase + (d.x & 63)) * (int64_t)a.N, col, a.N, (d.x >> 30) & 1, d.y, a.is_mean);
-          }
-          wave_lds_fence();
-        }
-      }
-
-      // (3b) long segments: all slots work on one row, slot s takes entries s, s+NS, ...
-      unsigned long long todo = __ballot(valid && !is_short);
-      while (todo) {
-        const int i = __builtin_ctzll(todo);
-        todo &= todo - 1;
-        const int ps = __builtin_amdgcn_readlane(my_ps, i);
-        const int pe = __builtin_amdgcn_readlane(my_pe, i);
-        Vec<V> acc[T];
-#pragma unroll
-        for (int t = 0; t < T; ++t)
-#pragma unroll
-          for (int x = 0; x < V; ++x) acc[t].v[x] = fold_identity<F>();
-        for (int base = ps; base < pe; base += U * NS) {
-          const int first = base + slot;
-          const int left = (pe - first + NS - 1) / NS;       // entries first, first+NS, ... below pe
-          if constexpr (STAGED)
-            staged_pass<F, G, T, U>(acc, X, first, NS, left, S, g);
-          else
-            gather_pass<F, V, T, U>(acc, ka, left > 0 ? first : pe - 1, NS, left, a.B, a.N, colc);
-        }
-#pragma unroll
-        for (int off = G; off < kWave; off <<= 1)
+    // (3a) short segments: one per slot, 64/G rows at a time, no cross-lane exchange
+    if (NS > 1) {
+      const unsigned long long smask = __ballot(is_short);
+      const int nshort = __builtin_popcountll(smask);
+      if (nshort > 0) {
+        const int rank = __builtin_amdgcn_mbcnt_hi((unsigned)(smask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)smask, 0u));
+        if (is_short)   // lane | offset << 6 | length << 18 | whole << 30 ; full row length
+          short_rows[rank] = make_int2(lane | (my_ps << 6) | ((my_pe - my_ps) << 18) | ((int)my_whole << 30), my_e - my_s);
+        wave_lds_fence();
+        for (int t0 = 0; t0 < nshort; t0 += NS) {
+          const bool have = t0 + slot < nshort;
+          const int2 d = short_rows[have ? t0 + slot : nshort - 1];
+          const int r_ps = (d.x >> 6) & 4095;
+          const int r_len = have ? (d.x >> 18) & 4095 : 0;
+          Vec<V> acc[T];
 #pragma unroll
           for (int t = 0; t < T; ++t)
 #pragma unroll
-            for (int x = 0; x < V; ++x) acc[t].v[x] = fold2<F>(acc[t].v[x], __shfl_xor(acc[t].v[x], off, kWave));
-        if (slot == 0) {
-          const int s = __builtin_amdgcn_readlane(my_s, i);
-          const int e = __builtin_amdgcn_readlane(my_e, i);
-          emit<F, V, T>(acc, a.C + (rbase + i) * (int64_t)a.N, col, a.N, s >= cs && e <= ce, e - s, a.is_mean);
+            for (int x = 0; x < V; ++x) acc[t].v[x] = fold_identity<F>();
+          for (int it = 0; __ballot(it < r_len) != 0ull; it += U)
+            gather_pass<F, V, T, U>(acc, ka, r_ps + (it < r_len ? it : 0), 1, r_len - it, a.B, a.N, colc);
+          if (have)
+            emit<F, V, T>(acc, a.C + (rbase + (d.x & 63)) * (int64_t)a.N, col, a.N, (d.x >> 30) & 1, d.y, a.is_mean);
         }
+        wave_lds_fence();
       }
-
-      // the next 64 rows are needed only if they still start inside this chunk; otherwise
-      // the batch is kept: its last rows may belong to the next chunk
-      const int next_start = __builtin_amdgcn_readlane(my_e, kWave - 1);
-      if (rbase + kWave >= a.M || next_start >= ce) break;
-      rbase += kWave;
-      const int64_t rr = rbase + lane < a.M ? rbase + lane : a.M;
-      my_s = a.rowptr[rr];
-      my_e = a.rowptr[rr < a.M ? rr + 1 : a.M];
     }
+
+    // (3b) long segments: all slots work on one row, slot s takes entries s, s+NS, ...
+    unsigned long long todo = __ballot(valid && !is_short);
+    while (todo) {
+      const int i = __builtin_ctzll(todo);
+      todo &= todo - 1;
+      const int ps = __builtin_amdgcn_readlane(my_ps, i);
+      const int pe = __builtin_amdgcn_readlane(my_pe, i);
+      Vec<V> acc[T];
+#pragma unroll
+      for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int x = 0; x < V; ++x) acc[t].v[x] = fold_identity<F>();
+      for (int base = ps; base < pe; base += U * NS) {
+        const int first = base + slot;
+        const int left = (pe - first + NS - 1) / NS;       // entries first, first+NS, ... below pe
+        gather_pass<F, V, T, U>(acc, ka, left > 0 ? first : pe - 1, NS, left, a.B, a.N, colc);
+      }
+#pragma unroll
+      for (int off = G; off < kWave; off <<= 1)
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+#pragma unroll
+          for (int x = 0; x < V; ++x) acc[t].v[x] = fold2<F>(acc[t].v[x], __shfl_xor(acc[t].v[x], off, kWave));
+      if (slot == 0) {
+        const int s = __builtin_amdgcn_readlane(my_s, i);
+        const int e = __builtin_amdgcn_readlane(my_e, i);
+        emit<F, V, T>(acc, a.C + (rbase + i) * (int64_t)a.N, col, a.N, s >= cs && e <= ce, e - s, a.is_mean);
+      }
+    }
+    // the next batch of rows is needed only if it still starts inside the chunk
+    const int next_start = __builtin_amdgcn_readlane(my_e, kWave - 1);
+    if (rbase + kWave >= a.M || next_start >= ce) break;
   }
 }
 
@@ -478,34 +381,30 @@ __global__ void __launch_bounds__(kBlock) spmm_chunks(const KernelArgs a) {
 using MainKernel = void (*)(const KernelArgs);
 
 template <int F, int V>
-MainKernel pick_gt(int G, int T, bool staged) {
-#define GESPMM_CASE(GG, TT) if (!staged && G == GG && T == TT) return spmm_chunks<F, V, GG, TT, false>;
+MainKernel pick_gt(int G, int T) {
+#define GESPMM_CASE(GG, TT) if (G == GG && T == TT) return spmm_chunks<F, V, GG, TT>;
   GESPMM_CASE(1, 1) GESPMM_CASE(2, 1) GESPMM_CASE(4, 1) GESPMM_CASE(8, 1)
   GESPMM_CASE(16, 1) GESPMM_CASE(32, 1) GESPMM_CASE(64, 1)
   GESPMM_CASE(4, 2) GESPMM_CASE(8, 2) GESPMM_CASE(16, 2) GESPMM_CASE(32, 2) GESPMM_CASE(64, 2)
   GESPMM_CASE(8, 4) GESPMM_CASE(16, 4) GESPMM_CASE(32, 4) GESPMM_CASE(64, 4)
 #undef GESPMM_CASE
-  if constexpr (V == 4) {
-#define GESPMM_CASE(GG) if (staged && G == GG && T == 1) return spmm_chunks<F, 4, GG, 1, true>;
-    GESPMM_CASE(1) GESPMM_CASE(2) GESPMM_CASE(4) GESPMM_CASE(8) GESPMM_CASE(16)
-#undef GESPMM_CASE
-  }
   return nullptr;
 }
 
-MainKernel pick_kernel(int fold, int vec, int G, int T, bool staged) {
+MainKernel pick_kernel(int fold, int vec, int G, int T) {
   if (vec == 4) {
-    if (fold == kAdd) return pick_gt<kAdd, 4>(G, T, staged);
-    if (fold == kMax) return pick_gt<kMax, 4>(G, T, staged);
-    return pick_gt<kMin, 4>(G, T, staged);
+    if (fold == kAdd) return pick_gt<kAdd, 4>(G, T);
+    if (fold == kMax) return pick_gt<kMax, 4>(G, T);
+    return pick_gt<kMin, 4>(G, T);
   }
-  if (fold == kAdd) return pick_gt<kAdd, 1>(G, T, staged);
-  if (fold == kMax) return pick_gt<kMax, 1>(G, T, staged);
-  return pick_gt<kMin, 1>(G, T, staged);
+  if (fold == kAdd) return pick_gt<kAdd, 1>(G, T);
+  if (fold == kMax) return pick_gt<kMax, 1>(G, T);
+  return pick_gt<kMin, 1>(G, T);
 }
 
-bool has_kernel(int G, int T) { return pick_gt<kAdd, 4>(G, T, false) != nullptr; }
-bool has_staged_kernel(int G, int T) { return pick_gt<kAdd, 4>(G, T, true) != nullptr; }
+bool has_kernel(int G, int T) {
+  return pick_gt<kAdd, 4>(G, T) != nullptr;
+}
 
 int next_pow2(int64_t x) {
   int p = 1;
@@ -514,22 +413,13 @@ int next_pow2(int64_t x) {
 }
 
 // process-wide tuning overrides (-1 = automatic)
-int g_force_g = -1, g_force_t = -1, g_force_remap = -1, g_force_shift = -1, g_force_short = -1,
-    g_force_cpw = -1, g_force_staged = -1;
+int g_force_g = -1, g_force_t = -1, g_force_remap = -1, g_force_shift = -1, g_force_short = -1;
 
 // Waves the chip holds at full occupancy (256 CUs x 4 SIMDs x 8): a problem with fewer
 // chunks than this gets smaller chunks, so that its rows are spread over more wavefronts.
 constexpr int64_t kResidentWaves = 8192;
-constexpr int64_t kMaxLdsPerBlock = 64 * 1024;
-
-int64_t lds_bytes_for(int shift, int G, int T, bool staged) {
-  const int64_t S = 1ll << shift;
-  const int64_t per_wave = S + kWave + (staged ? 2ll * G * T * (S + 1) : 0);   // int2 units
-  return kWavesPerBlock * per_wave * (int64_t)sizeof(int2);
-}
 
 void make_plan(int64_t M, int64_t N, int64_t nnz, bool aligned16, gespmm_plan_t* p) {
-  (void)M;
   const int vec = (aligned16 && N > 0 && N % 4 == 0) ? 4 : 1;
   const int64_t ncv = N > 0 ? (N + vec - 1) / vec : 1;     // vector columns to cover
   // widest slot that is still <= 16 lanes for wide N, so several entries of a row are in
@@ -539,18 +429,11 @@ void make_plan(int64_t M, int64_t N, int64_t nnz, bool aligned16, gespmm_plan_t*
   if (ncv > 64 && G * T < 128) { G = 64; T = 2; }
   if (g_force_g > 0) G = g_force_g;
   if (g_force_t > 0) T = g_force_t;
-  // narrow B rows: stage the chunk's products in LDS (every gather lane busy)
-  bool staged = vec == 4 && T == 1 && G <= 8;
-  if (g_force_staged >= 0) staged = g_force_staged != 0;
-  if (staged && !(vec == 4 && has_staged_kernel(G, T))) staged = false;
-  // chunk size: about the same gathered bytes per wavefront for every width (64 KiB),
-  // halved while the problem has too few chunks to fill the chip, or while the staged
-  // products do not fit the workgroup's LDS
-  int shift = 8;
-  while (shift < kMaxChunkShift && ((int64_t)vec * G * T << shift) < 16384) ++shift;
+  // chunk size: 256 stored entries, 512 for narrow column blocks (less data per entry);
+  // halved while the problem has too few chunks to fill the chip
+  int shift = (int64_t)vec * G * T <= 16 ? 9 : 8;
   while (shift > 6 && ((nnz + (1ll << shift) - 1) >> shift) < kResidentWaves) --shift;
   if (g_force_shift >= kMinChunkShift) shift = g_force_shift;
-  while (shift > kMinChunkShift && lds_bytes_for(shift, G, T, staged) > kMaxLdsPerBlock) --shift;
   p->vec = vec;
   p->lanes_per_row = G;
   p->tiles_per_lane = T;
@@ -558,20 +441,15 @@ void make_plan(int64_t M, int64_t N, int64_t nnz, bool aligned16, gespmm_plan_t*
   p->chunk_nnz = 1 << shift;
   p->col_blocks = (int32_t)((ncv + (int64_t)G * T - 1) / ((int64_t)G * T));
   p->chunks = (nnz + p->chunk_nnz - 1) >> shift;
-  // a wavefront walks several consecutive chunks when there are plenty of them: the search
-  // for its first row is then paid once per run
-  int64_t cpw = p->chunks / (2 * kResidentWaves);
-  if (cpw < 1) cpw = 1;
-  if (cpw > 8) cpw = 8;
-  if (g_force_cpw > 0) cpw = g_force_cpw;
-  p->chunks_per_wave = (int32_t)cpw;
-  const int64_t waves = (p->chunks + cpw - 1) / cpw;
-  p->grid_x = (waves + kWavesPerBlock - 1) / kWavesPerBlock;
+  p->grid_x = (p->chunks + kWavesPerBlock - 1) / kWavesPerBlock;
   p->block_threads = kBlock;
-  p->xcd_remap = g_force_remap >= 0 ? g_force_remap : 1;
-  p->short_len = g_force_short >= 0 ? g_force_short : 2 * p->slots;
-  p->staged = staged ? 1 : 0;
-  p->lds_bytes = (int32_t)lds_bytes_for(shift, G, T, staged);
+  // rows much longer than a chunk are finished by atomics from many consecutive chunks:
+  // keep those chunks on one XCD (one L2); otherwise deal the chunks round-robin
+  const bool long_rows = M > 0 && nnz / M >= p->chunk_nnz / 2;
+  p->xcd_remap = g_force_remap >= 0 ? g_force_remap : (long_rows ? 1 : 0);
+  const int auto_short = 2 * p->slots < 16 ? 2 * p->slots : 16;
+  p->short_len = g_force_short >= 0 ? g_force_short : auto_short;
+  p->lds_bytes = (int32_t)(kWavesPerBlock * (p->chunk_nnz + kWave) * sizeof(int2));
 }
 
 // profiling state
@@ -602,13 +480,12 @@ int gespmm_plan(int64_t M, int64_t N, int64_t nnz, int aligned16, gespmm_plan_t*
   return GESPMM_OK;
 }
 
-int gespmm_set_tuning(int lanes_per_row, int tiles_per_lane, int xcd_remap, int chunk_nnz, int short_len,
-                      int chunks_per_wave, int staged) {
+int gespmm_set_tuning(int lanes_per_row, int tiles_per_lane, int xcd_remap, int chunk_nnz, int short_len) {
   const int G = lanes_per_row, T = tiles_per_lane;
   if (G > 0 && (G > kWave || (G & (G - 1)) != 0)) return GESPMM_ERR_BAD_ARG;
   if (T > 0 && T != 1 && T != 2 && T != 4) return GESPMM_ERR_BAD_ARG;
   if (G > 0 && T > 0 && !has_kernel(G, T)) return GESPMM_ERR_BAD_ARG;
-  if (xcd_remap > 1 || staged > 1 || chunks_per_wave > 64) return GESPMM_ERR_BAD_ARG;
+  if (xcd_remap > 1) return GESPMM_ERR_BAD_ARG;
   int shift = -1;
   if (chunk_nnz > 0) {
     for (int sh = kMinChunkShift; sh <= kMaxChunkShift; ++sh)
@@ -621,8 +498,6 @@ int gespmm_set_tuning(int lanes_per_row, int tiles_per_lane, int xcd_remap, int 
   g_force_remap = xcd_remap >= 0 ? xcd_remap : -1;
   g_force_shift = shift;
   g_force_short = short_len >= 0 ? short_len : -1;
-  g_force_cpw = chunks_per_wave > 0 ? chunks_per_wave : -1;
-  g_force_staged = staged >= 0 ? staged : -1;
   return GESPMM_OK;
 }
 
@@ -637,7 +512,7 @@ int gespmm_csr(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowp
   gespmm_plan_t plan;
   make_plan(M, N, nnz, aligned16, &plan);
   const int fold = op == GESPMM_MAX ? kMax : (op == GESPMM_MIN ? kMin : kAdd);
-  MainKernel kernel = pick_kernel(fold, plan.vec, plan.lanes_per_row, plan.tiles_per_lane, plan.staged != 0);
+  MainKernel kernel = pick_kernel(fold, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
   if (!kernel) return GESPMM_ERR_BAD_ARG;
 
   // (a) empty rows -> 0, rows shared by several chunks -> reduce identity
@@ -667,7 +542,6 @@ int gespmm_csr(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowp
   a.xcd_remap = plan.xcd_remap;
   a.chunk_shift = shift;
   a.short_len = plan.short_len;
-  a.chunks_per_wave = plan.chunks_per_wave;
   a.rowptr = rowptr;
   a.colind = colind;
   a.vals = vals;

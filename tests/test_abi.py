@@ -78,7 +78,7 @@ def test_plan_covers_all_columns_vectorised(N, G, T, blocks):
     assert p["vec"] == 4 and (p["lanes_per_row"], p["tiles_per_lane"], p["col_blocks"]) == (G, T, blocks)
     assert p["vec"] * G * T * blocks >= N and p["slots"] * G == 64
     assert p["chunks"] == -(-10_000 // p["chunk_nnz"])
-    assert p["grid_x"] * (p["block_threads"] // 64) * p["chunks_per_wave"] >= p["chunks"]
+    assert p["grid_x"] * (p["block_threads"] // 64) >= p["chunks"]
 
 
 @pytest.mark.parametrize("N,aligned", [(1, True), (3, True), (7, False), (33, True), (100, False), (64, False)])
@@ -102,13 +102,8 @@ def test_tuning_override_is_validated():
         gs.gespmm_set_tuning(chunk_nnz=1024, short_len=5)
         p = gs.gespmm_plan(1000, 64, 10_000)
         assert (p["lanes_per_row"], p["chunk_nnz"], p["short_len"], p["chunks"]) == (16, 1024, 5, 10)
-        assert p["lds_bytes"] == 4 * (1024 + 64) * 8 and p["staged"] == 0
-        gs.gespmm_set_tuning(chunks_per_wave=3, staged=1, lanes_per_row=4, tiles_per_lane=1)
-        p = gs.gespmm_plan(1000, 16, 10_000)
-        assert (p["chunks_per_wave"], p["staged"], p["chunk_nnz"]) == (3, 1, 64)
-        assert p["grid_x"] * 4 * 3 >= p["chunks"]
-        for bad in (dict(chunk_nnz=100), dict(chunk_nnz=2048), dict(chunk_nnz=8), dict(short_len=5000),
-                    dict(chunks_per_wave=65), dict(staged=2)):
+        assert p["lds_bytes"] == 4 * (1024 + 64) * 8
+        for bad in (dict(chunk_nnz=100), dict(chunk_nnz=2048), dict(chunk_nnz=8), dict(short_len=5000)):
             with pytest.raises(gs.GespmmError):
                 gs.gespmm_set_tuning(**bad)
     finally:
@@ -117,16 +112,15 @@ def test_tuning_override_is_validated():
 
 
 def test_chunk_size_follows_width_and_problem_size():
-    # big problems: about the same gathered bytes per wavefront whatever the width
     big = 100_000_000
     plans = [gs.gespmm_plan(10**6, N, big) for N in (8, 16, 32, 64, 128, 512)]
-    assert [p["chunk_nnz"] for p in plans] == [256, 128, 64, 256, 256, 256]
-    assert [p["staged"] for p in plans] == [1, 1, 1, 0, 0, 0]        # narrow widths park products in LDS
-    assert all(p["lds_bytes"] <= 65536 and p["chunks_per_wave"] == 8 for p in plans)
-    assert gs.gespmm_plan(10**6, 8, big, aligned16=False)["staged"] == 0
+    assert [p["chunk_nnz"] for p in plans] == [512, 512, 256, 256, 256, 256]
+    assert [p["short_len"] for p in plans] == [16, 16, 16, 8, 8, 2]
+    assert all(p["lds_bytes"] == 4 * (p["chunk_nnz"] + 64) * 8 for p in plans)
     # small problems: smaller chunks, so the rows spread over more wavefronts
     assert gs.gespmm_plan(19717, 512, 88_648)["chunk_nnz"] == 64
     assert gs.gespmm_plan(2708, 16, 10_556)["chunk_nnz"] == 64
-    assert gs.gespmm_plan(19717, 512, 88_648)["chunks_per_wave"] == 1
     p = gs.gespmm_plan(169_343, 128, 2_330_033)
-    assert p["chunk_nnz"] == 256 and p["short_len"] == 2 * p["slots"]
+    assert p["chunk_nnz"] == 256 and p["xcd_remap"] == 0
+    # rows much longer than a chunk: consecutive chunks stay on one XCD
+    assert gs.gespmm_plan(232_965, 64, 114_693_532)["xcd_remap"] == 1

@@ -18,11 +18,8 @@ OPS = ("sum", "mean", "max", "min")
 KERNEL_SHAPES = [(1, 1), (2, 1), (4, 1), (8, 1), (16, 1), (32, 1), (64, 1),
                  (4, 2), (8, 2), (16, 2), (32, 2), (64, 2),
                  (8, 4), (16, 4), (32, 4), (64, 4)]
-# (xcd_remap, chunk_nnz, short_len, chunks_per_wave, staged): smallest and largest chunks,
-# slot-per-row mode off / default / always, one or several chunks per wavefront, products
-# parked in LDS or not (staged is honoured only where such a kernel exists)
-LAUNCH_VARIANTS = [(0, 64, 0, 1, 0), (1, 256, -1, 3, 0), (1, 1024, 1024, 1, 0), (0, 128, 3, 2, 0),
-                   (1, 64, -1, 2, 1), (0, 256, 0, 1, 1), (1, 16, 1024, 5, 1)]
+# (xcd_remap, chunk_nnz, short_len): smallest and largest chunks, slot-per-row mode off / default / always
+LAUNCH_VARIANTS = [(0, 16, 0), (1, 64, -1), (1, 256, 16), (1, 1024, 1024), (0, 128, 3)]
 
 
 @pytest.fixture(scope="module")
@@ -147,17 +144,14 @@ def test_every_kernel_shape(gs, vec_n):
     dA, dB = (dev(rp), dev(ci), dev(v)), dev(B)
     try:
         for G, T in KERNEL_SHAPES:
-            for remap, chunk, short, cpw, staged in LAUNCH_VARIANTS:
-                gs.gespmm_set_tuning(G, T, remap, chunk, short, cpw, staged)
+            for remap, chunk, short in LAUNCH_VARIANTS:
+                gs.gespmm_set_tuning(G, T, remap, chunk, short)
                 plan = gs.gespmm_plan(300, N, len(ci))
                 assert plan["vec"] == vec and plan["lanes_per_row"] == G and plan["tiles_per_lane"] == T
-                assert plan["chunk_nnz"] <= chunk and plan["xcd_remap"] == remap
-                assert plan["chunks_per_wave"] == cpw and plan["lds_bytes"] <= 65536
-                if staged and not plan["staged"]:
-                    continue                    # no staged kernel for this shape: same launch as above
+                assert plan["chunk_nnz"] == chunk and plan["xcd_remap"] == remap
                 for op in ("sum", "mean", "max", "min"):
                     check(gs, rp, ci, v, B, op, dA=dA, dB=dB,
-                          label=f"G={G} T={T} remap={remap} S={plan['chunk_nnz']} short={short} cpw={cpw} staged={plan['staged']}")
+                          label=f"G={G} T={T} remap={remap} S={chunk} short={short}")
     finally:
         gs.gespmm_set_tuning()
 
