@@ -28,7 +28,13 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 # HBM bytes per launch of the chunk kernel, measured with rocprofv3 --pmc (one FETCH_SIZE
 # run and one WRITE_SIZE run, each scaled by the calibration copy kernel of known size;
 # the summaries are under profiles/).  Key: "<workload>/N<width>/<op>".  Missing = null.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    "large_dense_degree/N64/sum": 25.618e9,   # profiles/spmm_chunks_large_dense_degree_N64_sum.md
+    "general_ops/N128/sum": 1.1635e9,         # profiles/spmm_chunks_general_ops_N128_sum.md
+    "skew_narrow/N8/sum": 0.63301e9,          # profiles/spmm_chunks_skew_narrow_N8_sum.md
+    "skew_narrow/N32/sum": 1.2062e9,          # profiles/spmm_chunks_skew_narrow_N32_sum.md
+    "width_sweep/N512/sum": 0.19870e9,        # profiles/spmm_chunks_width_sweep_N512_sum.md
+}
 
 
 def model_bytes(M, N, nnz, has_vals=True):
@@ -70,18 +76,23 @@ class DeviceCase:
         self.B = torch.from_numpy(self.B_host).to(dev)
         self.C = torch.empty((w.M, N), dtype=torch.float32, device=dev)
 
-    def time(self, gs, torch, op, steps, warmup):
+    def time(self, gs, torch, op, steps, warmup, bracket_kernel=True):
+        """Time `steps` whole calls.  With bracket_kernel the library also records a HIP event
+        pair around every chunk-kernel launch inside the same timed region (needed for the
+        roofline figure; the two extra event records per step cost a few microseconds, which
+        only matters for microsecond-scale workloads)."""
         stream = torch.cuda.current_stream()
         for _ in range(warmup):
             gs.gespmm_csr(self.rp, self.ci, self.v, self.B, op, C=self.C, stream=stream)
         torch.cuda.synchronize()
-        gs.gespmm_profile_begin(steps)
+        if bracket_kernel:
+            gs.gespmm_profile_begin(steps)
         t0 = time.perf_counter()
         for _ in range(steps):
             gs.gespmm_csr(self.rp, self.ci, self.v, self.B, op, C=self.C, stream=stream)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        main_ms_sum, launches = gs.gespmm_profile_end()
+        main_ms_sum, launches = gs.gespmm_profile_end() if bracket_kernel else (float("nan"), 0)
         w, N = self.w, self.N
         ms = (t1 - t0) * 1e3 / steps
         main_ms = main_ms_sum / max(launches, 1)
@@ -103,7 +114,9 @@ def sweep(args, gs, torch, graphgen, dev):
             case = DeviceCase(w, N, torch, dev)
             for op in w.ops:
                 steps = args.steps if w.nnz * N > 5e8 else max(args.steps, 200)
-                r = case.time(gs, torch, op, steps, args.warmup)
+                k = case.time(gs, torch, op, steps, args.warmup)                      # kernel bracketed
+                r = case.time(gs, torch, op, steps, args.warmup, bracket_kernel=False)  # clean step time
+                r["main_kernel_ms"], r["model_GBps_kernel"] = k["main_kernel_ms"], k["model_GBps_kernel"]
                 rows.append(r)
                 print(f"{r['workload']:20s} N={N:4d} {op:5s} step {r['ms_per_step']*1e3:9.1f} us  kernel "
                       f"{r['main_kernel_ms']*1e3:9.1f} us  {r['gflops']:8.1f} GFLOP/s  model "
@@ -128,7 +141,9 @@ def main():
     ap.add_argument("--sweep-out", default="", help="write the sweep rows to this JSON file")
     ap.add_argument("--copy-gib", type=float, default=0.0,
                     help="launch the calibration copy kernel once on this many GiB (traffic-counter yardstick)")
-    ap.add_argument("--tuning", default="", help="G,T,remap override (each -1 = automatic)")
+    ap.add_argument("--tuning", default="",
+                    help="lanes_per_row,tiles_per_lane,xcd_remap,chunk_nnz,short_len override, e.g. "
+                         "--tuning=-1,-1,0,512,16 (each -1 = automatic)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
