@@ -107,7 +107,7 @@ class DeviceCase:
 def sweep(args, gs, torch, graphgen, dev):
     """Every workload / width / op of the five configurations; table on stderr."""
     rows = []
-    for name in graphgen.WORKLOAD_NAMES:
+    for name in graphgen.WORKLOAD_NAMES + graphgen.EXTRA_WORKLOAD_NAMES:
         w = graphgen.workload(name, args.scale)
         print(f"# {w.describe()}", file=sys.stderr, flush=True)
         for N in w.widths:

@@ -157,6 +157,8 @@ class Workload:
 
 
 WORKLOAD_NAMES = ("tiny_citation", "width_sweep", "general_ops", "large_dense_degree", "skew_narrow")
+# extra shapes: the uniform random graphs of the paper's Section V-B (Tables V and VI), N = 512
+EXTRA_WORKLOAD_NAMES = ("uniform_random_65k", "uniform_random_262k")
 
 # number of Chung-Lu candidate pairs for "large_dense_degree": hub-hub pairs repeat
 # and are merged, so more than 114.6M/2 candidates are needed to land near 114.6M nnz
@@ -169,9 +171,16 @@ def workload(which, scale: float = 1.0) -> Workload:
     `scale` < 1 shrinks M and the edge budget proportionally (used by CPU tests
     and by quick parity runs); scale == 1 is the full size.
     """
+    s = float(scale)
+    if which in EXTRA_WORKLOAD_NAMES:
+        log2m, draws = (16, 650_000) if which == "uniform_random_65k" else (18, 2_600_000)
+        M = max(8, int(round((1 << log2m) * s)))
+        sc = max(3, int(np.ceil(np.log2(M))))
+        M, K, rp, ci = rmat(M, sc, int(round(draws * s)), seed=10 + log2m, a=0.25, b=0.25, c=0.25)
+        return Workload(which, M, K, rp, ci, uniform_01(ci.shape[0], 10 + log2m), 10 + log2m,
+                        "uniform_pm1", (512,), ("sum", "max"))
     idx = WORKLOAD_NAMES.index(which) if isinstance(which, str) else int(which)
     name = WORKLOAD_NAMES[idx]
-    s = float(scale)
     if idx == 0:
         M = max(8, int(round(2708 * s)))
         e = max(4, int(round(5278 * s)))

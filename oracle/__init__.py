@@ -33,6 +33,13 @@ def _bind(path):
     i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
     L.spmm_oracle.restype = ci
     L.spmm_oracle.argtypes = [i64, i64, i64, vp, vp, vp, vp, ci, vp, i64, vp, vp, ci]
+    i32p = vp
+    L.spmm_oracle_arg.restype = ci
+    L.spmm_oracle_arg.argtypes = [i64, i64, i64, vp, vp, vp, vp, ci, vp, i64, vp, i32p, ci]
+    L.spmm_oracle_transposed.restype = ci
+    L.spmm_oracle_transposed.argtypes = [i64, i64, i64, vp, vp, vp, vp, ci, vp, vp, ci]
+    L.spmm_oracle_pool_backward.restype = ci
+    L.spmm_oracle_pool_backward.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, vp]
     L.spmm_oracle_max_threads.restype = ci
     return L
 
@@ -82,6 +89,80 @@ def spmm(rowptr, colind, vals, B, op, rows=None, threads=0, _lib_override=None):
     if rc != 0:
         raise ValueError("spmm_oracle: bad argument")
     return Cref, Sabs
+
+
+def _csr(rowptr, colind, vals):
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int32)
+    colind = np.ascontiguousarray(colind, dtype=np.int32)
+    if vals is not None:
+        vals = np.ascontiguousarray(vals, dtype=np.float32)
+        assert vals.shape[0] == colind.shape[0]
+    assert int(rowptr[-1]) == colind.shape[0]
+    return rowptr, colind, vals
+
+
+def spmm_arg(rowptr, colind, vals, B, op, rows=None, threads=0, _lib_override=None):
+    """max / min and the position of the extreme: returns (Cref float64, arg int32); arg is the
+    index into colind/vals of the first stored entry that supplies the result, -1 for empty rows."""
+    L = _lib_override or _load()
+    rowptr, colind, vals = _csr(rowptr, colind, vals)
+    B = np.ascontiguousarray(B, dtype=np.float32)
+    M, (K, N) = rowptr.shape[0] - 1, B.shape
+    if colind.size:
+        assert colind.min() >= 0 and colind.max() < K
+    if rows is not None:
+        rows = np.ascontiguousarray(rows, dtype=np.int64)
+        count = rows.shape[0]
+    else:
+        count = M
+    Cref = np.empty((count, N), dtype=np.float64)
+    arg = np.empty((count, N), dtype=np.int32)
+    rc = L.spmm_oracle_arg(M, K, N, rowptr.ctypes.data, colind.ctypes.data,
+                           vals.ctypes.data if vals is not None else None, B.ctypes.data, OPS[op],
+                           rows.ctypes.data if rows is not None else None, count,
+                           Cref.ctypes.data, arg.ctypes.data, int(threads))
+    if rc != 0:
+        raise ValueError("spmm_oracle_arg: bad argument")
+    return Cref, arg
+
+
+def spmm_transposed(rowptr, colind, vals, dC, op, K, threads=0, _lib_override=None):
+    """Gradient of sum / mean w.r.t. B: dB = A^T (x) dC from the CSR of A.  Returns (dBref, Sabs), K x N."""
+    L = _lib_override or _load()
+    rowptr, colind, vals = _csr(rowptr, colind, vals)
+    dC = np.ascontiguousarray(dC, dtype=np.float32)
+    M, N = dC.shape
+    assert M == rowptr.shape[0] - 1
+    if colind.size:
+        assert colind.min() >= 0 and colind.max() < K
+    dB = np.empty((K, N), dtype=np.float64)
+    Sabs = np.empty((K, N), dtype=np.float64)
+    rc = L.spmm_oracle_transposed(M, K, N, rowptr.ctypes.data, colind.ctypes.data,
+                                  vals.ctypes.data if vals is not None else None, dC.ctypes.data,
+                                  OPS[op], dB.ctypes.data, Sabs.ctypes.data, int(threads))
+    if rc != 0:
+        raise ValueError("spmm_oracle_transposed: bad argument")
+    return dB, Sabs
+
+
+def pool_backward(colind, vals, arg, dC, K, _lib_override=None):
+    """Gradient of max / min w.r.t. B, routed through the positions `arg`.  Returns (dBref, Sabs)."""
+    L = _lib_override or _load()
+    colind = np.ascontiguousarray(colind, dtype=np.int32)
+    if vals is not None:
+        vals = np.ascontiguousarray(vals, dtype=np.float32)
+    arg = np.ascontiguousarray(arg, dtype=np.int32)
+    dC = np.ascontiguousarray(dC, dtype=np.float32)
+    M, N = dC.shape
+    assert arg.shape == (M, N) and (arg.size == 0 or (arg.min() >= -1 and arg.max() < colind.shape[0]))
+    dB = np.empty((K, N), dtype=np.float64)
+    Sabs = np.empty((K, N), dtype=np.float64)
+    rc = L.spmm_oracle_pool_backward(M, K, N, colind.ctypes.data,
+                                     vals.ctypes.data if vals is not None else None,
+                                     arg.ctypes.data, dC.ctypes.data, dB.ctypes.data, Sabs.ctypes.data)
+    if rc != 0:
+        raise ValueError("spmm_oracle_pool_backward: bad argument")
+    return dB, Sabs
 
 
 def compare(op, C, Cref, Sabs):

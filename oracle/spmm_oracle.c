@@ -25,6 +25,9 @@
  * result, the oracle returns Sabs = sum_p |vals[p] * B[colind[p], j]| (divided
  * by the row length for mean), the scale of the fp32 error bound.
  *
+ * The same file holds the three gradient-side references (position of the extreme for
+ * max/min, the transposed product for sum/mean, the routed gradient of max/min).
+ *
  * Pins (tests/test_oracle_pins.py): brute-force dense products and explicit
  * per-entry loops on tiny inputs, the identity matrix, an all-ones B, closed
  * forms, scipy's CSR product in float64, a hand-worked example, and a set of
@@ -97,6 +100,114 @@ int spmm_oracle(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const in
   for (int64_t r = 0; r < count; ++r) {
     const int64_t i = rows ? rows[r] : r;
     oracle_row(i, N, rowptr, colind, vals, B, op, Cref + r * N, Sabs + r * N);
+  }
+  return 0;
+}
+
+/*
+ * max / min together with the position of the extreme: arg[i, j] is the index p (into
+ * colind / vals) of the stored entry of row i whose product supplies C[i, j]; among
+ * entries with the very same product it is the first in storage order; -1 for an empty
+ * row.  This is what routes the gradient of a pooling aggregation (the GraphSAGE-pool
+ * use of the SpMM-like operation, Section V-E; the operator has a gradient definition,
+ * Section IV-B).  Same products, same zero rule as above.
+ */
+static void oracle_row_arg(int64_t i, int64_t N, const int32_t* rowptr, const int32_t* colind,
+                           const float* vals, const float* B, int op, double* out_c, int32_t* out_arg) {
+  const int64_t row_start = rowptr[i];
+  const int64_t row_end = rowptr[i + 1];
+  for (int64_t j = 0; j < N; ++j) {
+    double best = 0.0;
+    int64_t where = -1;
+    for (int64_t ptr = row_start; ptr < row_end; ++ptr) {
+      const int64_t k = colind[ptr];
+      const double a = vals ? (double)vals[ptr] : 1.0;
+      const double x = a * (double)B[k * N + j];
+      int better;
+      if (where < 0) better = 1;
+      else if (op == OP_MAX) better = x > best || (x == best && signbit(best) && !signbit(x));
+      else better = x < best || (x == best && !signbit(best) && signbit(x));
+      if (better) {
+        best = x;
+        where = ptr;
+      }
+    }
+    out_c[j] = best;
+    out_arg[j] = (int32_t)where;
+  }
+}
+
+int spmm_oracle_arg(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colind,
+                    const float* vals, const float* B, int op, const int64_t* rows, int64_t nrows,
+                    double* Cref, int32_t* arg, int threads) {
+  if (M < 0 || K < 0 || N < 0 || (op != OP_MAX && op != OP_MIN)) return -1;
+  if (!rowptr || !Cref || !arg) return -1;
+  const int64_t count = rows ? nrows : M;
+  const int nt = threads > 0 ? threads : omp_get_max_threads();
+#pragma omp parallel for schedule(dynamic, 256) num_threads(nt)
+  for (int64_t r = 0; r < count; ++r) {
+    const int64_t i = rows ? rows[r] : r;
+    oracle_row_arg(i, N, rowptr, colind, vals, B, op, Cref + r * N, arg + r * N);
+  }
+  return 0;
+}
+
+/*
+ * Gradient of sum / mean with respect to B, i.e. the product with the transposed sparse
+ * matrix taken from the same CSR arrays (the backward pass of a graph convolution is again
+ * an SpMM, Section I; gradient definition of the operator, Section IV-B):
+ *     dB[k, j] = sum over stored entries p with colind[p] == k of  w_p * dC[row(p), j],
+ *     w_p = vals[p] for sum, vals[p] / (stored length of row(p)) for mean.
+ * Sabs[k, j] is the same sum over |w_p * dC|.  Columns j are independent, so the threads
+ * split the columns; every thread walks all entries in storage order.
+ */
+int spmm_oracle_transposed(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colind,
+                           const float* vals, const float* dC, int op, double* dBref, double* Sabs,
+                           int threads) {
+  if (M < 0 || K < 0 || N < 0 || (op != OP_SUM && op != OP_MEAN)) return -1;
+  if (!rowptr || !dBref || !Sabs) return -1;
+  const int nt = threads > 0 ? threads : omp_get_max_threads();
+#pragma omp parallel for schedule(static) num_threads(nt)
+  for (int64_t j = 0; j < N; ++j) {
+    for (int64_t k = 0; k < K; ++k) {
+      dBref[k * N + j] = 0.0;
+      Sabs[k * N + j] = 0.0;
+    }
+    for (int64_t i = 0; i < M; ++i) {
+      const int64_t len = rowptr[i + 1] - rowptr[i];
+      for (int64_t ptr = rowptr[i]; ptr < rowptr[i + 1]; ++ptr) {
+        const int64_t k = colind[ptr];
+        double w = vals ? (double)vals[ptr] : 1.0;
+        if (op == OP_MEAN) w /= (double)len;
+        const double x = w * (double)dC[i * N + j];
+        dBref[k * N + j] += x;
+        Sabs[k * N + j] += fabs(x);
+      }
+    }
+  }
+  return 0;
+}
+
+/*
+ * Gradient of max / min with respect to B, given the positions arg from the forward pass:
+ *     dB[colind[arg[i, j]], j] += vals[arg[i, j]] * dC[i, j]     for every (i, j) with arg >= 0.
+ */
+int spmm_oracle_pool_backward(int64_t M, int64_t K, int64_t N, const int32_t* colind, const float* vals,
+                              const int32_t* arg, const float* dC, double* dBref, double* Sabs) {
+  if (M < 0 || K < 0 || N < 0 || !arg || !dBref || !Sabs) return -1;
+  for (int64_t e = 0; e < K * N; ++e) {
+    dBref[e] = 0.0;
+    Sabs[e] = 0.0;
+  }
+  for (int64_t i = 0; i < M; ++i) {
+    for (int64_t j = 0; j < N; ++j) {
+      const int64_t ptr = arg[i * N + j];
+      if (ptr < 0) continue;
+      const int64_t k = colind[ptr];
+      const double x = (vals ? (double)vals[ptr] : 1.0) * (double)dC[i * N + j];
+      dBref[k * N + j] += x;
+      Sabs[k * N + j] += fabs(x);
+    }
   }
   return 0;
 }

@@ -514,6 +514,7 @@ int gespmm_csr(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowp
   const int fold = op == GESPMM_MAX ? kMax : (op == GESPMM_MIN ? kMin : kAdd);
   MainKernel kernel = pick_kernel(fold, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
   if (!kernel) return GESPMM_ERR_BAD_ARG;
+  if (plan.col_blocks > 65535) return GESPMM_ERR_TOO_LARGE;   // grid.y limit (N beyond ~33 million)
 
   // (a) empty rows -> 0, rows shared by several chunks -> reduce identity
   float identity = 0.0f;

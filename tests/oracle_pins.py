@@ -258,3 +258,147 @@ def pin_invariants(spmm):
 PINS = (pin_brute_force_tiny, pin_dense_matmul, pin_identity, pin_all_ones_B,
         pin_closed_form_long_row, pin_negative_rows_and_signed_zero, pin_hand_worked,
         pin_scipy_float64, pin_invariants)
+
+
+# ------------------------------------------------ gradient-side pins -------
+# These take the oracle module (or an object with the same functions):
+#   O.spmm, O.spmm_arg, O.spmm_transposed, O.pool_backward
+def _brute_arg(rowptr, colind, vals, B, op):
+    M, N = len(rowptr) - 1, B.shape[1]
+    C = np.zeros((M, N))
+    arg = np.full((M, N), -1, dtype=np.int32)
+    for i in range(M):
+        for j in range(N):
+            best, where = 0.0, -1
+            for p in range(rowptr[i], rowptr[i + 1]):
+                x = (float(vals[p]) if vals is not None else 1.0) * float(B[colind[p], j])
+                key_x = (x, math.copysign(1.0, x))          # value, then +0 above -0
+                key_b = (best, math.copysign(1.0, best))
+                if where < 0 or (key_x > key_b if op == "max" else key_x < key_b):
+                    best, where = x, p
+            C[i, j], arg[i, j] = best, where
+    return C, arg
+
+
+def pin_arg_brute_force_with_ties(O):
+    """Position of the extreme: per-entry Python scan; ties must go to the first stored entry."""
+    rp, ci, v = graphgen.random_csr(30, 12, 5.0, 61, empty_frac=0.2, duplicates=True, sort_cols=False)
+    B = np.round(graphgen.random_dense(12, 4, 61) * 3.0).astype(np.float32)      # few distinct values: ties
+    v = np.round(v * 2.0).astype(np.float32)
+    v[v == 0] = 1.0
+    B[3] = 0.0
+    B[4] = -0.0
+    for op in ("max", "min"):
+        for vv in (v, None):
+            want_c, want_a = _brute_arg(rp, ci, vv, B, op)
+            got_c, got_a = O.spmm_arg(rp, ci, vv, B, op)
+            _same_bits(got_c, want_c)
+            assert np.array_equal(got_a, want_a)
+            ties = 0
+            for i in range(30):
+                for j in range(4):
+                    prods = [(float(vv[p]) if vv is not None else 1.0) * float(B[ci[p], j]) for p in range(rp[i], rp[i + 1])]
+                    ties += prods.count(want_c[i, j]) > 1
+            assert ties > 5, "the case must contain ties to mean anything"
+    rows = np.array([7, 0, 29], dtype=np.int64)
+    full_c, full_a = O.spmm_arg(rp, ci, v, B, "max")
+    sub_c, sub_a = O.spmm_arg(rp, ci, v, B, "max", rows=rows)
+    _same_bits(sub_c, full_c[rows])
+    assert np.array_equal(sub_a, full_a[rows])
+
+
+def pin_arg_consistent_with_forward(O):
+    """The value at the reported position is the forward result, and the position lies in the row."""
+    w = graphgen.workload(2, 0.01)
+    B = w.B(5)
+    vals = graphgen.uniform_pm1(w.nnz, 77)
+    for op in ("max", "min"):
+        c_fwd, _ = O.spmm(w.rowptr, w.colind, vals, B, op)
+        c, a = O.spmm_arg(w.rowptr, w.colind, vals, B, op)
+        _same_bits(c, c_fwd)
+        lens = np.diff(w.rowptr)
+        assert np.all(a[lens == 0] == -1) and np.all(a[lens > 0] >= 0)
+        i, j = np.nonzero(a >= 0)
+        p = a[i, j]
+        assert np.all(p >= w.rowptr[i]) and np.all(p < w.rowptr[i + 1])
+        _same_bits(vals[p].astype(np.float64) * B[w.colind[p], j].astype(np.float64), c[i, j])
+
+
+def pin_transposed_dense_and_scipy(O):
+    """dB = A^T dC against the float64 dense product and scipy; mean scales each row by 1/len."""
+    rp, ci, v = graphgen.random_csr(33, 29, 5.0, 71, empty_frac=0.15, duplicates=True, sort_cols=False)
+    dC = graphgen.random_dense(33, 6, 72)
+    rows = np.repeat(np.arange(33), np.diff(rp))
+    lens = np.diff(rp).astype(np.float64)
+    for op in ("sum", "mean"):
+        for vv in (v, None):
+            wts = (vv.astype(np.float64) if vv is not None else np.ones(len(ci)))
+            if op == "mean":
+                wts = wts / lens[rows]
+            A = np.zeros((33, 29)); Aabs = np.zeros((33, 29))
+            np.add.at(A, (rows, ci), wts)
+            np.add.at(Aabs, (rows, ci), np.abs(wts))
+            want = A.T @ dC.astype(np.float64)
+            want_s = Aabs.T @ np.abs(dC.astype(np.float64))
+            got, got_s = O.spmm_transposed(rp, ci, vv, dC, op, 29)
+            _close(got, want, scale=want_s + 1e-30)
+            _close(got_s, want_s)
+    w = graphgen.workload(2, 0.02)
+    dC = w.B(4)[: w.M]
+    A = sp.csr_matrix((w.vals.astype(np.float64), w.colind, w.rowptr), shape=(w.M, w.K))
+    got, got_s = O.spmm_transposed(w.rowptr, w.colind, w.vals, dC, "sum", w.K)
+    _close(got, A.T @ dC.astype(np.float64), scale=got_s + 1e-30)
+
+
+def pin_transposed_is_the_adjoint(O):
+    """<A (x) B, dC> == <B, A^T (x) dC> for sum and for mean."""
+    rp, ci, v = graphgen.random_csr(41, 37, 6.0, 81, empty_frac=0.1)
+    B = graphgen.random_dense(37, 5, 81)
+    dC = graphgen.random_dense(41, 5, 82)
+    for op in ("sum", "mean"):
+        C, S = O.spmm(rp, ci, v, B, op)
+        dB, _ = O.spmm_transposed(rp, ci, v, dC, op, 37)
+        lhs = float(np.sum(C * dC.astype(np.float64)))
+        rhs = float(np.sum(B.astype(np.float64) * dB))
+        assert abs(lhs - rhs) <= 1e-12 * float(np.sum(S * np.abs(dC))), (lhs, rhs)
+
+
+def pin_pool_backward_numeric_gradient(O):
+    """Routed gradient of max/min equals central differences of f(B) = sum(C(B) * dC) (piecewise linear)."""
+    rng = np.random.default_rng(5)
+    M, K, N = 9, 7, 3
+    rp, ci, _ = graphgen.random_csr(M, K, 3.0, 91, empty_frac=0.2)
+    v = rng.choice(np.array([1.0, -1.0, 2.0], dtype=np.float32), size=len(ci))
+    dC = rng.integers(-4, 5, size=(M, N)).astype(np.float32)
+    # integer-valued B with well separated products, so that +-h never changes which entry wins
+    B = (rng.permutation(K * N).reshape(K, N) * 16 - 150).astype(np.float32)
+    h = 0.25
+    for op in ("max", "min"):
+        C, arg = O.spmm_arg(rp, ci, v, B, op)
+        for i in range(M):                                   # the margins the argument needs
+            for j in range(N):
+                prods = sorted(float(v[p]) * float(B[ci[p], j]) for p in range(rp[i], rp[i + 1]))
+                assert all(b - a >= 4 for a, b in zip(prods, prods[1:]))
+        dB, dS = O.pool_backward(ci, v, arg, dC, K)
+
+        def f(Bx):
+            c, _ = O.spmm(rp, ci, v, Bx, op)
+            return float(np.sum(c * dC.astype(np.float64)))
+        for k in range(K):
+            for j in range(N):
+                Bp, Bm = B.copy(), B.copy()
+                Bp[k, j] += h
+                Bm[k, j] -= h
+                num = (f(Bp) - f(Bm)) / (2 * h)
+                assert num == dB[k, j], (op, k, j, num, dB[k, j])
+        assert np.all(dS >= np.abs(dB))
+    # entry 0 is a legitimate position; -1 routes nothing
+    arg = np.array([[0, -1]], dtype=np.int32)
+    dB, _ = O.pool_backward(np.array([2], np.int32), np.array([3.0], np.float32), arg,
+                            np.array([[5.0, 7.0]], np.float32), 4)
+    want = np.zeros((4, 2)); want[2, 0] = 15.0
+    _same_bits(dB, want)
+
+
+GRAD_PINS = (pin_arg_brute_force_with_ties, pin_arg_consistent_with_forward, pin_transposed_dense_and_scipy,
+             pin_transposed_is_the_adjoint, pin_pool_backward_numeric_gradient)

@@ -94,3 +94,11 @@ def test_random_csr_is_valid(kw):
     assert (np.diff(rp) >= 0).all() and ci.min() >= 0 and ci.max() < 700
     if "long_rows" in kw:
         assert rp[4] - rp[3] == 500
+
+
+def test_uniform_random_extra_workload():
+    w = graphgen.workload("uniform_random_65k")
+    _check_csr(w.M, w.K, w.rowptr, w.colind)
+    lens = np.diff(w.rowptr)
+    assert w.M == 65536 and abs(w.nnz - 650_000) < 5_000
+    assert lens.max() < 40 and abs(lens.mean() - 9.9) < 0.2       # no skew

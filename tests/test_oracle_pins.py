@@ -5,7 +5,7 @@ import re
 import pytest
 
 import oracle
-from oracle_pins import PINS
+from oracle_pins import GRAD_PINS, PINS
 
 ORACLE_SRC = os.path.join(os.path.dirname(os.path.abspath(oracle.__file__)), "spmm_oracle.c")
 
@@ -13,6 +13,11 @@ ORACLE_SRC = os.path.join(os.path.dirname(os.path.abspath(oracle.__file__)), "sp
 @pytest.mark.parametrize("pin", PINS, ids=lambda p: p.__name__)
 def test_oracle_passes_pin(pin):
     pin(oracle.spmm)
+
+
+@pytest.mark.parametrize("pin", GRAD_PINS, ids=lambda p: p.__name__)
+def test_gradient_side_oracle_passes_pin(pin):
+    pin(oracle)
 
 
 # One plausible single mistake each (dropped term, wrong sign, wrong index, flipped operand,
@@ -39,25 +44,66 @@ MUTANTS = [
      "const double x = (double)((float)a * B[k * N + j]);"),
     ("row_subset_ignored", "rows ? rows[r] : r;", "r;"),
     ("next_row_start_as_end", "const int64_t row_end = rowptr[i + 1];",
-     "const int64_t row_end = rowptr[i + 1] - (rowptr[i + 1] - rowptr[i] > 2);"),
+     "const int64_t row_end = rowptr[i + 1] - (rowptr[i + 1] - rowptr[i] > 2);", 0),
+    # gradient-side functions
+    ("arg_tie_goes_to_last", "better = x > best ||", "better = x >= best ||"),
+    ("arg_min_tie_goes_to_last", "else better = x < best ||", "else better = x <= best ||"),
+    ("arg_relative_to_row", "out_arg[j] = (int32_t)where;", "out_arg[j] = (int32_t)(where < 0 ? where : where - row_start);"),
+    ("arg_zero_rule_dropped", "(x == best && signbit(best) && !signbit(x))", "0"),
+    ("transposed_mean_multiplies", "if (op == OP_MEAN) w /= (double)len;", "if (op == OP_MEAN) w *= (double)len;"),
+    ("transposed_not_transposed", "dBref[k * N + j] += x;", "dBref[(k < M ? i % K : k) * N + j] += x;", 0),
+    ("transposed_sabs_signed", "Sabs[k * N + j] += fabs(x);", "Sabs[k * N + j] += x;", 0),
+    ("pool_skips_entry_zero", "if (ptr < 0) continue;", "if (ptr <= 0) continue;"),
+    ("pool_forgets_the_weight", "const double x = (vals ? (double)vals[ptr] : 1.0) * (double)dC[i * N + j];",
+     "const double x = (double)dC[i * N + j];"),
+    ("pool_adds_to_the_row_index", "dBref[k * N + j] += x;", "dBref[(i % K) * N + j] += x;", 1),
+    ("arg_drop_last_term", "ptr < row_end; ++ptr", "ptr < row_end - 1; ++ptr", 1),
+    ("arg_column_of_B_flipped", "B[k * N + j]", "B[k * N + (N - 1 - j)]", 1),
+    ("arg_null_vals_as_zero", ": 1.0;", ": 0.0;", 1),
 ]
+MUTANTS = [m if len(m) == 4 else (*m, None) for m in MUTANTS]
 
 
-@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
-def test_pins_reject_planted_mistake(tmp_path, name, old, new):
+class _Mutant:
+    """The oracle's Python face bound to a mutated library."""
+
+    def __init__(self, lib):
+        self.lib = lib
+
+    def spmm(self, rowptr, colind, vals, B, op, rows=None):
+        return oracle.spmm(rowptr, colind, vals, B, op, rows=rows, _lib_override=self.lib)
+
+    def spmm_arg(self, rowptr, colind, vals, B, op, rows=None):
+        return oracle.spmm_arg(rowptr, colind, vals, B, op, rows=rows, _lib_override=self.lib)
+
+    def spmm_transposed(self, rowptr, colind, vals, dC, op, K):
+        return oracle.spmm_transposed(rowptr, colind, vals, dC, op, K, _lib_override=self.lib)
+
+    def pool_backward(self, colind, vals, arg, dC, K):
+        return oracle.pool_backward(colind, vals, arg, dC, K, _lib_override=self.lib)
+
+
+@pytest.mark.parametrize("name,old,new,which", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_pins_reject_planted_mistake(tmp_path, name, old, new, which):
     src = open(ORACLE_SRC).read()
-    assert src.count(old) == 1, f"mutation site for {name} must occur exactly once"
+    which = which or 0                      # occurrence to change (0-based); the forward function comes first
+    parts = src.split(old)
+    assert len(parts) > which + 1, f"mutation site {which} for {name} not found"
+    mutated_src = old.join(parts[: which + 1]) + new + old.join(parts[which + 1:])
+    assert mutated_src != src
     mutated = tmp_path / f"oracle_{name}.c"
-    mutated.write_text(src.replace(old, new))
-    lib = oracle._bind(oracle.build(force=True, src=str(mutated), lib=str(tmp_path / f"lib_{name}.so")))
-
-    def mutant(rowptr, colind, vals, B, op, rows=None):
-        return oracle.spmm(rowptr, colind, vals, B, op, rows=rows, _lib_override=lib)
+    mutated.write_text(mutated_src)
+    m = _Mutant(oracle._bind(oracle.build(force=True, src=str(mutated), lib=str(tmp_path / f"lib_{name}.so"))))
 
     rejected = []
     for pin in PINS:
         try:
-            pin(mutant)
+            pin(m.spmm)
+        except AssertionError:
+            rejected.append(pin.__name__)
+    for pin in GRAD_PINS:
+        try:
+            pin(m)
         except AssertionError:
             rejected.append(pin.__name__)
     assert rejected, f"no pin noticed the planted mistake '{name}'"
