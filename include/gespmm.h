@@ -80,6 +80,51 @@ int gespmm_csr_simple(int64_t M, int64_t K, int64_t N, const int32_t* rowptr,
                       void* stream);
 
 /*
+ * max or min together with the POSITION of the extreme: what a pooling aggregation
+ * (the GraphSAGE-pool use of the SpMM-like operation, Section V-E) needs in order to
+ * route its gradient (the operator carries a gradient definition, Section IV-B).
+ * Arguments as gespmm_csr, op must be GESPMM_MAX or GESPMM_MIN, plus
+ *   arg   device, int32[M*N], row-major like C; overwritten.  arg[i*N+j] is the index p
+ *         into colind / vals of the stored entry of row i whose product vals[p] *
+ *         B[colind[p], j] has exactly the bits of C[i, j]; if several entries do, the
+ *         smallest p (first in storage order); -1 for an empty row.
+ * Runs gespmm_csr and then one more pass over the matrix (about twice the time).
+ * For the vector kernels arg must be 16-byte aligned as well.  Same errors as gespmm_csr;
+ * GESPMM_ERR_BAD_ARG for any other op; GESPMM_ERR_NULL for arg == NULL.
+ */
+int gespmm_csr_arg(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                   const int32_t* colind, const float* vals, const float* B, float* C, int32_t* arg,
+                   int op, void* stream);
+
+/*
+ * Gradient of sum / mean with respect to B (the backward pass of a graph convolution is
+ * again an SpMM, Section I; gradient definition, Section IV-B), taken from the SAME CSR
+ * arrays, without a transposed copy of A:
+ *     dB[k, j] = sum over stored entries p with colind[p] == k of  w_p * dC[row(p), j],
+ *     w_p = vals[p] (GESPMM_SUM) or vals[p] / (stored length of row(p)) (GESPMM_MEAN).
+ *   dC   device, fp32[M*N], row-major;  dB  device, fp32[K*N], row-major, overwritten
+ *   (zero-filled by the call, then accumulated with fp32 atomic adds: the last bits can
+ *   differ from run to run).  K == 0 or N == 0 returns at once; op other than SUM / MEAN
+ *   is GESPMM_ERR_BAD_ARG.  For a symmetric A with symmetric values this equals
+ *   gespmm_csr(A, dC), which is the faster way to get it.
+ */
+int gespmm_csr_transposed(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                          const int32_t* colind, const float* vals, const float* dC, float* dB, int op,
+                          void* stream);
+
+/*
+ * Gradient of max / min with respect to B, routed through the positions from
+ * gespmm_csr_arg (Sections IV-B, V-E):
+ *     dB[colind[p], j] += vals[p] * dC[i, j]   with p = arg[i*N+j], for every p >= 0.
+ *   colind, vals (NULL = all ones) as in the forward call; arg int32[M*N]; dC fp32[M*N];
+ *   dB fp32[K*N], overwritten (zero-filled, then fp32 atomic adds).  arg values must be
+ *   -1 or valid entry indices (not validated).
+ */
+int gespmm_pool_backward(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* colind,
+                         const float* vals, const int32_t* arg, const float* dC, float* dB,
+                         void* stream);
+
+/*
  * The kernel selection of Section IV-A ("GE-SpMM for different matrix sizes"),
  * redone for 64-lane wavefronts: pure host function, touches no device.
  * Fills the launch shape gespmm_csr would use for these sizes.

@@ -49,6 +49,12 @@ def lib():
         L.gespmm_csr.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, ci, vp]
         L.gespmm_csr_simple.restype = ci
         L.gespmm_csr_simple.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, ci, vp]
+        L.gespmm_csr_arg.restype = ci
+        L.gespmm_csr_arg.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, vp, ci, vp]
+        L.gespmm_csr_transposed.restype = ci
+        L.gespmm_csr_transposed.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, ci, vp]
+        L.gespmm_pool_backward.restype = ci
+        L.gespmm_pool_backward.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, vp]
         L.gespmm_plan.restype = ci
         L.gespmm_plan.argtypes = [i64, i64, i64, ci, ctypes.POINTER(gespmm_plan_t)]
         L.gespmm_set_tuning.restype = ci
@@ -124,6 +130,53 @@ def gespmm_csr_simple(rowptr, colind, vals, B, op, C=None, stream=None):
     _check(lib().gespmm_csr_simple(M, K, N, _ptr(rowptr), _ptr(colind), _ptr(vals), _ptr(B),
                                    _ptr(C), code, _stream(stream)))
     return C
+
+
+def gespmm_csr_arg(rowptr, colind, vals, B, op, C=None, arg=None, stream=None):
+    """max / min and the position of the extreme; returns (C, arg) with arg int32 (M, N)."""
+    import torch
+    M, (K, N) = rowptr.numel() - 1, B.shape
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.float32, device=B.device)
+    if arg is None:
+        arg = torch.empty((M, N), dtype=torch.int32, device=B.device)
+    _check_tensors(rowptr, colind, vals, B, C)
+    assert arg.is_cuda and arg.dtype == torch.int32 and arg.is_contiguous() and arg.shape == C.shape
+    code = OPS[op] if isinstance(op, str) else int(op)
+    _check(lib().gespmm_csr_arg(M, K, N, colind.numel(), _ptr(rowptr), _ptr(colind), _ptr(vals),
+                                _ptr(B), _ptr(C), _ptr(arg), code, _stream(stream)))
+    return C, arg
+
+
+def gespmm_csr_transposed(rowptr, colind, vals, dC, op, K, dB=None, stream=None):
+    """Gradient of sum / mean w.r.t. B from the CSR of A: dB = A^T (x) dC, shape (K, N)."""
+    import torch
+    M, N = dC.shape
+    assert rowptr.numel() - 1 == M
+    if dB is None:
+        dB = torch.empty((K, N), dtype=torch.float32, device=dC.device)
+    _check_tensors(rowptr, colind, vals, dC, dC)          # CSR arrays and dC as (M, N)
+    assert dB.is_cuda and dB.dtype == torch.float32 and dB.is_contiguous() and dB.shape == (K, N)
+    code = OPS[op] if isinstance(op, str) else int(op)
+    _check(lib().gespmm_csr_transposed(M, K, N, colind.numel(), _ptr(rowptr), _ptr(colind), _ptr(vals),
+                                       _ptr(dC), _ptr(dB), code, _stream(stream)))
+    return dB
+
+
+def gespmm_pool_backward(colind, vals, arg, dC, K, dB=None, stream=None):
+    """Gradient of max / min w.r.t. B routed through the positions `arg`; shape (K, N)."""
+    import torch
+    M, N = dC.shape
+    if dB is None:
+        dB = torch.empty((K, N), dtype=torch.float32, device=dC.device)
+    assert arg.is_cuda and arg.dtype == torch.int32 and arg.is_contiguous() and arg.shape == dC.shape
+    assert dC.is_cuda and dC.dtype == torch.float32 and dC.is_contiguous()
+    assert dB.is_cuda and dB.dtype == torch.float32 and dB.is_contiguous() and dB.shape == (K, N)
+    assert colind.is_cuda and colind.dtype == torch.int32 and colind.is_contiguous()
+    assert vals is None or (vals.is_cuda and vals.dtype == torch.float32 and vals.numel() == colind.numel())
+    _check(lib().gespmm_pool_backward(M, K, N, colind.numel(), _ptr(colind), _ptr(vals), _ptr(arg),
+                                      _ptr(dC), _ptr(dB), _stream(stream)))
+    return dB
 
 
 def gespmm_plan(M, N, nnz, aligned16=True) -> dict:

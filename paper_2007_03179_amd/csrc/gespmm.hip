@@ -58,8 +58,10 @@ struct KernelArgs {
   const int32_t* rowptr;
   const int32_t* colind;
   const float* vals;
-  const float* B;
-  float* C;
+  const float* B;         // dense input (the gradient dC for the transposed job)
+  float* C;               // dense output (dB for the transposed job)
+  const float* Cin;       // finished max/min result, read by the position job
+  int32_t* arg;           // output of the position job
 };
 
 // ------------------------------------------------------------------ vectors --
@@ -121,12 +123,13 @@ __device__ __forceinline__ int64_t logical_block(int64_t b, int64_t nb, int rema
 
 // ------------------------------------------------------------- init kernel --
 // One lane per row decides; then groups of 2^lanes_shift lanes write one row each:
-// empty rows get zeros; rows whose entries lie in more than one chunk get the reduce
-// identity (they are completed by atomics in the main kernel).
+// empty rows get `empty_value` (0 for the result, the bits of -1 for positions); rows whose
+// entries lie in more than one chunk get `split_value` (the reduce identity, or the bits
+// of INT_MAX for positions): they are completed by atomics in the chunk kernel.
 template <int V>
 __global__ void __launch_bounds__(kBlock) init_rows(int32_t M, int32_t N, const int32_t* __restrict__ rowptr,
-                                                   float* __restrict__ C, float identity, int chunk_shift,
-                                                   int lanes_shift) {
+                                                   float* __restrict__ C, float empty_value, float split_value,
+                                                   int chunk_shift, int lanes_shift) {
   const int lane = threadIdx.x & (kWave - 1);
   const int64_t base = ((int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)) * kWave;
   if (base >= M) return;
@@ -151,7 +154,7 @@ __global__ void __launch_bounds__(kBlock) init_rows(int32_t M, int32_t N, const 
       float* row = C + (base + j + sub) * (int64_t)N;
       Vec<V> out;
 #pragma unroll
-      for (int x = 0; x < V; ++x) out.v[x] = f == 1 ? 0.0f : identity;
+      for (int x = 0; x < V; ++x) out.v[x] = f == 1 ? empty_value : split_value;
       for (int c = c0; c < N; c += lanes * V) out.store(row + c);
     }
   }
@@ -165,62 +168,17 @@ __global__ void __launch_bounds__(kBlock) copy_f4(const float4* __restrict__ src
   for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += stride) dst[i] = src[i];
 }
 
-// ------------------------------------------------------------- main kernel --
-// F: fold; V: floats per lane per load; G: lanes per slot; T: column tiles per lane.
-//
-// One pass over `U` entries of one row segment for the column tiles of this lane.
-// `first` is the LDS index of the lane's first entry of the pass, `stride` the distance
-// to its next one, `left` how many of the U entries exist (<= 0: none).  An entry that
-// does not exist re-reads the previous one: harmless for max/min (idempotent) and given
-// weight 0 for the sum, so the pass is straight-line code with all gathers issued first.
-template <int F, int V, int T, int U>
-__device__ __forceinline__ void gather_pass(Vec<V> (&acc)[T], const int2* ka, int first, int stride, int left,
-                                            const float* __restrict__ B, int N, const int (&colc)[T]) {
-  int2 e2[U];
-  Vec<V> b[U][T];
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const int uu = u < left ? u : (left > 0 ? left - 1 : 0);
-    e2[u] = ka[first + uu * stride];
-    if (F == kAdd && u >= left) e2[u].y = 0;
-  }
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    const float* brow = B + (int64_t)e2[u].x * N;
-#pragma unroll
-    for (int t = 0; t < T; ++t) b[u][t] = Vec<V>::load(brow + colc[t]);
-  }
-#pragma unroll
-  for (int u = 0; u < U; ++u)
-#pragma unroll
-    for (int t = 0; t < T; ++t)
-#pragma unroll
-      for (int x = 0; x < V; ++x) acc[t].v[x] = fold<F>(acc[t].v[x], __int_as_float(e2[u].y), b[u][t].v[x]);
-}
-
-// Write one finished row segment: plain store when the whole row lay in this chunk,
-// atomics otherwise (the row was preset to the identity by init_rows).
-template <int F, int V, int T>
-__device__ __forceinline__ void emit(Vec<V> (&acc)[T], float* crow, const int (&col)[T], int N, bool whole,
-                                     int row_len, int is_mean) {
-  const float len = (float)row_len;
-#pragma unroll
-  for (int t = 0; t < T; ++t) {
-    if (col[t] < N) {
-      if (whole) {
-        if (is_mean) {
-#pragma unroll
-          for (int x = 0; x < V; ++x) acc[t].v[x] = acc[t].v[x] / len;
-        }
-        acc[t].store(crow + col[t]);
-      } else {
-        const float w = is_mean ? 1.0f / len : 1.0f;
-#pragma unroll
-        for (int x = 0; x < V; ++x) atomic_fold<F>(crow + col[t] + x, F == kAdd ? acc[t].v[x] * w : acc[t].v[x]);
-      }
-    }
-  }
-}
+// ------------------------------------------------------------ chunk kernel --
+// The walk over chunks, rows and row segments is the same for three jobs; what is done
+// with a row segment is a policy:
+//   FoldRows        the SpMM-like operation itself            C = A (x) B
+//   ArgRows         position of the extreme for max / min     arg[i,j] = first entry that gives C[i,j]
+//   TransposedRows  gradient of sum / mean w.r.t. B           dB += A^T (x) dC, by scatter-add
+// A policy has a per-row State and four steps: begin (per row), pass (U entries of the
+// segment for the lane's column tiles), combine (fold the slots that shared a long row),
+// end (write the row).  In `pass`, `first` is the LDS index of the lane's first entry,
+// `stride` the distance to its next one, `left` how many of the U entries exist (<= 0:
+// none); `first` itself always is a valid index.
 
 __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -228,8 +186,205 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int F, int V, int G, int T>
-__global__ void __launch_bounds__(kBlock) spmm_chunks(const KernelArgs a) {
+template <int F, int V, int T>
+struct FoldRows {
+  struct State { Vec<V> acc[T]; };
+
+  __device__ static void begin(State& s, const KernelArgs&, int64_t, int, const int (&)[T]) {
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+#pragma unroll
+      for (int x = 0; x < V; ++x) s.acc[t].v[x] = fold_identity<F>();
+  }
+
+  // An entry that does not exist re-reads the last one that does: harmless for max/min
+  // (idempotent) and given weight 0 for the sum, so the pass is straight-line code with
+  // all gathers issued before the first use.
+  template <int U>
+  __device__ static void pass(State& s, const KernelArgs& a, const int2* ka, int, int first, int stride, int left,
+                              const int (&)[T], const int (&colc)[T]) {
+    int2 e2[U];
+    Vec<V> b[U][T];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int uu = u < left ? u : (left > 0 ? left - 1 : 0);
+      e2[u] = ka[first + uu * stride];
+      if (F == kAdd && u >= left) e2[u].y = 0;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float* brow = a.B + (int64_t)e2[u].x * a.N;
+#pragma unroll
+      for (int t = 0; t < T; ++t) b[u][t] = Vec<V>::load(brow + colc[t]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int x = 0; x < V; ++x) s.acc[t].v[x] = fold<F>(s.acc[t].v[x], __int_as_float(e2[u].y), b[u][t].v[x]);
+  }
+
+  template <int G>
+  __device__ static void combine(State& s) {
+#pragma unroll
+    for (int off = G; off < kWave; off <<= 1)
+#pragma unroll
+      for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int x = 0; x < V; ++x) s.acc[t].v[x] = fold2<F>(s.acc[t].v[x], __shfl_xor(s.acc[t].v[x], off, kWave));
+  }
+
+  // Plain store when the whole row lay in this chunk, atomics otherwise (the row was
+  // preset to the identity by init_rows).
+  __device__ static void end(State& s, const KernelArgs& a, int64_t row, bool whole, int row_len, const int (&col)[T]) {
+    float* crow = a.C + row * (int64_t)a.N;
+    const float len = (float)row_len;
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+      if (col[t] < a.N) {
+        if (whole) {
+          if (a.is_mean) {
+#pragma unroll
+            for (int x = 0; x < V; ++x) s.acc[t].v[x] = s.acc[t].v[x] / len;
+          }
+          s.acc[t].store(crow + col[t]);
+        } else {
+          const float w = a.is_mean ? 1.0f / len : 1.0f;
+#pragma unroll
+          for (int x = 0; x < V; ++x) atomic_fold<F>(crow + col[t] + x, F == kAdd ? s.acc[t].v[x] * w : s.acc[t].v[x]);
+        }
+      }
+    }
+  }
+};
+
+// Position of the extreme (run after the max / min result C is complete): an entry whose
+// product has exactly the bits of C[i, j] is a candidate; the smallest entry index wins,
+// i.e. the first in storage order.  Rows inside one chunk are stored, split rows are
+// combined with an integer atomic min on a row preset to INT_MAX.
+template <int V, int T>
+struct ArgRows {
+  struct State { int best[T][V]; int want[T][V]; };
+
+  __device__ static void begin(State& s, const KernelArgs& a, int64_t row, int, const int (&colc)[T]) {
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+      const Vec<V> c = Vec<V>::load(a.Cin + row * (int64_t)a.N + colc[t]);
+#pragma unroll
+      for (int x = 0; x < V; ++x) {
+        s.want[t][x] = __float_as_int(c.v[x]);
+        s.best[t][x] = INT32_MAX;
+      }
+    }
+  }
+
+  template <int U>
+  __device__ static void pass(State& s, const KernelArgs& a, const int2* ka, int cs, int first, int stride, int left,
+                              const int (&)[T], const int (&colc)[T]) {
+    int2 e2[U];
+    int where[U];
+    Vec<V> b[U][T];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {          // a missing entry repeats an existing one: same index, harmless
+      const int uu = u < left ? u : (left > 0 ? left - 1 : 0);
+      e2[u] = ka[first + uu * stride];
+      where[u] = cs + first + uu * stride;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float* brow = a.B + (int64_t)e2[u].x * a.N;
+#pragma unroll
+      for (int t = 0; t < T; ++t) b[u][t] = Vec<V>::load(brow + colc[t]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int x = 0; x < V; ++x) {
+          const float prod = __int_as_float(e2[u].y) * b[u][t].v[x];
+          if (__float_as_int(prod) == s.want[t][x] && where[u] < s.best[t][x]) s.best[t][x] = where[u];
+        }
+  }
+
+  template <int G>
+  __device__ static void combine(State& s) {
+#pragma unroll
+    for (int off = G; off < kWave; off <<= 1)
+#pragma unroll
+      for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int x = 0; x < V; ++x) {
+          const int other = __shfl_xor(s.best[t][x], off, kWave);
+          s.best[t][x] = other < s.best[t][x] ? other : s.best[t][x];
+        }
+  }
+
+  __device__ static void end(State& s, const KernelArgs& a, int64_t row, bool whole, int, const int (&col)[T]) {
+    int32_t* arow = a.arg + row * (int64_t)a.N;
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+      if (col[t] < a.N) {
+        if (whole) {
+          Vec<V> out;
+#pragma unroll
+          for (int x = 0; x < V; ++x) out.v[x] = __int_as_float(s.best[t][x]);
+          out.store(reinterpret_cast<float*>(arow + col[t]));
+        } else {
+#pragma unroll
+          for (int x = 0; x < V; ++x)
+            if (s.best[t][x] != INT32_MAX)
+              __hip_atomic_fetch_min(arow + col[t] + x, s.best[t][x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+    }
+  }
+};
+
+// Gradient of sum / mean with respect to B from the CSR of A itself: every stored entry
+// (i, k) adds  w * dC[i, :]  into dB[k, :]  (w = val, or val / row length for mean) with
+// fp32 atomic adds; dB was zero-filled before.  Here KernelArgs::B is dC and ::C is dB.
+template <int V, int T>
+struct TransposedRows {
+  struct State { Vec<V> d[T]; };
+
+  __device__ static void begin(State& s, const KernelArgs& a, int64_t row, int row_len, const int (&colc)[T]) {
+    const float w = a.is_mean ? 1.0f / (float)row_len : 1.0f;
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+      s.d[t] = Vec<V>::load(a.B + row * (int64_t)a.N + colc[t]);
+#pragma unroll
+      for (int x = 0; x < V; ++x) s.d[t].v[x] *= w;
+    }
+  }
+
+  template <int U>
+  __device__ static void pass(State& s, const KernelArgs& a, const int2* ka, int, int first, int stride, int left,
+                              const int (&col)[T], const int (&)[T]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (u < left) {                      // no padding here: every atomic must be a real entry
+        const int2 e = ka[first + u * stride];
+        float* out = a.C + (int64_t)e.x * a.N;
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+          if (col[t] < a.N) {
+#pragma unroll
+            for (int x = 0; x < V; ++x)
+              __hip_atomic_fetch_add(out + col[t] + x, __int_as_float(e.y) * s.d[t].v[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+      }
+    }
+  }
+
+  template <int G> __device__ static void combine(State&) {}
+  __device__ static void end(State&, const KernelArgs&, int64_t, bool, int, const int (&)[T]) {}
+};
+
+// P: row policy; V: floats per lane per load; G: lanes per slot; T: column tiles per lane.
+template <class P, int V, int G, int T>
+__global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
   constexpr int NS = kWave / G;                 // slots
   constexpr int U = loads_in_flight(G) / T > 0 ? loads_in_flight(G) / T : 1;   // entries per lane per pass
   extern __shared__ int2 s_dyn[];               // per wavefront: S entries (colind, val) + 64 row descriptors
@@ -325,18 +480,15 @@ __global__ void __launch_bounds__(kBlock) spmm_chunks(const KernelArgs a) {
         wave_lds_fence();
         for (int t0 = 0; t0 < nshort; t0 += NS) {
           const bool have = t0 + slot < nshort;
-          const int2 d = short_rows[have ? t0 + slot : nshort - 1];
+          const int2 d = short_rows[have ? t0 + slot : nshort - 1];   // an idle slot shadows the last row
           const int r_ps = (d.x >> 6) & 4095;
           const int r_len = have ? (d.x >> 18) & 4095 : 0;
-          Vec<V> acc[T];
-#pragma unroll
-          for (int t = 0; t < T; ++t)
-#pragma unroll
-            for (int x = 0; x < V; ++x) acc[t].v[x] = fold_identity<F>();
+          const int64_t row = rbase + (d.x & 63);
+          typename P::State st;
+          P::begin(st, a, row, d.y, colc);
           for (int it = 0; __ballot(it < r_len) != 0ull; it += U)
-            gather_pass<F, V, T, U>(acc, ka, r_ps + (it < r_len ? it : 0), 1, r_len - it, a.B, a.N, colc);
-          if (have)
-            emit<F, V, T>(acc, a.C + (rbase + (d.x & 63)) * (int64_t)a.N, col, a.N, (d.x >> 30) & 1, d.y, a.is_mean);
+            P::template pass<U>(st, a, ka, cs, r_ps + (it < r_len ? it : 0), 1, r_len - it, col, colc);
+          if (have) P::end(st, a, row, (d.x >> 30) & 1, d.y, col);
         }
         wave_lds_fence();
       }
@@ -349,27 +501,17 @@ __global__ void __launch_bounds__(kBlock) spmm_chunks(const KernelArgs a) {
       todo &= todo - 1;
       const int ps = __builtin_amdgcn_readlane(my_ps, i);
       const int pe = __builtin_amdgcn_readlane(my_pe, i);
-      Vec<V> acc[T];
-#pragma unroll
-      for (int t = 0; t < T; ++t)
-#pragma unroll
-        for (int x = 0; x < V; ++x) acc[t].v[x] = fold_identity<F>();
+      const int s = __builtin_amdgcn_readlane(my_s, i);
+      const int e = __builtin_amdgcn_readlane(my_e, i);
+      typename P::State st;
+      P::begin(st, a, rbase + i, e - s, colc);
       for (int base = ps; base < pe; base += U * NS) {
         const int first = base + slot;
         const int left = (pe - first + NS - 1) / NS;       // entries first, first+NS, ... below pe
-        gather_pass<F, V, T, U>(acc, ka, left > 0 ? first : pe - 1, NS, left, a.B, a.N, colc);
+        P::template pass<U>(st, a, ka, cs, left > 0 ? first : pe - 1, NS, left, col, colc);
       }
-#pragma unroll
-      for (int off = G; off < kWave; off <<= 1)
-#pragma unroll
-        for (int t = 0; t < T; ++t)
-#pragma unroll
-          for (int x = 0; x < V; ++x) acc[t].v[x] = fold2<F>(acc[t].v[x], __shfl_xor(acc[t].v[x], off, kWave));
-      if (slot == 0) {
-        const int s = __builtin_amdgcn_readlane(my_s, i);
-        const int e = __builtin_amdgcn_readlane(my_e, i);
-        emit<F, V, T>(acc, a.C + (rbase + i) * (int64_t)a.N, col, a.N, s >= cs && e <= ce, e - s, a.is_mean);
-      }
+      P::template combine<G>(st);
+      if (slot == 0) P::end(st, a, rbase + i, s >= cs && e <= ce, e - s, col);
     }
     // the next batch of rows is needed only if it still starts inside the chunk
     const int next_start = __builtin_amdgcn_readlane(my_e, kWave - 1);
@@ -377,12 +519,37 @@ __global__ void __launch_bounds__(kBlock) spmm_chunks(const KernelArgs a) {
   }
 }
 
+// -------------------------------------------------- small helper kernels -----
+// dst[0..n) = value (a row-major matrix seen as a flat array)
+__global__ void __launch_bounds__(kBlock) fill_f32(float* __restrict__ dst, int64_t n, float value) {
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) dst[i] = value;
+}
+
+// Gradient of max / min w.r.t. B: element (i, j) adds val[p] * dC[i, j] into dB[colind[p], j]
+// for p = arg[i, j] >= 0.  One lane per element, reads coalesced, atomics scattered.
+__global__ void __launch_bounds__(kBlock) pool_backward_scatter(int64_t total, int32_t N, const int32_t* __restrict__ colind,
+                                                               const float* __restrict__ vals,
+                                                               const int32_t* __restrict__ arg,
+                                                               const float* __restrict__ dC, float* __restrict__ dB) {
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  for (int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x; e < total; e += stride) {
+    const int p = arg[e];
+    if (p >= 0) {
+      const float w = vals ? vals[p] : 1.0f;
+      __hip_atomic_fetch_add(dB + (int64_t)colind[p] * N + (e % N), w * dC[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
 // --------------------------------------------------------------- host side --
 using MainKernel = void (*)(const KernelArgs);
 
-template <int F, int V>
+enum Job { kJobAdd = kAdd, kJobMax = kMax, kJobMin = kMin, kJobArg = 3, kJobTransposed = 4 };
+
+template <template <int, int> class P, int V>
 MainKernel pick_gt(int G, int T) {
-#define GESPMM_CASE(GG, TT) if (G == GG && T == TT) return spmm_chunks<F, V, GG, TT>;
+#define GESPMM_CASE(GG, TT) if (G == GG && T == TT) return chunk_kernel<P<V, TT>, V, GG, TT>;
   GESPMM_CASE(1, 1) GESPMM_CASE(2, 1) GESPMM_CASE(4, 1) GESPMM_CASE(8, 1)
   GESPMM_CASE(16, 1) GESPMM_CASE(32, 1) GESPMM_CASE(64, 1)
   GESPMM_CASE(4, 2) GESPMM_CASE(8, 2) GESPMM_CASE(16, 2) GESPMM_CASE(32, 2) GESPMM_CASE(64, 2)
@@ -391,20 +558,27 @@ MainKernel pick_gt(int G, int T) {
   return nullptr;
 }
 
-MainKernel pick_kernel(int fold, int vec, int G, int T) {
-  if (vec == 4) {
-    if (fold == kAdd) return pick_gt<kAdd, 4>(G, T);
-    if (fold == kMax) return pick_gt<kMax, 4>(G, T);
-    return pick_gt<kMin, 4>(G, T);
+template <int V, int T> using AddRows = FoldRows<kAdd, V, T>;
+template <int V, int T> using MaxRows = FoldRows<kMax, V, T>;
+template <int V, int T> using MinRows = FoldRows<kMin, V, T>;
+
+template <int V>
+MainKernel pick_job(int job, int G, int T) {
+  switch (job) {
+    case kJobAdd: return pick_gt<AddRows, V>(G, T);
+    case kJobMax: return pick_gt<MaxRows, V>(G, T);
+    case kJobMin: return pick_gt<MinRows, V>(G, T);
+    case kJobArg: return pick_gt<ArgRows, V>(G, T);
+    case kJobTransposed: return pick_gt<TransposedRows, V>(G, T);
+    default: return nullptr;
   }
-  if (fold == kAdd) return pick_gt<kAdd, 1>(G, T);
-  if (fold == kMax) return pick_gt<kMax, 1>(G, T);
-  return pick_gt<kMin, 1>(G, T);
 }
 
-bool has_kernel(int G, int T) {
-  return pick_gt<kAdd, 4>(G, T) != nullptr;
+MainKernel pick_kernel(int job, int vec, int G, int T) {
+  return vec == 4 ? pick_job<4>(job, G, T) : pick_job<1>(job, G, T);
 }
+
+bool has_kernel(int G, int T) { return pick_gt<AddRows, 4>(G, T) != nullptr; }
 
 int next_pow2(int64_t x) {
   int p = 1;
@@ -469,6 +643,94 @@ int validate(int64_t M, int64_t K, int64_t N, int64_t nnz, const void* rowptr, c
   return GESPMM_OK;
 }
 
+float bits_as_float(int32_t bits) {
+  float f;
+  std::memcpy(&f, &bits, sizeof(f));
+  return f;
+}
+
+int launch_fill(float* dst, int64_t n, float value, hipStream_t stream) {
+  if (n <= 0) return GESPMM_OK;
+  int64_t blocks = (n + kBlock - 1) / kBlock;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  hipLaunchKernelGGL(fill_f32, dim3((unsigned)blocks), dim3(kBlock), 0, stream, dst, n, value);
+  return hipGetLastError() == hipSuccess ? GESPMM_OK : GESPMM_ERR_HIP;
+}
+
+// One pass of the chunk kernel over the matrix, preceded (when init_target is set) by the
+// row-initialisation kernel for that output.
+struct ChunkLaunch {
+  int job = kJobAdd;
+  int64_t M = 0, N = 0, nnz = 0;
+  const int32_t* rowptr = nullptr;
+  const int32_t* colind = nullptr;
+  const float* vals = nullptr;
+  const float* dense_in = nullptr;     // B, or dC
+  float* dense_out = nullptr;          // C, or dB
+  const float* result_in = nullptr;    // finished C for the position job
+  int32_t* arg = nullptr;
+  const void* also_aligned = nullptr;  // further buffer that must be 16-byte aligned for the vector kernels
+  bool is_mean = false;
+  float* init_target = nullptr;        // M x N output preset by init_rows, or nullptr
+  float empty_value = 0.0f, split_value = 0.0f;
+  bool timed = false;                  // bracket the chunk kernel with profiling events
+};
+
+int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
+  const bool aligned16 = (((uintptr_t)L.dense_in | (uintptr_t)L.dense_out | (uintptr_t)L.result_in |
+                           (uintptr_t)L.also_aligned) & 15u) == 0;
+  gespmm_plan_t plan;
+  make_plan(L.M, L.N, L.nnz, aligned16, &plan);
+  MainKernel kernel = pick_kernel(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
+  if (!kernel) return GESPMM_ERR_BAD_ARG;
+  if (plan.col_blocks > 65535) return GESPMM_ERR_TOO_LARGE;   // grid.y limit (N beyond ~33 million)
+  int shift = 0;
+  while ((1 << shift) < plan.chunk_nnz) ++shift;
+
+  // (a) empty rows and rows shared by several chunks are preset
+  if (L.init_target) {
+    int lanes_shift = 0;                          // lanes that write one row in init_rows
+    while ((1 << lanes_shift) < kWave && ((int64_t)plan.vec << lanes_shift) < L.N) ++lanes_shift;
+    const unsigned init_blocks = (unsigned)((L.M + kBlock - 1) / kBlock);
+    if (plan.vec == 4)
+      hipLaunchKernelGGL(init_rows<4>, dim3(init_blocks), dim3(kBlock), 0, stream, (int32_t)L.M, (int32_t)L.N, L.rowptr,
+                         L.init_target, L.empty_value, L.split_value, shift, lanes_shift);
+    else
+      hipLaunchKernelGGL(init_rows<1>, dim3(init_blocks), dim3(kBlock), 0, stream, (int32_t)L.M, (int32_t)L.N, L.rowptr,
+                         L.init_target, L.empty_value, L.split_value, shift, lanes_shift);
+    if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
+  }
+  if (L.nnz == 0) return GESPMM_OK;
+
+  // (b) the chunks
+  KernelArgs a;
+  a.M = (int32_t)L.M;
+  a.N = (int32_t)L.N;
+  a.nnz = (int32_t)L.nnz;
+  a.is_mean = L.is_mean ? 1 : 0;
+  a.chunks = plan.chunks;
+  a.chunk_blocks = plan.grid_x;
+  a.xcd_remap = plan.xcd_remap;
+  a.chunk_shift = shift;
+  a.short_len = plan.short_len;
+  a.rowptr = L.rowptr;
+  a.colind = L.colind;
+  a.vals = L.vals;
+  a.B = L.dense_in;
+  a.C = L.dense_out;
+  a.Cin = L.result_in;
+  a.arg = L.arg;
+  const bool timed = L.timed && g_profiling && g_ev_used < (int)g_ev_start.size();
+  if (timed && hipEventRecord(g_ev_start[g_ev_used], stream) != hipSuccess) return GESPMM_ERR_HIP;
+  hipLaunchKernelGGL(kernel, dim3((unsigned)plan.grid_x, (unsigned)plan.col_blocks), dim3(kBlock), (size_t)plan.lds_bytes, stream, a);
+  if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
+  if (timed) {
+    if (hipEventRecord(g_ev_stop[g_ev_used], stream) != hipSuccess) return GESPMM_ERR_HIP;
+    ++g_ev_used;
+  }
+  return GESPMM_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -506,57 +768,84 @@ int gespmm_csr(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowp
                void* stream_) {
   const int st = validate(M, K, N, nnz, rowptr, colind, B, C, op);
   if (st != GESPMM_OK || M == 0 || N == 0) return st;
-  hipStream_t stream = (hipStream_t)stream_;
-
-  const bool aligned16 = (((uintptr_t)B | (uintptr_t)C) & 15u) == 0;
-  gespmm_plan_t plan;
-  make_plan(M, N, nnz, aligned16, &plan);
-  const int fold = op == GESPMM_MAX ? kMax : (op == GESPMM_MIN ? kMin : kAdd);
-  MainKernel kernel = pick_kernel(fold, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
-  if (!kernel) return GESPMM_ERR_BAD_ARG;
-  if (plan.col_blocks > 65535) return GESPMM_ERR_TOO_LARGE;   // grid.y limit (N beyond ~33 million)
-
-  // (a) empty rows -> 0, rows shared by several chunks -> reduce identity
+  const int job = op == GESPMM_MAX ? kJobMax : (op == GESPMM_MIN ? kJobMin : kJobAdd);
   float identity = 0.0f;
-  if (fold == kMax) identity = -__builtin_inff();
-  if (fold == kMin) identity = __builtin_inff();
-  int shift = 0;
-  while ((1 << shift) < plan.chunk_nnz) ++shift;
-  int lanes_shift = 0;                            // lanes that write one row in init_rows
-  while ((1 << lanes_shift) < kWave && ((int64_t)plan.vec << lanes_shift) < N) ++lanes_shift;
-  const unsigned init_blocks = (unsigned)((M + kBlock - 1) / kBlock);
-  if (plan.vec == 4)
-    hipLaunchKernelGGL(init_rows<4>, dim3(init_blocks), dim3(kBlock), 0, stream, (int32_t)M, (int32_t)N, rowptr, C, identity, shift, lanes_shift);
-  else
-    hipLaunchKernelGGL(init_rows<1>, dim3(init_blocks), dim3(kBlock), 0, stream, (int32_t)M, (int32_t)N, rowptr, C, identity, shift, lanes_shift);
-  if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
-  if (nnz == 0) return GESPMM_OK;
+  if (job == kJobMax) identity = -__builtin_inff();
+  if (job == kJobMin) identity = __builtin_inff();
+  ChunkLaunch L;
+  L.job = job;
+  L.M = M; L.N = N; L.nnz = nnz;
+  L.rowptr = rowptr; L.colind = colind; L.vals = vals;
+  L.dense_in = B; L.dense_out = C;
+  L.is_mean = op == GESPMM_MEAN;
+  L.init_target = C; L.empty_value = 0.0f; L.split_value = identity;
+  L.timed = true;
+  return launch_chunks(L, (hipStream_t)stream_);
+}
 
-  // (b) the chunks
-  KernelArgs a;
-  a.M = (int32_t)M;
-  a.N = (int32_t)N;
-  a.nnz = (int32_t)nnz;
-  a.is_mean = op == GESPMM_MEAN;
-  a.chunks = plan.chunks;
-  a.chunk_blocks = plan.grid_x;
-  a.xcd_remap = plan.xcd_remap;
-  a.chunk_shift = shift;
-  a.short_len = plan.short_len;
-  a.rowptr = rowptr;
-  a.colind = colind;
-  a.vals = vals;
-  a.B = B;
-  a.C = C;
-  const bool timed = g_profiling && g_ev_used < (int)g_ev_start.size();
-  if (timed && hipEventRecord(g_ev_start[g_ev_used], stream) != hipSuccess) return GESPMM_ERR_HIP;
-  hipLaunchKernelGGL(kernel, dim3((unsigned)plan.grid_x, (unsigned)plan.col_blocks), dim3(kBlock), (size_t)plan.lds_bytes, stream, a);
-  if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
-  if (timed) {
-    if (hipEventRecord(g_ev_stop[g_ev_used], stream) != hipSuccess) return GESPMM_ERR_HIP;
-    ++g_ev_used;
-  }
-  return GESPMM_OK;
+int gespmm_csr_arg(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                   const int32_t* colind, const float* vals, const float* B, float* C, int32_t* arg,
+                   int op, void* stream_) {
+  if (op != GESPMM_MAX && op != GESPMM_MIN) return GESPMM_ERR_BAD_ARG;
+  const int st = validate(M, K, N, nnz, rowptr, colind, B, C, op);
+  if (st != GESPMM_OK || M == 0 || N == 0) return st;
+  if (!arg) return GESPMM_ERR_NULL;
+  // the result first (all atomics of split rows have landed when the next kernel starts) ...
+  const int fwd = gespmm_csr(M, K, N, nnz, rowptr, colind, vals, B, C, op, stream_);
+  if (fwd != GESPMM_OK) return fwd;
+  // ... then the positions: empty rows -> -1, split rows -> INT_MAX and an atomic min
+  ChunkLaunch L;
+  L.job = kJobArg;
+  L.M = M; L.N = N; L.nnz = nnz;
+  L.rowptr = rowptr; L.colind = colind; L.vals = vals;
+  L.dense_in = B; L.dense_out = nullptr; L.result_in = C; L.arg = arg;
+  L.init_target = reinterpret_cast<float*>(arg);
+  L.empty_value = bits_as_float(-1);
+  L.split_value = bits_as_float(INT32_MAX);
+  L.also_aligned = arg;
+  return launch_chunks(L, (hipStream_t)stream_);
+}
+
+int gespmm_csr_transposed(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                          const int32_t* colind, const float* vals, const float* dC, float* dB, int op,
+                          void* stream_) {
+  if (op != GESPMM_SUM && op != GESPMM_MEAN) return GESPMM_ERR_BAD_ARG;
+  if (M < 0 || K < 0 || N < 0 || nnz < 0) return GESPMM_ERR_BAD_ARG;
+  if (M >= INT32_MAX || K > INT32_MAX || nnz > INT32_MAX - (1 << kMaxChunkShift) || N > INT32_MAX / 8) return GESPMM_ERR_TOO_LARGE;
+  if (nnz > 0 && (M == 0 || K == 0)) return GESPMM_ERR_BAD_ARG;
+  if (K == 0 || N == 0) return GESPMM_OK;
+  if (!dB) return GESPMM_ERR_NULL;
+  if (nnz > 0 && (!rowptr || !colind || !dC)) return GESPMM_ERR_NULL;
+  hipStream_t stream = (hipStream_t)stream_;
+  const int fill = launch_fill(dB, K * N, 0.0f, stream);
+  if (fill != GESPMM_OK || nnz == 0) return fill;
+  ChunkLaunch L;
+  L.job = kJobTransposed;
+  L.M = M; L.N = N; L.nnz = nnz;
+  L.rowptr = rowptr; L.colind = colind; L.vals = vals;
+  L.dense_in = dC; L.dense_out = dB;
+  L.is_mean = op == GESPMM_MEAN;
+  return launch_chunks(L, stream);
+}
+
+int gespmm_pool_backward(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* colind,
+                         const float* vals, const int32_t* arg, const float* dC, float* dB,
+                         void* stream_) {
+  if (M < 0 || K < 0 || N < 0 || nnz < 0) return GESPMM_ERR_BAD_ARG;
+  if (M >= INT32_MAX || K > INT32_MAX || nnz > INT32_MAX || N > INT32_MAX / 8) return GESPMM_ERR_TOO_LARGE;
+  if (K == 0 || N == 0) return GESPMM_OK;
+  if (!dB) return GESPMM_ERR_NULL;
+  if (M > 0 && (!arg || !dC)) return GESPMM_ERR_NULL;
+  if (nnz > 0 && M > 0 && !colind) return GESPMM_ERR_NULL;
+  hipStream_t stream = (hipStream_t)stream_;
+  const int fill = launch_fill(dB, K * N, 0.0f, stream);
+  if (fill != GESPMM_OK || M == 0 || nnz == 0) return fill;
+  const int64_t total = M * N;
+  int64_t blocks = (total + kBlock - 1) / kBlock;
+  if (blocks > 256 * 64) blocks = 256 * 64;
+  hipLaunchKernelGGL(pool_backward_scatter, dim3((unsigned)blocks), dim3(kBlock), 0, stream, total, (int32_t)N,
+                     colind, vals, arg, dC, dB);
+  return hipGetLastError() == hipSuccess ? GESPMM_OK : GESPMM_ERR_HIP;
 }
 
 int gespmm_csr_simple(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colind,

@@ -28,7 +28,7 @@ def test_every_declared_symbol_is_exported(L):
     names = _declared_functions()
     assert {"gespmm_csr", "gespmm_csr_simple", "gespmm_plan", "gespmm_set_tuning",
             "gespmm_profile_begin", "gespmm_profile_end", "gespmm_status_string",
-            "gespmm_calibration_copy",
+            "gespmm_calibration_copy", "gespmm_csr_arg", "gespmm_csr_transposed", "gespmm_pool_backward",
             "gespmm_version"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
@@ -62,6 +62,20 @@ def test_argument_errors_come_before_any_device_work(L):
     assert L.gespmm_csr_simple(-1, 4, 4, p, p, p, p, p, 0, None) == 1
     assert L.gespmm_csr_simple(4, 4, 4, None, p, p, p, p, 0, None) == 2
     assert L.gespmm_csr_simple(0, 4, 4, p, p, p, p, p, 0, None) == 0
+    # gradient-side entry points
+    assert L.gespmm_csr_arg(4, 4, 4, 8, p, p, p, p, p, p, 0, None) == 1      # sum has no position
+    assert L.gespmm_csr_arg(4, 4, 4, 8, p, p, p, p, p, None, 2, None) == 2   # arg NULL
+    assert L.gespmm_csr_arg(4, 4, 4, -1, p, p, p, p, p, p, 2, None) == 1
+    assert L.gespmm_csr_arg(0, 4, 4, 0, p, p, p, p, p, p, 3, None) == 0
+    assert L.gespmm_csr_transposed(4, 4, 4, 8, p, p, p, p, p, 2, None) == 1  # max has no transposed sum
+    assert L.gespmm_csr_transposed(4, 4, 4, 8, p, p, p, p, None, 0, None) == 2
+    assert L.gespmm_csr_transposed(4, 4, 4, 8, None, p, p, p, p, 1, None) == 2
+    assert L.gespmm_csr_transposed(4, 2**31 + 1, 4, 8, p, p, p, p, p, 0, None) == 3
+    assert L.gespmm_csr_transposed(4, 0, 4, 0, p, p, p, p, p, 0, None) == 0
+    assert L.gespmm_pool_backward(4, 4, 4, 8, p, p, None, p, p, None) == 2
+    assert L.gespmm_pool_backward(4, 4, 4, 8, p, p, p, p, None, None) == 2
+    assert L.gespmm_pool_backward(-4, 4, 4, 8, p, p, p, p, p, None) == 1
+    assert L.gespmm_pool_backward(4, 4, 0, 8, p, p, p, p, p, None) == 0
     assert L.gespmm_plan(4, 4, 4, 1, None) == 2
     assert L.gespmm_profile_end(None, None) == 1                  # not profiling
     assert L.gespmm_calibration_copy(p, p, 24, None) == 1         # not a multiple of 16

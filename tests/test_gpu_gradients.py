@@ -1,0 +1,182 @@
+"""GPU parity of the gradient-side entry points against the CPU oracle, through the C ABI.
+
+positions (arg): the value is bit-exact and the position is unique by definition (smallest entry
+index among the entries whose product has the bits of the result), so both are compared exactly;
+transposed sum/mean and the routed pooling gradient: |dB - dBref| <= 1e-5 * Sabs + 1e-6.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import graphgen
+import oracle
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gs():
+    import paper_2007_03179_amd as gs
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    gs.lib()
+    yield gs
+    gs.gespmm_set_tuning()
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def dev(x):
+    return None if x is None else torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def check_arg(gs, rp, ci, v, B, op, rows=None, label="", dA=None, dB=None):
+    say(f"  case arg {label} op={op} M={len(rp) - 1} N={B.shape[1]} nnz={len(ci)}")
+    d_rp, d_ci, d_v = dA if dA is not None else (dev(rp), dev(ci), dev(v))
+    C, arg = gs.gespmm_csr_arg(d_rp, d_ci, d_v, dB if dB is not None else dev(B), op)
+    torch.cuda.synchronize()
+    C, arg = C.cpu().numpy(), arg.cpu().numpy()
+    Cref, aref = oracle.spmm_arg(rp, ci, v, B, op, rows=rows)
+    got_c, got_a = (C, arg) if rows is None else (C[rows], arg[rows])
+    assert np.array_equal(got_c.view(np.uint32), Cref.astype(np.float32).view(np.uint32)), f"{label}: value bits"
+    bad = np.flatnonzero(got_a != aref)
+    assert bad.size == 0, f"{label}: {bad.size} positions differ, first at flat index {bad[:1]}"
+    return C, arg
+
+
+def check_transposed(gs, rp, ci, v, dC, op, K, label="", dA=None):
+    say(f"  case transposed {label} op={op} M={len(rp) - 1} K={K} N={dC.shape[1]} nnz={len(ci)}")
+    d_rp, d_ci, d_v = dA if dA is not None else (dev(rp), dev(ci), dev(v))
+    out = gs.gespmm_csr_transposed(d_rp, d_ci, d_v, dev(dC), op, K)
+    torch.cuda.synchronize()
+    ref, sabs = oracle.spmm_transposed(rp, ci, v, dC, op, K)
+    ok, worst = oracle.compare("sum", out.cpu().numpy(), ref, sabs)
+    assert ok, f"{label} transposed {op}: worst={worst}"
+    return out
+
+
+def check_pool_backward(gs, ci, v, arg, dC, K, label=""):
+    say(f"  case pool-backward {label} M={dC.shape[0]} K={K} N={dC.shape[1]}")
+    out = gs.gespmm_pool_backward(dev(ci), dev(v), dev(arg), dev(dC), K)
+    torch.cuda.synchronize()
+    ref, sabs = oracle.pool_backward(ci, v, arg, dC, K)
+    ok, worst = oracle.compare("sum", out.cpu().numpy(), ref, sabs)
+    assert ok, f"{label} pool backward: worst={worst}"
+    return out
+
+
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("N", [1, 4, 7, 8, 32, 33, 64, 128, 520])
+def test_positions_widths_ties_and_split_rows(gs, N):
+    # few distinct values -> many ties; a row spanning many chunks; duplicates; empty rows; M != K
+    rp, ci, v = graphgen.random_csr(600, 400, 8.0, 300 + N, empty_frac=0.1, long_rows=((77, 2500),),
+                                    duplicates=True, sort_cols=False)
+    B = np.round(graphgen.random_dense(400, N, N) * 4.0).astype(np.float32)
+    v = np.round(v * 2.0).astype(np.float32)
+    v[v == 0] = 1.0
+    B[5] = -0.0
+    B[6] = 0.0
+    for op in ("max", "min"):
+        for vv in (v, None):
+            check_arg(gs, rp, ci, vv, B, op, label=f"ties N={N}")
+
+
+def test_positions_every_launch_shape(gs):
+    rp, ci, v = graphgen.random_csr(300, 260, 7.0, 56, empty_frac=0.1, long_rows=((11, 900), (12, 300)))
+    B = np.round(graphgen.random_dense(260, 72, 56) * 8.0).astype(np.float32)
+    dA, dB = (dev(rp), dev(ci), dev(v)), dev(B)
+    shapes = [(1, 1), (2, 1), (8, 1), (16, 1), (64, 1), (4, 2), (16, 2), (64, 2), (8, 4), (64, 4)]
+    try:
+        for G, T in shapes:
+            for remap, chunk, short in ((0, 16, 0), (1, 256, -1), (1, 1024, 1024)):
+                gs.gespmm_set_tuning(G, T, remap, chunk, short)
+                for op in ("max", "min"):
+                    check_arg(gs, rp, ci, v, B, op, label=f"G={G} T={T} S={chunk} short={short}", dA=dA, dB=dB)
+    finally:
+        gs.gespmm_set_tuning()
+
+
+def test_positions_degenerate(gs):
+    B = graphgen.random_dense(5, 8, 1)
+    rp, ci, v = np.zeros(4, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32)
+    C, arg = check_arg(gs, rp, ci, v, B, "max", label="nnz=0")
+    assert (arg == -1).all() and not C.any()
+    n = 1000                                        # one long row between empty rows, all products equal
+    rp = np.array([0, 0, n, n], dtype=np.int32)
+    ci = np.full(n, 3, dtype=np.int32)
+    v = np.ones(n, dtype=np.float32)
+    C, arg = check_arg(gs, rp, ci, v, B, "min", label="all-equal long row")
+    assert (arg[1] == 0).all() and (arg[0] == -1).all() and (arg[2] == -1).all()
+
+
+@pytest.mark.parametrize("N", [1, 4, 7, 16, 64, 100, 256])
+def test_transposed_widths(gs, N):
+    rp, ci, v = graphgen.random_csr(500, 350, 9.0, 400 + N, empty_frac=0.1, long_rows=((9, 2000),),
+                                    duplicates=True, sort_cols=False)
+    dC = graphgen.random_dense(500, N, N + 1)
+    for op in ("sum", "mean"):
+        check_transposed(gs, rp, ci, v, dC, op, 350, label=f"N={N}")
+        check_transposed(gs, rp, ci, None, dC, op, 350, label=f"N={N} vals=NULL")
+
+
+def test_transposed_degenerate_and_adjoint(gs):
+    dC = graphgen.random_dense(3, 8, 2)
+    out = check_transposed(gs, np.zeros(4, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32), dC, "sum", 6,
+                           label="nnz=0")
+    assert not out.cpu().numpy().any()
+    # <A (x) B, dC> == <B, A^T (x) dC> with both sides from the GPU
+    rp, ci, v = graphgen.random_csr(800, 700, 10.0, 5, empty_frac=0.05, long_rows=((3, 3000),))
+    B, dC = graphgen.random_dense(700, 32, 5), graphgen.random_dense(800, 32, 6)
+    dA = dev(rp), dev(ci), dev(v)
+    for op in ("sum", "mean"):
+        C = gs.gespmm_csr(*dA, dev(B), op).double().cpu().numpy()
+        dBt = gs.gespmm_csr_transposed(*dA, dev(dC), op, 700).double().cpu().numpy()
+        lhs, rhs = float((C * dC).sum()), float((B * dBt).sum())
+        scale = float((np.abs(C) * np.abs(dC)).sum())
+        assert abs(lhs - rhs) <= 1e-4 * scale, (op, lhs, rhs)
+
+
+def test_pool_backward_matches_oracle_and_forward_positions(gs):
+    rp, ci, v = graphgen.random_csr(700, 500, 9.0, 8, empty_frac=0.1, long_rows=((350, 3000),), duplicates=True)
+    for N in (4, 7, 64):
+        B = graphgen.random_dense(500, N, N)
+        dC = graphgen.random_dense(700, N, N + 9)
+        for op in ("max", "min"):
+            _, arg = check_arg(gs, rp, ci, v, B, op, label="for pool backward")
+            check_pool_backward(gs, ci, v, arg, dC, 500, label=f"{op} N={N}")
+            check_pool_backward(gs, ci, None, arg, dC, 500, label=f"{op} N={N} vals=NULL")
+    # nothing routed: all rows empty
+    arg = np.full((5, 8), -1, dtype=np.int32)
+    out = check_pool_backward(gs, np.zeros(1, np.int32), np.ones(1, np.float32), arg, graphgen.random_dense(5, 8, 1), 3)
+    assert not out.cpu().numpy().any()
+
+
+@pytest.mark.parametrize("which", [2, 4])
+def test_gradient_side_on_workloads(gs, which):
+    w = graphgen.workload(which)
+    say(" ", w.describe())
+    N = w.widths[-1]
+    B = w.B(N)
+    dC = graphgen.uniform_pm1((w.M, N), 99, stream=N)
+    vals = graphgen.uniform_pm1(w.nnz, 98)              # signed weights: max and min both non-trivial
+    dA = dev(w.rowptr), dev(w.colind), dev(vals)
+    lens = np.diff(w.rowptr)
+    rows = np.unique(np.concatenate([np.argsort(lens)[-16:], np.flatnonzero(lens == 0)[:8],
+                                     np.random.default_rng(which).integers(0, w.M, 4000)])).astype(np.int64)
+    for op in ("max", "min"):
+        C, arg = check_arg(gs, w.rowptr, w.colind, vals, B, op, rows=rows, label=w.name, dA=dA)
+        # properties at full size: the position lies in its row and reproduces the value bit for bit
+        i, j = np.nonzero(arg >= 0)
+        p = arg[i, j]
+        assert (arg[lens == 0] == -1).all() and (arg[lens > 0] >= 0).all()
+        assert (p >= w.rowptr[i]).all() and (p < w.rowptr[i + 1]).all()
+        prod = vals[p] * B[w.colind[p], j]              # one fp32 product, as the kernel forms it
+        assert np.array_equal(prod.view(np.uint32), C[i, j].view(np.uint32))
+        if op == "max":
+            check_pool_backward(gs, w.colind, vals, arg, dC, w.K, label=w.name)
+    for op in ("sum", "mean"):
+        check_transposed(gs, w.rowptr, w.colind, vals, dC, op, w.K, label=w.name, dA=dA)
