@@ -3,6 +3,7 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--width N] [--op OP]
     python bench.py --sweep            # every workload / width / op, table on stderr
+    python bench.py --gradients        # also time the gradient-side entry points
     python bench.py --copy-gib 1       # also launch the calibration copy kernel (for --pmc runs)
 
 One "step" is one whole gespmm_csr call (row-initialisation kernel + chunk kernel) on a
@@ -104,6 +105,53 @@ class DeviceCase:
                 "compulsory_bytes": compulsory_bytes(w.M, w.K, N, w.nnz)}
 
 
+def gradient_bytes(kind, M, K, N, nnz):
+    """Algorithmic bytes of the gradient-side calls (same counting rules as model_bytes)."""
+    walk = 4 * (M + 1) + 8 * nnz                       # rowptr + colind + vals
+    if kind == "arg":                                  # forward, then: walk + gathers + read C + write arg
+        return model_bytes(M, N, nnz) + walk + 4 * nnz * N + 8 * M * N
+    if kind == "transposed":                           # zero dB + walk + read dC + one add of N floats per entry
+        return 4 * K * N + walk + 4 * M * N + 4 * nnz * N
+    if kind == "pool_backward":                        # zero dB + arg, dC, colind[arg], vals[arg], one add per element
+        return 4 * K * N + 20 * M * N
+    raise ValueError(kind)
+
+
+def time_gradients(args, gs, torch, graphgen, dev):
+    """Gradient-side entry points on three workloads; table on stderr."""
+    rows = []
+    for name, N in (("general_ops", 128), ("skew_narrow", 32), ("large_dense_degree", 64)):
+        w = graphgen.workload(name, args.scale)
+        case = DeviceCase(w, N, torch, dev)
+        dC = torch.from_numpy(graphgen.uniform_pm1((w.M, N), 99, stream=N)).to(dev)
+        arg = torch.empty((w.M, N), dtype=torch.int32, device=dev)
+        dB = torch.empty((w.K, N), dtype=torch.float32, device=dev)
+        calls = {
+            "arg": lambda: gs.gespmm_csr_arg(case.rp, case.ci, case.v, case.B, "max", C=case.C, arg=arg),
+            "transposed": lambda: gs.gespmm_csr_transposed(case.rp, case.ci, case.v, dC, "sum", w.K, dB=dB),
+            "pool_backward": lambda: gs.gespmm_pool_backward(case.ci, case.v, arg, dC, w.K, dB=dB),
+        }
+        for kind, call in calls.items():                # "arg" runs first and leaves valid positions behind
+            steps = max(10, args.steps // (10 if w.nnz > 5e7 else 1))
+            for _ in range(3):
+                call()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                call()
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / steps
+            gb = gradient_bytes(kind, w.M, w.K, N, w.nnz)
+            rows.append({"workload": name, "N": N, "kind": kind, "ms_per_call": ms, "model_bytes": gb,
+                         "model_GBps": gb / (ms * 1e-3) / 1e9})
+            print(f"{name:20s} N={N:4d} {kind:14s} {ms*1e3:10.1f} us  model {gb/1e9:8.3f} GB  "
+                  f"{gb/(ms*1e-3)/1e9:8.1f} GB/s ({gb/(ms*1e-3)/1e9/HBM_PEAK_GBPS*100:5.1f}% of HBM peak)",
+                  file=sys.stderr, flush=True)
+        del case, dC, arg, dB
+        torch.cuda.empty_cache()
+    return rows
+
+
 def sweep(args, gs, torch, graphgen, dev):
     """Every workload / width / op of the five configurations; table on stderr."""
     rows = []
@@ -139,6 +187,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--sweep", action="store_true", help="also time every workload/width/op")
     ap.add_argument("--sweep-out", default="", help="write the sweep rows to this JSON file")
+    ap.add_argument("--gradients", action="store_true",
+                    help="also time the gradient-side entry points (positions, transposed, pooling gradient)")
     ap.add_argument("--copy-gib", type=float, default=0.0,
                     help="launch the calibration copy kernel once on this many GiB (traffic-counter yardstick)")
     ap.add_argument("--tuning", default="",
@@ -175,6 +225,8 @@ def main():
         with open(args.sweep_out, "w") as f:
             json.dump(sweep_rows, f, indent=1)
 
+    grad_rows = time_gradients(args, gs, torch, graphgen, dev) if args.gradients else None
+
     w = graphgen.workload(args.workload, args.scale)
     N = args.width or w.widths[0]
     op = args.op
@@ -208,6 +260,8 @@ def main():
     if sweep_rows is not None:
         out["sweep"] = [{k: row[k] for k in ("workload", "N", "op", "ms_per_step", "gflops", "model_GBps_step")}
                         for row in sweep_rows]
+    if grad_rows is not None:
+        out["gradients"] = grad_rows
     print(json.dumps(out), flush=True)
 
 

@@ -25,7 +25,7 @@ _lib = None
 
 def build(force: bool = False) -> str:
     """Compile graphgen.cpp into libgraphgen.so (g++, OpenMP)."""
-    if force or not os.path.exists(_LIB):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["g++", "-O3", "-fopenmp", "-shared", "-fPIC", "-std=c++17", "-o", _LIB, _SRC]
         subprocess.run(cmd, check=True)
     return _LIB

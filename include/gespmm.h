@@ -105,12 +105,37 @@ int gespmm_csr_arg(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* 
  *   dC   device, fp32[M*N], row-major;  dB  device, fp32[K*N], row-major, overwritten
  *   (zero-filled by the call, then accumulated with fp32 atomic adds: the last bits can
  *   differ from run to run).  K == 0 or N == 0 returns at once; op other than SUM / MEAN
- *   is GESPMM_ERR_BAD_ARG.  For a symmetric A with symmetric values this equals
- *   gespmm_csr(A, dC), which is the faster way to get it.
+ *   is GESPMM_ERR_BAD_ARG.  This is the no-extra-memory route; fp32 atomics make it 20-30x
+ *   slower than a forward call, so for repeated use build the transposed arrays once with
+ *   gespmm_csr_transpose and call gespmm_csr on them (for a symmetric A with symmetric
+ *   values, gespmm_csr on A itself already is the answer).
  */
 int gespmm_csr_transposed(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
                           const int32_t* colind, const float* vals, const float* dC, float* dB, int op,
                           void* stream);
+
+/*
+ * The CSR arrays of the transposed matrix, built on the device from the CSR arrays of A.
+ * GNN frameworks keep both orientations of the graph; with this one, the gradient of
+ * sum / mean with respect to B (Sections I, IV-B) is a plain gespmm_csr call,
+ *     dB = gespmm_csr(K, M, N, nnz, rowptrT, colindT, valsT, dC, GESPMM_SUM),
+ * at forward speed, and the arrays can be reused for every training step on the graph.
+ *   scale_by_row_length   0: valsT holds vals (ones if vals is NULL);
+ *                         1: vals[p] / (stored length of p's row in A): the weights of the
+ *                            gradient of GESPMM_MEAN (correctly rounded fp32 quotient).
+ *   rowptrT  device, int32[K+1], written;  colindT  device, int32[nnz], written (row indices
+ *   of A; the ORDER inside a transposed row is unspecified and can differ from run to run);
+ *   valsT  device, fp32[nnz], written.
+ *   workspace  device memory of at least gespmm_csr_transpose_workspace_bytes(K) bytes,
+ *   4-byte aligned, owned by the caller, contents destroyed; the library allocates nothing.
+ * Errors: GESPMM_ERR_NULL (an output or the workspace is NULL), GESPMM_ERR_BAD_ARG
+ * (negative size, workspace too small), GESPMM_ERR_TOO_LARGE, GESPMM_ERR_HIP.
+ */
+size_t gespmm_csr_transpose_workspace_bytes(int64_t K);   /* pure host function */
+int gespmm_csr_transpose(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr,
+                         const int32_t* colind, const float* vals, int scale_by_row_length,
+                         int32_t* rowptrT, int32_t* colindT, float* valsT, void* workspace,
+                         size_t workspace_bytes, void* stream);
 
 /*
  * Gradient of max / min with respect to B, routed through the positions from

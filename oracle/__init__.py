@@ -22,7 +22,7 @@ OPS = {"sum": 0, "mean": 1, "max": 2, "min": 3}
 
 def build(force: bool = False, src: str = _SRC, lib: str = _LIB) -> str:
     """Compile the oracle with gcc (-O2, OpenMP over rows; no fast-math)."""
-    if force or not os.path.exists(lib):
+    if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(src):
         subprocess.run(["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC", "-o", lib, src,
                         "-lm"], check=True)
     return lib
@@ -40,6 +40,8 @@ def _bind(path):
     L.spmm_oracle_transposed.argtypes = [i64, i64, i64, vp, vp, vp, vp, ci, vp, vp, ci]
     L.spmm_oracle_pool_backward.restype = ci
     L.spmm_oracle_pool_backward.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, vp]
+    L.spmm_oracle_csr_transpose.restype = ci
+    L.spmm_oracle_csr_transpose.argtypes = [i64, i64, vp, vp, vp, ci, vp, vp, vp]
     L.spmm_oracle_max_threads.restype = ci
     return L
 
@@ -163,6 +165,26 @@ def pool_backward(colind, vals, arg, dC, K, _lib_override=None):
     if rc != 0:
         raise ValueError("spmm_oracle_pool_backward: bad argument")
     return dB, Sabs
+
+
+def csr_transpose(rowptr, colind, vals, K, scale_by_row_length=False, _lib_override=None):
+    """CSR of the transposed matrix (stable: rows of A in increasing order inside each result row).
+    Returns (rowptrT int32[K+1], colindT int32[nnz], valsT float32[nnz])."""
+    L = _lib_override or _load()
+    rowptr, colind, vals = _csr(rowptr, colind, vals)
+    M, nnz = rowptr.shape[0] - 1, colind.shape[0]
+    if nnz:
+        assert colind.min() >= 0 and colind.max() < K
+    rowptrT = np.empty(K + 1, dtype=np.int32)
+    colindT = np.empty(nnz, dtype=np.int32)
+    valsT = np.empty(nnz, dtype=np.float32)
+    rc = L.spmm_oracle_csr_transpose(M, K, rowptr.ctypes.data, colind.ctypes.data,
+                                     vals.ctypes.data if vals is not None else None,
+                                     int(bool(scale_by_row_length)), rowptrT.ctypes.data,
+                                     colindT.ctypes.data, valsT.ctypes.data)
+    if rc != 0:
+        raise ValueError("spmm_oracle_csr_transpose: bad argument")
+    return rowptrT, colindT, valsT
 
 
 def compare(op, C, Cref, Sabs):

@@ -36,6 +36,7 @@
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <omp.h>
 
 enum { OP_SUM = 0, OP_MEAN = 1, OP_MAX = 2, OP_MIN = 3 };
@@ -209,6 +210,39 @@ int spmm_oracle_pool_backward(int64_t M, int64_t K, int64_t N, const int32_t* co
       Sabs[k * N + j] += fabs(x);
     }
   }
+  return 0;
+}
+
+/*
+ * The transposed matrix in CSR, built from the CSR of A by a stable counting sort over the
+ * column indices: row k of the result lists, in increasing row order of A, every stored
+ * entry of A whose column is k, as (row index of A, weight).  weight = vals[p], divided by
+ * the stored length of the entry's row when scale_by_row_length is set (then the forward
+ * sum over the result is the gradient of mean).  With it the gradient of sum / mean with
+ * respect to B is the forward operation on the transposed arrays (Sections I, IV-B).
+ */
+int spmm_oracle_csr_transpose(int64_t M, int64_t K, const int32_t* rowptr, const int32_t* colind,
+                              const float* vals, int scale_by_row_length, int32_t* rowptrT,
+                              int32_t* colindT, float* valsT) {
+  if (M < 0 || K < 0 || !rowptr || !rowptrT) return -1;
+  const int64_t nnz = rowptr[M];
+  for (int64_t k = 0; k <= K; ++k) rowptrT[k] = 0;
+  for (int64_t ptr = 0; ptr < nnz; ++ptr) rowptrT[colind[ptr] + 1] += 1;
+  for (int64_t k = 0; k < K; ++k) rowptrT[k + 1] += rowptrT[k];
+  int32_t* next = (int32_t*)malloc((size_t)(K > 0 ? K : 1) * sizeof(int32_t));
+  if (!next) return -1;
+  for (int64_t k = 0; k < K; ++k) next[k] = rowptrT[k];
+  for (int64_t i = 0; i < M; ++i) {
+    const double len = (double)(rowptr[i + 1] - rowptr[i]);
+    for (int64_t ptr = rowptr[i]; ptr < rowptr[i + 1]; ++ptr) {
+      const int32_t place = next[colind[ptr]]++;
+      double w = vals ? (double)vals[ptr] : 1.0;
+      if (scale_by_row_length) w /= len;
+      colindT[place] = (int32_t)i;
+      valsT[place] = (float)w;     /* the correctly rounded fp32 quotient */
+    }
+  }
+  free(next);
   return 0;
 }
 

@@ -55,6 +55,10 @@ def lib():
         L.gespmm_csr_transposed.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, ci, vp]
         L.gespmm_pool_backward.restype = ci
         L.gespmm_pool_backward.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, vp]
+        L.gespmm_csr_transpose_workspace_bytes.restype = ctypes.c_size_t
+        L.gespmm_csr_transpose_workspace_bytes.argtypes = [i64]
+        L.gespmm_csr_transpose.restype = ci
+        L.gespmm_csr_transpose.argtypes = [i64, i64, i64, vp, vp, vp, ci, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.gespmm_plan.restype = ci
         L.gespmm_plan.argtypes = [i64, i64, i64, ci, ctypes.POINTER(gespmm_plan_t)]
         L.gespmm_set_tuning.restype = ci
@@ -161,6 +165,30 @@ def gespmm_csr_transposed(rowptr, colind, vals, dC, op, K, dB=None, stream=None)
     _check(lib().gespmm_csr_transposed(M, K, N, colind.numel(), _ptr(rowptr), _ptr(colind), _ptr(vals),
                                        _ptr(dC), _ptr(dB), code, _stream(stream)))
     return dB
+
+
+def gespmm_csr_transpose_workspace_bytes(K: int) -> int:
+    return int(lib().gespmm_csr_transpose_workspace_bytes(int(K)))
+
+
+def gespmm_csr_transpose(rowptr, colind, vals, K, scale_by_row_length=False, stream=None):
+    """CSR arrays of the transposed matrix: returns (rowptrT, colindT, valsT) as new CUDA tensors
+    (the workspace is a torch tensor allocated here; the library itself allocates nothing)."""
+    import torch
+    M, nnz = rowptr.numel() - 1, colind.numel()
+    assert rowptr.is_cuda and rowptr.dtype == torch.int32 and rowptr.is_contiguous()
+    assert colind.is_cuda and colind.dtype == torch.int32 and colind.is_contiguous()
+    assert vals is None or (vals.is_cuda and vals.dtype == torch.float32 and vals.numel() == nnz)
+    dev = rowptr.device
+    rowptrT = torch.empty(K + 1, dtype=torch.int32, device=dev)
+    colindT = torch.empty(nnz, dtype=torch.int32, device=dev)
+    valsT = torch.empty(nnz, dtype=torch.float32, device=dev)
+    nbytes = gespmm_csr_transpose_workspace_bytes(K)
+    work = torch.empty(max(nbytes // 4, 1), dtype=torch.int32, device=dev)
+    _check(lib().gespmm_csr_transpose(M, K, nnz, _ptr(rowptr), _ptr(colind), _ptr(vals),
+                                      int(bool(scale_by_row_length)), _ptr(rowptrT), _ptr(colindT),
+                                      _ptr(valsT), _ptr(work), nbytes, _stream(stream)))
+    return rowptrT, colindT, valsT
 
 
 def gespmm_pool_backward(colind, vals, arg, dC, K, dB=None, stream=None):

@@ -61,7 +61,8 @@ struct KernelArgs {
   const float* B;         // dense input (the gradient dC for the transposed job)
   float* C;               // dense output (dB for the transposed job)
   const float* Cin;       // finished max/min result, read by the position job
-  int32_t* arg;           // output of the position job
+  int32_t* arg;           // output of the position job; row indices of the transposed arrays
+  int32_t* cursor;        // next free place of every transposed row (structure-transpose job)
 };
 
 // ------------------------------------------------------------------ vectors --
@@ -382,6 +383,38 @@ struct TransposedRows {
   __device__ static void end(State&, const KernelArgs&, int64_t, bool, int, const int (&)[T]) {}
 };
 
+// Building the CSR of the transposed matrix: every stored entry (i, k, val) takes the next
+// free place of transposed row k (an atomic counter per row, preset to the row's start)
+// and writes (i, val) there - val divided by the length of row i when the weights are
+// wanted for the gradient of mean.  Runs as the <V=1, G=1, T=1> instance: 64 slots, one
+// lane per entry.  KernelArgs::C is the value array and ::arg the index array written.
+template <int V, int T>
+struct ScatterRows {
+  struct State { float len; int row; };
+
+  __device__ static void begin(State& s, const KernelArgs&, int64_t row, int row_len, const int (&)[T]) {
+    s.len = (float)row_len;
+    s.row = (int)row;
+  }
+
+  template <int U>
+  __device__ static void pass(State& s, const KernelArgs& a, const int2* ka, int, int first, int stride, int left,
+                              const int (&col)[T], const int (&)[T]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (u < left && col[0] == 0) {
+        const int2 e = ka[first + u * stride];
+        const int place = __hip_atomic_fetch_add(a.cursor + e.x, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        a.arg[place] = s.row;
+        a.C[place] = a.is_mean ? __int_as_float(e.y) / s.len : __int_as_float(e.y);
+      }
+    }
+  }
+
+  template <int G> __device__ static void combine(State&) {}
+  __device__ static void end(State&, const KernelArgs&, int64_t, bool, int, const int (&)[T]) {}
+};
+
 // P: row policy; V: floats per lane per load; G: lanes per slot; T: column tiles per lane.
 template <class P, int V, int G, int T>
 __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
@@ -542,10 +575,90 @@ __global__ void __launch_bounds__(kBlock) pool_backward_scatter(int64_t total, i
   }
 }
 
+// ------------------------------------------- column counts and their scan ----
+constexpr int kScanTile = 4 * kBlock;             // elements one workgroup scans
+
+__global__ void __launch_bounds__(kBlock) count_columns(int64_t nnz, const int32_t* __restrict__ colind, int32_t* __restrict__ counts) {
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  for (int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x; p < nnz; p += stride)
+    __hip_atomic_fetch_add(counts + colind[p], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Exclusive scan of one tile held as 4 values per thread; returns this thread's prefix and
+// leaves the tile total in *total (same for all threads).
+__device__ __forceinline__ int tile_exclusive_scan(const int (&v)[4], int* total) {
+  __shared__ int wave_sums[kWavesPerBlock];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+  const int mine = v[0] + v[1] + v[2] + v[3];
+  int incl = mine;
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const int up = __shfl_up(incl, off, kWave);
+    if (lane >= off) incl += up;
+  }
+  __syncthreads();                                 // previous use of wave_sums is over
+  if (lane == kWave - 1) wave_sums[wave] = incl;
+  __syncthreads();
+  int before = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < kWavesPerBlock; ++w) {
+    if (w < wave) before += wave_sums[w];
+    all += wave_sums[w];
+  }
+  *total = all;
+  return before + incl - mine;
+}
+
+// In-place exclusive scan inside every tile of kScanTile elements; tile totals to sums[].
+__global__ void __launch_bounds__(kBlock) scan_tiles(int32_t* __restrict__ data, int64_t n, int32_t* __restrict__ sums) {
+  const int64_t base = (int64_t)blockIdx.x * kScanTile + threadIdx.x * 4;
+  int v[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) v[j] = base + j < n ? data[base + j] : 0;
+  int total;
+  int prefix = tile_exclusive_scan(v, &total);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (base + j < n) data[base + j] = prefix;
+    prefix += v[j];
+  }
+  if (threadIdx.x == 0) sums[blockIdx.x] = total;
+}
+
+// One workgroup: in-place exclusive scan of the tile totals, tile after tile with a carry.
+__global__ void __launch_bounds__(kBlock) scan_sums(int32_t* __restrict__ sums, int64_t count) {
+  int carry = 0;
+  for (int64_t tile = 0; tile < count; tile += kScanTile) {
+    const int64_t base = tile + threadIdx.x * 4;
+    int v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = base + j < count ? sums[base + j] : 0;
+    int total;
+    int prefix = carry + tile_exclusive_scan(v, &total);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (base + j < count) sums[base + j] = prefix;
+      prefix += v[j];
+    }
+    carry += total;
+  }
+}
+
+// data[i] += (scanned) total of the tiles before i's tile; cursor[i] = data[i] for i < K.
+__global__ void __launch_bounds__(kBlock) add_tile_offsets(int32_t* __restrict__ data, int64_t n, const int32_t* __restrict__ sums,
+                                                          int32_t* __restrict__ cursor, int64_t K) {
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) {
+    const int value = data[i] + sums[i / kScanTile];
+    data[i] = value;
+    if (i < K) cursor[i] = value;
+  }
+}
+
 // --------------------------------------------------------------- host side --
 using MainKernel = void (*)(const KernelArgs);
 
-enum Job { kJobAdd = kAdd, kJobMax = kMax, kJobMin = kMin, kJobArg = 3, kJobTransposed = 4 };
+enum Job { kJobAdd = kAdd, kJobMax = kMax, kJobMin = kMin, kJobArg = 3, kJobTransposed = 4, kJobScatter = 5 };
 
 template <template <int, int> class P, int V>
 MainKernel pick_gt(int G, int T) {
@@ -570,6 +683,7 @@ MainKernel pick_job(int job, int G, int T) {
     case kJobMin: return pick_gt<MinRows, V>(G, T);
     case kJobArg: return pick_gt<ArgRows, V>(G, T);
     case kJobTransposed: return pick_gt<TransposedRows, V>(G, T);
+    case kJobScatter: return (V == 1 && G == 1 && T == 1) ? chunk_kernel<ScatterRows<1, 1>, 1, 1, 1> : nullptr;
     default: return nullptr;
   }
 }
@@ -674,6 +788,8 @@ struct ChunkLaunch {
   float* init_target = nullptr;        // M x N output preset by init_rows, or nullptr
   float empty_value = 0.0f, split_value = 0.0f;
   bool timed = false;                  // bracket the chunk kernel with profiling events
+  int32_t* cursor = nullptr;           // structure-transpose job only
+  bool one_lane_per_entry = false;     // use the <V=1, G=1, T=1> instance whatever N is
 };
 
 int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
@@ -681,6 +797,14 @@ int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
                            (uintptr_t)L.also_aligned) & 15u) == 0;
   gespmm_plan_t plan;
   make_plan(L.M, L.N, L.nnz, aligned16, &plan);
+  if (L.one_lane_per_entry) {
+    plan.vec = 1;
+    plan.lanes_per_row = 1;
+    plan.tiles_per_lane = 1;
+    plan.slots = kWave;
+    plan.col_blocks = 1;
+    plan.short_len = 16;
+  }
   MainKernel kernel = pick_kernel(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
   if (!kernel) return GESPMM_ERR_BAD_ARG;
   if (plan.col_blocks > 65535) return GESPMM_ERR_TOO_LARGE;   // grid.y limit (N beyond ~33 million)
@@ -720,6 +844,7 @@ int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
   a.C = L.dense_out;
   a.Cin = L.result_in;
   a.arg = L.arg;
+  a.cursor = L.cursor;
   const bool timed = L.timed && g_profiling && g_ev_used < (int)g_ev_start.size();
   if (timed && hipEventRecord(g_ev_start[g_ev_used], stream) != hipSuccess) return GESPMM_ERR_HIP;
   hipLaunchKernelGGL(kernel, dim3((unsigned)plan.grid_x, (unsigned)plan.col_blocks), dim3(kBlock), (size_t)plan.lds_bytes, stream, a);
@@ -825,6 +950,57 @@ int gespmm_csr_transposed(int64_t M, int64_t K, int64_t N, int64_t nnz, const in
   L.rowptr = rowptr; L.colind = colind; L.vals = vals;
   L.dense_in = dC; L.dense_out = dB;
   L.is_mean = op == GESPMM_MEAN;
+  return launch_chunks(L, stream);
+}
+
+size_t gespmm_csr_transpose_workspace_bytes(int64_t K) {
+  if (K < 0) return 0;
+  const int64_t tiles = (K + 1 + kScanTile - 1) / kScanTile;
+  return (size_t)(K + tiles + 4) * sizeof(int32_t);
+}
+
+int gespmm_csr_transpose(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+                         const float* vals, int scale_by_row_length, int32_t* rowptrT, int32_t* colindT,
+                         float* valsT, void* workspace, size_t workspace_bytes, void* stream_) {
+  if (M < 0 || K < 0 || nnz < 0) return GESPMM_ERR_BAD_ARG;
+  if (M >= INT32_MAX || K >= INT32_MAX || nnz > INT32_MAX - (1 << kMaxChunkShift)) return GESPMM_ERR_TOO_LARGE;
+  if (nnz > 0 && (M == 0 || K == 0)) return GESPMM_ERR_BAD_ARG;
+  if (!rowptrT) return GESPMM_ERR_NULL;
+  if (nnz > 0 && (!rowptr || !colind || !colindT || !valsT)) return GESPMM_ERR_NULL;
+  if (!workspace) return GESPMM_ERR_NULL;
+  if (workspace_bytes < gespmm_csr_transpose_workspace_bytes(K)) return GESPMM_ERR_BAD_ARG;
+  hipStream_t stream = (hipStream_t)stream_;
+  int32_t* cursor = static_cast<int32_t*>(workspace);          // K entries
+  int32_t* sums = cursor + K;                                  // one per scan tile
+  const int64_t n = K + 1;
+  const int64_t tiles = (n + kScanTile - 1) / kScanTile;
+
+  // column counts -> exclusive scan -> row starts of the transposed matrix (and the cursors)
+  int st = launch_fill(reinterpret_cast<float*>(rowptrT), n, 0.0f, stream);
+  if (st != GESPMM_OK) return st;
+  if (nnz > 0) {
+    int64_t blocks = (nnz + kBlock - 1) / kBlock;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(count_columns, dim3((unsigned)blocks), dim3(kBlock), 0, stream, nnz, colind, rowptrT);
+  }
+  hipLaunchKernelGGL(scan_tiles, dim3((unsigned)tiles), dim3(kBlock), 0, stream, rowptrT, n, sums);
+  hipLaunchKernelGGL(scan_sums, dim3(1), dim3(kBlock), 0, stream, sums, tiles);
+  {
+    int64_t blocks = (n + kBlock - 1) / kBlock;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(add_tile_offsets, dim3((unsigned)blocks), dim3(kBlock), 0, stream, rowptrT, n, sums, cursor, K);
+  }
+  if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
+  if (nnz == 0) return GESPMM_OK;
+
+  // every stored entry takes the next free place of its column's row
+  ChunkLaunch L;
+  L.job = kJobScatter;
+  L.M = M; L.N = 1; L.nnz = nnz;
+  L.rowptr = rowptr; L.colind = colind; L.vals = vals;
+  L.dense_out = valsT; L.arg = colindT; L.cursor = cursor;
+  L.is_mean = scale_by_row_length != 0;
+  L.one_lane_per_entry = true;
   return launch_chunks(L, stream);
 }
 

@@ -400,5 +400,37 @@ def pin_pool_backward_numeric_gradient(O):
     _same_bits(dB, want)
 
 
-GRAD_PINS = (pin_arg_brute_force_with_ties, pin_arg_consistent_with_forward, pin_transposed_dense_and_scipy,
+def pin_csr_transpose(O):
+    """Transposed CSR against scipy, as a permutation of the entries, and through the forward op."""
+    rp, ci, v = graphgen.random_csr(45, 31, 5.0, 95, empty_frac=0.2, duplicates=True, sort_cols=False)
+    rpT, ciT, vT = O.csr_transpose(rp, ci, v, 31)
+    rows = np.repeat(np.arange(45), np.diff(rp))
+    # every stored entry appears exactly once, under its column, rows of A ascending (stable)
+    assert rpT[0] == 0 and rpT[-1] == len(ci) and np.array_equal(np.diff(rpT), np.bincount(ci, minlength=31))
+    order = np.argsort(ci, kind="stable")
+    assert np.array_equal(ciT, rows[order]) and np.array_equal(vT.view(np.uint32), v[order].view(np.uint32))
+    A = sp.csr_matrix((v.astype(np.float64), ci, rp), shape=(45, 31))
+    AT = sp.csr_matrix((vT.astype(np.float64), ciT, rpT), shape=(31, 45))
+    assert abs(A.T - AT).max() < 1e-15
+    # mean scaling: weights divided by the length of the entry's own row, rounded once to fp32
+    _, _, vS = O.csr_transpose(rp, ci, v, 31, scale_by_row_length=True)
+    lens = np.diff(rp).astype(np.float64)
+    want = (v[order].astype(np.float64) / lens[rows[order]]).astype(np.float32)
+    assert np.array_equal(vS.view(np.uint32), want.view(np.uint32))
+    # vals == NULL stands for ones
+    _, ciN, vN = O.csr_transpose(rp, ci, None, 31)
+    assert np.array_equal(ciN, ciT) and (vN == 1).all()
+    # the forward sum over the transposed arrays is the transposed product (gradient of sum / mean)
+    dC = graphgen.random_dense(45, 4, 96)
+    for scale, op in ((False, "sum"), (True, "mean")):
+        rT, cT, wT = O.csr_transpose(rp, ci, v, 31, scale_by_row_length=scale)
+        fwd, fs = O.spmm(rT, cT, wT, dC, "sum")
+        ref, rs = O.spmm_transposed(rp, ci, v, dC, op, 31)
+        _close(fwd, ref, scale=rs + 1e-30, tol=1e-7)       # the weights were rounded to fp32 once
+    # empty matrix and trailing empty columns
+    rT, cT, wT = O.csr_transpose(np.zeros(4, np.int32), np.zeros(0, np.int32), None, 6)
+    assert not rT.any() and cT.size == 0
+
+
+GRAD_PINS = (pin_csr_transpose, pin_arg_brute_force_with_ties, pin_arg_consistent_with_forward, pin_transposed_dense_and_scipy,
              pin_transposed_is_the_adjoint, pin_pool_backward_numeric_gradient)

@@ -155,6 +155,48 @@ def test_pool_backward_matches_oracle_and_forward_positions(gs):
     assert not out.cpu().numpy().any()
 
 
+def check_transpose(gs, rp, ci, v, K, scale, label=""):
+    """Transposed CSR: row starts exact; inside a row the order is free, so rows are compared as sorted
+    lists of (row index of A, value bits)."""
+    say(f"  case transpose {label} M={len(rp) - 1} K={K} nnz={len(ci)} scale={scale}")
+    rpT, ciT, vT = gs.gespmm_csr_transpose(dev(rp), dev(ci), dev(v), K, scale_by_row_length=scale)
+    torch.cuda.synchronize()
+    rpT, ciT, vT = rpT.cpu().numpy(), ciT.cpu().numpy(), vT.cpu().numpy()
+    rpR, ciR, vR = oracle.csr_transpose(rp, ci, v, K, scale_by_row_length=scale)
+    assert np.array_equal(rpT, rpR), f"{label}: row starts"
+    rowsT = np.repeat(np.arange(K, dtype=np.int64), np.diff(rpR))
+    key_g = np.lexsort((vT.view(np.uint32), ciT, rowsT))
+    key_r = np.lexsort((vR.view(np.uint32), ciR, rowsT))
+    assert np.array_equal(ciT[key_g], ciR[key_r]), f"{label}: row indices"
+    assert np.array_equal(vT.view(np.uint32)[key_g], vR.view(np.uint32)[key_r]), f"{label}: values"
+    return rpT, ciT, vT
+
+
+def test_transpose_structure_small_and_degenerate(gs):
+    for M, K, mean_len, seed, kw in ((500, 350, 9.0, 1, dict(empty_frac=0.1, duplicates=True, sort_cols=False,
+                                                              long_rows=((9, 2000),))),
+                                     (3000, 5000, 2.0, 2, dict(empty_frac=0.5)),          # several scan tiles
+                                     (1, 1, 1.0, 3, {}), (40, 3, 30.0, 4, dict(duplicates=True))):
+        rp, ci, v = graphgen.random_csr(M, K, mean_len, seed, **kw)
+        for scale in (False, True):
+            check_transpose(gs, rp, ci, v, K, scale, label=f"M={M}")
+        check_transpose(gs, rp, ci, None, K, False, label=f"M={M} vals=NULL")
+    rpT, ciT, vT = check_transpose(gs, np.zeros(4, np.int32), np.zeros(0, np.int32), None, 7, False, label="nnz=0")
+    assert not rpT.any()
+
+
+def test_gradient_of_sum_and_mean_through_the_transposed_arrays(gs):
+    rp, ci, v = graphgen.random_csr(900, 700, 10.0, 6, empty_frac=0.05, long_rows=((3, 3000),), duplicates=True)
+    dC = graphgen.random_dense(900, 64, 7)
+    for scale, op in ((False, "sum"), (True, "mean")):
+        rpT, ciT, vT = gs.gespmm_csr_transpose(dev(rp), dev(ci), dev(v), 700, scale_by_row_length=scale)
+        out = gs.gespmm_csr(rpT, ciT, vT, dev(dC), "sum")
+        torch.cuda.synchronize()
+        ref, sabs = oracle.spmm_transposed(rp, ci, v, dC, op, 700)
+        ok, worst = oracle.compare("sum", out.cpu().numpy(), ref, sabs)
+        assert ok, (op, worst)
+
+
 @pytest.mark.parametrize("which", [2, 4])
 def test_gradient_side_on_workloads(gs, which):
     w = graphgen.workload(which)
@@ -180,3 +222,4 @@ def test_gradient_side_on_workloads(gs, which):
             check_pool_backward(gs, w.colind, vals, arg, dC, w.K, label=w.name)
     for op in ("sum", "mean"):
         check_transposed(gs, w.rowptr, w.colind, vals, dC, op, w.K, label=w.name, dA=dA)
+    check_transpose(gs, w.rowptr, w.colind, vals, w.K, True, label=w.name)

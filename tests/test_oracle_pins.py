@@ -57,6 +57,10 @@ MUTANTS = [
     ("pool_forgets_the_weight", "const double x = (vals ? (double)vals[ptr] : 1.0) * (double)dC[i * N + j];",
      "const double x = (double)dC[i * N + j];"),
     ("pool_adds_to_the_row_index", "dBref[k * N + j] += x;", "dBref[(i % K) * N + j] += x;", 1),
+    ("transpose_prefix_sum_skipped", "rowptrT[k + 1] += rowptrT[k];", ";"),
+    ("transpose_stores_column", "colindT[place] = (int32_t)i;", "colindT[place] = colind[ptr];"),
+    ("transpose_scale_inverted", "if (scale_by_row_length) w /= len;", "if (scale_by_row_length) w *= len;"),
+    ("transpose_places_not_advanced", "next[colind[ptr]]++;", "next[colind[ptr]];"),
     ("arg_drop_last_term", "ptr < row_end; ++ptr", "ptr < row_end - 1; ++ptr", 1),
     ("arg_column_of_B_flipped", "B[k * N + j]", "B[k * N + (N - 1 - j)]", 1),
     ("arg_null_vals_as_zero", ": 1.0;", ": 0.0;", 1),
@@ -81,6 +85,9 @@ class _Mutant:
 
     def pool_backward(self, colind, vals, arg, dC, K):
         return oracle.pool_backward(colind, vals, arg, dC, K, _lib_override=self.lib)
+
+    def csr_transpose(self, rowptr, colind, vals, K, scale_by_row_length=False):
+        return oracle.csr_transpose(rowptr, colind, vals, K, scale_by_row_length, _lib_override=self.lib)
 
 
 @pytest.mark.parametrize("name,old,new,which", MUTANTS, ids=[m[0] for m in MUTANTS])
