@@ -114,6 +114,10 @@ def gradient_bytes(kind, M, K, N, nnz):
         return 4 * K * N + walk + 4 * M * N + 4 * nnz * N
     if kind == "pool_backward":                        # zero dB + arg, dC, colind[arg], vals[arg], one add per element
         return 4 * K * N + 20 * M * N
+    if kind == "csr_transpose":                        # counts (read colind, add), scan, walk, write row ids + values
+        return 4 * nnz + 4 * nnz + 16 * (K + 1) + walk + 8 * nnz
+    if kind == "forward_on_transposed":                # a forward call with the roles of M and K swapped
+        return model_bytes(K, N, nnz)
     raise ValueError(kind)
 
 
@@ -131,6 +135,9 @@ def time_gradients(args, gs, torch, graphgen, dev):
             "transposed": lambda: gs.gespmm_csr_transposed(case.rp, case.ci, case.v, dC, "sum", w.K, dB=dB),
             "pool_backward": lambda: gs.gespmm_pool_backward(case.ci, case.v, arg, dC, w.K, dB=dB),
         }
+        rpT, ciT, vT = gs.gespmm_csr_transpose(case.rp, case.ci, case.v, w.K)
+        calls["csr_transpose"] = lambda: gs.gespmm_csr_transpose(case.rp, case.ci, case.v, w.K)
+        calls["forward_on_transposed"] = lambda: gs.gespmm_csr(rpT, ciT, vT, dC, "sum", C=dB)
         for kind, call in calls.items():                # "arg" runs first and leaves valid positions behind
             steps = max(10, args.steps // (10 if w.nnz > 5e7 else 1))
             for _ in range(3):
@@ -147,7 +154,7 @@ def time_gradients(args, gs, torch, graphgen, dev):
             print(f"{name:20s} N={N:4d} {kind:14s} {ms*1e3:10.1f} us  model {gb/1e9:8.3f} GB  "
                   f"{gb/(ms*1e-3)/1e9:8.1f} GB/s ({gb/(ms*1e-3)/1e9/HBM_PEAK_GBPS*100:5.1f}% of HBM peak)",
                   file=sys.stderr, flush=True)
-        del case, dC, arg, dB
+        del case, dC, arg, dB, rpT, ciT, vT
         torch.cuda.empty_cache()
     return rows
 
