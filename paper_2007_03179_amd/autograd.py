@@ -1,0 +1,79 @@
+"""The SpMM-like operation as a PyTorch autograd function (paper: Section IV-B, "wrap the kernel
+inside a custom autograd function ... an aggregation step on the graph").
+
+Thin glue over the C ABI: the forward pass is gespmm_csr (sum, mean) or gespmm_csr_arg (max, min);
+the backward pass with respect to the dense features is gespmm_csr on the transposed arrays
+(built once per graph by gespmm_csr_transpose and cached) or gespmm_pool_backward.  The edge
+values are treated as constants (no gradient), as in the paper's operator.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as _b
+
+
+class CsrGraph:
+    """A sparse matrix A (M x K) in CSR on the GPU, plus lazily built transposed arrays."""
+
+    def __init__(self, rowptr, colind, vals, K):
+        assert rowptr.is_cuda and rowptr.dtype == torch.int32
+        assert colind.is_cuda and colind.dtype == torch.int32
+        assert vals is None or (vals.is_cuda and vals.dtype == torch.float32)
+        self.rowptr, self.colind, self.vals = rowptr.contiguous(), colind.contiguous(), vals
+        self.M, self.K = rowptr.numel() - 1, int(K)
+        self._transposed = {}
+
+    def transposed(self, mean: bool):
+        """(rowptrT, colindT, valsT); with mean weights val / row length when `mean`."""
+        if mean not in self._transposed:
+            self._transposed[mean] = _b.gespmm_csr_transpose(self.rowptr, self.colind, self.vals, self.K,
+                                                             scale_by_row_length=mean)
+        return self._transposed[mean]
+
+
+class _SpMM(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, B, graph, op):
+        B = B.contiguous()
+        ctx.graph, ctx.op = graph, op
+        if op in ("max", "min"):
+            C, arg = _b.gespmm_csr_arg(graph.rowptr, graph.colind, graph.vals, B, op)
+            ctx.save_for_backward(arg)
+            ctx.mark_non_differentiable(arg)
+            return C
+        return _b.gespmm_csr(graph.rowptr, graph.colind, graph.vals, B, op)
+
+    @staticmethod
+    def backward(ctx, dC):
+        graph, op = ctx.graph, ctx.op
+        dC = dC.contiguous()
+        if op in ("max", "min"):
+            (arg,) = ctx.saved_tensors
+            dB = _b.gespmm_pool_backward(graph.colind, graph.vals, arg, dC, graph.K)
+        else:
+            rowptrT, colindT, valsT = graph.transposed(op == "mean")
+            dB = _b.gespmm_csr(rowptrT, colindT, valsT, dC, "sum")
+        return dB, None, None
+
+
+def spmm(graph: CsrGraph, B: torch.Tensor, op: str = "sum") -> torch.Tensor:
+    """C = A (x) B with gradient with respect to B.  B: (K, N) float32 CUDA tensor."""
+    assert op in _b.OPS and B.is_cuda and B.dtype == torch.float32 and B.shape[0] == graph.K
+    return _SpMM.apply(B, graph, op)
+
+
+class GraphConv(torch.nn.Module):
+    """One graph-convolution layer: aggregate(A, X W) + b, the layer both GCN (op='sum' with
+    normalised edge values) and GraphSAGE-pool (op='max') are built from (Section V-E)."""
+
+    def __init__(self, in_features, out_features, op="sum", bias=True):
+        super().__init__()
+        self.op = op
+        self.weight = torch.nn.Parameter(torch.empty(in_features, out_features))
+        self.bias = torch.nn.Parameter(torch.zeros(out_features)) if bias else None
+        torch.nn.init.xavier_uniform_(self.weight)
+
+    def forward(self, graph: CsrGraph, X):
+        out = spmm(graph, X @ self.weight, self.op)
+        return out if self.bias is None else out + self.bias

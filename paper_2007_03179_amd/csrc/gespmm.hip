@@ -400,13 +400,20 @@ struct ScatterRows {
   template <int U>
   __device__ static void pass(State& s, const KernelArgs& a, const int2* ka, int, int first, int stride, int left,
                               const int (&col)[T], const int (&)[T]) {
+    int2 e[U];
+    int place[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {          // all counters first: the returns come back together
+      const bool live = u < left && col[0] == 0;
+      e[u] = ka[first + (live ? u * stride : 0)];
+      place[u] = -1;
+      if (live) place[u] = __hip_atomic_fetch_add(a.cursor + e[u].x, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      if (u < left && col[0] == 0) {
-        const int2 e = ka[first + u * stride];
-        const int place = __hip_atomic_fetch_add(a.cursor + e.x, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        a.arg[place] = s.row;
-        a.C[place] = a.is_mean ? __int_as_float(e.y) / s.len : __int_as_float(e.y);
+      if (place[u] >= 0) {
+        a.arg[place[u]] = s.row;
+        a.C[place[u]] = a.is_mean ? __int_as_float(e[u].y) / s.len : __int_as_float(e[u].y);
       }
     }
   }
