@@ -65,6 +65,25 @@ def cpu_baseline(w, B, op, budget_s=12.0, max_passes=60):
                       f"mean {mean:.3f} s per pass"}
 
 
+def time_graph_replay(gs, torch, case, op, steps, calls_per_graph=20):
+    """Step time when `calls_per_graph` whole calls are captured into one HIP graph and replayed
+    (the way a launch-bound inner loop would be run)."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for _ in range(calls_per_graph):
+            gs.gespmm_csr(case.rp, case.ci, case.v, case.B, op, C=case.C)
+    replays = max(1, steps // calls_per_graph)
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(replays):
+        graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / (replays * calls_per_graph)
+
+
 class DeviceCase:
     """One workload at one width, resident on the GPU."""
 
@@ -172,10 +191,12 @@ def sweep(args, gs, torch, graphgen, dev):
                 k = case.time(gs, torch, op, steps, args.warmup)                      # kernel bracketed
                 r = case.time(gs, torch, op, steps, args.warmup, bracket_kernel=False)  # clean step time
                 r["main_kernel_ms"], r["model_GBps_kernel"] = k["main_kernel_ms"], k["model_GBps_kernel"]
+                r["graph_ms_per_step"] = time_graph_replay(gs, torch, case, op, steps) if w.nnz * N < 5e8 else None
                 rows.append(r)
                 print(f"{r['workload']:20s} N={N:4d} {op:5s} step {r['ms_per_step']*1e3:9.1f} us  kernel "
                       f"{r['main_kernel_ms']*1e3:9.1f} us  {r['gflops']:8.1f} GFLOP/s  model "
-                      f"{r['model_GBps_step']:8.1f} GB/s ({r['model_GBps_step']/HBM_PEAK_GBPS*100:5.1f}% of HBM peak)",
+                      f"{r['model_GBps_step']:8.1f} GB/s ({r['model_GBps_step']/HBM_PEAK_GBPS*100:5.1f}% of HBM peak)"
+                      + (f"  in a HIP graph {r['graph_ms_per_step']*1e3:7.1f} us" if r["graph_ms_per_step"] else ""),
                       file=sys.stderr, flush=True)
             del case
             torch.cuda.empty_cache()

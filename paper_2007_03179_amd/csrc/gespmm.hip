@@ -39,9 +39,9 @@ constexpr int kBlock = kWave * kWavesPerBlock;
 constexpr int kMinChunkShift = 4;               // chunks hold 16 .. 1024 stored entries
 constexpr int kMaxChunkShift = 10;
 constexpr int kXcds = 8;
-// 16-byte gathers a lane issues before it waits: narrow slots (few lanes per row) carry
-// less data per load instruction, so they keep more loads in flight
-constexpr int loads_in_flight(int G) { return G <= 8 ? 8 : 4; }
+// 16-byte gathers a lane issues before it waits (measured: 8 beats 4 and 16 for slots of
+// up to 16 lanes; wider slots already move 512 B and more per load instruction)
+constexpr int loads_in_flight(int G) { return G <= 16 ? 8 : 4; }
 
 enum Fold { kAdd = 0, kMax = 1, kMin = 2 };
 
@@ -717,16 +717,25 @@ constexpr int64_t kResidentWaves = 8192;
 void make_plan(int64_t M, int64_t N, int64_t nnz, bool aligned16, gespmm_plan_t* p) {
   const int vec = (aligned16 && N > 0 && N % 4 == 0) ? 4 : 1;
   const int64_t ncv = N > 0 ? (N + vec - 1) / vec : 1;     // vector columns to cover
-  // widest slot that is still <= 16 lanes for wide N, so several entries of a row are in
-  // flight per step; two tiles per lane from 32 vector columns up (sparse chunk read once)
+  // Column blocks of one 128-byte line (8 lanes x 16 bytes) up to N = 128, of two lines
+  // beyond; wider N is covered by grid.y.  The blocks of one grid.y index run together in
+  // time, so the part of B that is live at any moment is K x 128 (or 256) bytes, which the
+  // L2s keep far better than whole rows of B; the sparse arrays are re-read per block,
+  // which costs 8 bytes per entry against 128 gathered.
   int G = next_pow2(ncv), T = 1;
-  if (G > 16) { G /= 2; T = 2; }
-  if (ncv > 64 && G * T < 128) { G = 64; T = 2; }
+  if (vec == 4) {
+    if (G > 8) G = N <= 128 ? 8 : 16;
+  } else if (G > 16) {
+    G /= 2;
+    T = 2;
+    if (ncv > 64 && G * T < 128) { G = 64; T = 2; }
+  }
   if (g_force_g > 0) G = g_force_g;
   if (g_force_t > 0) T = g_force_t;
-  // chunk size: 256 stored entries, 512 for narrow column blocks (less data per entry);
-  // halved while the problem has too few chunks to fill the chip
-  int shift = (int64_t)vec * G * T <= 16 ? 9 : 8;
+  // chunk size: 256 stored entries; 512 for column blocks of up to 16 floats (less data
+  // per entry) and for matrices with long rows (fewer split rows); halved while the
+  // problem has too few chunks to fill the chip
+  int shift = ((int64_t)vec * G * T <= 16 || (M > 0 && nnz / M >= 128)) ? 9 : 8;
   while (shift > 6 && ((nnz + (1ll << shift) - 1) >> shift) < kResidentWaves) --shift;
   if (g_force_shift >= kMinChunkShift) shift = g_force_shift;
   p->vec = vec;

@@ -93,9 +93,9 @@ def test_argument_errors_come_before_any_device_work(L):
     assert L.gespmm_calibration_copy(p, p, 0, None) == 0
 
 
-@pytest.mark.parametrize("N,G,T,blocks", [(8, 2, 1, 1), (16, 4, 1, 1), (32, 8, 1, 1), (64, 16, 1, 1),
-                                          (128, 16, 2, 1), (256, 32, 2, 1), (512, 64, 2, 1),
-                                          (1024, 64, 2, 2), (4, 1, 1, 1), (100, 16, 2, 1)])
+@pytest.mark.parametrize("N,G,T,blocks", [(8, 2, 1, 1), (16, 4, 1, 1), (32, 8, 1, 1), (64, 8, 1, 2),
+                                          (128, 8, 1, 4), (256, 16, 1, 4), (512, 16, 1, 8),
+                                          (1024, 16, 1, 16), (4, 1, 1, 1), (100, 8, 1, 4)])
 def test_plan_covers_all_columns_vectorised(N, G, T, blocks):
     p = gs.gespmm_plan(1000, N, 10_000)
     assert p["vec"] == 4 and (p["lanes_per_row"], p["tiles_per_lane"], p["col_blocks"]) == (G, T, blocks)
@@ -124,21 +124,23 @@ def test_tuning_override_is_validated():
         assert (p["lanes_per_row"], p["tiles_per_lane"], p["xcd_remap"], p["col_blocks"]) == (32, 1, 0, 1)
         gs.gespmm_set_tuning(chunk_nnz=1024, short_len=5)
         p = gs.gespmm_plan(1000, 64, 10_000)
-        assert (p["lanes_per_row"], p["chunk_nnz"], p["short_len"], p["chunks"]) == (16, 1024, 5, 10)
+        assert (p["lanes_per_row"], p["chunk_nnz"], p["short_len"], p["chunks"]) == (8, 1024, 5, 10)
         assert p["lds_bytes"] == 4 * (1024 + 64) * 8
         for bad in (dict(chunk_nnz=100), dict(chunk_nnz=2048), dict(chunk_nnz=8), dict(short_len=5000)):
             with pytest.raises(gs.GespmmError):
                 gs.gespmm_set_tuning(**bad)
     finally:
         gs.gespmm_set_tuning()
-    assert gs.gespmm_plan(1000, 64, 10_000)["lanes_per_row"] == 16
+    assert gs.gespmm_plan(1000, 64, 10_000)["lanes_per_row"] == 8
 
 
 def test_chunk_size_follows_width_and_problem_size():
     big = 100_000_000
     plans = [gs.gespmm_plan(10**6, N, big) for N in (8, 16, 32, 64, 128, 512)]
     assert [p["chunk_nnz"] for p in plans] == [512, 512, 256, 256, 256, 256]
-    assert [p["short_len"] for p in plans] == [16, 16, 16, 8, 8, 2]
+    assert [p["short_len"] for p in plans] == [16, 16, 16, 16, 16, 8]
+    # long rows (mean length >= 128): larger chunks, fewer split rows
+    assert gs.gespmm_plan(232_965, 64, 114_693_532)["chunk_nnz"] == 512
     assert all(p["lds_bytes"] == 4 * (p["chunk_nnz"] + 64) * 8 for p in plans)
     # small problems: smaller chunks, so the rows spread over more wavefronts
     assert gs.gespmm_plan(19717, 512, 88_648)["chunk_nnz"] == 64
