@@ -30,11 +30,11 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 # run and one WRITE_SIZE run, each scaled by the calibration copy kernel of known size;
 # the summaries are under profiles/).  Key: "<workload>/N<width>/<op>".  Missing = null.
 MEASURED_TRAFFIC_BYTES = {
-    "large_dense_degree/N64/sum": 25.618e9,   # profiles/spmm_chunks_large_dense_degree_N64_sum.md
-    "general_ops/N128/sum": 1.1635e9,         # profiles/spmm_chunks_general_ops_N128_sum.md
-    "skew_narrow/N8/sum": 0.63301e9,          # profiles/spmm_chunks_skew_narrow_N8_sum.md
-    "skew_narrow/N32/sum": 1.2062e9,          # profiles/spmm_chunks_skew_narrow_N32_sum.md
-    "width_sweep/N512/sum": 0.19870e9,        # profiles/spmm_chunks_width_sweep_N512_sum.md
+    "large_dense_degree/N64/sum": 22.991e9,   # profiles/chunk_kernel_large_dense_degree_N64_sum.md
+    "general_ops/N128/sum": 1.0056e9,         # profiles/chunk_kernel_general_ops_N128_sum.md
+    "skew_narrow/N8/sum": 0.63295e9,          # profiles/chunk_kernel_skew_narrow_N8_sum.md
+    "skew_narrow/N32/sum": 1.2061e9,          # profiles/chunk_kernel_skew_narrow_N32_sum.md
+    "width_sweep/N512/sum": 0.18050e9,        # profiles/chunk_kernel_width_sweep_N512_sum.md
 }
 
 
@@ -272,12 +272,12 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: M=K={w.M}, nnz={w.nnz}, N={N}, reduce={op}, seed={w.seed}",
                    "csr_hash": desc["csr_hash"], "max_row": desc["max_row"],
-                   "kernel": f"spmm_chunks vec={plan['vec']} G={plan['lanes_per_row']} "
-                             f"T={plan['tiles_per_lane']} S={plan['chunk_nnz']}"},
+                   "kernel": f"chunk_kernel<FoldRows> vec={plan['vec']} G={plan['lanes_per_row']} "
+                             f"T={plan['tiles_per_lane']} S={plan['chunk_nnz']} col_blocks={plan['col_blocks']}"},
         "model_GBps_whole_step": r["model_GBps_step"],
         "frac_of_hbm_peak_whole_step": r["model_GBps_step"] / HBM_PEAK_GBPS,
         "compulsory_bytes": r["compulsory_bytes"],
-        "roofline": {"bound": "hbm", "kernel": "spmm_chunks", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "chunk_kernel<FoldRows>", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(f"{w.name}/N{N}/{op}"),
                      "algorithmic_bytes_per_launch": r["model_bytes"],
