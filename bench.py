@@ -211,6 +211,7 @@ def main():
     ap.add_argument("--workload", default="large_dense_degree")
     ap.add_argument("--width", type=int, default=0, help="feature width N (default: the workload's first)")
     ap.add_argument("--op", default="sum")
+    ap.add_argument("--mtx", default="", help="benchmark a user-supplied Matrix Market file instead of --workload")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--sweep", action="store_true", help="also time every workload/width/op")
@@ -255,7 +256,7 @@ def main():
 
     grad_rows = time_gradients(args, gs, torch, graphgen, dev) if args.gradients else None
 
-    w = graphgen.workload(args.workload, args.scale)
+    w = graphgen.workload_from_matrix_market(args.mtx) if args.mtx else graphgen.workload(args.workload, args.scale)
     N = args.width or w.widths[0]
     op = args.op
     case = DeviceCase(w, N, torch, dev)

@@ -218,6 +218,15 @@ def workload(which, scale: float = 1.0) -> Workload:
     raise ValueError(which)
 
 
+def workload_from_matrix_market(path, widths=(128, 256, 512), seed=100) -> Workload:
+    """A user-supplied Matrix Market file (e.g. from SuiteSparse) as a workload; the feature
+    matrix is seeded uniform(-1, 1) and the stored values are the file's."""
+    from .mtx import read_matrix_market
+    M, K, rp, ci, v = read_matrix_market(path)
+    return Workload(os.path.basename(str(path)), M, K, rp, ci, v, seed, "uniform_pm1", tuple(widths),
+                    ("sum", "max"), {"source": "matrix market file"})
+
+
 # --------------------------------------------------------------------------
 # Small random CSR matrices for unit tests (numpy's seeded PCG64)
 # --------------------------------------------------------------------------

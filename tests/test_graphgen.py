@@ -102,3 +102,28 @@ def test_uniform_random_extra_workload():
     lens = np.diff(w.rowptr)
     assert w.M == 65536 and abs(w.nnz - 650_000) < 5_000
     assert lens.max() < 40 and abs(lens.mean() - 9.9) < 0.2       # no skew
+
+
+def test_matrix_market_reader_against_scipy(tmp_path):
+    import scipy.io
+    import scipy.sparse as sp
+    from graphgen.mtx import read_matrix_market
+    rng = np.random.default_rng(0)
+    A = sp.random(37, 23, density=0.15, random_state=1, format="coo")
+    A.data = np.round(A.data * 100) / 4
+    scipy.io.mmwrite(str(tmp_path / "general.mtx"), A)
+    S = sp.random(19, 19, density=0.2, random_state=2, format="coo")
+    S = sp.coo_matrix(sp.triu(S) + sp.triu(S, 1).T)
+    scipy.io.mmwrite(str(tmp_path / "symmetric.mtx"), S, symmetry="symmetric")
+    P = sp.coo_matrix((np.ones(5), ([0, 3, 3, 6, 6], [1, 0, 4, 2, 6])), shape=(7, 7))
+    scipy.io.mmwrite(str(tmp_path / "pattern.mtx"), P, field="pattern")
+    for name, ref in (("general", A), ("symmetric", S), ("pattern", P)):
+        M, K, rp, ci, v = read_matrix_market(tmp_path / f"{name}.mtx")
+        assert (M, K) == ref.shape and rp.dtype == np.int32 and ci.dtype == np.int32 and v.dtype == np.float32
+        got = sp.csr_matrix((v.astype(np.float64), ci, rp), shape=(M, K))
+        assert abs(got - sp.csr_matrix(scipy.io.mmread(str(tmp_path / f"{name}.mtx")))).max() < 1e-6
+        rows = np.repeat(np.arange(M), np.diff(rp))
+        assert (np.diff(rows * K + ci) > 0).all()
+    (tmp_path / "bad.mtx").write_text("%%MatrixMarket matrix array real general\n2 2\n1\n2\n3\n4\n")
+    with pytest.raises(ValueError):
+        read_matrix_market(tmp_path / "bad.mtx")
