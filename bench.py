@@ -178,6 +178,57 @@ def time_gradients(args, gs, torch, graphgen, dev):
     return rows
 
 
+def gcn_share(args, gs, torch, graphgen, dev):
+    """Share of the aggregation (SpMM, forward and backward) in a 2-layer GCN training step on the
+    synthetic graphs, in the spirit of the paper's Table I (which profiles DGL's GCN example)."""
+    from paper_2007_03179_amd import autograd as ag
+    rows = []
+    for name, feats, hidden, classes in (("tiny_citation", 1433, 16, 7), ("width_sweep", 500, 16, 3),
+                                         ("general_ops", 128, 256, 40)):
+        w = graphgen.workload(name, args.scale)
+        g = ag.CsrGraph(torch.from_numpy(w.rowptr).to(dev), torch.from_numpy(w.colind).to(dev),
+                        torch.from_numpy(w.vals).to(dev), w.K)
+        X = torch.from_numpy(graphgen.uniform_pm1((w.M, feats), 7, stream=feats)).to(dev)
+        y = torch.from_numpy((graphgen.uniform_01(w.M, 8) * classes).astype("int64") % classes).to(dev)
+        torch.manual_seed(0)
+        l1, l2 = ag.GraphConv(feats, hidden).to(dev), ag.GraphConv(hidden, classes).to(dev)
+        opt = torch.optim.Adam(list(l1.parameters()) + list(l2.parameters()), lr=0.01)
+
+        def train_step():
+            opt.zero_grad()
+            loss = torch.nn.functional.cross_entropy(l2(g, torch.relu(l1(g, X))), y)
+            loss.backward()
+            opt.step()
+
+        H1 = torch.randn(w.M, hidden, device=dev)
+        H2 = torch.randn(w.M, classes, device=dev)
+        t1, t2 = g.transposed(False)[:], None
+
+        def aggregation_only():                      # the four SpMM calls of one step, same shapes
+            for H in (H1, H2):
+                gs.gespmm_csr(g.rowptr, g.colind, g.vals, H, "sum")
+                gs.gespmm_csr(t1[0], t1[1], t1[2], H, "sum")
+
+        out = {}
+        for label, fn in (("step", train_step), ("aggregation", aggregation_only)):
+            for _ in range(5):
+                fn()
+            torch.cuda.synchronize()
+            n = max(20, args.steps)
+            t0 = time.perf_counter()
+            for _ in range(n):
+                fn()
+            torch.cuda.synchronize()
+            out[label] = (time.perf_counter() - t0) * 1e3 / n
+        rows.append({"workload": name, "features": feats, "hidden": hidden, "classes": classes,
+                     "train_step_ms": out["step"], "aggregation_ms": out["aggregation"],
+                     "aggregation_share": out["aggregation"] / out["step"]})
+        print(f"{name:20s} GCN {feats}-{hidden}-{classes}: step {out['step']*1e3:9.1f} us, aggregation (2 fwd + 2 bwd SpMM) "
+              f"{out['aggregation']*1e3:8.1f} us = {out['aggregation']/out['step']*100:5.1f} % of the step",
+              file=sys.stderr, flush=True)
+    return rows
+
+
 def sweep(args, gs, torch, graphgen, dev):
     """Every workload / width / op of the five configurations; table on stderr."""
     rows = []
@@ -216,6 +267,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--sweep", action="store_true", help="also time every workload/width/op")
     ap.add_argument("--sweep-out", default="", help="write the sweep rows to this JSON file")
+    ap.add_argument("--gcn", action="store_true",
+                    help="also time a 2-layer GCN training step and the share of the aggregation in it")
     ap.add_argument("--gradients", action="store_true",
                     help="also time the gradient-side entry points (positions, transposed, pooling gradient)")
     ap.add_argument("--copy-gib", type=float, default=0.0,
@@ -255,6 +308,7 @@ def main():
             json.dump(sweep_rows, f, indent=1)
 
     grad_rows = time_gradients(args, gs, torch, graphgen, dev) if args.gradients else None
+    gcn_rows = gcn_share(args, gs, torch, graphgen, dev) if args.gcn else None
 
     w = graphgen.workload_from_matrix_market(args.mtx) if args.mtx else graphgen.workload(args.workload, args.scale)
     N = args.width or w.widths[0]
@@ -291,6 +345,8 @@ def main():
                         for row in sweep_rows]
     if grad_rows is not None:
         out["gradients"] = grad_rows
+    if gcn_rows is not None:
+        out["gcn"] = gcn_rows
     print(json.dumps(out), flush=True)
 
 
