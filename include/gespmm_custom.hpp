@@ -1,0 +1,24 @@
+// gespmm_custom.hpp - user-defined SpMM-like operations, compiled in at build time.
+//
+// The paper's general operation (Eq. 1; Section IV-A) lets the user provide an
+// initialisation function and a reduce function that are inlined into the kernel when it
+// is compiled.  This header is that mechanism for the gfx950 kernels: write a small struct,
+// include this file in a .hip translation unit, and call gespmm::csr_custom<YourReduce>().
+//
+//   struct SumOfSquares {
+//     static __host__ __device__ float identity() { return 0.0f; }                 // initial value
+//     static __device__ float step(float acc, float a, float b) { float x = a * b; return acc + x * x; }
+//     static __device__ float merge(float x, float y) { return x + y; }            // two partial results
+//   };
+//   int status = gespmm::csr_custom<SumOfSquares>(M, K, N, nnz, rowptr, colind, vals, B, C, stream);
+//
+// Requirements (Section IV-A: "the parallel execution requires the reduction function to be
+// associative and commutative"): merge is associative and commutative, identity() is its neutral
+// element, and step(acc, a, b) == merge(acc, step(identity(), a, b)).  Arguments, layout,
+// ownership and error codes are those of gespmm_csr (include/gespmm.h); an empty row yields 0;
+// rows that are split across wavefronts are combined with a compare-and-swap loop around merge.
+// Compile with hipcc --offload-arch=gfx950 and the include paths of this repository's
+// `include/` and `paper_2007_03179_amd/csrc/` directories.
+#pragma once
+
+#include "gespmm_kernels.hpp"

@@ -18,6 +18,7 @@ _LIB = os.path.join(_HERE, "liboracle.so")
 _lib = None
 
 OPS = {"sum": 0, "mean": 1, "max": 2, "min": 3}
+STEP_FN = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.c_double, ctypes.c_double, ctypes.c_double)
 
 
 def build(force: bool = False, src: str = _SRC, lib: str = _LIB) -> str:
@@ -42,6 +43,8 @@ def _bind(path):
     L.spmm_oracle_pool_backward.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, vp]
     L.spmm_oracle_csr_transpose.restype = ci
     L.spmm_oracle_csr_transpose.argtypes = [i64, i64, vp, vp, vp, ci, vp, vp, vp]
+    L.spmm_oracle_custom.restype = ci
+    L.spmm_oracle_custom.argtypes = [i64, i64, i64, vp, vp, vp, vp, ctypes.c_double, STEP_FN, vp]
     L.spmm_oracle_max_threads.restype = ci
     return L
 
@@ -185,6 +188,25 @@ def csr_transpose(rowptr, colind, vals, K, scale_by_row_length=False, _lib_overr
     if rc != 0:
         raise ValueError("spmm_oracle_csr_transpose: bad argument")
     return rowptrT, colindT, valsT
+
+
+def spmm_custom(rowptr, colind, vals, B, init, step, _lib_override=None):
+    """General SpMM-like operation: `init` is the initial accumulator, `step(acc, a, b)` a Python
+    function folding one stored entry (a = stored value, b = B element), everything in double.
+    Small inputs only (one interpreter call per product).  Returns Cref float64 (M, N)."""
+    L = _lib_override or _load()
+    rowptr, colind, vals = _csr(rowptr, colind, vals)
+    B = np.ascontiguousarray(B, dtype=np.float32)
+    M, (K, N) = rowptr.shape[0] - 1, B.shape
+    if colind.size:
+        assert colind.min() >= 0 and colind.max() < K
+    Cref = np.empty((M, N), dtype=np.float64)
+    rc = L.spmm_oracle_custom(M, K, N, rowptr.ctypes.data, colind.ctypes.data,
+                              vals.ctypes.data if vals is not None else None, B.ctypes.data,
+                              float(init), STEP_FN(step), Cref.ctypes.data)
+    if rc != 0:
+        raise ValueError("spmm_oracle_custom: bad argument")
+    return Cref
 
 
 def compare(op, C, Cref, Sabs):

@@ -246,4 +246,29 @@ int spmm_oracle_csr_transpose(int64_t M, int64_t K, const int32_t* rowptr, const
   return 0;
 }
 
+/*
+ * The general SpMM-like operation with a user-supplied initial value and fold (Eq. 1 and
+ * Section IV-A: "an initialization function and a reduce function"): for every output,
+ * start from `init` and fold the stored entries of the row in storage order with
+ * `step(acc, stored value, B element)`, all in double.  An empty row yields 0.  Serial:
+ * the fold may be a callback into an interpreter.
+ */
+typedef double (*oracle_step_fn)(double acc, double a, double b);
+
+int spmm_oracle_custom(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const int32_t* colind,
+                       const float* vals, const float* B, double init, oracle_step_fn step, double* Cref) {
+  if (M < 0 || K < 0 || N < 0 || !rowptr || !step || !Cref) return -1;
+  for (int64_t i = 0; i < M; ++i) {
+    for (int64_t j = 0; j < N; ++j) {
+      double acc = init;
+      for (int64_t ptr = rowptr[i]; ptr < rowptr[i + 1]; ++ptr) {
+        const double a = vals ? (double)vals[ptr] : 1.0;
+        acc = step(acc, a, (double)B[(int64_t)colind[ptr] * N + j]);
+      }
+      Cref[i * N + j] = rowptr[i + 1] > rowptr[i] ? acc : 0.0;
+    }
+  }
+  return 0;
+}
+
 int spmm_oracle_max_threads(void) { return omp_get_max_threads(); }

@@ -14,6 +14,7 @@ HIPCC_FLAGS = [
     "-munsafe-fp-atomics",                                   # hardware fp32 atomic add
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-I", os.path.join(ROOT, "include"),
+    "-I", os.path.join(HERE, "csrc"),
 ]
 
 
@@ -26,5 +27,19 @@ def build(force: bool = True, extra=()) -> str:
     return LIB
 
 
+CUSTOM_SRC = os.path.join(ROOT, "tests", "custom_ops", "custom_ops.hip")
+CUSTOM_LIB = os.path.join(ROOT, "tests", "custom_ops", "libcustom_ops.so")
+
+
+def build_custom_example(force: bool = True) -> str:
+    """Compile the two example user-defined reduce operations (tests/custom_ops)."""
+    if not force and os.path.exists(CUSTOM_LIB):
+        return CUSTOM_LIB
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    subprocess.run([hipcc, *HIPCC_FLAGS, "-o", CUSTOM_LIB, CUSTOM_SRC], check=True)
+    return CUSTOM_LIB
+
+
 if __name__ == "__main__":
     print(build())
+    print(build_custom_example())

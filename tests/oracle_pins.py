@@ -432,5 +432,26 @@ def pin_csr_transpose(O):
     assert not rT.any() and cT.size == 0
 
 
-GRAD_PINS = (pin_csr_transpose, pin_arg_brute_force_with_ties, pin_arg_consistent_with_forward, pin_transposed_dense_and_scipy,
+def pin_custom_fold(O):
+    """The general fold with a user-supplied step: the built-in ops are special cases of it, and a
+    fold that is none of them is checked against a per-entry Python loop."""
+    rp, ci, v = graphgen.random_csr(25, 18, 4.0, 97, empty_frac=0.2, duplicates=True, sort_cols=False)
+    B = graphgen.random_dense(18, 3, 97)
+    for vv in (v, None):
+        got = O.spmm_custom(rp, ci, vv, B, 0.0, lambda acc, a, b: acc + a * b)
+        _same_bits(got, O.spmm(rp, ci, vv, B, "sum")[0])
+        got = O.spmm_custom(rp, ci, vv, B, -math.inf, lambda acc, a, b: max(acc, a * b))
+        _same_bits(got, O.spmm(rp, ci, vv, B, "max")[0])
+        got = O.spmm_custom(rp, ci, vv, B, 0.0, lambda acc, a, b: acc + (a * b) ** 2)
+        for i in range(25):
+            for j in range(3):
+                terms = [((float(vv[p]) if vv is not None else 1.0) * float(B[ci[p], j])) ** 2
+                         for p in range(rp[i], rp[i + 1])]
+                want = 0.0
+                for t in terms:
+                    want += t
+                assert got[i, j] == want
+
+
+GRAD_PINS = (pin_custom_fold, pin_csr_transpose, pin_arg_brute_force_with_ties, pin_arg_consistent_with_forward, pin_transposed_dense_and_scipy,
              pin_transposed_is_the_adjoint, pin_pool_backward_numeric_gradient)

@@ -61,6 +61,9 @@ MUTANTS = [
     ("transpose_stores_column", "colindT[place] = (int32_t)i;", "colindT[place] = colind[ptr];"),
     ("transpose_scale_inverted", "if (scale_by_row_length) w /= len;", "if (scale_by_row_length) w *= len;"),
     ("transpose_places_not_advanced", "next[colind[ptr]]++;", "next[colind[ptr]];"),
+    ("custom_restarts_every_step", "acc = step(acc, a, (double)B[(int64_t)colind[ptr] * N + j]);",
+     "acc = step(init, a, (double)B[(int64_t)colind[ptr] * N + j]);"),
+    ("custom_empty_row_keeps_init", "Cref[i * N + j] = rowptr[i + 1] > rowptr[i] ? acc : 0.0;", "Cref[i * N + j] = acc;"),
     ("arg_drop_last_term", "ptr < row_end; ++ptr", "ptr < row_end - 1; ++ptr", 1),
     ("arg_column_of_B_flipped", "B[k * N + j]", "B[k * N + (N - 1 - j)]", 1),
     ("arg_null_vals_as_zero", ": 1.0;", ": 0.0;", 1),
@@ -85,6 +88,9 @@ class _Mutant:
 
     def pool_backward(self, colind, vals, arg, dC, K):
         return oracle.pool_backward(colind, vals, arg, dC, K, _lib_override=self.lib)
+
+    def spmm_custom(self, rowptr, colind, vals, B, init, step):
+        return oracle.spmm_custom(rowptr, colind, vals, B, init, step, _lib_override=self.lib)
 
     def csr_transpose(self, rowptr, colind, vals, K, scale_by_row_length=False):
         return oracle.csr_transpose(rowptr, colind, vals, K, scale_by_row_length, _lib_override=self.lib)
