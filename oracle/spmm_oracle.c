@@ -13,7 +13,7 @@
  * SpMM-like generalisation (Eq. 1, Section IV-A) swaps the initial value and
  * the fold, nothing else: the multiply stays for every op.
  *
- * Readings where the paper is silent (also listed in the design notes):
+ * Readings where the paper is silent:
  *   - mean divides by the number of STORED entries of the row;
  *   - an empty row yields 0 for every op;
  *   - max/min on signed zeros follow IEEE-754 maximum/minimum (+0 > -0);

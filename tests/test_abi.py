@@ -57,6 +57,7 @@ def test_argument_errors_come_before_any_device_work(L):
     assert call(2**31, 4, 4, 8, p, p, p, p, p, 0, None) == 3
     assert call(4, 2**31 + 1, 4, 8, p, p, p, p, p, 0, None) == 3
     assert call(4, 4, 4, 2**31, p, p, p, p, p, 0, None) == 3
+    assert call(4, 4, 40_000_000, 8, p, p, p, p, p, 0, None) == 3  # more column blocks than a grid holds
     # nothing to do: success without touching a device
     assert call(0, 4, 4, 0, p, p, p, p, p, 0, None) == 0
     assert call(4, 4, 0, 8, p, p, p, p, p, 0, None) == 0

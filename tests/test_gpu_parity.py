@@ -3,6 +3,7 @@
 sum / mean: |C - Cref| <= 1e-5 * Sabs + 1e-6 per element (Sabs = sum |a||b|, divided by the
 row length for mean); max / min: bit-for-bit equal to the oracle rounded once to fp32.
 """
+import ctypes
 import sys
 
 import numpy as np
@@ -275,6 +276,42 @@ def test_workload_full_size_sampled_rows_and_properties(gs, which):
             _, Sabs = oracle.spmm(w.rowptr, w.colind, w.vals, B, "sum", rows=rows)
             err = np.abs(out["mean"][rows].astype(np.float64) * lens[rows] - out["sum"][rows])
             assert (err <= 2e-5 * Sabs + 2e-6 * np.maximum(lens[rows], 1)).all()
+
+
+def test_wide_feature_matrix_many_column_blocks(gs):
+    rp, ci, v = graphgen.random_csr(64, 50, 6.0, 77, empty_frac=0.1, long_rows=((5, 400),), duplicates=True)
+    B = graphgen.random_dense(50, 4100, 77)           # 4100 columns: 65 column blocks, ragged last one
+    for op in OPS:
+        check(gs, rp, ci, v, B, op, label="N=4100")
+
+
+def test_entry_count_near_the_32_bit_limit(gs):
+    """nnz = 2^31 - 2048 (the largest the library accepts is 2^31 - 1025): chunk offsets, the row search
+    and the atomics of split rows at the top of the int32 range.  Inputs are built on the device and
+    chosen so that the results are exact: 1024 equal rows of ones against an all-ones / ramp B."""
+    nnz = 2**31 - 2048
+    M, K, N = 1024, 1000, 4
+    per_row = nnz // M                                  # 2,097,150: row sums stay below 2^24, exact in fp32
+    assert per_row * M == nnz
+    say(f"  case near-limit nnz={nnz}")
+    colind = torch.arange(nnz, dtype=torch.int32, device="cuda").remainder_(K)
+    rowptr = (torch.arange(M + 1, dtype=torch.int64, device="cuda") * per_row).to(torch.int32)
+    ones = torch.ones((K, N), dtype=torch.float32, device="cuda")
+    ramp = torch.arange(K, dtype=torch.float32, device="cuda")[:, None].repeat(1, N).contiguous()
+    C = gs.gespmm_csr(rowptr, colind, None, ones, "sum")
+    torch.cuda.synchronize()
+    assert bool((C == float(per_row)).all())
+    C = gs.gespmm_csr(rowptr, colind, None, ones, "mean")
+    torch.cuda.synchronize()
+    assert bool(((C - 1.0).abs() <= 1e-5).all())
+    C = gs.gespmm_csr(rowptr, colind, None, ramp, "max")
+    torch.cuda.synchronize()
+    assert bool((C == float(K - 1)).all())
+    C = gs.gespmm_csr(rowptr, colind, None, ramp, "min")
+    torch.cuda.synchronize()
+    assert bool((C == 0.0).all())
+    p = ctypes.c_void_p(0x1000)                         # beyond the limit: rejected on the host, nothing runs
+    assert gs.lib().gespmm_csr(M, K, N, 2**31 - 1, p, p, None, p, p, 0, None) == 3
 
 
 def test_zz_report_worst_error_ratio(gs):
