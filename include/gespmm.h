@@ -88,7 +88,9 @@ int gespmm_csr_simple(int64_t M, int64_t K, int64_t N, const int32_t* rowptr,
  *         into colind / vals of the stored entry of row i whose product vals[p] *
  *         B[colind[p], j] has exactly the bits of C[i, j]; if several entries do, the
  *         smallest p (first in storage order); -1 for an empty row.
- * Runs gespmm_csr and then one more pass over the matrix (about twice the time).
+ * One fused pass gives values everywhere and positions for rows that lie inside one chunk of
+ * the work partition; a second pass finds the positions of the rows that were split (1.6 to
+ * 1.9 times the cost of gespmm_csr).
  * For the vector kernels arg must be 16-byte aligned as well.  Same errors as gespmm_csr;
  * GESPMM_ERR_BAD_ARG for any other op; GESPMM_ERR_NULL for arg == NULL.
  */

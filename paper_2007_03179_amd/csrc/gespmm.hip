@@ -62,20 +62,35 @@ int gespmm_csr_arg(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* 
   const int st = validate(M, K, N, nnz, rowptr, colind, B, C, op);
   if (st != GESPMM_OK || M == 0 || N == 0) return st;
   if (!arg) return GESPMM_ERR_NULL;
-  // the result first (all atomics of split rows have landed when the next kernel starts) ...
-  const int fwd = gespmm_csr(M, K, N, nnz, rowptr, colind, vals, B, C, op, stream_);
-  if (fwd != GESPMM_OK) return fwd;
-  // ... then the positions: empty rows -> -1, split rows -> INT_MAX and an atomic min
+  // One fused pass gives the value everywhere and the position for every row that lies inside
+  // one chunk; rows split across chunks get their value by atomics.  Both outputs are preset:
+  // empty rows -> 0 / -1, split rows -> reduce identity / INT_MAX.
+  hipStream_t stream = (hipStream_t)stream_;
   ChunkLaunch L;
-  L.job = kJobArg;
+  L.job = op == GESPMM_MAX ? kJobMaxWithArg : kJobMinWithArg;
   L.M = M; L.N = N; L.nnz = nnz;
   L.rowptr = rowptr; L.colind = colind; L.vals = vals;
-  L.dense_in = B; L.dense_out = nullptr; L.result_in = C; L.arg = arg;
-  L.init_target = reinterpret_cast<float*>(arg);
-  L.empty_value = bits_as_float(-1);
-  L.split_value = bits_as_float(INT32_MAX);
+  L.dense_in = B; L.dense_out = C; L.arg = arg;
   L.also_aligned = arg;
-  return launch_chunks(L, (hipStream_t)stream_);
+  L.init_target = C;
+  L.empty_value = 0.0f;
+  L.split_value = op == GESPMM_MAX ? -__builtin_inff() : __builtin_inff();
+  L.init2_target = reinterpret_cast<float*>(arg);
+  L.empty2_value = bits_as_float(-1);
+  L.split2_value = bits_as_float(INT32_MAX);
+  L.timed = true;
+  const int fused = launch_chunks(L, stream);
+  if (fused != GESPMM_OK || nnz == 0) return fused;
+  // Second pass, split rows only (their values are final once the first kernel has ended):
+  // entries whose product has the bits of C[i, j] compete by atomic min on their index.
+  ChunkLaunch S;
+  S.job = kJobArg;
+  S.M = M; S.N = N; S.nnz = nnz;
+  S.rowptr = rowptr; S.colind = colind; S.vals = vals;
+  S.dense_in = B; S.result_in = C; S.arg = arg;
+  S.also_aligned = arg;
+  S.only_split = true;
+  return launch_chunks(S, stream);
 }
 
 int gespmm_csr_transposed(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,

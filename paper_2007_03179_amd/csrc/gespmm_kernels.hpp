@@ -68,6 +68,7 @@ struct KernelArgs {
   const float* Cin;       // finished max/min result, read by the position job
   int32_t* arg;           // output of the position job; row indices of the transposed arrays
   int32_t* cursor;        // next free place of every transposed row (structure-transpose job)
+  int32_t only_split;     // position job: rows inside one chunk were already done by the fused pass
 };
 
 // ------------------------------------------------------------------ vectors --
@@ -194,6 +195,7 @@ __device__ __forceinline__ void wave_lds_fence() {
 
 template <int F, int V, int T>
 struct FoldRows {
+  static constexpr bool kCanSkipWholeRows = false;
   struct State { Vec<V> acc[T]; };
 
   __device__ static void begin(State& s, const KernelArgs&, int64_t, int, const int (&)[T]) {
@@ -265,12 +267,119 @@ struct FoldRows {
   }
 };
 
+// max / min that also tracks WHERE the extreme came from, for rows that lie inside one
+// chunk: value and entry index travel together through the fold, the slot combine and the
+// store.  The order is the total order of the float bit patterns (so +0 is above -0, as in
+// the plain fold) and ties go to the smaller entry index, which is exactly "the first entry
+// whose product has the bits of the result".  Split rows only get their value here (by
+// atomics, as in FoldRows); their positions are found by ArgRows afterwards.
+template <int F, int V, int T>
+struct FoldArgRows {
+  static constexpr bool kCanSkipWholeRows = false;
+  static_assert(F == kMax || F == kMin, "positions exist for max and min only");
+  struct State { int key[T][V]; int where[T][V]; };
+
+  // monotone map float bits -> signed int (larger float <=> larger key; -0 below +0)
+  __device__ static int key_of(float x) {
+    const int b = __float_as_int(x);
+    return b ^ ((b >> 31) & 0x7fffffff);
+  }
+  __device__ static float value_of(int key) { return __int_as_float(key ^ ((key >> 31) & 0x7fffffff)); }
+  __device__ static bool better(int k, int w, int best_k, int best_w) {
+    return F == kMax ? (k > best_k || (k == best_k && w < best_w)) : (k < best_k || (k == best_k && w < best_w));
+  }
+
+  __device__ static void begin(State& s, const KernelArgs&, int64_t, int, const int (&)[T]) {
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+#pragma unroll
+      for (int x = 0; x < V; ++x) {
+        s.key[t][x] = key_of(fold_identity<F>());
+        s.where[t][x] = INT32_MAX;
+      }
+  }
+
+  template <int U>
+  __device__ static void pass(State& s, const KernelArgs& a, const int2* ka, int cs, int first, int stride, int left,
+                              const int (&)[T], const int (&colc)[T]) {
+    int2 e2[U];
+    int where[U];
+    Vec<V> b[U][T];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {          // a missing entry repeats an existing one: same value, same index
+      const int uu = u < left ? u : (left > 0 ? left - 1 : 0);
+      e2[u] = ka[first + uu * stride];
+      where[u] = cs + first + uu * stride;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float* brow = a.B + (int64_t)e2[u].x * a.N;
+#pragma unroll
+      for (int t = 0; t < T; ++t) b[u][t] = Vec<V>::load(brow + colc[t]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int x = 0; x < V; ++x) {
+          // a lane meets its entries in increasing index order, so "first among equals" is
+          // simply "replace on strict improvement only"
+          const int k = key_of(__int_as_float(e2[u].y) * b[u][t].v[x]);
+          const bool improves = F == kMax ? k > s.key[t][x] : k < s.key[t][x];
+          s.key[t][x] = improves ? k : s.key[t][x];
+          s.where[t][x] = improves ? where[u] : s.where[t][x];
+        }
+  }
+
+  template <int G>
+  __device__ static void combine(State& s) {
+#pragma unroll
+    for (int off = G; off < kWave; off <<= 1)
+#pragma unroll
+      for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int x = 0; x < V; ++x) {
+          const int k = __shfl_xor(s.key[t][x], off, kWave);
+          const int w = __shfl_xor(s.where[t][x], off, kWave);
+          if (better(k, w, s.key[t][x], s.where[t][x])) {
+            s.key[t][x] = k;
+            s.where[t][x] = w;
+          }
+        }
+  }
+
+  __device__ static void end(State& s, const KernelArgs& a, int64_t row, bool whole, int, const int (&col)[T]) {
+    float* crow = a.C + row * (int64_t)a.N;
+    int32_t* arow = a.arg + row * (int64_t)a.N;
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+      if (col[t] < a.N) {
+        if (whole) {
+          Vec<V> value, place;
+#pragma unroll
+          for (int x = 0; x < V; ++x) {
+            value.v[x] = value_of(s.key[t][x]);
+            place.v[x] = __int_as_float(s.where[t][x]);
+          }
+          value.store(crow + col[t]);
+          place.store(reinterpret_cast<float*>(arow + col[t]));
+        } else {
+#pragma unroll
+          for (int x = 0; x < V; ++x) atomic_fold<F>(crow + col[t] + x, value_of(s.key[t][x]));
+        }
+      }
+    }
+  }
+};
+
 // Position of the extreme (run after the max / min result C is complete): an entry whose
 // product has exactly the bits of C[i, j] is a candidate; the smallest entry index wins,
 // i.e. the first in storage order.  Rows inside one chunk are stored, split rows are
 // combined with an integer atomic min on a row preset to INT_MAX.
 template <int V, int T>
 struct ArgRows {
+  static constexpr bool kCanSkipWholeRows = true;
   struct State { int best[T][V]; int want[T][V]; };
 
   __device__ static void begin(State& s, const KernelArgs& a, int64_t row, int, const int (&colc)[T]) {
@@ -353,6 +462,7 @@ struct ArgRows {
 // fp32 atomic adds; dB was zero-filled before.  Here KernelArgs::B is dC and ::C is dB.
 template <int V, int T>
 struct TransposedRows {
+  static constexpr bool kCanSkipWholeRows = false;
   struct State { Vec<V> d[T]; };
 
   __device__ static void begin(State& s, const KernelArgs& a, int64_t row, int row_len, const int (&colc)[T]) {
@@ -395,6 +505,7 @@ struct TransposedRows {
 // lane per entry.  KernelArgs::C is the value array and ::arg the index array written.
 template <int V, int T>
 struct ScatterRows {
+  static constexpr bool kCanSkipWholeRows = false;
   struct State { float len; int row; };
 
   __device__ static void begin(State& s, const KernelArgs&, int64_t row, int row_len, const int (&)[T]) {
@@ -437,6 +548,7 @@ struct ScatterRows {
 // Split rows are combined in memory with a compare-and-swap loop around merge.
 template <class R, int V, int T>
 struct CustomRows {
+  static constexpr bool kCanSkipWholeRows = false;
   struct State { Vec<V> acc[T]; };
 
   __device__ static void begin(State& s, const KernelArgs&, int64_t, int, const int (&)[T]) {
@@ -589,10 +701,11 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
     if (rr > a.M) rr = a.M;
     const int my_s = a.rowptr[rr];
     const int my_e = a.rowptr[rr < a.M ? rr + 1 : a.M];
-    const bool valid = rbase + lane < a.M && my_e > my_s && my_s < ce;
+    const bool my_whole = my_s >= cs && my_e <= ce;
+    const bool valid = rbase + lane < a.M && my_e > my_s && my_s < ce &&
+                       !(P::kCanSkipWholeRows && a.only_split && my_whole);
     const int my_ps = (my_s > cs ? my_s : cs) - cs;     // the row's segment inside the chunk,
     const int my_pe = (my_e < ce ? my_e : ce) - cs;     // as offsets into the LDS slice
-    const bool my_whole = my_s >= cs && my_e <= ce;
     const bool is_short = NS > 1 && valid && (my_pe - my_ps) <= a.short_len;
 
     // (3a) short segments: one per slot, 64/G rows at a time, no cross-lane exchange
@@ -751,7 +864,8 @@ static __global__ void __launch_bounds__(kBlock) add_tile_offsets(int32_t* __res
 // --------------------------------------------------------------- host side --
 using MainKernel = void (*)(const KernelArgs);
 
-enum Job { kJobAdd = kAdd, kJobMax = kMax, kJobMin = kMin, kJobArg = 3, kJobTransposed = 4, kJobScatter = 5 };
+enum Job { kJobAdd = kAdd, kJobMax = kMax, kJobMin = kMin, kJobArg = 3, kJobTransposed = 4, kJobScatter = 5,
+           kJobMaxWithArg = 6, kJobMinWithArg = 7 };
 
 template <template <int, int> class P, int V>
 MainKernel pick_gt(int G, int T) {
@@ -767,6 +881,8 @@ MainKernel pick_gt(int G, int T) {
 template <int V, int T> using AddRows = FoldRows<kAdd, V, T>;
 template <int V, int T> using MaxRows = FoldRows<kMax, V, T>;
 template <int V, int T> using MinRows = FoldRows<kMin, V, T>;
+template <int V, int T> using MaxArgRows = FoldArgRows<kMax, V, T>;
+template <int V, int T> using MinArgRows = FoldArgRows<kMin, V, T>;
 
 template <int V>
 MainKernel pick_job(int job, int G, int T) {
@@ -775,6 +891,8 @@ MainKernel pick_job(int job, int G, int T) {
     case kJobMax: return pick_gt<MaxRows, V>(G, T);
     case kJobMin: return pick_gt<MinRows, V>(G, T);
     case kJobArg: return pick_gt<ArgRows, V>(G, T);
+    case kJobMaxWithArg: return pick_gt<MaxArgRows, V>(G, T);
+    case kJobMinWithArg: return pick_gt<MinArgRows, V>(G, T);
     case kJobTransposed: return pick_gt<TransposedRows, V>(G, T);
     case kJobScatter: return (V == 1 && G == 1 && T == 1) ? chunk_kernel<ScatterRows<1, 1>, 1, 1, 1> : nullptr;
     default: return nullptr;
@@ -889,6 +1007,9 @@ struct ChunkLaunch {
   bool is_mean = false;
   float* init_target = nullptr;        // M x N output preset by init_rows, or nullptr
   float empty_value = 0.0f, split_value = 0.0f;
+  float* init2_target = nullptr;       // a second M x N output to preset (positions of the fused pass)
+  float empty2_value = 0.0f, split2_value = 0.0f;
+  bool only_split = false;             // position job: leave rows that lie inside one chunk alone
   bool timed = false;                  // bracket the chunk kernel with profiling events
   MainKernel (*picker)(int vec, int G, int T) = nullptr;   // user-defined reduce: its own kernel table
   int32_t* cursor = nullptr;           // structure-transpose job only
@@ -926,6 +1047,14 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
     else
       hipLaunchKernelGGL(init_rows<1>, dim3(init_blocks), dim3(kBlock), 0, stream, (int32_t)L.M, (int32_t)L.N, L.rowptr,
                          L.init_target, L.empty_value, L.split_value, shift, lanes_shift);
+    if (L.init2_target) {
+      if (plan.vec == 4)
+        hipLaunchKernelGGL(init_rows<4>, dim3(init_blocks), dim3(kBlock), 0, stream, (int32_t)L.M, (int32_t)L.N, L.rowptr,
+                           L.init2_target, L.empty2_value, L.split2_value, shift, lanes_shift);
+      else
+        hipLaunchKernelGGL(init_rows<1>, dim3(init_blocks), dim3(kBlock), 0, stream, (int32_t)L.M, (int32_t)L.N, L.rowptr,
+                           L.init2_target, L.empty2_value, L.split2_value, shift, lanes_shift);
+    }
     if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
   }
   if (L.nnz == 0) return GESPMM_OK;
@@ -949,6 +1078,7 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
   a.Cin = L.result_in;
   a.arg = L.arg;
   a.cursor = L.cursor;
+  a.only_split = L.only_split ? 1 : 0;
   const bool timed = L.timed && g_profiling && g_ev_used < (int)g_ev_start.size();
   if (timed && hipEventRecord(g_ev_start[g_ev_used], stream) != hipSuccess) return GESPMM_ERR_HIP;
   hipLaunchKernelGGL(kernel, dim3((unsigned)plan.grid_x, (unsigned)plan.col_blocks), dim3(kBlock), (size_t)plan.lds_bytes, stream, a);
