@@ -641,12 +641,11 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
   int2* ka = s_dyn + wave * (S + kWave);
   int2* short_rows = ka + S;
 
-  // (1) coalesced load of the chunk's (colind, val) into this wavefront's LDS slice, four
-  //     loads of each array in flight at a time (indices past the end repeat the last
-  //     entry; those copies are never consumed)
-  for (int u0 = 0; u0 < cnt; u0 += 4 * kWave) {
-    int k[4];
-    float v[4];
+  // (1) coalesced load of the chunk's (colind, val) into this wavefront's LDS slice, in groups
+  //     of four loads per array (indices past the end repeat the last entry; those copies
+  //     are never consumed).  The first group is issued before the row search below and
+  //     written to LDS after it, so its latency overlaps the search's.
+  auto load_group = [&](int u0, int (&k)[4], float (&v)[4]) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int idx = u0 + u * kWave + lane;
@@ -662,12 +661,17 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
 #pragma unroll
       for (int u = 0; u < 4; ++u) v[u] = 1.0f;
     }
+  };
+  auto store_group = [&](int u0, const int (&k)[4], const float (&v)[4]) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int idx = u0 + u * kWave + lane;
       if (idx < S) ka[idx] = make_int2(k[u], __float_as_int(v[u]));
     }
-  }
+  };
+  int k0[4];
+  float v0[4];
+  load_group(0, k0, v0);
 
   // (2) first row of the chunk: the last r with rowptr[r] <= cs, found by a 64-way search
   int lo = 0, hi = a.M;                          // rowptr[lo] <= cs < rowptr[hi]
@@ -681,6 +685,14 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
     if (nhi > hi) nhi = hi;
     lo = (int)nlo;
     hi = (int)nhi;
+  }
+
+  store_group(0, k0, v0);
+  for (int u0 = 4 * kWave; u0 < cnt; u0 += 4 * kWave) {
+    int k[4];
+    float v[4];
+    load_group(u0, k, v);
+    store_group(u0, k, v);
   }
 
   // column tiles of this lane (loads use a clamped column so they are never masked)
