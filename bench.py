@@ -31,10 +31,10 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 # the summaries are under profiles/).  Key: "<workload>/N<width>/<op>".  Missing = null.
 MEASURED_TRAFFIC_BYTES = {
     "large_dense_degree/N64/sum": 22.991e9,   # profiles/chunk_kernel_large_dense_degree_N64_sum.md
-    "general_ops/N128/sum": 1.0056e9,         # profiles/chunk_kernel_general_ops_N128_sum.md
-    "skew_narrow/N8/sum": 0.63295e9,          # profiles/chunk_kernel_skew_narrow_N8_sum.md
-    "skew_narrow/N32/sum": 1.2061e9,          # profiles/chunk_kernel_skew_narrow_N32_sum.md
-    "width_sweep/N512/sum": 0.18050e9,        # profiles/chunk_kernel_width_sweep_N512_sum.md
+    "general_ops/N128/sum": 1.0067e9,         # profiles/chunk_kernel_general_ops_N128_sum.md
+    "skew_narrow/N8/sum": 0.63313e9,          # profiles/chunk_kernel_skew_narrow_N8_sum.md
+    "skew_narrow/N32/sum": 1.2064e9,          # profiles/chunk_kernel_skew_narrow_N32_sum.md
+    "width_sweep/N512/sum": 0.18090e9,        # profiles/chunk_kernel_width_sweep_N512_sum.md
 }
 
 
