@@ -4,6 +4,7 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--width N] [--op OP]
     python bench.py --sweep            # every workload / width / op, table on stderr
     python bench.py --gradients        # also time the gradient-side entry points
+    python bench.py --suite [--vendor] # shape suite at N = 128/256/512, geometric means
     python bench.py --copy-gib 1       # also launch the calibration copy kernel (for --pmc runs)
 
 One "step" is one whole gespmm_csr call (row-initialisation kernel + chunk kernel) on a
@@ -124,6 +125,60 @@ class DeviceCase:
                 "compulsory_bytes": compulsory_bytes(w.M, w.K, N, w.nnz)}
 
 
+class Evictor:
+    """Pushes 2 GiB through the chip (the library's plain copy kernel, 1 GiB read + 1 GiB written)
+    so that the next call starts with neither L2 nor the 256 MB Infinity Cache holding its
+    operands; also yields the copy bandwidth this machine reaches, a practical ceiling next to the
+    published peak."""
+
+    def __init__(self, gs, torch, dev, gib=1.0):
+        n = int(gib * (1 << 30)) // 16 * 4
+        self.gs, self.torch, self.bytes = gs, torch, 8 * n
+        self.src = torch.ones(n, dtype=torch.float32, device=dev)
+        self.dst = torch.empty_like(self.src)
+
+    def __call__(self):
+        self.gs.gespmm_calibration_copy(self.src, self.dst)
+
+    def copy_GBps(self, reps=10):
+        torch = self.torch
+        for _ in range(2):
+            self()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev[0].record()
+        for _ in range(reps):
+            self()
+        ev[1].record()
+        torch.cuda.synchronize()
+        return self.bytes * reps / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
+
+
+def per_call_times(gs, torch, case, op, calls, before_each=None):
+    """Milliseconds of `calls` single calls, each between its own event pair on torch's current
+    stream (the one the calls are enqueued on); `before_each` runs outside the pair."""
+    stream = torch.cuda.current_stream()
+    pairs = []
+    for _ in range(calls):
+        if before_each is not None:
+            before_each()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        gs.gespmm_csr(case.rp, case.ci, case.v, case.B, op, C=case.C, stream=stream)
+        b.record(stream)
+        pairs.append((a, b))
+    torch.cuda.synchronize()
+    return [a.elapsed_time(b) for a, b in pairs]
+
+
+def warm_and_cold(gs, torch, case, op, evictor, calls=30):
+    """Per-call minimum and mean, back to back (warm) and after the caches were flushed (cold)."""
+    per_call_times(gs, torch, case, op, 3)
+    warm = per_call_times(gs, torch, case, op, calls)
+    cold = per_call_times(gs, torch, case, op, calls, before_each=evictor)
+    return {"warm_min_ms": min(warm), "warm_mean_ms": sum(warm) / len(warm),
+            "cold_min_ms": min(cold), "cold_mean_ms": sum(cold) / len(cold), "calls": calls}
+
+
 def gradient_bytes(kind, M, K, N, nnz):
     """Algorithmic bytes of the gradient-side calls (same counting rules as model_bytes)."""
     walk = 4 * (M + 1) + 8 * nnz                       # rowptr + colind + vals
@@ -229,7 +284,7 @@ def gcn_share(args, gs, torch, graphgen, dev):
     return rows
 
 
-def sweep(args, gs, torch, graphgen, dev):
+def sweep(args, gs, torch, graphgen, dev, evictor):
     """Every workload / width / op of the five configurations; table on stderr."""
     rows = []
     for name in graphgen.WORKLOAD_NAMES + graphgen.EXTRA_WORKLOAD_NAMES:
@@ -243,15 +298,72 @@ def sweep(args, gs, torch, graphgen, dev):
                 r = case.time(gs, torch, op, steps, args.warmup, bracket_kernel=False)  # clean step time
                 r["main_kernel_ms"], r["model_GBps_kernel"] = k["main_kernel_ms"], k["model_GBps_kernel"]
                 r["graph_ms_per_step"] = time_graph_replay(gs, torch, case, op, steps) if w.nnz * N < 5e8 else None
+                r.update(warm_and_cold(gs, torch, case, op, evictor, calls=20))
                 rows.append(r)
                 print(f"{r['workload']:20s} N={N:4d} {op:5s} step {r['ms_per_step']*1e3:9.1f} us  kernel "
                       f"{r['main_kernel_ms']*1e3:9.1f} us  {r['gflops']:8.1f} GFLOP/s  model "
                       f"{r['model_GBps_step']:8.1f} GB/s ({r['model_GBps_step']/HBM_PEAK_GBPS*100:5.1f}% of HBM peak)"
+                      f"  single call min {r['warm_min_ms']*1e3:8.1f} us, caches flushed {r['cold_mean_ms']*1e3:8.1f} us"
                       + (f"  in a HIP graph {r['graph_ms_per_step']*1e3:7.1f} us" if r["graph_ms_per_step"] else ""),
                       file=sys.stderr, flush=True)
             del case
             torch.cuda.empty_cache()
     return rows
+
+
+def geomean(xs):
+    import math
+    xs = [x for x in xs if x]
+    return math.exp(sum(math.log(x) for x in xs) / len(xs)) if xs else None
+
+
+def shape_suite(args, gs, torch, graphgen, dev):
+    """The shape suite at N = 128 / 256 / 512, geometric means per width as in the paper's
+    Table VII.  With --vendor the same product through torch's CSR matmul (the vendor sparse
+    library underneath) is timed beside it, as context."""
+    rows = []
+    for name in graphgen.SUITE_NAMES:
+        w = graphgen.suite_matrix(name)
+        d = w.describe()
+        print(f"# {name}: M={w.M} nnz={w.nnz} mean row {d['mean_row']:.1f} longest {d['max_row']}",
+              file=sys.stderr, flush=True)
+        A = None
+        if args.vendor:
+            A = torch.sparse_csr_tensor(torch.from_numpy(w.rowptr).to(dev), torch.from_numpy(w.colind).to(dev),
+                                        torch.from_numpy(w.vals).to(dev), size=(w.M, w.K))
+        for N in w.widths:
+            case = DeviceCase(w, N, torch, dev)
+            steps = max(20, min(args.steps, int(2e11 / (w.nnz * N))))
+            r = case.time(gs, torch, "sum", steps, 3, bracket_kernel=False)
+            r["vendor_ms"] = None
+            if A is not None:
+                for _ in range(2):
+                    torch.sparse.mm(A, case.B)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(steps):
+                    torch.sparse.mm(A, case.B)
+                torch.cuda.synchronize()
+                r["vendor_ms"] = (time.perf_counter() - t0) * 1e3 / steps
+            rows.append(r)
+            print(f"{name:22s} N={N:4d} {r['ms_per_step']*1e3:9.1f} us {r['gflops']:8.1f} GFLOP/s  model "
+                  f"{r['model_GBps_step']:8.1f} GB/s ({r['model_GBps_step']/HBM_PEAK_GBPS*100:5.1f}% of HBM peak)"
+                  + (f"  vendor CSR matmul {r['vendor_ms']*1e3:9.1f} us ({r['vendor_ms']/r['ms_per_step']:5.2f}x)"
+                     if r["vendor_ms"] else ""), file=sys.stderr, flush=True)
+            del case
+            torch.cuda.empty_cache()
+    summary = []
+    for N in (128, 256, 512):
+        sel = [r for r in rows if r["N"] == N]
+        g = {"N": N, "matrices": len(sel), "geomean_gflops": geomean([r["gflops"] for r in sel]),
+             "geomean_model_GBps": geomean([r["model_GBps_step"] for r in sel]),
+             "geomean_speedup_over_vendor": geomean([r["vendor_ms"] / r["ms_per_step"] for r in sel if r["vendor_ms"]])}
+        summary.append(g)
+        print(f"geometric mean N={N:4d}: {g['geomean_gflops']:8.1f} GFLOP/s, model {g['geomean_model_GBps']:8.1f} GB/s"
+              + (f", {g['geomean_speedup_over_vendor']:.2f}x the vendor CSR matmul" if g["geomean_speedup_over_vendor"] else ""),
+              file=sys.stderr, flush=True)
+    return {"rows": [{k: r[k] for k in ("workload", "N", "ms_per_step", "gflops", "model_GBps_step", "vendor_ms")}
+                     for r in rows], "summary": summary}
 
 
 def main():
@@ -265,10 +377,16 @@ def main():
     ap.add_argument("--mtx", default="", help="benchmark a user-supplied Matrix Market file instead of --workload")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-cold", action="store_true",
+                    help="skip the single-call / flushed-cache / copy-bandwidth figures (used under counter runs)")
     ap.add_argument("--sweep", action="store_true", help="also time every workload/width/op")
     ap.add_argument("--sweep-out", default="", help="write the sweep rows to this JSON file")
     ap.add_argument("--gcn", action="store_true",
                     help="also time a 2-layer GCN training step and the share of the aggregation in it")
+    ap.add_argument("--suite", action="store_true",
+                    help="also run the shape suite at N = 128/256/512 and print geometric means (Table VII's layout)")
+    ap.add_argument("--vendor", action="store_true",
+                    help="with --suite: time torch's CSR matmul (vendor sparse library) beside each case")
     ap.add_argument("--gradients", action="store_true",
                     help="also time the gradient-side entry points (positions, transposed, pooling gradient)")
     ap.add_argument("--copy-gib", type=float, default=0.0,
@@ -302,13 +420,17 @@ def main():
         print(f"# calibration copy: {n * 4} bytes read, {n * 4} bytes written", file=sys.stderr)
         del src, dst
 
-    sweep_rows = sweep(args, gs, torch, graphgen, dev) if args.sweep else None
+    evictor = None if args.no_cold else Evictor(gs, torch, dev)
+    if args.sweep and evictor is None:
+        evictor = Evictor(gs, torch, dev)
+    sweep_rows = sweep(args, gs, torch, graphgen, dev, evictor) if args.sweep else None
     if sweep_rows is not None and args.sweep_out:
         with open(args.sweep_out, "w") as f:
             json.dump(sweep_rows, f, indent=1)
 
     grad_rows = time_gradients(args, gs, torch, graphgen, dev) if args.gradients else None
     gcn_rows = gcn_share(args, gs, torch, graphgen, dev) if args.gcn else None
+    suite_out = shape_suite(args, gs, torch, graphgen, dev) if args.suite else None
 
     w = graphgen.workload_from_matrix_market(args.mtx) if args.mtx else graphgen.workload(args.workload, args.scale)
     N = args.width or w.widths[0]
@@ -338,15 +460,26 @@ def main():
                      "algorithmic_bytes_per_launch": r["model_bytes"],
                      "avg_launch_ms": r["main_kernel_ms"], "launches_timed": r["launches_timed"]},
     }
+    if evictor is not None:
+        # outside the timed region: one call at a time, back to back and with L2 and Infinity Cache
+        # flushed before each call, and the plain-copy bandwidth of this machine as a practical ceiling
+        out["single_call"] = warm_and_cold(gs, torch, case, op, evictor)
+        copy = evictor.copy_GBps()
+        out["measured_copy_GBps"] = copy
+        out["roofline"]["frac_of_measured_copy"] = achieved / copy
+        out["single_call"]["cold_model_GBps"] = r["model_bytes"] / (out["single_call"]["cold_mean_ms"] * 1e-3) / 1e9
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, case.B_host, op)
     if sweep_rows is not None:
-        out["sweep"] = [{k: row[k] for k in ("workload", "N", "op", "ms_per_step", "gflops", "model_GBps_step")}
+        out["sweep"] = [{k: row[k] for k in ("workload", "N", "op", "ms_per_step", "gflops", "model_GBps_step",
+                                             "warm_min_ms", "cold_mean_ms")}
                         for row in sweep_rows]
     if grad_rows is not None:
         out["gradients"] = grad_rows
     if gcn_rows is not None:
         out["gcn"] = gcn_rows
+    if suite_out is not None:
+        out["suite"] = suite_out
     print(json.dumps(out), flush=True)
 
 

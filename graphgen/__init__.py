@@ -228,6 +228,75 @@ def workload_from_matrix_market(path, widths=(128, 256, 512), seed=100) -> Workl
 
 
 # --------------------------------------------------------------------------
+# A suite of matrix shapes standing in for the range of a sparse-matrix collection
+# (Section V-A evaluates on many collection matrices and reports geometric means,
+# Table VII).  Every matrix is generated here from a seed; none is a collection file.
+# --------------------------------------------------------------------------
+def _csr_from_offsets(dims, offsets):
+    """Stencil on a regular grid of shape `dims`: vertex x is joined to x + o for every offset
+    vector o that stays inside the grid (no wrap-around).  Rows come out with sorted columns."""
+    dims = tuple(int(d) for d in dims)
+    M = int(np.prod(dims))
+    coords = np.unravel_index(np.arange(M, dtype=np.int64), dims)
+    strides = [int(np.prod(dims[a + 1:])) for a in range(len(dims))]
+    offsets = sorted(offsets, key=lambda o: sum(x * st for x, st in zip(o, strides)))
+    cols = np.full((M, len(offsets)), -1, dtype=np.int64)
+    for t, o in enumerate(offsets):
+        ok = np.ones(M, dtype=bool)
+        for a, d in enumerate(dims):
+            ok &= (coords[a] + o[a] >= 0) & (coords[a] + o[a] < d)
+        cols[ok, t] = np.arange(M, dtype=np.int64)[ok] + sum(x * st for x, st in zip(o, strides))
+    keep = cols >= 0
+    rowptr = np.zeros(M + 1, dtype=np.int64)
+    np.cumsum(keep.sum(axis=1), out=rowptr[1:])
+    return M, M, rowptr.astype(np.int32), cols[keep].astype(np.int32)
+
+
+def grid2d(n):
+    """5-point stencil on an n x n grid (mesh / road-network-like: short rows, banded)."""
+    return _csr_from_offsets((n, n), [(0, 0), (0, 1), (0, -1), (1, 0), (-1, 0)])
+
+
+def grid3d(n):
+    """27-point stencil on an n^3 grid (finite-element-like: equal rows of up to 27 entries)."""
+    offs = [(a, b, c) for a in (-1, 0, 1) for b in (-1, 0, 1) for c in (-1, 0, 1)]
+    return _csr_from_offsets((n, n, n), offs)
+
+
+SUITE = {
+    # name: (builder, seed); M, entries and degree structure span a few 10^4 .. 10^6 rows,
+    # mean row length 3 .. 130, flat / power-law / R-MAT-skewed / banded
+    "powerlaw_30k_d8":    (lambda: chung_lu_symmetric(30_000, 120_000, seed=201, max_over_mean=30.0), 201),
+    "powerlaw_100k_d30":  (lambda: chung_lu_symmetric(100_000, 1_500_000, seed=202, max_over_mean=60.0), 202),
+    "powerlaw_400k_d10":  (lambda: chung_lu_symmetric(400_000, 2_000_000, seed=203, max_over_mean=200.0), 203),
+    "powerlaw_1m_d6":     (lambda: chung_lu_symmetric(1_000_000, 3_000_000, seed=204, max_over_mean=400.0), 204),
+    "web_200k_d20":       (lambda: chung_lu_directed(200_000, 4_000_000, seed=205, max_over_mean_out=40.0,
+                                                     max_over_mean_in=400.0), 205),
+    "web_800k_d6":        (lambda: chung_lu_directed(800_000, 4_800_000, seed=206, max_over_mean_out=100.0,
+                                                     max_over_mean_in=1000.0, empty_frac=0.1), 206),
+    "rmat_64k_d16":       (lambda: rmat(1 << 16, 16, 1 << 20, seed=207), 207),
+    "rmat_256k_d16":      (lambda: rmat(1 << 18, 18, 1 << 22, seed=208), 208),
+    "rmat_1m_d8":         (lambda: rmat(1 << 20, 20, 1 << 23, seed=209), 209),
+    "uniform_128k_d10":   (lambda: rmat(1 << 17, 17, 1_310_000, seed=210, a=0.25, b=0.25, c=0.25), 210),
+    "uniform_512k_d4":    (lambda: rmat(1 << 19, 19, 2_100_000, seed=211, a=0.25, b=0.25, c=0.25), 211),
+    "dense_rows_40k_d130": (lambda: chung_lu_symmetric(40_000, 2_600_000, seed=212, max_over_mean=10.0), 212),
+    "grid2d_1000":        (lambda: grid2d(1000), 213),
+    "grid2d_300":         (lambda: grid2d(300), 214),
+    "grid3d_64":          (lambda: grid3d(64), 215),
+    "grid3d_100":         (lambda: grid3d(100), 216),
+}
+SUITE_NAMES = tuple(SUITE)
+
+
+def suite_matrix(name) -> Workload:
+    """One matrix of the shape suite, values uniform(0, 1], run at N = 128 / 256 / 512 as in Table VII."""
+    builder, seed = SUITE[name]
+    M, K, rp, ci = builder()
+    return Workload(name, M, K, rp, ci, uniform_01(ci.shape[0], seed), seed, "uniform_pm1",
+                    (128, 256, 512), ("sum",), {"source": "shape suite"})
+
+
+# --------------------------------------------------------------------------
 # Small random CSR matrices for unit tests (numpy's seeded PCG64)
 # --------------------------------------------------------------------------
 def random_csr(M, K, mean_len, seed, empty_frac=0.0, duplicates=False, sort_cols=True,

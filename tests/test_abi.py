@@ -144,8 +144,14 @@ def test_chunk_size_follows_width_and_problem_size():
     assert gs.gespmm_plan(232_965, 64, 114_693_532)["chunk_nnz"] == 512
     assert all(p["lds_bytes"] == 4 * (p["chunk_nnz"] + 64) * 8 for p in plans)
     # small problems: smaller chunks, so the rows spread over more wavefronts
-    assert gs.gespmm_plan(19717, 512, 88_648)["chunk_nnz"] == 64
+    # (fewer than 2048 wavefronts over all column blocks -> halve, down to 64 entries)
+    assert [gs.gespmm_plan(19717, N, 88_648)["chunk_nnz"] for N in (32, 64, 128, 256, 512)] == [64, 64, 128, 128, 256]
     assert gs.gespmm_plan(2708, 16, 10_556)["chunk_nnz"] == 64
+    assert gs.gespmm_plan(65_536, 512, 649_959)["chunk_nnz"] == 256
+    # mean row of 17 .. 48 entries: one slot per row up to 32 entries
+    assert [gs.gespmm_plan(262_144, N, 6_859_000)["short_len"] for N in (32, 128, 512)] == [32, 32, 32]
+    assert gs.gespmm_plan(100_000, 128, 1_600_000)["short_len"] == 16
+    assert gs.gespmm_plan(100_000, 128, 4_900_000)["short_len"] == 16
     p = gs.gespmm_plan(169_343, 128, 2_330_033)
     assert p["chunk_nnz"] == 256 and p["xcd_remap"] == 0
     # rows much longer than a chunk: consecutive chunks stay on one XCD

@@ -223,6 +223,16 @@ def test_profile_brackets_main_kernel(gs):
     assert n == 3 and 0 < ms < 1000
 
 
+@pytest.mark.parametrize("floats", [4, 1020, 4 * 256 * 8192 * 4 + 4 * 77, 4 * 256 * 8192 * 9 + 4])
+def test_calibration_copy_is_a_copy(gs, floats):
+    src = torch.arange(floats, dtype=torch.int32, device="cuda").view(torch.float32)
+    dst = torch.full((floats + 8,), -1.0, device="cuda")
+    gs.gespmm_calibration_copy(src, dst[4:4 + floats])
+    torch.cuda.synchronize()
+    assert torch.equal(dst[4:4 + floats].view(torch.int32), src.view(torch.int32))
+    assert bool((dst[:4] == -1).all()) and bool((dst[-4:] == -1).all())
+
+
 # ------------------------------------------------------------ the workloads --
 @pytest.mark.parametrize("which", [0, 1, 2, "uniform_random_65k"])
 def test_workload_full_size_every_element(gs, which):
@@ -276,6 +286,19 @@ def test_workload_full_size_sampled_rows_and_properties(gs, which):
             _, Sabs = oracle.spmm(w.rowptr, w.colind, w.vals, B, "sum", rows=rows)
             err = np.abs(out["mean"][rows].astype(np.float64) * lens[rows] - out["sum"][rows])
             assert (err <= 2e-5 * Sabs + 2e-6 * np.maximum(lens[rows], 1)).all()
+
+
+@pytest.mark.parametrize("name", ["grid2d_300", "rmat_64k_d16", "grid3d_64", "web_800k_d6"])
+def test_shape_suite_matrices(gs, name):
+    """Matrices of the benchmark's shape suite at its widths: banded equal rows, R-MAT skew, many empty rows."""
+    w = graphgen.suite_matrix(name)
+    say(" ", w.describe())
+    dA = dev(w.rowptr), dev(w.colind), dev(w.vals)
+    rows = None if w.nnz < 1_000_000 else _sample_rows(w.rowptr, 2000, 5)
+    for N in ((128, 512) if rows is None else (128, 256, 512)):
+        B = w.B(N)
+        for op in ("sum", "max"):
+            check(gs, w.rowptr, w.colind, w.vals, B, op, rows=rows, label=name, dA=dA)
 
 
 def test_wide_feature_matrix_many_column_blocks(gs):

@@ -127,3 +127,29 @@ def test_matrix_market_reader_against_scipy(tmp_path):
     (tmp_path / "bad.mtx").write_text("%%MatrixMarket matrix array real general\n2 2\n1\n2\n3\n4\n")
     with pytest.raises(ValueError):
         read_matrix_market(tmp_path / "bad.mtx")
+
+
+def test_grid_stencils_have_the_textbook_structure():
+    for n in (1, 2, 7):
+        M, K, rp, ci = graphgen.grid2d(n)
+        _check_csr(M, K, rp, ci)
+        assert M == n * n and ci.shape[0] == 5 * n * n - 4 * n            # n^2 centres + 4 n (n - 1) neighbours
+    for n in (1, 3, 5):
+        M, K, rp, ci = graphgen.grid3d(n)
+        _check_csr(M, K, rp, ci)
+        assert M == n ** 3 and ci.shape[0] == (3 * n - 2) ** 3            # product of the 1-D counts 3 n - 2
+    M, K, rp, ci = graphgen.grid2d(4)
+    A = np.zeros((16, 16), dtype=int)
+    A[np.repeat(np.arange(16), np.diff(rp)), ci] = 1
+    assert (A == A.T).all() and A[5].nonzero()[0].tolist() == [1, 4, 5, 6, 9] and A[0].nonzero()[0].tolist() == [0, 1, 4]
+    M, K, rp, ci = graphgen.grid3d(3)
+    assert rp[14] - rp[13] == 27 and rp[1] - rp[0] == 8                   # centre cell, corner cell
+
+
+def test_shape_suite_is_seeded_and_valid():
+    for name in ("powerlaw_30k_d8", "rmat_64k_d16", "grid2d_300"):
+        a, b = graphgen.suite_matrix(name), graphgen.suite_matrix(name)
+        _check_csr(a.M, a.K, a.rowptr, a.colind)
+        assert a.describe()["csr_hash"] == b.describe()["csr_hash"] and a.widths == (128, 256, 512)
+        assert a.vals.min() > 0 and a.vals.max() <= 1
+    assert len(graphgen.SUITE_NAMES) == 16
