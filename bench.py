@@ -5,6 +5,7 @@
     python bench.py --sweep            # every workload / width / op, table on stderr
     python bench.py --gradients        # also time the gradient-side entry points
     python bench.py --suite [--vendor] # shape suite at N = 128/256/512, geometric means
+    python bench.py --tile-study       # every lanes-per-row x tiles-per-lane kernel shape
     python bench.py --copy-gib 1       # also launch the calibration copy kernel (for --pmc runs)
 
 One "step" is one whole gespmm_csr call (row-initialisation kernel + chunk kernel) on a
@@ -311,6 +312,43 @@ def sweep(args, gs, torch, graphgen, dev, evictor):
     return rows
 
 
+def tile_study(args, gs, torch, graphgen, dev):
+    """Lanes per row x column tiles per lane (the second is what the paper calls the coarsening
+    factor, Table VI / Fig. 9) at fixed width, on a uniform random graph as in Section V-B and on
+    two matrices of different locality; the automatic choice is marked."""
+    rows = []
+    cases = (("uniform_random_65k", 512), ("general_ops", 128), ("grid3d_64", 128), ("large_dense_degree", 64))
+    for name, N in cases:
+        w = graphgen.suite_matrix(name) if name in graphgen.SUITE_NAMES else graphgen.workload(name, args.scale)
+        case = DeviceCase(w, N, torch, dev)
+        auto = gs.gespmm_plan(w.M, N, w.nnz)
+        steps = max(20, min(args.steps, int(2e11 / (w.nnz * N))))
+        try:
+            for G in (4, 8, 16, 32, 64):
+                for T in (1, 2, 4):
+                    if 4 * G * T > max(N, 16) * 1 or 4 * G * T < 32:      # no wider than the row, no narrower than 128 bytes
+                        continue
+                    try:
+                        gs.gespmm_set_tuning(G, T)
+                        case.time(gs, torch, "sum", 5, 2)
+                    except gs.GespmmError:                                # this shape is not instantiated
+                        continue
+                    r = case.time(gs, torch, "sum", steps, 3)
+                    p = gs.gespmm_plan(w.M, N, w.nnz)
+                    is_auto = (G, T) == (auto["lanes_per_row"], auto["tiles_per_lane"])
+                    rows.append({"workload": name, "N": N, "lanes_per_row": G, "tiles_per_lane": T,
+                                 "col_blocks": p["col_blocks"], "kernel_ms": r["main_kernel_ms"],
+                                 "gflops_kernel": 2.0 * w.nnz * N / (r["main_kernel_ms"] * 1e-3) / 1e9, "auto": is_auto})
+                    print(f"{name:20s} N={N:4d} lanes/row {G:2d} tiles/lane {T}  column blocks {p['col_blocks']:2d}  kernel "
+                          f"{r['main_kernel_ms']*1e3:9.1f} us {rows[-1]['gflops_kernel']:8.1f} GFLOP/s"
+                          + ("   <- automatic" if is_auto else ""), file=sys.stderr, flush=True)
+        finally:
+            gs.gespmm_set_tuning()
+        del case
+        torch.cuda.empty_cache()
+    return rows
+
+
 def geomean(xs):
     import math
     xs = [x for x in xs if x]
@@ -387,6 +425,8 @@ def main():
                     help="also run the shape suite at N = 128/256/512 and print geometric means (Table VII's layout)")
     ap.add_argument("--vendor", action="store_true",
                     help="with --suite: time torch's CSR matmul (vendor sparse library) beside each case")
+    ap.add_argument("--tile-study", action="store_true",
+                    help="also time every lanes-per-row x tiles-per-lane kernel shape on four matrices (Table VI's question)")
     ap.add_argument("--gradients", action="store_true",
                     help="also time the gradient-side entry points (positions, transposed, pooling gradient)")
     ap.add_argument("--copy-gib", type=float, default=0.0,
@@ -431,6 +471,7 @@ def main():
     grad_rows = time_gradients(args, gs, torch, graphgen, dev) if args.gradients else None
     gcn_rows = gcn_share(args, gs, torch, graphgen, dev) if args.gcn else None
     suite_out = shape_suite(args, gs, torch, graphgen, dev) if args.suite else None
+    tile_rows = tile_study(args, gs, torch, graphgen, dev) if args.tile_study else None
 
     w = graphgen.workload_from_matrix_market(args.mtx) if args.mtx else graphgen.workload(args.workload, args.scale)
     N = args.width or w.widths[0]
@@ -480,6 +521,8 @@ def main():
         out["gcn"] = gcn_rows
     if suite_out is not None:
         out["suite"] = suite_out
+    if tile_rows is not None:
+        out["tile_study"] = tile_rows
     print(json.dumps(out), flush=True)
 
 
