@@ -473,7 +473,12 @@ def main():
     suite_out = shape_suite(args, gs, torch, graphgen, dev) if args.suite else None
     tile_rows = tile_study(args, gs, torch, graphgen, dev) if args.tile_study else None
 
-    w = graphgen.workload_from_matrix_market(args.mtx) if args.mtx else graphgen.workload(args.workload, args.scale)
+    if args.mtx:
+        w = graphgen.workload_from_matrix_market(args.mtx)
+    elif args.workload in graphgen.SUITE_NAMES:
+        w = graphgen.suite_matrix(args.workload)
+    else:
+        w = graphgen.workload(args.workload, args.scale)
     N = args.width or w.widths[0]
     op = args.op
     case = DeviceCase(w, N, torch, dev)
