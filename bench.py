@@ -235,19 +235,25 @@ def time_gradients(args, gs, torch, graphgen, dev):
 
 
 def gcn_share(args, gs, torch, graphgen, dev):
-    """Share of the aggregation (SpMM, forward and backward) in a 2-layer GCN training step on the
-    synthetic graphs, in the spirit of the paper's Table I (which profiles DGL's GCN example)."""
+    """Share of the aggregation (forward and backward) in a 2-layer GCN and a 2-layer GraphSAGE-pool
+    training step on the synthetic graphs, in the spirit of the paper's Table I (which profiles DGL's
+    GCN example) and of its GraphSAGE-pool experiment (Section V-E)."""
     from paper_2007_03179_amd import autograd as ag
     rows = []
-    for name, feats, hidden, classes in (("tiny_citation", 1433, 16, 7), ("width_sweep", 500, 16, 3),
-                                         ("general_ops", 128, 256, 40)):
+    for model, name, feats, hidden, classes in (("gcn", "tiny_citation", 1433, 16, 7), ("gcn", "width_sweep", 500, 16, 3),
+                                                ("gcn", "general_ops", 128, 256, 40),
+                                                ("sage-pool", "width_sweep", 500, 16, 3),
+                                                ("sage-pool", "general_ops", 128, 256, 40)):
         w = graphgen.workload(name, args.scale)
         g = ag.CsrGraph(torch.from_numpy(w.rowptr).to(dev), torch.from_numpy(w.colind).to(dev),
-                        torch.from_numpy(w.vals).to(dev), w.K)
+                        torch.from_numpy(w.vals).to(dev) if model == "gcn" else None, w.K)
         X = torch.from_numpy(graphgen.uniform_pm1((w.M, feats), 7, stream=feats)).to(dev)
         y = torch.from_numpy((graphgen.uniform_01(w.M, 8) * classes).astype("int64") % classes).to(dev)
         torch.manual_seed(0)
-        l1, l2 = ag.GraphConv(feats, hidden).to(dev), ag.GraphConv(hidden, classes).to(dev)
+        if model == "gcn":
+            l1, l2 = ag.GraphConv(feats, hidden).to(dev), ag.GraphConv(hidden, classes).to(dev)
+        else:
+            l1, l2 = ag.SageConv(feats, hidden, "pool").to(dev), ag.SageConv(hidden, classes, "pool").to(dev)
         opt = torch.optim.Adam(list(l1.parameters()) + list(l2.parameters()), lr=0.01)
 
         def train_step():
@@ -256,14 +262,23 @@ def gcn_share(args, gs, torch, graphgen, dev):
             loss.backward()
             opt.step()
 
-        H1 = torch.randn(w.M, hidden, device=dev)
-        H2 = torch.randn(w.M, classes, device=dev)
-        t1, t2 = g.transposed(False)[:], None
+        if model == "gcn":                           # aggregation after the dense layer: widths hidden, classes
+            H1 = torch.randn(w.M, hidden, device=dev)
+            H2 = torch.randn(w.M, classes, device=dev)
+            t1 = g.transposed(False)
 
-        def aggregation_only():                      # the four SpMM calls of one step, same shapes
-            for H in (H1, H2):
-                gs.gespmm_csr(g.rowptr, g.colind, g.vals, H, "sum")
-                gs.gespmm_csr(t1[0], t1[1], t1[2], H, "sum")
+            def aggregation_only():                  # the four SpMM calls of one step, same shapes
+                for H in (H1, H2):
+                    gs.gespmm_csr(g.rowptr, g.colind, g.vals, H, "sum")
+                    gs.gespmm_csr(t1[0], t1[1], t1[2], H, "sum")
+        else:                                        # pooling over the layer's input width: feats, hidden
+            H1 = torch.randn(w.M, feats, device=dev)
+            H2 = torch.randn(w.M, hidden, device=dev)
+
+            def aggregation_only():                  # max with positions forward, pooled gradient backward
+                for H in (H1, H2):
+                    _, arg = gs.gespmm_csr_arg(g.rowptr, g.colind, None, H, "max")
+                    gs.gespmm_pool_backward(g.colind, None, arg, H, w.K)
 
         out = {}
         for label, fn in (("step", train_step), ("aggregation", aggregation_only)):
@@ -276,10 +291,10 @@ def gcn_share(args, gs, torch, graphgen, dev):
                 fn()
             torch.cuda.synchronize()
             out[label] = (time.perf_counter() - t0) * 1e3 / n
-        rows.append({"workload": name, "features": feats, "hidden": hidden, "classes": classes,
+        rows.append({"model": model, "workload": name, "features": feats, "hidden": hidden, "classes": classes,
                      "train_step_ms": out["step"], "aggregation_ms": out["aggregation"],
                      "aggregation_share": out["aggregation"] / out["step"]})
-        print(f"{name:20s} GCN {feats}-{hidden}-{classes}: step {out['step']*1e3:9.1f} us, aggregation (2 fwd + 2 bwd SpMM) "
+        print(f"{name:20s} {model} {feats}-{hidden}-{classes}: step {out['step']*1e3:9.1f} us, aggregation (2 forward + 2 backward calls) "
               f"{out['aggregation']*1e3:8.1f} us = {out['aggregation']/out['step']*100:5.1f} % of the step",
               file=sys.stderr, flush=True)
     return rows

@@ -77,3 +77,25 @@ class GraphConv(torch.nn.Module):
     def forward(self, graph: CsrGraph, X):
         out = spmm(graph, X @ self.weight, self.op)
         return out if self.bias is None else out + self.bias
+
+
+class SageConv(torch.nn.Module):
+    """One GraphSAGE layer, h_v = W_self x_v + W_neigh agg_{u in N(v)} m_u (+ b).  aggregator 'mean'
+    takes m_u = x_u with the mean over the stored entries of row v (an SpMM); aggregator 'pool' takes
+    m_u = relu(W_pool x_u + b_pool) with the element-wise maximum (the SpMM-like operation the paper
+    singles out, Section V-E).  Use a graph with vals = None (or all ones) for the textbook layer."""
+
+    def __init__(self, in_features, out_features, aggregator="mean", bias=True):
+        super().__init__()
+        assert aggregator in ("mean", "pool")
+        self.aggregator = aggregator
+        self.w_self = torch.nn.Linear(in_features, out_features, bias=bias)
+        self.w_neigh = torch.nn.Linear(in_features, out_features, bias=False)
+        self.w_pool = torch.nn.Linear(in_features, in_features) if aggregator == "pool" else None
+
+    def forward(self, graph: CsrGraph, X):
+        if self.aggregator == "mean":
+            agg = spmm(graph, X, "mean")
+        else:
+            agg = spmm(graph, torch.relu(self.w_pool(X)), "max")
+        return self.w_self(X) + self.w_neigh(agg)

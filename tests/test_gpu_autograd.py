@@ -98,3 +98,39 @@ def test_two_layer_gcn_trains(ag):
         losses.append(float(loss.detach()))
     print("  gcn losses", losses[0], losses[-1], flush=True)
     assert np.isfinite(losses).all() and losses[-1] < losses[0] * 0.8
+
+
+@pytest.mark.parametrize("aggregator", ["mean", "pool"])
+def test_sage_layer_matches_dense_pytorch(ag, aggregator):
+    """Output and every gradient of a GraphSAGE layer against the same layer written with dense tensors."""
+    rp, ci, _ = graphgen.random_csr(50, 50, 4.0, 41, empty_frac=0.1)
+    print(f"  case sage {aggregator}", flush=True)
+    g = _graph(ag, rp, ci, None, 50)
+    rows = np.repeat(np.arange(50), np.diff(rp))
+    mask = np.zeros((50, 50), dtype=bool)
+    mask[rows, ci] = True
+    maskd = torch.from_numpy(mask).cuda()
+    lens = torch.from_numpy(np.diff(rp).astype(np.float32)).cuda()
+    torch.manual_seed(3)
+    layer = ag.SageConv(12, 8, aggregator).cuda()
+    X1 = torch.from_numpy(graphgen.random_dense(50, 12, 8)).cuda().requires_grad_(True)
+    X2 = X1.detach().clone().requires_grad_(True)
+    dOut = torch.from_numpy(graphgen.random_dense(50, 8, 9)).cuda()
+    out = layer(g, X1)
+    out.backward(dOut)
+    got = [X1.grad.clone()] + [p.grad.clone() for p in layer.parameters()]
+    layer.zero_grad()
+    if aggregator == "mean":
+        agg = (maskd.float() @ X2) / lens.clamp(min=1)[:, None]
+    else:
+        m = torch.relu(layer.w_pool(X2))
+        prod = torch.where(maskd[:, :, None], m[None, :, :], torch.full((50, 50, 12), -float("inf"), device="cuda"))
+        agg = prod.max(dim=1).values
+        agg = torch.where(torch.isinf(agg), torch.zeros_like(agg), agg)
+    ref = layer.w_self(X2) + layer.w_neigh(agg)
+    ref.backward(dOut)
+    want = [X2.grad] + [p.grad for p in layer.parameters()]
+    torch.cuda.synchronize()
+    assert torch.allclose(out, ref, rtol=1e-5, atol=1e-5)
+    for a, b in zip(got, want):
+        assert torch.allclose(a, b, rtol=1e-4, atol=1e-5)
