@@ -40,15 +40,25 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
+B_ELEM_BYTES = 4                # 2 with --b-dtype bf16 / f16 (B stored in 16 bits; arithmetic and C stay fp32)
+
+
 def model_bytes(M, N, nnz, has_vals=True):
     """Algorithmic bytes of one SpMM: rowptr + colind + vals + one B-row gather per stored
     entry + C written once (fp32 / int32)."""
-    return 4 * (M + 1) + 4 * nnz + (4 * nnz if has_vals else 0) + 4 * nnz * N + 4 * M * N
+    return 4 * (M + 1) + 4 * nnz + (4 * nnz if has_vals else 0) + B_ELEM_BYTES * nnz * N + 4 * M * N
 
 
 def compulsory_bytes(M, K, N, nnz, has_vals=True):
     """Same, but B counted once (what must cross HBM when caches keep every reuse)."""
-    return 4 * (M + 1) + 4 * nnz + (4 * nnz if has_vals else 0) + 4 * K * N + 4 * M * N
+    return 4 * (M + 1) + 4 * nnz + (4 * nnz if has_vals else 0) + B_ELEM_BYTES * K * N + 4 * M * N
+
+
+B_TORCH_DTYPE = None
+
+
+def forward(gs):
+    return gs.gespmm_csr if B_ELEM_BYTES == 4 else gs.gespmm_csr_b16
 
 
 def cpu_baseline(w, B, op, budget_s=12.0, max_passes=60):
@@ -75,7 +85,7 @@ def time_graph_replay(gs, torch, case, op, steps, calls_per_graph=20):
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=side):
         for _ in range(calls_per_graph):
-            gs.gespmm_csr(case.rp, case.ci, case.v, case.B, op, C=case.C)
+            forward(gs)(case.rp, case.ci, case.v, case.B, op, C=case.C)
     replays = max(1, steps // calls_per_graph)
     graph.replay()
     torch.cuda.synchronize()
@@ -96,6 +106,9 @@ class DeviceCase:
         self.ci = torch.from_numpy(w.colind).to(dev)
         self.v = torch.from_numpy(w.vals).to(dev)
         self.B = torch.from_numpy(self.B_host).to(dev)
+        if B_ELEM_BYTES == 2:                            # stored in 16 bits; the host copy keeps the rounded values
+            self.B = self.B.to(B_TORCH_DTYPE)
+            self.B_host = self.B.float().cpu().numpy()
         self.C = torch.empty((w.M, N), dtype=torch.float32, device=dev)
 
     def time(self, gs, torch, op, steps, warmup, bracket_kernel=True):
@@ -105,13 +118,13 @@ class DeviceCase:
         only matters for microsecond-scale workloads)."""
         stream = torch.cuda.current_stream()
         for _ in range(warmup):
-            gs.gespmm_csr(self.rp, self.ci, self.v, self.B, op, C=self.C, stream=stream)
+            forward(gs)(self.rp, self.ci, self.v, self.B, op, C=self.C, stream=stream)
         torch.cuda.synchronize()
         if bracket_kernel:
             gs.gespmm_profile_begin(steps)
         t0 = time.perf_counter()
         for _ in range(steps):
-            gs.gespmm_csr(self.rp, self.ci, self.v, self.B, op, C=self.C, stream=stream)
+            forward(gs)(self.rp, self.ci, self.v, self.B, op, C=self.C, stream=stream)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         main_ms_sum, launches = gs.gespmm_profile_end() if bracket_kernel else (float("nan"), 0)
@@ -164,7 +177,7 @@ def per_call_times(gs, torch, case, op, calls, before_each=None):
             before_each()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record(stream)
-        gs.gespmm_csr(case.rp, case.ci, case.v, case.B, op, C=case.C, stream=stream)
+        forward(gs)(case.rp, case.ci, case.v, case.B, op, C=case.C, stream=stream)
         b.record(stream)
         pairs.append((a, b))
     torch.cuda.synchronize()
@@ -446,6 +459,8 @@ def main():
                     help="also time the gradient-side entry points (positions, transposed, pooling gradient)")
     ap.add_argument("--copy-gib", type=float, default=0.0,
                     help="launch the calibration copy kernel once on this many GiB (traffic-counter yardstick)")
+    ap.add_argument("--b-dtype", default="f32", choices=("f32", "bf16", "f16"),
+                    help="storage type of the dense input B (arithmetic and C stay fp32); f32 is the paper's setting")
     ap.add_argument("--tuning", default="",
                     help="lanes_per_row,tiles_per_lane,xcd_remap,chunk_nnz,short_len override, e.g. "
                          "--tuning=-1,-1,0,512,16 (each -1 = automatic)")
@@ -460,6 +475,10 @@ def main():
     import paper_2007_03179_amd as gs
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    global B_ELEM_BYTES, B_TORCH_DTYPE
+    if args.b_dtype != "f32":
+        B_ELEM_BYTES, B_TORCH_DTYPE = 2, {"bf16": torch.bfloat16, "f16": torch.float16}[args.b_dtype]
+        assert not (args.gradients or args.gcn or args.tile_study or args.vendor), "--b-dtype applies to the forward call only"
     gs.lib()
     dev = torch.device("cuda:0")
     if args.tuning:
@@ -498,7 +517,7 @@ def main():
     op = args.op
     case = DeviceCase(w, N, torch, dev)
     r = case.time(gs, torch, op, args.steps, args.warmup)
-    plan = gs.gespmm_plan(w.M, N, w.nnz)
+    plan = gs.gespmm_plan_b16(w.M, N, w.nnz, args.b_dtype)
     desc = w.describe()
     achieved = r["model_GBps_kernel"]
     out = {
@@ -508,7 +527,8 @@ def main():
         "ms_per_step": r["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{w.name}: M=K={w.M}, nnz={w.nnz}, N={N}, reduce={op}, seed={w.seed}",
+        "config": {"workload": f"{w.name}: M=K={w.M}, nnz={w.nnz}, N={N}, reduce={op}, seed={w.seed}"
+                               + ("" if args.b_dtype == "f32" else f", B stored as {args.b_dtype}"),
                    "csr_hash": desc["csr_hash"], "max_row": desc["max_row"],
                    "kernel": f"chunk_kernel<FoldRows> vec={plan['vec']} G={plan['lanes_per_row']} "
                              f"T={plan['tiles_per_lane']} S={plan['chunk_nnz']} col_blocks={plan['col_blocks']}"},
@@ -517,7 +537,7 @@ def main():
         "compulsory_bytes": r["compulsory_bytes"],
         "roofline": {"bound": "hbm", "kernel": "chunk_kernel<FoldRows>", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(f"{w.name}/N{N}/{op}"),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(f"{w.name}/N{N}/{op}") if args.b_dtype == "f32" else None,
                      "algorithmic_bytes_per_launch": r["model_bytes"],
                      "avg_launch_ms": r["main_kernel_ms"], "launches_timed": r["launches_timed"]},
     }

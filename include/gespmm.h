@@ -80,6 +80,25 @@ int gespmm_csr_simple(int64_t M, int64_t K, int64_t N, const int32_t* rowptr,
                       void* stream);
 
 /*
+ * The same operation with B stored in a 16-bit floating-point format.  This goes beyond the
+ * paper, which evaluates fp32 only (Section V-A): the result is still Algorithm 1 / Eq. 1,
+ * every element of B is widened to fp32 (exactly) before use, products, sums, comparisons and
+ * C are fp32, so the accuracy statement of gespmm_csr holds unchanged with respect to the
+ * values B actually stores.  What changes is the traffic: a gathered row of B is half as long.
+ *   B        device, 16-bit elements [K*N], row-major, leading dimension N.
+ *   b_dtype  GESPMM_BF16 (1 sign, 8 exponent, 7 fraction bits) or GESPMM_F16 (IEEE binary16);
+ *            GESPMM_F32 makes the call identical to gespmm_csr (B then points to fp32 data).
+ * Everything else as gespmm_csr.  16-byte aligned B and C with N a multiple of 4 take the
+ * vectorised kernels (4 columns per lane, 8-byte loads), anything else one column per lane.
+ * Errors as gespmm_csr; GESPMM_ERR_BAD_ARG for an unknown b_dtype.
+ */
+typedef enum { GESPMM_F32 = 0, GESPMM_BF16 = 1, GESPMM_F16 = 2 } gespmm_dtype_t;
+
+int gespmm_csr_b16(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                   const int32_t* colind, const float* vals, const void* B, int b_dtype, float* C,
+                   int op, void* stream);
+
+/*
  * max or min together with the POSITION of the extreme: what a pooling aggregation
  * (the GraphSAGE-pool use of the SpMM-like operation, Section V-E) needs in order to
  * route its gradient (the operator carries a gradient definition, Section IV-B).
@@ -157,7 +176,7 @@ int gespmm_pool_backward(int64_t M, int64_t K, int64_t N, int64_t nnz, const int
  * Fills the launch shape gespmm_csr would use for these sizes.
  */
 typedef struct {
-  int32_t vec;            /* floats per lane per load: 4 (vectorised) or 1 (scalar)      */
+  int32_t vec;            /* columns per lane per load: 4 (vectorised) or 1 (scalar)      */
   int32_t lanes_per_row;  /* G: lanes that cover one column block of a sparse row         */
   int32_t tiles_per_lane; /* T: column tiles each lane accumulates (row loaded once)      */
   int32_t slots;          /* 64 / G: non-zeros of a row consumed per wavefront step       */
@@ -172,6 +191,8 @@ typedef struct {
 } gespmm_plan_t;
 
 int gespmm_plan(int64_t M, int64_t N, int64_t nnz, int aligned16, gespmm_plan_t* out);
+/* The same for gespmm_csr_b16. */
+int gespmm_plan_b16(int64_t M, int64_t N, int64_t nnz, int aligned16, int b_dtype, gespmm_plan_t* out);
 
 /*
  * Tuning override for tests and benchmarks (process-wide, not thread-safe):

@@ -47,6 +47,10 @@ def lib():
         i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
         L.gespmm_csr.restype = ci
         L.gespmm_csr.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, ci, vp]
+        L.gespmm_csr_b16.restype = ci
+        L.gespmm_csr_b16.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, ci, vp, ci, vp]
+        L.gespmm_plan_b16.restype = ci
+        L.gespmm_plan_b16.argtypes = [i64, i64, i64, ci, ci, ctypes.POINTER(gespmm_plan_t)]
         L.gespmm_csr_simple.restype = ci
         L.gespmm_csr_simple.argtypes = [i64, i64, i64, vp, vp, vp, vp, vp, ci, vp]
         L.gespmm_csr_arg.restype = ci
@@ -99,13 +103,14 @@ def _stream(stream):
     return ctypes.c_void_p(s.cuda_stream)
 
 
-def _check_tensors(rowptr, colind, vals, B, C):
+def _check_tensors(rowptr, colind, vals, B, C, b_dtype=None):
     import torch
+    b_dtype = b_dtype or torch.float32
     assert rowptr.is_cuda and rowptr.dtype == torch.int32 and rowptr.is_contiguous()
     assert colind.is_cuda and colind.dtype == torch.int32 and colind.is_contiguous()
     assert vals is None or (vals.is_cuda and vals.dtype == torch.float32 and vals.is_contiguous()
                             and vals.numel() == colind.numel())
-    assert B.is_cuda and B.dtype == torch.float32 and B.is_contiguous() and B.dim() == 2
+    assert B.is_cuda and B.dtype == b_dtype and B.is_contiguous() and B.dim() == 2
     assert C.is_cuda and C.dtype == torch.float32 and C.is_contiguous() and C.dim() == 2
     assert C.shape == (rowptr.numel() - 1, B.shape[1])
 
@@ -121,6 +126,29 @@ def gespmm_csr(rowptr, colind, vals, B, op, C=None, stream=None):
     _check(lib().gespmm_csr(M, K, N, colind.numel(), _ptr(rowptr), _ptr(colind), _ptr(vals),
                             _ptr(B), _ptr(C), code, _stream(stream)))
     return C
+
+
+DTYPES = {"f32": 0, "bf16": 1, "f16": 2}
+
+
+def gespmm_csr_b16(rowptr, colind, vals, B, op, C=None, stream=None):
+    """C = A (x) B with B stored as torch.bfloat16 or torch.float16 (fp32 arithmetic and result)."""
+    import torch
+    M, (K, N) = rowptr.numel() - 1, B.shape
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.float32, device=B.device)
+    code_b = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}[B.dtype]
+    _check_tensors(rowptr, colind, vals, B, C, b_dtype=B.dtype)
+    code = OPS[op] if isinstance(op, str) else int(op)
+    _check(lib().gespmm_csr_b16(M, K, N, colind.numel(), _ptr(rowptr), _ptr(colind), _ptr(vals),
+                                _ptr(B), code_b, _ptr(C), code, _stream(stream)))
+    return C
+
+
+def gespmm_plan_b16(M, N, nnz, b_dtype="bf16", aligned16=True) -> dict:
+    p = gespmm_plan_t()
+    _check(lib().gespmm_plan_b16(M, N, nnz, int(bool(aligned16)), DTYPES[b_dtype], ctypes.byref(p)))
+    return {name: int(getattr(p, name)) for name, _ in p._fields_}
 
 
 def gespmm_csr_simple(rowptr, colind, vals, B, op, C=None, stream=None):

@@ -14,6 +14,14 @@ int gespmm_plan(int64_t M, int64_t N, int64_t nnz, int aligned16, gespmm_plan_t*
   return GESPMM_OK;
 }
 
+int gespmm_plan_b16(int64_t M, int64_t N, int64_t nnz, int aligned16, int b_dtype, gespmm_plan_t* out) {
+  if (!out) return GESPMM_ERR_NULL;
+  if (M < 0 || N < 0 || nnz < 0) return GESPMM_ERR_BAD_ARG;
+  if (b_dtype != GESPMM_F32 && b_dtype != GESPMM_BF16 && b_dtype != GESPMM_F16) return GESPMM_ERR_BAD_ARG;
+  make_plan(M, N, nnz, aligned16 != 0, out, b_dtype == GESPMM_F32 ? 4 : 2);
+  return GESPMM_OK;
+}
+
 int gespmm_set_tuning(int lanes_per_row, int tiles_per_lane, int xcd_remap, int chunk_nnz, int short_len) {
   const int G = lanes_per_row, T = tiles_per_lane;
   if (G > 0 && (G > kWave || (G & (G - 1)) != 0)) return GESPMM_ERR_BAD_ARG;
@@ -49,6 +57,29 @@ int gespmm_csr(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowp
   L.M = M; L.N = N; L.nnz = nnz;
   L.rowptr = rowptr; L.colind = colind; L.vals = vals;
   L.dense_in = B; L.dense_out = C;
+  L.is_mean = op == GESPMM_MEAN;
+  L.init_target = C; L.empty_value = 0.0f; L.split_value = identity;
+  L.timed = true;
+  return launch_chunks(L, (hipStream_t)stream_);
+}
+
+int gespmm_csr_b16(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                   const int32_t* colind, const float* vals, const void* B, int b_dtype, float* C,
+                   int op, void* stream_) {
+  if (b_dtype == GESPMM_F32) return gespmm_csr(M, K, N, nnz, rowptr, colind, vals, (const float*)B, C, op, stream_);
+  if (b_dtype != GESPMM_BF16 && b_dtype != GESPMM_F16) return GESPMM_ERR_BAD_ARG;
+  const int st = validate(M, K, N, nnz, rowptr, colind, B, C, op);
+  if (st != GESPMM_OK || M == 0 || N == 0) return st;
+  const int job = op == GESPMM_MAX ? kJobMax : (op == GESPMM_MIN ? kJobMin : kJobAdd);
+  float identity = 0.0f;
+  if (job == kJobMax) identity = -__builtin_inff();
+  if (job == kJobMin) identity = __builtin_inff();
+  ChunkLaunch L;
+  L.job = job;
+  L.b_dtype = b_dtype;
+  L.M = M; L.N = N; L.nnz = nnz;
+  L.rowptr = rowptr; L.colind = colind; L.vals = vals;
+  L.dense_in = (const float*)B; L.dense_out = C;
   L.is_mean = op == GESPMM_MEAN;
   L.init_target = C; L.empty_value = 0.0f; L.split_value = identity;
   L.timed = true;

@@ -86,6 +86,52 @@ template <> struct Vec<1> {
   __device__ static Vec load(const float* p) { return Vec{{*p}}; }
   __device__ void store(float* p) const { *p = v[0]; }
 };
+// Element types of the dense input.  The 16-bit types are storage formats only: every
+// value is widened to fp32 (exactly) before the multiply, and products and sums are fp32.
+struct bf16_t { uint16_t bits; };               // 1 sign, 8 exponent, 7 fraction bits: the top half of an fp32
+struct f16_t { uint16_t bits; };                // IEEE binary16
+
+// BLoad<V, BT>: one load of V consecutive elements of type BT, kept as loaded (Raw) until
+// it is used, so that all loads of a pass can be in flight together; unpack widens to fp32.
+template <int V, class BT> struct BLoad;
+template <> struct BLoad<4, float> {
+  using Raw = float4;
+  __device__ static Raw load(const float* p) { return *reinterpret_cast<const float4*>(p); }
+  __device__ static void unpack(const Raw& r, float (&o)[4]) { o[0] = r.x; o[1] = r.y; o[2] = r.z; o[3] = r.w; }
+};
+template <> struct BLoad<1, float> {
+  using Raw = float;
+  __device__ static Raw load(const float* p) { return *p; }
+  __device__ static void unpack(const Raw& r, float (&o)[1]) { o[0] = r; }
+};
+__device__ __forceinline__ void widen_pair(bf16_t, unsigned w, float& lo, float& hi) {
+  lo = __uint_as_float(w << 16);
+  hi = __uint_as_float(w & 0xffff0000u);
+}
+__device__ __forceinline__ void widen_pair(f16_t, unsigned w, float& lo, float& hi) {
+  typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+  const half2_t h = __builtin_bit_cast(half2_t, w);
+  lo = (float)h.x;
+  hi = (float)h.y;
+}
+template <class BT> struct BLoad<4, BT> {       // BT = bf16_t or f16_t: 8 bytes = 4 elements
+  using Raw = uint2;
+  __device__ static Raw load(const BT* p) { return *reinterpret_cast<const uint2*>(p); }
+  __device__ static void unpack(const Raw& r, float (&o)[4]) {
+    widen_pair(BT{}, r.x, o[0], o[1]);
+    widen_pair(BT{}, r.y, o[2], o[3]);
+  }
+};
+template <> struct BLoad<1, bf16_t> {
+  using Raw = uint16_t;
+  __device__ static Raw load(const bf16_t* p) { return p->bits; }
+  __device__ static void unpack(const Raw& r, float (&o)[1]) { o[0] = __uint_as_float((unsigned)r << 16); }
+};
+template <> struct BLoad<1, f16_t> {
+  using Raw = uint16_t;
+  __device__ static Raw load(const f16_t* p) { return p->bits; }
+  __device__ static void unpack(const Raw& r, float (&o)[1]) { o[0] = (float)__builtin_bit_cast(_Float16, r); }
+};
 
 template <int F> __device__ __forceinline__ float fold_identity() {
   return F == kAdd ? 0.0f : (F == kMax ? -__builtin_inff() : __builtin_inff());
@@ -198,7 +244,7 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int F, int V, int T>
+template <int F, int V, int T, class BT = float>
 struct FoldRows {
   static constexpr bool kCanSkipWholeRows = false;
   struct State { Vec<V> acc[T]; };
@@ -216,8 +262,9 @@ struct FoldRows {
   template <int U>
   __device__ static void pass(State& s, const KernelArgs& a, const int2* ka, int, int first, int stride, int left,
                               const int (&)[T], const int (&colc)[T]) {
+    using Load = BLoad<V, BT>;
     int2 e2[U];
-    Vec<V> b[U][T];
+    typename Load::Raw b[U][T];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int uu = u < left ? u : (left > 0 ? left - 1 : 0);
@@ -226,16 +273,19 @@ struct FoldRows {
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const float* brow = a.B + (int64_t)e2[u].x * a.N;
+      const BT* brow = reinterpret_cast<const BT*>(a.B) + (int64_t)e2[u].x * a.N;
 #pragma unroll
-      for (int t = 0; t < T; ++t) b[u][t] = Vec<V>::load(brow + colc[t]);
+      for (int t = 0; t < T; ++t) b[u][t] = Load::load(brow + colc[t]);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int t = 0; t < T; ++t)
+      for (int t = 0; t < T; ++t) {
+        float bx[V];
+        Load::unpack(b[u][t], bx);
 #pragma unroll
-        for (int x = 0; x < V; ++x) s.acc[t].v[x] = fold<F>(s.acc[t].v[x], __int_as_float(e2[u].y), b[u][t].v[x]);
+        for (int x = 0; x < V; ++x) s.acc[t].v[x] = fold<F>(s.acc[t].v[x], __int_as_float(e2[u].y), bx[x]);
+      }
   }
 
   template <int G>
@@ -920,6 +970,30 @@ inline MainKernel pick_kernel(int job, int vec, int G, int T) {
   return vec == 4 ? pick_job<4>(job, G, T) : pick_job<1>(job, G, T);
 }
 
+// 16-bit feature matrices: the three folds, one tile per lane; four columns per lane (one
+// 8-byte load, the same four fp32 accumulators per lane as the fp32 kernels; measured 10-40 %
+// faster than eight columns per lane with 16-byte loads) in slots of up to 32 lanes, or one
+// column per lane in slots of any width.
+template <int F, class BT>
+MainKernel pick_b16_fold(int vec, int G, int T) {
+  if (T != 1) return nullptr;
+#define GESPMM_CASE(VV, GG) if (vec == VV && G == GG) return chunk_kernel<FoldRows<F, VV, 1, BT>, VV, GG, 1>;
+  GESPMM_CASE(4, 1) GESPMM_CASE(4, 2) GESPMM_CASE(4, 4) GESPMM_CASE(4, 8) GESPMM_CASE(4, 16) GESPMM_CASE(4, 32)
+  GESPMM_CASE(1, 1) GESPMM_CASE(1, 2) GESPMM_CASE(1, 4) GESPMM_CASE(1, 8) GESPMM_CASE(1, 16) GESPMM_CASE(1, 32) GESPMM_CASE(1, 64)
+#undef GESPMM_CASE
+  return nullptr;
+}
+
+template <class BT>
+MainKernel pick_b16(int job, int vec, int G, int T) {
+  switch (job) {
+    case kJobAdd: return pick_b16_fold<kAdd, BT>(vec, G, T);
+    case kJobMax: return pick_b16_fold<kMax, BT>(vec, G, T);
+    case kJobMin: return pick_b16_fold<kMin, BT>(vec, G, T);
+    default: return nullptr;
+  }
+}
+
 inline bool has_kernel(int G, int T) { return pick_gt<AddRows, 4>(G, T) != nullptr; }
 
 inline int next_pow2(int64_t x) {
@@ -937,8 +1011,14 @@ inline int g_force_g = -1, g_force_t = -1, g_force_remap = -1, g_force_shift = -
 // by atomics) and the extra row searches cost more than the added parallelism brings.
 constexpr int64_t kMinWaves = 2048;
 
-inline void make_plan(int64_t M, int64_t N, int64_t nnz, bool aligned16, gespmm_plan_t* p) {
-  const int vec = (aligned16 && N > 0 && N % 4 == 0) ? 4 : 1;
+// elem_bytes: size of one element of the dense input (4, or 2 for the 16-bit formats); a lane
+// loads four columns at once when the width and the alignment allow it, one otherwise.
+inline void make_plan(int64_t M, int64_t N, int64_t nnz, bool aligned16, gespmm_plan_t* p, int elem_bytes = 4) {
+  int vec = 1;
+  if (aligned16 && N > 0) {
+    if (elem_bytes == 4) vec = N % 4 == 0 ? 4 : 1;
+    else vec = N % 4 == 0 ? 4 : 1;              // 16-bit elements: 8-byte loads
+  }
   const int64_t ncv = N > 0 ? (N + vec - 1) / vec : 1;     // vector columns to cover
   // Column blocks of one 128-byte line (8 lanes x 16 bytes) up to N = 128, of two lines
   // beyond; wider N is covered by grid.y.  The blocks of one grid.y index run together in
@@ -946,8 +1026,11 @@ inline void make_plan(int64_t M, int64_t N, int64_t nnz, bool aligned16, gespmm_
   // L2s keep far better than whole rows of B; the sparse arrays are re-read per block,
   // which costs 8 bytes per entry against 128 gathered.
   int G = next_pow2(ncv), T = 1;
-  if (vec == 4) {
-    if (G > 8) G = N <= 128 ? 8 : 16;
+  if (vec > 1) {
+    const int line = 128 / (vec * elem_bytes);  // lanes that cover one 128-byte line of a row of B
+    if (G > line) G = ncv <= 4 * line ? line : 2 * line;   // one line; two lines for wide N
+  } else if (elem_bytes == 2) {
+    if (G > 64) G = 64;                         // one column per lane, one tile: up to 64 columns per block
   } else if (G > 16) {
     G /= 2;
     T = 2;
@@ -955,11 +1038,11 @@ inline void make_plan(int64_t M, int64_t N, int64_t nnz, bool aligned16, gespmm_
   }
   if (g_force_g > 0) G = g_force_g;
   if (g_force_t > 0) T = g_force_t;
-  // chunk size: 256 stored entries; 512 for column blocks of up to 16 floats (less data
+  // chunk size: 256 stored entries; 512 for column blocks of up to 64 bytes (less data
   // per entry) and for matrices with long rows (fewer split rows); halved while the
   // problem has too few chunks to fill the chip
   const int64_t col_blocks = (ncv + (int64_t)G * T - 1) / ((int64_t)G * T);
-  int shift = ((int64_t)vec * G * T <= 16 || (M > 0 && nnz / M >= 128)) ? 9 : 8;
+  int shift = ((int64_t)vec * G * T * elem_bytes <= 64 || (M > 0 && nnz / M >= 128)) ? 9 : 8;
   while (shift > 6 && ((nnz + (1ll << shift) - 1) >> shift) * col_blocks < kMinWaves) --shift;
   if (g_force_shift >= kMinChunkShift) shift = g_force_shift;
   p->vec = vec;
@@ -1041,13 +1124,14 @@ struct ChunkLaunch {
   MainKernel (*picker)(int vec, int G, int T) = nullptr;   // user-defined reduce: its own kernel table
   int32_t* cursor = nullptr;           // structure-transpose job only
   bool one_lane_per_entry = false;     // use the <V=1, G=1, T=1> instance whatever N is
+  int b_dtype = GESPMM_F32;            // element type of dense_in (16-bit types: fold jobs only)
 };
 
 inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
   const bool aligned16 = (((uintptr_t)L.dense_in | (uintptr_t)L.dense_out | (uintptr_t)L.result_in |
                            (uintptr_t)L.also_aligned) & 15u) == 0;
   gespmm_plan_t plan;
-  make_plan(L.M, L.N, L.nnz, aligned16, &plan);
+  make_plan(L.M, L.N, L.nnz, aligned16, &plan, L.b_dtype == GESPMM_F32 ? 4 : 2);
   if (L.one_lane_per_entry) {
     plan.vec = 1;
     plan.lanes_per_row = 1;
@@ -1056,8 +1140,11 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
     plan.col_blocks = 1;
     plan.short_len = 16;
   }
-  MainKernel kernel = L.picker ? L.picker(plan.vec, plan.lanes_per_row, plan.tiles_per_lane)
-                               : pick_kernel(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
+  MainKernel kernel = nullptr;
+  if (L.picker) kernel = L.picker(plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
+  else if (L.b_dtype == GESPMM_BF16) kernel = pick_b16<bf16_t>(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
+  else if (L.b_dtype == GESPMM_F16) kernel = pick_b16<f16_t>(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
+  else kernel = pick_kernel(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
   if (!kernel) return GESPMM_ERR_BAD_ARG;
   if (plan.col_blocks > 65535) return GESPMM_ERR_TOO_LARGE;   // grid.y limit (N beyond ~33 million)
   int shift = 0;

@@ -21,7 +21,7 @@ def L():
 
 def _declared_functions():
     text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
-    return sorted(set(re.findall(r"\b(gespmm_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(gespmm_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(L):
@@ -30,9 +30,29 @@ def test_every_declared_symbol_is_exported(L):
             "gespmm_profile_begin", "gespmm_profile_end", "gespmm_status_string",
             "gespmm_calibration_copy", "gespmm_csr_arg", "gespmm_csr_transposed", "gespmm_pool_backward",
             "gespmm_csr_transpose", "gespmm_csr_transpose_workspace_bytes",
-            "gespmm_version"} <= set(names)
+            "gespmm_csr_b16", "gespmm_plan_b16", "gespmm_version"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
+
+
+def test_b16_entry_point_argument_errors_and_plan(L):
+    p = ctypes.c_void_p(0x1000)
+    call = L.gespmm_csr_b16
+    assert call(4, 4, 8, 8, p, p, p, p, 3, p, 0, None) == 1          # unknown element type
+    assert call(4, 4, 8, 8, p, p, p, p, -1, p, 0, None) == 1
+    assert call(4, 4, 8, 8, p, p, p, None, 1, p, 0, None) == 2       # B NULL
+    assert call(4, 4, 8, 8, p, p, p, p, 2, p, 9, None) == 1          # unknown op
+    assert call(0, 4, 8, 0, p, p, p, p, 1, p, 0, None) == 0          # nothing to do
+    assert call(4, 4, 8, 2**31, p, p, p, p, 1, p, 0, None) == 3
+    # 8-byte loads of 4 columns; 16 lanes cover a 128-byte line = 64 columns, 32 lanes two lines beyond N = 256
+    want = {8: (4, 2, 1), 16: (4, 4, 1), 32: (4, 8, 1), 64: (4, 16, 1), 128: (4, 16, 2), 256: (4, 16, 4), 512: (4, 32, 4),
+            12: (4, 4, 1), 100: (4, 16, 2), 4: (4, 1, 1), 6: (1, 8, 1), 130: (1, 64, 3)}
+    for N, (vec, G, blocks) in want.items():
+        for dt in ("bf16", "f16"):
+            q = gs.gespmm_plan_b16(10**6, N, 10**8, dt)
+            assert (q["vec"], q["lanes_per_row"], q["tiles_per_lane"], q["col_blocks"]) == (vec, G, 1, blocks), (N, q)
+    assert gs.gespmm_plan_b16(10**6, 64, 10**8, "bf16", aligned16=False)["vec"] == 1
+    assert gs.gespmm_plan_b16(10**6, 64, 10**8, "f32") == gs.gespmm_plan(10**6, 64, 10**8)
 
 
 def test_version_and_status_strings(L):
