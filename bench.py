@@ -32,11 +32,15 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 # run and one WRITE_SIZE run, each scaled by the calibration copy kernel of known size;
 # the summaries are under profiles/).  Key: "<workload>/N<width>/<op>".  Missing = null.
 MEASURED_TRAFFIC_BYTES = {
-    "large_dense_degree/N64/sum": 22.991e9,   # profiles/chunk_kernel_large_dense_degree_N64_sum.md
-    "general_ops/N128/sum": 1.0067e9,         # profiles/chunk_kernel_general_ops_N128_sum.md
-    "skew_narrow/N8/sum": 0.63313e9,          # profiles/chunk_kernel_skew_narrow_N8_sum.md
+    "large_dense_degree/N64/sum": 22.989e9,   # profiles/chunk_kernel_large_dense_degree_N64_sum.md
+    "general_ops/N128/sum": 1.0068e9,         # profiles/chunk_kernel_general_ops_N128_sum.md
+    "skew_narrow/N8/sum": 0.63324e9,          # profiles/chunk_kernel_skew_narrow_N8_sum.md
     "skew_narrow/N32/sum": 1.2064e9,          # profiles/chunk_kernel_skew_narrow_N32_sum.md
-    "width_sweep/N512/sum": 0.18090e9,        # profiles/chunk_kernel_width_sweep_N512_sum.md
+    "width_sweep/N512/sum": 0.18092e9,        # profiles/chunk_kernel_width_sweep_N512_sum.md
+    "uniform_512k_d4/N128/sum": 1.4172e9,     # profiles/chunk_kernel_uniform_512k_d4_N128_sum.md
+}
+MEASURED_TRAFFIC_BYTES_BF16 = {
+    "large_dense_degree/N64/sum": 11.679e9,   # profiles/chunk_kernel_large_dense_degree_N64_bf16_sum.md
 }
 
 
@@ -537,7 +541,8 @@ def main():
         "compulsory_bytes": r["compulsory_bytes"],
         "roofline": {"bound": "hbm", "kernel": "chunk_kernel<FoldRows>", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(f"{w.name}/N{N}/{op}") if args.b_dtype == "f32" else None,
+                     "traffic": (MEASURED_TRAFFIC_BYTES if args.b_dtype == "f32" else
+                                 MEASURED_TRAFFIC_BYTES_BF16 if args.b_dtype == "bf16" else {}).get(f"{w.name}/N{N}/{op}"),
                      "algorithmic_bytes_per_launch": r["model_bytes"],
                      "avg_launch_ms": r["main_kernel_ms"], "launches_timed": r["launches_timed"]},
     }
