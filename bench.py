@@ -546,6 +546,9 @@ def main():
                      "algorithmic_bytes_per_launch": r["model_bytes"],
                      "avg_launch_ms": r["main_kernel_ms"], "launches_timed": r["launches_timed"]},
     }
+    if out["roofline"]["traffic"]:
+        # what actually crossed the L2 / fabric boundary per second (Infinity Cache hits included)
+        out["roofline"]["traffic_GBps"] = out["roofline"]["traffic"] / (r["main_kernel_ms"] * 1e-3) / 1e9
     if evictor is not None:
         # outside the timed region: one call at a time, back to back and with L2 and Infinity Cache
         # flushed before each call, and the plain-copy bandwidth of this machine as a practical ceiling

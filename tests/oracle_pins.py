@@ -215,7 +215,8 @@ def pin_scipy_float64(spmm):
 
 
 def pin_invariants(spmm):
-    """Column independence, in-row permutation, max/min duality, mean * len == sum, row subsets."""
+    """Column independence, in-row permutation, max/min duality, mean * len == sum, row subsets,
+    min <= mean <= max, linearity in B, row-permutation equivariance."""
     M, K, N = 60, 45, 9
     rp, ci, v = graphgen.random_csr(M, K, 6.0, 51, empty_frac=0.1)
     B = graphgen.random_dense(K, N, 51)
@@ -253,6 +254,26 @@ def pin_invariants(spmm):
     hi, _ = spmm(rp, ci, None, B, "max")
     mid, _ = spmm(rp, ci, None, B, "mean")
     assert np.all(lo <= mid + 1e-15) and np.all(mid <= hi + 1e-15)
+    # linearity in B for sum and mean (values chosen so that B1 + B2 is exact in fp32)
+    B1 = np.round(B * 64).astype(np.float32) / 64
+    B2 = np.round(graphgen.random_dense(K, N, 52) * 64).astype(np.float32) / 64
+    for op in ("sum", "mean"):
+        both, bs = spmm(rp, ci, v, B1 + B2, op)
+        one, s1 = spmm(rp, ci, v, B1, op)
+        two, s2 = spmm(rp, ci, v, B2, op)
+        _close(both, one + two, scale=s1 + s2 + 1e-30)
+    # permuting the rows of A permutes the rows of C (all ops, bit for bit)
+    order = rng.permutation(M)
+    lens_i = np.diff(rp)
+    rp3 = np.zeros(M + 1, dtype=np.int32)
+    np.cumsum(lens_i[order], out=rp3[1:])
+    ci3 = np.concatenate([ci[rp[i]:rp[i + 1]] for i in order]).astype(np.int32)
+    v3 = np.concatenate([v[rp[i]:rp[i + 1]] for i in order]).astype(np.float32)
+    for op in OPS:
+        moved, ms = spmm(rp3, ci3, v3, B, op)
+        plain, ps = spmm(rp, ci, v, B, op)
+        _same_bits(moved, plain[order])
+        _same_bits(ms, ps[order])
 
 
 PINS = (pin_brute_force_tiny, pin_dense_matmul, pin_identity, pin_all_ones_B,

@@ -301,6 +301,45 @@ def test_shape_suite_matrices(gs, name):
             check(gs, w.rowptr, w.colind, w.vals, B, op, rows=rows, label=name, dA=dA)
 
 
+def test_invariants_on_the_gpu_at_workload_size(gs):
+    """Properties that hold at any size, on workload 3 at full size: permuting the rows of A permutes the
+    rows of C (bit for bit for max / min, within twice the bound for sum), min <= mean <= max for unit
+    values, and sum is linear in B up to rounding."""
+    w = graphgen.workload(2)
+    rng = np.random.default_rng(11)
+    N = 128
+    B = w.B(N)
+    order = rng.permutation(w.M)
+    lens = np.diff(w.rowptr)
+    rp2 = np.zeros(w.M + 1, dtype=np.int32)
+    np.cumsum(lens[order], out=rp2[1:])
+    starts = w.rowptr[:-1][order]
+    src = (np.repeat(starts - rp2[:-1], lens[order]) + np.arange(w.nnz)).astype(np.int64)
+    ci2 = w.colind[src]
+    dB = dev(B)
+    out, moved = {}, {}
+    for op in OPS:
+        say(f"  case invariants {op}")
+        out[op] = gs.gespmm_csr(dev(w.rowptr), dev(w.colind), None, dB, op).cpu().numpy()
+        moved[op] = gs.gespmm_csr(dev(rp2), dev(ci2), None, dB, op).cpu().numpy()
+    for op in ("max", "min"):
+        assert np.array_equal(moved[op].view(np.uint32), out[op][order].view(np.uint32))
+    rows = _sample_rows(w.rowptr, 1500, 3)
+    _, Sabs = oracle.spmm(w.rowptr, w.colind, None, B, "sum", rows=rows)
+    inv = np.empty(w.M, dtype=np.int64)
+    inv[order] = np.arange(w.M)
+    assert (np.abs(moved["sum"][inv[rows]].astype(np.float64) - out["sum"][rows]) <= 2e-5 * Sabs + 2e-6).all()
+    nonempty = lens > 0
+    assert (out["min"][nonempty] <= out["mean"][nonempty] + 1e-6).all()
+    assert (out["mean"][nonempty] <= out["max"][nonempty] + 1e-6).all()
+    B2 = w.B(N + 1)[:, :N].copy()
+    both = gs.gespmm_csr(dev(w.rowptr), dev(w.colind), None, dev(B + B2), "sum").cpu().numpy()
+    two = gs.gespmm_csr(dev(w.rowptr), dev(w.colind), None, dev(B2), "sum").cpu().numpy()
+    _, Sabs2 = oracle.spmm(w.rowptr, w.colind, None, B2, "sum", rows=rows)
+    err = np.abs(both[rows].astype(np.float64) - (out["sum"][rows].astype(np.float64) + two[rows]))
+    assert (err <= 4e-5 * (Sabs + Sabs2) + 4e-6).all()      # B + B2 is itself rounded to fp32 (relative 6e-8)
+
+
 def test_wide_feature_matrix_many_column_blocks(gs):
     rp, ci, v = graphgen.random_csr(64, 50, 6.0, 77, empty_frac=0.1, long_rows=((5, 400),), duplicates=True)
     B = graphgen.random_dense(50, 4100, 77)           # 4100 columns: 65 column blocks, ragged last one
