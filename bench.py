@@ -200,8 +200,8 @@ def warm_and_cold(gs, torch, case, op, evictor, calls=30):
 def gradient_bytes(kind, M, K, N, nnz):
     """Algorithmic bytes of the gradient-side calls (same counting rules as model_bytes)."""
     walk = 4 * (M + 1) + 8 * nnz                       # rowptr + colind + vals
-    if kind == "arg":                                  # forward, then: walk + gathers + read C + write arg
-        return model_bytes(M, N, nnz) + walk + 4 * nnz * N + 8 * M * N
+    if kind == "arg":                                  # the forward bytes plus the positions written
+        return model_bytes(M, N, nnz) + 4 * M * N
     if kind == "transposed":                           # zero dB + walk + read dC + one add of N floats per entry
         return 4 * K * N + walk + 4 * M * N + 4 * nnz * N
     if kind == "pool_backward":                        # zero dB + arg, dC, colind[arg], vals[arg], one add per element

@@ -107,10 +107,12 @@ int gespmm_csr_b16(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* 
  *         into colind / vals of the stored entry of row i whose product vals[p] *
  *         B[colind[p], j] has exactly the bits of C[i, j]; if several entries do, the
  *         smallest p (first in storage order); -1 for an empty row.
- * One fused pass gives values everywhere and positions for rows that lie inside one chunk of
- * the work partition; a second pass finds the positions of the rows that were split (1.6 to
- * 1.9 times the cost of gespmm_csr).
- * For the vector kernels arg must be 16-byte aligned as well.  Same errors as gespmm_csr;
+ * One fused pass carries (value, position) pairs through the reduction; rows that several
+ * wavefronts share combine their pairs as packed 64-bit words held, during the call, in the
+ * row's own C and arg storage, and a small kernel unpacks them at the end (1.1 to 1.7 times
+ * the cost of gespmm_csr).  That route needs the vector kernels (N a multiple of 4; B, C and
+ * arg 16-byte aligned) and N <= 1024; otherwise split rows get their positions from a second
+ * pass over the matrix (up to 1.9 times the cost of gespmm_csr).  Same errors as gespmm_csr;
  * GESPMM_ERR_BAD_ARG for any other op; GESPMM_ERR_NULL for arg == NULL.
  */
 int gespmm_csr_arg(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,

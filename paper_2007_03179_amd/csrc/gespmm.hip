@@ -93,9 +93,7 @@ int gespmm_csr_arg(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* 
   const int st = validate(M, K, N, nnz, rowptr, colind, B, C, op);
   if (st != GESPMM_OK || M == 0 || N == 0) return st;
   if (!arg) return GESPMM_ERR_NULL;
-  // One fused pass gives the value everywhere and the position for every row that lies inside
-  // one chunk; rows split across chunks get their value by atomics.  Both outputs are preset:
-  // empty rows -> 0 / -1, split rows -> reduce identity / INT_MAX.
+  // One fused pass gives value and position for every row that lies inside one chunk.
   hipStream_t stream = (hipStream_t)stream_;
   ChunkLaunch L;
   L.job = op == GESPMM_MAX ? kJobMaxWithArg : kJobMinWithArg;
@@ -104,12 +102,23 @@ int gespmm_csr_arg(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* 
   L.dense_in = B; L.dense_out = C; L.arg = arg;
   L.also_aligned = arg;
   L.init_target = C;
-  L.empty_value = 0.0f;
-  L.split_value = op == GESPMM_MAX ? -__builtin_inff() : __builtin_inff();
   L.init2_target = reinterpret_cast<float*>(arg);
+  L.empty_value = 0.0f;
   L.empty2_value = bits_as_float(-1);
-  L.split2_value = bits_as_float(INT32_MAX);
   L.timed = true;
+  // Rows split across chunks.  Vector kernels, N <= 1024: their (value, position) pairs are
+  // combined as packed 64-bit words kept in the row's own C and arg storage (preset to zero)
+  // and unpacked by a small kernel after the pass.  Otherwise: values by atomics in this pass
+  // (rows preset to the reduce identity / INT_MAX), positions by a second pass over the matrix.
+  const bool vector = N % 4 == 0 && (((uintptr_t)B | (uintptr_t)C | (uintptr_t)arg) & 15u) == 0;
+  L.packed_split = vector && N <= kWave * kFinishWords && nnz > 0;
+  if (L.packed_split) {
+    L.split_value = 0.0f;
+    L.split2_value = 0.0f;
+    return launch_chunks(L, stream);
+  }
+  L.split_value = op == GESPMM_MAX ? -__builtin_inff() : __builtin_inff();
+  L.split2_value = bits_as_float(INT32_MAX);
   const int fused = launch_chunks(L, stream);
   if (fused != GESPMM_OK || nnz == 0) return fused;
   // Second pass, split rows only (their values are final once the first kernel has ended):

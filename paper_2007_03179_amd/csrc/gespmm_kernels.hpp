@@ -69,6 +69,7 @@ struct KernelArgs {
   int32_t* arg;           // output of the position job; row indices of the transposed arrays
   int32_t* cursor;        // next free place of every transposed row (structure-transpose job)
   int32_t only_split;     // position job: rows inside one chunk were already done by the fused pass
+  int32_t packed_split;   // fused value+position pass: split rows collect (value, position) pairs in 64-bit slots
 };
 
 // ------------------------------------------------------------------ vectors --
@@ -326,8 +327,14 @@ struct FoldRows {
 // chunk: value and entry index travel together through the fold, the slot combine and the
 // store.  The order is the total order of the float bit patterns (so +0 is above -0, as in
 // the plain fold) and ties go to the smaller entry index, which is exactly "the first entry
-// whose product has the bits of the result".  Split rows only get their value here (by
-// atomics, as in FoldRows); their positions are found by ArgRows afterwards.
+// whose product has the bits of the result".
+// Rows split across chunks are combined in one of two ways.  packed_split: value and position
+// are packed into one 64-bit word, ordered so that an unsigned atomic max keeps the better
+// value and, among equal values, the smaller position; the N words of row i live in the
+// storage of the row itself (the first N/2 in C[i, :], the rest in arg[i, :], both preset to
+// zero, which is below every packed word) and finish_split_rows unpacks them in place
+// afterwards.  Otherwise split rows only get their value here (by atomics, as in FoldRows)
+// and their positions are found by ArgRows in a second pass over the matrix.
 template <int F, int V, int T>
 struct FoldArgRows {
   static constexpr bool kCanSkipWholeRows = false;
@@ -419,6 +426,15 @@ struct FoldArgRows {
           }
           value.store(crow + col[t]);
           place.store(reinterpret_cast<float*>(arow + col[t]));
+        } else if (a.packed_split) {
+          const int half = a.N >> 1;         // N is even; a lane's V words can straddle the two halves
+#pragma unroll
+          for (int x = 0; x < V; ++x) {
+            const int j = col[t] + x;
+            unsigned long long* slot = j < half ? reinterpret_cast<unsigned long long*>(crow) + j
+                                                : reinterpret_cast<unsigned long long*>(arow) + (j - half);
+            __hip_atomic_fetch_max(slot, pack(s.key[t][x], s.where[t][x]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
         } else {
 #pragma unroll
           for (int x = 0; x < V; ++x) atomic_fold<F>(crow + col[t] + x, value_of(s.key[t][x]));
@@ -426,7 +442,73 @@ struct FoldArgRows {
       }
     }
   }
+
+  // (value key, position) -> 64-bit word whose unsigned order is "better value first, then
+  // smaller position"; every word of a real entry is > 0.  unpack is the inverse.
+  __device__ static unsigned long long pack(int key, int where) {
+    unsigned ukey = (unsigned)key ^ 0x80000000u;            // signed order -> unsigned order
+    if (F == kMin) ukey = ~ukey;                            // smaller value <=> larger word
+    return ((unsigned long long)ukey << 32) | (unsigned)~where;
+  }
+  __device__ static void unpack(unsigned long long word, float& value, int& where) {
+    unsigned ukey = (unsigned)(word >> 32);
+    if (F == kMin) ukey = ~ukey;
+    value = value_of((int)(ukey ^ 0x80000000u));
+    where = (int)~(unsigned)word;
+  }
 };
+
+// After the fused value+position pass with packed_split: every row whose entries lie in more
+// than one chunk holds N packed words in its C and arg storage; one wavefront per such row
+// reads them all, then writes the row's values and positions over them.  N <= 64 * kFinishWords.
+constexpr int kFinishWords = 16;
+template <int F>
+__global__ void __launch_bounds__(kBlock) finish_split_rows(int32_t M, int32_t N, const int32_t* __restrict__ rowptr,
+                                                           float* C, int32_t* arg, int chunk_shift) {
+  using Rows = FoldArgRows<F, 4, 1>;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t base = ((int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)) * kWave;
+  if (base >= M) return;
+  const int64_t r = base + lane;
+  bool split = false;
+  if (r < M) {
+    const int s = rowptr[r], e = rowptr[r + 1];
+    split = e > s && (s >> chunk_shift) != ((e - 1) >> chunk_shift);
+  }
+  unsigned long long todo = __ballot(split);
+  const int half = N >> 1;
+  while (todo) {
+    const int i = __builtin_ctzll(todo);
+    todo &= todo - 1;
+    float* crow = C + (base + i) * (int64_t)N;
+    int32_t* arow = arg + (base + i) * (int64_t)N;
+    const unsigned long long* cslots = reinterpret_cast<const unsigned long long*>(crow);
+    const unsigned long long* aslots = reinterpret_cast<const unsigned long long*>(arow);
+    unsigned long long word[kFinishWords];
+#pragma unroll
+    for (int k = 0; k < kFinishWords; ++k) {
+      const int j = lane + k * kWave;
+      word[k] = j < N ? (j < half ? cslots[j] : aslots[j - half]) : 0ull;
+    }
+    // every word of the row has been read (by all lanes) before any lane overwrites the row:
+    // a workgroup-scope fence waits for this wavefront's outstanding loads and keeps the
+    // compiler from moving memory operations across it (no cache maintenance is needed, the
+    // row belongs to this wavefront alone)
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int k = 0; k < kFinishWords; ++k) {
+      const int j = lane + k * kWave;
+      if (j < N) {
+        float value;
+        int where;
+        Rows::unpack(word[k], value, where);
+        crow[j] = value;
+        arow[j] = where;
+      }
+    }
+  }
+}
 
 // Position of the extreme (run after the max / min result C is complete): an entry whose
 // product has exactly the bits of C[i, j] is a candidate; the smallest entry index wins,
@@ -1120,6 +1202,7 @@ struct ChunkLaunch {
   float* init2_target = nullptr;       // a second M x N output to preset (positions of the fused pass)
   float empty2_value = 0.0f, split2_value = 0.0f;
   bool only_split = false;             // position job: leave rows that lie inside one chunk alone
+  bool packed_split = false;           // fused value+position job: packed words for split rows, unpacked at the end
   bool timed = false;                  // bracket the chunk kernel with profiling events
   MainKernel (*picker)(int vec, int G, int T) = nullptr;   // user-defined reduce: its own kernel table
   int32_t* cursor = nullptr;           // structure-transpose job only
@@ -1193,6 +1276,8 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
   a.arg = L.arg;
   a.cursor = L.cursor;
   a.only_split = L.only_split ? 1 : 0;
+  a.packed_split = L.packed_split ? 1 : 0;
+  if (L.packed_split && (plan.vec != 4 || L.N > kWave * kFinishWords || !L.arg)) return GESPMM_ERR_BAD_ARG;
   const bool timed = L.timed && g_profiling && g_ev_used < (int)g_ev_start.size();
   if (timed && hipEventRecord(g_ev_start[g_ev_used], stream) != hipSuccess) return GESPMM_ERR_HIP;
   hipLaunchKernelGGL(kernel, dim3((unsigned)plan.grid_x, (unsigned)plan.col_blocks), dim3(kBlock), (size_t)plan.lds_bytes, stream, a);
@@ -1200,6 +1285,16 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
   if (timed) {
     if (hipEventRecord(g_ev_stop[g_ev_used], stream) != hipSuccess) return GESPMM_ERR_HIP;
     ++g_ev_used;
+  }
+  if (L.packed_split) {
+    const unsigned blocks = (unsigned)((L.M + kBlock - 1) / kBlock);
+    if (L.job == kJobMaxWithArg)
+      hipLaunchKernelGGL(finish_split_rows<kMax>, dim3(blocks), dim3(kBlock), 0, stream, (int32_t)L.M, (int32_t)L.N, L.rowptr,
+                         L.dense_out, L.arg, shift);
+    else
+      hipLaunchKernelGGL(finish_split_rows<kMin>, dim3(blocks), dim3(kBlock), 0, stream, (int32_t)L.M, (int32_t)L.N, L.rowptr,
+                         L.dense_out, L.arg, shift);
+    if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
   }
   return GESPMM_OK;
 }

@@ -70,7 +70,7 @@ def check_pool_backward(gs, ci, v, arg, dC, K, label=""):
 
 
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("N", [1, 4, 7, 8, 32, 33, 64, 128, 520])
+@pytest.mark.parametrize("N", [1, 4, 7, 8, 32, 33, 64, 128, 520, 1024, 1028])
 def test_positions_widths_ties_and_split_rows(gs, N):
     # few distinct values -> many ties; a row spanning many chunks; duplicates; empty rows; M != K
     rp, ci, v = graphgen.random_csr(600, 400, 8.0, 300 + N, empty_frac=0.1, long_rows=((77, 2500),),
@@ -98,6 +98,26 @@ def test_positions_every_launch_shape(gs):
                     check_arg(gs, rp, ci, v, B, op, label=f"G={G} T={T} S={chunk} short={short}", dA=dA, dB=dB)
     finally:
         gs.gespmm_set_tuning()
+
+
+def test_positions_unaligned_outputs_take_the_two_pass_route(gs):
+    """C or arg off a 16-byte boundary: scalar kernels, split rows finished by the second pass."""
+    rp, ci, v = graphgen.random_csr(300, 200, 6.0, 61, empty_frac=0.1, long_rows=((40, 1500),), duplicates=True)
+    B = np.round(graphgen.random_dense(200, 64, 61) * 4.0).astype(np.float32)
+    d = dev(rp), dev(ci), dev(v), dev(B)
+    for op in ("max", "min"):
+        Cref, aref = oracle.spmm_arg(rp, ci, v, B, op)
+        for off_c, off_a in ((1, 0), (0, 1), (2, 2)):
+            say(f"  case arg unaligned op={op} C+{off_c} arg+{off_a}")
+            rawc = torch.full((300 * 64 + 4,), 7.0, device="cuda")
+            rawa = torch.full((300 * 64 + 4,), 7, dtype=torch.int32, device="cuda")
+            C = rawc[off_c:off_c + 300 * 64].view(300, 64)
+            arg = rawa[off_a:off_a + 300 * 64].view(300, 64)
+            gs.gespmm_csr_arg(*d, op, C=C, arg=arg)
+            torch.cuda.synchronize()
+            assert np.array_equal(C.cpu().numpy().view(np.uint32), Cref.astype(np.float32).view(np.uint32))
+            assert np.array_equal(arg.cpu().numpy(), aref)
+            assert float(rawc[-1]) == 7.0 and int(rawa[-1]) == 7 and float(rawc[0]) in (7.0, float(C[0, 0]))
 
 
 def test_positions_degenerate(gs):
@@ -197,7 +217,7 @@ def test_gradient_of_sum_and_mean_through_the_transposed_arrays(gs):
         assert ok, (op, worst)
 
 
-@pytest.mark.parametrize("which", [2, 4])
+@pytest.mark.parametrize("which", [2, 4, 3])
 def test_gradient_side_on_workloads(gs, which):
     w = graphgen.workload(which)
     say(" ", w.describe())
@@ -220,6 +240,8 @@ def test_gradient_side_on_workloads(gs, which):
         assert np.array_equal(prod.view(np.uint32), C[i, j].view(np.uint32))
         if op == "max":
             check_pool_backward(gs, w.colind, vals, arg, dC, w.K, label=w.name)
+    if which == 3:          # the long-row workload: positions and pooled gradient only (every row is split)
+        return
     for op in ("sum", "mean"):
         check_transposed(gs, w.rowptr, w.colind, vals, dC, op, w.K, label=w.name, dA=dA)
     check_transpose(gs, w.rowptr, w.colind, vals, w.K, True, label=w.name)
