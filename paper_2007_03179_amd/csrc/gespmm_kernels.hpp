@@ -228,11 +228,14 @@ static __global__ void __launch_bounds__(kBlock) copy_f4(const float4* __restric
 }
 
 // ------------------------------------------------------------ chunk kernel --
-// The walk over chunks, rows and row segments is the same for three jobs; what is done
+// The walk over chunks, rows and row segments is the same for every job; what is done
 // with a row segment is a policy:
-//   FoldRows        the SpMM-like operation itself            C = A (x) B
-//   ArgRows         position of the extreme for max / min     arg[i,j] = first entry that gives C[i,j]
+//   FoldRows        the SpMM-like operation itself            C = A (x) B   (B in fp32, bf16 or half)
+//   FoldArgRows     max / min together with its position      C and arg[i,j] = first entry that gives C[i,j]
+//   ArgRows         positions only, from a finished C         (split rows of the scalar / very wide cases)
 //   TransposedRows  gradient of sum / mean w.r.t. B           dB += A^T (x) dC, by scatter-add
+//   ScatterRows     structure transpose                       every entry takes a place in its column's row
+//   CustomRows      a user-defined reduce                     (include/gespmm_custom.hpp)
 // A policy has a per-row State and four steps: begin (per row), pass (U entries of the
 // segment for the lane's column tiles), combine (fold the slots that shared a long row),
 // end (write the row).  In `pass`, `first` is the LDS index of the lane's first entry,
