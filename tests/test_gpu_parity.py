@@ -198,6 +198,26 @@ def test_simple_entry_point_and_side_stream(gs):
     assert ok, worst
 
 
+def test_calls_on_two_streams_at_once_do_not_disturb_each_other(gs):
+    """The library keeps no state between calls and owns no scratch memory: calls in flight on two streams
+    (different matrices, different ops, enqueued alternately) both give the oracle's result."""
+    cases = []
+    for seed, (M, K, N), op in ((31, (3000, 2500, 64), "sum"), (32, (2000, 3500, 128), "max")):
+        rp, ci, v = graphgen.random_csr(M, K, 12.0, seed, empty_frac=0.05, long_rows=((7, 4000),))
+        B = graphgen.random_dense(K, N, seed)
+        cases.append((rp, ci, v, B, op, (dev(rp), dev(ci), dev(v), dev(B)),
+                      torch.empty((M, N), dtype=torch.float32, device="cuda"), torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    say("  case two-streams")
+    for _ in range(20):
+        for rp, ci, v, B, op, d, C, stream in cases:
+            gs.gespmm_csr(*d, op, C=C, stream=stream)
+    torch.cuda.synchronize()
+    for rp, ci, v, B, op, d, C, stream in cases:
+        ok, worst = oracle.compare(op, C.cpu().numpy(), *oracle.spmm(rp, ci, v, B, op))
+        assert ok, (op, worst)
+
+
 def test_results_do_not_depend_on_what_C_held(gs):
     rp, ci, v = graphgen.random_csr(300, 200, 5.0, 33, empty_frac=0.3, long_rows=((5, 800),))
     B = graphgen.random_dense(200, 16, 33)
