@@ -198,6 +198,31 @@ def test_simple_entry_point_and_side_stream(gs):
     assert ok, worst
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_seeded_random_shapes(gs, seed):
+    """Five random problems per seed: sizes, widths (odd ones too), row-length mix, empty rows, duplicates,
+    hub rows and NULL values all drawn from the seed; forward call and value+position call."""
+    rng = np.random.default_rng(1000 + seed)
+    for _ in range(5):
+        M, K = int(rng.integers(1, 3000)), int(rng.integers(1, 3000))
+        N = int(rng.choice([1, 2, 3, 4, 5, 8, 12, 16, 20, 31, 32, 36, 64, 96, 100, 128, 130, 200, 256, 260, 384, 512, 640]))
+        mean_len = float(rng.choice([0.3, 1.0, 3.0, 10.0, 40.0]))
+        long_rows = tuple((int(rng.integers(0, M)), int(rng.integers(300, 5000))) for _ in range(int(rng.integers(0, 3))))
+        rp, ci, v = graphgen.random_csr(M, K, mean_len, int(rng.integers(1 << 30)), empty_frac=float(rng.choice([0, 0.2, 0.7])),
+                                        duplicates=True, sort_cols=bool(rng.integers(2)), long_rows=long_rows)
+        if rng.integers(4) == 0:
+            v = None
+        B = graphgen.random_dense(K, N, int(rng.integers(1 << 30)))
+        op = str(rng.choice(OPS))
+        check(gs, rp, ci, v, B, op, label=f"random seed={seed}")
+        if op in ("max", "min"):
+            C, arg = gs.gespmm_csr_arg(dev(rp), dev(ci), dev(v), dev(B), op)
+            torch.cuda.synchronize()
+            Cref, aref = oracle.spmm_arg(rp, ci, v, B, op)
+            assert np.array_equal(C.cpu().numpy().view(np.uint32), Cref.astype(np.float32).view(np.uint32))
+            assert np.array_equal(arg.cpu().numpy(), aref)
+
+
 def test_calls_on_two_streams_at_once_do_not_disturb_each_other(gs):
     """The library keeps no state between calls and owns no scratch memory: calls in flight on two streams
     (different matrices, different ops, enqueued alternately) both give the oracle's result."""
