@@ -176,3 +176,14 @@ def test_chunk_size_follows_width_and_problem_size():
     assert p["chunk_nnz"] == 256 and p["xcd_remap"] == 0
     # rows much longer than a chunk: consecutive chunks stay on one XCD
     assert gs.gespmm_plan(232_965, 64, 114_693_532)["xcd_remap"] == 1
+
+
+def test_header_is_plain_c_and_cxx():
+    """include/gespmm.h must compile on its own as C99 and as C++11 (no HIP or torch types in it)."""
+    import subprocess
+    for cmd in (["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", HEADER],
+                ["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", HEADER]):
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+    text = open(HEADER).read()
+    assert "hip/" not in text and "torch" not in text.lower()
