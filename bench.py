@@ -206,6 +206,8 @@ def gradient_bytes(kind, M, K, N, nnz):
         return 4 * K * N + walk + 4 * M * N + 4 * nnz * N
     if kind == "pool_backward":                        # zero dB + arg, dC, colind[arg], vals[arg], one add per element
         return 4 * K * N + 20 * M * N
+    if kind == "csr_transpose_sorted":                 # row ids and weights written, two sort passes of 28 bytes, row starts
+        return walk + 8 * nnz + 2 * 28 * nnz + 4 * nnz + 4 * (K + 1)
     if kind == "csr_transpose":                        # counts (read colind, add), scan, walk, write row ids + values
         return 4 * nnz + 4 * nnz + 16 * (K + 1) + walk + 8 * nnz
     if kind == "forward_on_transposed":                # a forward call with the roles of M and K swapped
@@ -229,6 +231,7 @@ def time_gradients(args, gs, torch, graphgen, dev):
         }
         rpT, ciT, vT = gs.gespmm_csr_transpose(case.rp, case.ci, case.v, w.K)
         calls["csr_transpose"] = lambda: gs.gespmm_csr_transpose(case.rp, case.ci, case.v, w.K)
+        calls["csr_transpose_sorted"] = lambda: gs.gespmm_csr_transpose_sorted(case.rp, case.ci, case.v, w.K)
         calls["forward_on_transposed"] = lambda: gs.gespmm_csr(rpT, ciT, vT, dC, "sum", C=dB)
         for kind, call in calls.items():                # "arg" runs first and leaves valid positions behind
             steps = max(10, args.steps // (10 if w.nnz > 5e7 else 1))

@@ -161,6 +161,22 @@ int gespmm_csr_transpose(int64_t M, int64_t K, int64_t nnz, const int32_t* rowpt
                          size_t workspace_bytes, void* stream);
 
 /*
+ * The same transposed arrays by a stable radix sort on the column index instead of per-column
+ * counters: every pass streams the entries (28 bytes per entry and pass, two passes up to 2^20
+ * columns, three beyond), so the time does not depend on the column distribution, and inside
+ * a transposed row the entries keep the order of A's rows: the result is unique, the same
+ * from run to run, and equal to a stable counting sort.  3 to 7 times faster than
+ * gespmm_csr_transpose on the graphs measured, at the price of a larger workspace:
+ * gespmm_csr_transpose_sorted_workspace_bytes(K, nnz) = about 24 bytes per stored entry.
+ * Arguments, ownership and errors as gespmm_csr_transpose.
+ */
+size_t gespmm_csr_transpose_sorted_workspace_bytes(int64_t K, int64_t nnz);   /* pure host function */
+int gespmm_csr_transpose_sorted(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr,
+                                const int32_t* colind, const float* vals, int scale_by_row_length,
+                                int32_t* rowptrT, int32_t* colindT, float* valsT, void* workspace,
+                                size_t workspace_bytes, void* stream);
+
+/*
  * Gradient of max / min with respect to B, routed through the positions from
  * gespmm_csr_arg (Sections IV-B, V-E):
  *     dB[colind[p], j] += vals[p] * dC[i, j]   with p = arg[i*N+j], for every p >= 0.

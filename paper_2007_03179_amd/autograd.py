@@ -3,7 +3,7 @@ inside a custom autograd function ... an aggregation step on the graph").
 
 Thin glue over the C ABI: the forward pass is gespmm_csr (sum, mean) or gespmm_csr_arg (max, min);
 the backward pass with respect to the dense features is gespmm_csr on the transposed arrays
-(built once per graph by gespmm_csr_transpose and cached) or gespmm_pool_backward.  The edge
+(built once per graph by gespmm_csr_transpose_sorted and cached) or gespmm_pool_backward.  The edge
 values are treated as constants (no gradient), as in the paper's operator.
 """
 from __future__ import annotations
@@ -27,8 +27,8 @@ class CsrGraph:
     def transposed(self, mean: bool):
         """(rowptrT, colindT, valsT); with mean weights val / row length when `mean`."""
         if mean not in self._transposed:
-            self._transposed[mean] = _b.gespmm_csr_transpose(self.rowptr, self.colind, self.vals, self.K,
-                                                             scale_by_row_length=mean)
+            self._transposed[mean] = _b.gespmm_csr_transpose_sorted(self.rowptr, self.colind, self.vals, self.K,
+                                                                    scale_by_row_length=mean)
         return self._transposed[mean]
 
 

@@ -63,6 +63,10 @@ def lib():
         L.gespmm_csr_transpose_workspace_bytes.argtypes = [i64]
         L.gespmm_csr_transpose.restype = ci
         L.gespmm_csr_transpose.argtypes = [i64, i64, i64, vp, vp, vp, ci, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.gespmm_csr_transpose_sorted_workspace_bytes.restype = ctypes.c_size_t
+        L.gespmm_csr_transpose_sorted_workspace_bytes.argtypes = [i64, i64]
+        L.gespmm_csr_transpose_sorted.restype = ci
+        L.gespmm_csr_transpose_sorted.argtypes = [i64, i64, i64, vp, vp, vp, ci, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.gespmm_plan.restype = ci
         L.gespmm_plan.argtypes = [i64, i64, i64, ci, ctypes.POINTER(gespmm_plan_t)]
         L.gespmm_set_tuning.restype = ci
@@ -216,6 +220,32 @@ def gespmm_csr_transpose(rowptr, colind, vals, K, scale_by_row_length=False, str
     _check(lib().gespmm_csr_transpose(M, K, nnz, _ptr(rowptr), _ptr(colind), _ptr(vals),
                                       int(bool(scale_by_row_length)), _ptr(rowptrT), _ptr(colindT),
                                       _ptr(valsT), _ptr(work), nbytes, _stream(stream)))
+    return rowptrT, colindT, valsT
+
+
+def gespmm_csr_transpose_sorted_workspace_bytes(K: int, nnz: int) -> int:
+    return int(lib().gespmm_csr_transpose_sorted_workspace_bytes(int(K), int(nnz)))
+
+
+def gespmm_csr_transpose_sorted(rowptr, colind, vals, K, scale_by_row_length=False, stream=None):
+    """CSR arrays of the transposed matrix by a stable radix sort on the columns (rows of A in
+    increasing order inside every transposed row): returns (rowptrT, colindT, valsT).  The
+    workspace (about 24 bytes per stored entry) is a torch tensor allocated here and released
+    on return; the library itself allocates nothing."""
+    import torch
+    M, nnz = rowptr.numel() - 1, colind.numel()
+    assert rowptr.is_cuda and rowptr.dtype == torch.int32 and rowptr.is_contiguous()
+    assert colind.is_cuda and colind.dtype == torch.int32 and colind.is_contiguous()
+    assert vals is None or (vals.is_cuda and vals.dtype == torch.float32 and vals.numel() == nnz)
+    dev = rowptr.device
+    rowptrT = torch.empty(K + 1, dtype=torch.int32, device=dev)
+    colindT = torch.empty(nnz, dtype=torch.int32, device=dev)
+    valsT = torch.empty(nnz, dtype=torch.float32, device=dev)
+    nbytes = gespmm_csr_transpose_sorted_workspace_bytes(K, nnz)
+    work = torch.empty(max(nbytes // 4, 1), dtype=torch.int32, device=dev)
+    _check(lib().gespmm_csr_transpose_sorted(M, K, nnz, _ptr(rowptr), _ptr(colind), _ptr(vals),
+                                             int(bool(scale_by_row_length)), _ptr(rowptrT), _ptr(colindT),
+                                             _ptr(valsT), _ptr(work), nbytes, _stream(stream)))
     return rowptrT, colindT, valsT
 
 

@@ -2,6 +2,7 @@
 // The kernels and launch helpers are in gespmm_kernels.hpp; this file validates arguments,
 // fills the launch descriptions and owns no device code of its own.
 #include "gespmm_kernels.hpp"
+#include "gespmm_sort.hpp"
 
 using namespace gespmm_detail;
 
@@ -204,6 +205,84 @@ int gespmm_csr_transpose(int64_t M, int64_t K, int64_t nnz, const int32_t* rowpt
   L.is_mean = scale_by_row_length != 0;
   L.one_lane_per_entry = true;
   return launch_chunks(L, stream);
+}
+
+size_t gespmm_csr_transpose_sorted_workspace_bytes(int64_t K, int64_t nnz) {
+  if (K < 0 || nnz < 0) return 0;
+  return make_sort_plan(K, nnz).bytes;
+}
+
+int gespmm_csr_transpose_sorted(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+                                const float* vals, int scale_by_row_length, int32_t* rowptrT, int32_t* colindT,
+                                float* valsT, void* workspace, size_t workspace_bytes, void* stream_) {
+  if (M < 0 || K < 0 || nnz < 0) return GESPMM_ERR_BAD_ARG;
+  if (M >= INT32_MAX || K >= INT32_MAX || nnz > INT32_MAX - (1 << kMaxChunkShift)) return GESPMM_ERR_TOO_LARGE;
+  if (nnz > 0 && (M == 0 || K == 0)) return GESPMM_ERR_BAD_ARG;
+  if (!rowptrT) return GESPMM_ERR_NULL;
+  if (nnz > 0 && (!rowptr || !colind || !colindT || !valsT)) return GESPMM_ERR_NULL;
+  if (!workspace) return GESPMM_ERR_NULL;
+  const SortPlan plan = make_sort_plan(K, nnz);
+  if (workspace_bytes < plan.bytes || ((uintptr_t)workspace & 3u) != 0) return GESPMM_ERR_BAD_ARG;
+  hipStream_t stream = (hipStream_t)stream_;
+  if (nnz == 0) return launch_fill(reinterpret_cast<float*>(rowptrT), K + 1, 0.0f, stream);
+
+  char* ws = static_cast<char*>(workspace);
+  int32_t* rowid = reinterpret_cast<int32_t*>(ws + plan.off_rowid);
+  float* weight = reinterpret_cast<float*>(ws + plan.off_val);
+  int32_t* keys_a = reinterpret_cast<int32_t*>(ws + plan.off_keys_a);
+  int32_t* keys_x = reinterpret_cast<int32_t*>(ws + plan.off_keys_x);
+  int32_t* rows_x = reinterpret_cast<int32_t*>(ws + plan.off_rows_x);
+  float* vals_x = reinterpret_cast<float*>(ws + plan.off_vals_x);
+  int32_t* counts = reinterpret_cast<int32_t*>(ws + plan.off_counts);
+  int32_t* sums = reinterpret_cast<int32_t*>(ws + plan.off_sums);
+
+  // (1) row index and weight of every stored entry, in entry order (the chunk walk, one lane per entry)
+  ChunkLaunch L;
+  L.job = kJobScatter;
+  L.M = M; L.N = 1; L.nnz = nnz;
+  L.rowptr = rowptr; L.colind = colind; L.vals = vals;
+  L.dense_out = weight; L.arg = rowid; L.cursor = nullptr;
+  L.is_mean = scale_by_row_length != 0;
+  L.one_lane_per_entry = true;
+  int st = launch_chunks(L, stream);
+  if (st != GESPMM_OK) return st;
+
+  // (2) stable radix sort of (column, row, weight) by column, least significant digit first; the buffers
+  //     alternate so that the last pass writes the caller's arrays
+  const int32_t* keys_in = colind;
+  const int32_t* rows_in = rowid;
+  const float* vals_in = weight;
+  bool to_caller = plan.passes % 2 == 1;
+  const unsigned tiles = (unsigned)plan.tiles;
+  for (int pass = 0; pass < plan.passes; ++pass) {
+    const int shift = pass * plan.bits_per_pass;
+    int32_t* keys_out = to_caller ? keys_a : keys_x;
+    int32_t* rows_out = to_caller ? colindT : rows_x;
+    float* vals_out = to_caller ? valsT : vals_x;
+    hipLaunchKernelGGL(radix_histogram, dim3(tiles), dim3(kBlock), 0, stream, keys_in, nnz, shift, plan.bits_per_pass,
+                       plan.tiles, counts);
+    hipLaunchKernelGGL(scan_tiles, dim3((unsigned)plan.count_tiles), dim3(kBlock), 0, stream, counts, plan.count_len, sums);
+    hipLaunchKernelGGL(scan_sums, dim3(1), dim3(kBlock), 0, stream, sums, plan.count_tiles);
+    {
+      int64_t blocks = (plan.count_len + kBlock - 1) / kBlock;
+      if (blocks > 256 * 32) blocks = 256 * 32;
+      hipLaunchKernelGGL(add_tile_offsets, dim3((unsigned)blocks), dim3(kBlock), 0, stream, counts, plan.count_len, sums,
+                         (int32_t*)nullptr, (int64_t)0);
+    }
+    hipLaunchKernelGGL(radix_scatter, dim3(tiles), dim3(kBlock), 0, stream, keys_in, rows_in, vals_in, nnz, shift,
+                       plan.bits_per_pass, plan.tiles, counts, keys_out, rows_out, vals_out);
+    if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
+    keys_in = keys_out; rows_in = rows_out; vals_in = vals_out;
+    to_caller = !to_caller;
+  }
+
+  // (3) row starts of the transposed matrix from the sorted columns
+  {
+    int64_t blocks = (K + 1 + kBlock - 1) / kBlock;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(row_starts_from_sorted_keys, dim3((unsigned)blocks), dim3(kBlock), 0, stream, keys_in, nnz, K, rowptrT);
+  }
+  return hipGetLastError() == hipSuccess ? GESPMM_OK : GESPMM_ERR_HIP;
 }
 
 int gespmm_pool_backward(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* colind,

@@ -654,7 +654,7 @@ struct ScatterRows {
   }
 
   template <int U>
-  __device__ static void pass(State& s, const KernelArgs& a, const int2* ka, int, int first, int stride, int left,
+  __device__ static void pass(State& s, const KernelArgs& a, const int2* ka, int cs, int first, int stride, int left,
                               const int (&col)[T], const int (&)[T]) {
     int2 e[U];
     int place[U];
@@ -663,7 +663,10 @@ struct ScatterRows {
       const bool live = u < left && col[0] == 0;
       e[u] = ka[first + (live ? u * stride : 0)];
       place[u] = -1;
-      if (live) place[u] = __hip_atomic_fetch_add(a.cursor + e[u].x, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (live) {                            // no cursors: the entry stays where it is (row ids and weights in entry order)
+        if (a.cursor) place[u] = __hip_atomic_fetch_add(a.cursor + e[u].x, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else place[u] = cs + first + u * stride;
+      }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {

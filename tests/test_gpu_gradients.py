@@ -192,6 +192,39 @@ def check_transpose(gs, rp, ci, v, K, scale, label=""):
     return rpT, ciT, vT
 
 
+def check_transpose_sorted(gs, rp, ci, v, K, scale, label=""):
+    """The radix-sort transpose is stable, so all three arrays equal the oracle's bit for bit."""
+    say(f"  case transpose-sorted {label} M={len(rp) - 1} K={K} nnz={len(ci)} scale={scale}")
+    rpT, ciT, vT = gs.gespmm_csr_transpose_sorted(dev(rp), dev(ci), dev(v), K, scale_by_row_length=scale)
+    torch.cuda.synchronize()
+    rpR, ciR, vR = oracle.csr_transpose(rp, ci, v, K, scale_by_row_length=scale)
+    assert np.array_equal(rpT.cpu().numpy(), rpR), f"{label}: row starts"
+    assert np.array_equal(ciT.cpu().numpy(), ciR), f"{label}: row indices"
+    assert np.array_equal(vT.cpu().numpy().view(np.uint32), vR.view(np.uint32)), f"{label}: values"
+
+
+@pytest.mark.parametrize("shape", [(500, 350, 9.0), (3000, 5000, 2.0), (1, 1, 1.0), (40, 3, 30.0), (4097, 1025, 1.0),
+                                   (200, 70_000, 25.0), (50, 1_100_000, 90.0), (9000, 2, 3.0)])
+def test_transpose_sorted_small_and_degenerate(gs, shape):
+    # 1, 2 and 3 sort passes (K up to 2^10, 2^20, beyond), tiles that end exactly at 4096, hub columns, empty rows
+    M, K, mean_len = shape
+    rp, ci, v = graphgen.random_csr(M, K, mean_len, M + K, empty_frac=0.2, duplicates=True, sort_cols=False,
+                                    long_rows=((M // 2, 5000),) if M > 100 else ())
+    if len(ci) > 300:
+        ci[100:300] = ci[0]                                   # a hub column
+    for scale in (False, True):
+        check_transpose_sorted(gs, rp, ci, v, K, scale, label=f"M={M} K={K}")
+    check_transpose_sorted(gs, rp, ci, None, K, True, label=f"M={M} K={K} vals=NULL")
+
+
+def test_transpose_sorted_nothing_stored_and_exact_tile(gs):
+    rpT, ciT, vT = gs.gespmm_csr_transpose_sorted(dev(np.zeros(4, np.int32)), dev(np.zeros(0, np.int32)), None, 7)
+    assert rpT.shape == (8,) and not rpT.cpu().numpy().any() and ciT.numel() == 0
+    rp = np.arange(0, 4096 * 2 + 1, 2, dtype=np.int32)          # exactly two full tiles
+    ci = np.tile(np.array([5, 0], dtype=np.int32), 4096)
+    check_transpose_sorted(gs, rp, ci, None, 6, False, label="two full tiles")
+
+
 def test_transpose_structure_small_and_degenerate(gs):
     for M, K, mean_len, seed, kw in ((500, 350, 9.0, 1, dict(empty_frac=0.1, duplicates=True, sort_cols=False,
                                                               long_rows=((9, 2000),))),
@@ -245,3 +278,4 @@ def test_gradient_side_on_workloads(gs, which):
     for op in ("sum", "mean"):
         check_transposed(gs, w.rowptr, w.colind, vals, dC, op, w.K, label=w.name, dA=dA)
     check_transpose(gs, w.rowptr, w.colind, vals, w.K, True, label=w.name)
+    check_transpose_sorted(gs, w.rowptr, w.colind, vals, w.K, True, label=w.name)
