@@ -342,7 +342,7 @@ template <int F, int V, int T>
 struct FoldArgRows {
   static constexpr bool kCanSkipWholeRows = false;
   static_assert(F == kMax || F == kMin, "positions exist for max and min only");
-  struct State { int key[T][V]; int where[T][V]; };
+  struct State { float best[T][V]; int where[T][V]; };
 
   // monotone map float bits -> signed int (larger float <=> larger key; -0 below +0)
   __device__ static int key_of(float x) {
@@ -359,7 +359,7 @@ struct FoldArgRows {
     for (int t = 0; t < T; ++t)
 #pragma unroll
       for (int x = 0; x < V; ++x) {
-        s.key[t][x] = key_of(fold_identity<F>());
+        s.best[t][x] = fold_identity<F>();
         s.where[t][x] = INT32_MAX;
       }
   }
@@ -368,13 +368,11 @@ struct FoldArgRows {
   __device__ static void pass(State& s, const KernelArgs& a, const int2* ka, int cs, int first, int stride, int left,
                               const int (&)[T], const int (&colc)[T]) {
     int2 e2[U];
-    int where[U];
     Vec<V> b[U][T];
 #pragma unroll
     for (int u = 0; u < U; ++u) {          // a missing entry repeats an existing one: same value, same index
       const int uu = u < left ? u : (left > 0 ? left - 1 : 0);
       e2[u] = ka[first + uu * stride];
-      where[u] = cs + first + uu * stride;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -383,18 +381,22 @@ struct FoldArgRows {
       for (int t = 0; t < T; ++t) b[u][t] = Vec<V>::load(brow + colc[t]);
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u)
+    for (int u = 0; u < U; ++u) {
+      const int uu = u < left ? u : (left > 0 ? left - 1 : 0);
+      const int where_u = cs + first + uu * stride;      // recomputed here rather than kept in registers across the loads
 #pragma unroll
       for (int t = 0; t < T; ++t)
 #pragma unroll
         for (int x = 0; x < V; ++x) {
-          // a lane meets its entries in increasing index order, so "first among equals" is
-          // simply "replace on strict improvement only"
-          const int k = key_of(__int_as_float(e2[u].y) * b[u][t].v[x]);
-          const bool improves = F == kMax ? k > s.key[t][x] : k < s.key[t][x];
-          s.key[t][x] = improves ? k : s.key[t][x];
-          s.where[t][x] = improves ? where[u] : s.where[t][x];
+          // A lane meets its entries in increasing index order, so "first among equals" is
+          // "replace on strict improvement only".  The hardware max / min orders the zeros
+          // (+0 above -0), so the running value changes its bits exactly when the entry improves it.
+          const float product = __int_as_float(e2[u].y) * b[u][t].v[x];
+          const float next = F == kMax ? __builtin_fmaxf(s.best[t][x], product) : __builtin_fminf(s.best[t][x], product);
+          s.where[t][x] = __float_as_int(next) != __float_as_int(s.best[t][x]) ? where_u : s.where[t][x];
+          s.best[t][x] = next;
         }
+    }
   }
 
   template <int G>
@@ -405,10 +407,10 @@ struct FoldArgRows {
       for (int t = 0; t < T; ++t)
 #pragma unroll
         for (int x = 0; x < V; ++x) {
-          const int k = __shfl_xor(s.key[t][x], off, kWave);
+          const float v = __shfl_xor(s.best[t][x], off, kWave);
           const int w = __shfl_xor(s.where[t][x], off, kWave);
-          if (better(k, w, s.key[t][x], s.where[t][x])) {
-            s.key[t][x] = k;
+          if (better(key_of(v), w, key_of(s.best[t][x]), s.where[t][x])) {
+            s.best[t][x] = v;
             s.where[t][x] = w;
           }
         }
@@ -424,7 +426,7 @@ struct FoldArgRows {
           Vec<V> value, place;
 #pragma unroll
           for (int x = 0; x < V; ++x) {
-            value.v[x] = value_of(s.key[t][x]);
+            value.v[x] = s.best[t][x];
             place.v[x] = __int_as_float(s.where[t][x]);
           }
           value.store(crow + col[t]);
@@ -436,11 +438,11 @@ struct FoldArgRows {
             const int j = col[t] + x;
             unsigned long long* slot = j < half ? reinterpret_cast<unsigned long long*>(crow) + j
                                                 : reinterpret_cast<unsigned long long*>(arow) + (j - half);
-            __hip_atomic_fetch_max(slot, pack(s.key[t][x], s.where[t][x]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_max(slot, pack(key_of(s.best[t][x]), s.where[t][x]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           }
         } else {
 #pragma unroll
-          for (int x = 0; x < V; ++x) atomic_fold<F>(crow + col[t] + x, value_of(s.key[t][x]));
+          for (int x = 0; x < V; ++x) atomic_fold<F>(crow + col[t] + x, s.best[t][x]);
         }
       }
     }
