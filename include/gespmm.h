@@ -118,6 +118,12 @@ int gespmm_csr_b16(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* 
 int gespmm_csr_arg(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
                    const int32_t* colind, const float* vals, const float* B, float* C, int32_t* arg,
                    int op, void* stream);
+/* gespmm_csr_arg with B stored in a 16-bit format (see gespmm_csr_b16 for b_dtype and the layout
+ * of B; everything else, including the exactness of values and positions with respect to the
+ * stored values of B, as gespmm_csr_arg). */
+int gespmm_csr_arg_b16(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                       const int32_t* colind, const float* vals, const void* B, int b_dtype, float* C,
+                       int32_t* arg, int op, void* stream);
 
 /*
  * Gradient of sum / mean with respect to B (the backward pass of a graph convolution is

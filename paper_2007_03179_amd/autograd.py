@@ -36,13 +36,13 @@ class _SpMM(torch.autograd.Function):
     @staticmethod
     def forward(ctx, B, graph, op):
         B = B.contiguous()
-        ctx.graph, ctx.op = graph, op
-        if op in ("max", "min"):
-            C, arg = _b.gespmm_csr_arg(graph.rowptr, graph.colind, graph.vals, B, op)
+        ctx.graph, ctx.op, ctx.b_dtype = graph, op, B.dtype
+        if op in ("max", "min"):          # (the *_b16 calls take fp32 as well)
+            C, arg = _b.gespmm_csr_arg_b16(graph.rowptr, graph.colind, graph.vals, B, op)
             ctx.save_for_backward(arg)
             ctx.mark_non_differentiable(arg)
             return C
-        return _b.gespmm_csr(graph.rowptr, graph.colind, graph.vals, B, op)
+        return _b.gespmm_csr_b16(graph.rowptr, graph.colind, graph.vals, B, op)
 
     @staticmethod
     def backward(ctx, dC):
@@ -54,12 +54,15 @@ class _SpMM(torch.autograd.Function):
         else:
             rowptrT, colindT, valsT = graph.transposed(op == "mean")
             dB = _b.gespmm_csr(rowptrT, colindT, valsT, dC, "sum")
-        return dB, None, None
+        return dB.to(ctx.b_dtype), None, None
 
 
 def spmm(graph: CsrGraph, B: torch.Tensor, op: str = "sum") -> torch.Tensor:
-    """C = A (x) B with gradient with respect to B.  B: (K, N) float32 CUDA tensor."""
-    assert op in _b.OPS and B.is_cuda and B.dtype == torch.float32 and B.shape[0] == graph.K
+    """C = A (x) B with gradient with respect to B.  B: (K, N) CUDA tensor, float32, or bfloat16 / float16
+    (stored features only: the arithmetic, C and the gradient computation are float32; the gradient is
+    rounded to B's type at the end)."""
+    assert op in _b.OPS and B.is_cuda and B.shape[0] == graph.K
+    assert B.dtype in (torch.float32, torch.bfloat16, torch.float16)
     return _SpMM.apply(B, graph, op)
 
 

@@ -49,6 +49,8 @@ def lib():
         L.gespmm_csr.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, ci, vp]
         L.gespmm_csr_b16.restype = ci
         L.gespmm_csr_b16.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, ci, vp, ci, vp]
+        L.gespmm_csr_arg_b16.restype = ci
+        L.gespmm_csr_arg_b16.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, ci, vp, vp, ci, vp]
         L.gespmm_plan_b16.restype = ci
         L.gespmm_plan_b16.argtypes = [i64, i64, i64, ci, ci, ctypes.POINTER(gespmm_plan_t)]
         L.gespmm_csr_simple.restype = ci
@@ -147,6 +149,23 @@ def gespmm_csr_b16(rowptr, colind, vals, B, op, C=None, stream=None):
     _check(lib().gespmm_csr_b16(M, K, N, colind.numel(), _ptr(rowptr), _ptr(colind), _ptr(vals),
                                 _ptr(B), code_b, _ptr(C), code, _stream(stream)))
     return C
+
+
+def gespmm_csr_arg_b16(rowptr, colind, vals, B, op, C=None, arg=None, stream=None):
+    """gespmm_csr_arg with B stored as torch.bfloat16 or torch.float16; returns (C fp32, arg int32)."""
+    import torch
+    M, (K, N) = rowptr.numel() - 1, B.shape
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.float32, device=B.device)
+    if arg is None:
+        arg = torch.empty((M, N), dtype=torch.int32, device=B.device)
+    code_b = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}[B.dtype]
+    _check_tensors(rowptr, colind, vals, B, C, b_dtype=B.dtype)
+    assert arg.is_cuda and arg.dtype == torch.int32 and arg.is_contiguous() and arg.shape == C.shape
+    code = OPS[op] if isinstance(op, str) else int(op)
+    _check(lib().gespmm_csr_arg_b16(M, K, N, colind.numel(), _ptr(rowptr), _ptr(colind), _ptr(vals),
+                                    _ptr(B), code_b, _ptr(C), _ptr(arg), code, _stream(stream)))
+    return C, arg
 
 
 def gespmm_plan_b16(M, N, nnz, b_dtype="bf16", aligned16=True) -> dict:

@@ -90,6 +90,14 @@ int gespmm_csr_b16(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* 
 int gespmm_csr_arg(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
                    const int32_t* colind, const float* vals, const float* B, float* C, int32_t* arg,
                    int op, void* stream_) {
+  return gespmm_csr_arg_b16(M, K, N, nnz, rowptr, colind, vals, B, GESPMM_F32, C, arg, op, stream_);
+}
+
+int gespmm_csr_arg_b16(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                       const int32_t* colind, const float* vals, const void* B_, int b_dtype, float* C,
+                       int32_t* arg, int op, void* stream_) {
+  if (b_dtype != GESPMM_F32 && b_dtype != GESPMM_BF16 && b_dtype != GESPMM_F16) return GESPMM_ERR_BAD_ARG;
+  const float* B = static_cast<const float*>(B_);
   if (op != GESPMM_MAX && op != GESPMM_MIN) return GESPMM_ERR_BAD_ARG;
   const int st = validate(M, K, N, nnz, rowptr, colind, B, C, op);
   if (st != GESPMM_OK || M == 0 || N == 0) return st;
@@ -101,6 +109,7 @@ int gespmm_csr_arg(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* 
   L.M = M; L.N = N; L.nnz = nnz;
   L.rowptr = rowptr; L.colind = colind; L.vals = vals;
   L.dense_in = B; L.dense_out = C; L.arg = arg;
+  L.b_dtype = b_dtype;
   L.also_aligned = arg;
   L.init_target = C;
   L.init2_target = reinterpret_cast<float*>(arg);
@@ -129,6 +138,7 @@ int gespmm_csr_arg(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* 
   S.M = M; S.N = N; S.nnz = nnz;
   S.rowptr = rowptr; S.colind = colind; S.vals = vals;
   S.dense_in = B; S.result_in = C; S.arg = arg;
+  S.b_dtype = b_dtype;
   S.also_aligned = arg;
   S.only_split = true;
   return launch_chunks(S, stream);

@@ -338,7 +338,7 @@ struct FoldRows {
 // zero, which is below every packed word) and finish_split_rows unpacks them in place
 // afterwards.  Otherwise split rows only get their value here (by atomics, as in FoldRows)
 // and their positions are found by ArgRows in a second pass over the matrix.
-template <int F, int V, int T>
+template <int F, int V, int T, class BT = float>
 struct FoldArgRows {
   static constexpr bool kCanSkipWholeRows = false;
   static_assert(F == kMax || F == kMin, "positions exist for max and min only");
@@ -367,8 +367,9 @@ struct FoldArgRows {
   template <int U>
   __device__ static void pass(State& s, const KernelArgs& a, const int2* ka, int cs, int first, int stride, int left,
                               const int (&)[T], const int (&colc)[T]) {
+    using Load = BLoad<V, BT>;
     int2 e2[U];
-    Vec<V> b[U][T];
+    typename Load::Raw b[U][T];
 #pragma unroll
     for (int u = 0; u < U; ++u) {          // a missing entry repeats an existing one: same value, same index
       const int uu = u < left ? u : (left > 0 ? left - 1 : 0);
@@ -376,26 +377,29 @@ struct FoldArgRows {
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const float* brow = a.B + (int64_t)e2[u].x * a.N;
+      const BT* brow = reinterpret_cast<const BT*>(a.B) + (int64_t)e2[u].x * a.N;
 #pragma unroll
-      for (int t = 0; t < T; ++t) b[u][t] = Vec<V>::load(brow + colc[t]);
+      for (int t = 0; t < T; ++t) b[u][t] = Load::load(brow + colc[t]);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int uu = u < left ? u : (left > 0 ? left - 1 : 0);
       const int where_u = cs + first + uu * stride;      // recomputed here rather than kept in registers across the loads
 #pragma unroll
-      for (int t = 0; t < T; ++t)
+      for (int t = 0; t < T; ++t) {
+        float bx[V];
+        Load::unpack(b[u][t], bx);
 #pragma unroll
         for (int x = 0; x < V; ++x) {
           // A lane meets its entries in increasing index order, so "first among equals" is
           // "replace on strict improvement only".  The hardware max / min orders the zeros
           // (+0 above -0), so the running value changes its bits exactly when the entry improves it.
-          const float product = __int_as_float(e2[u].y) * b[u][t].v[x];
+          const float product = __int_as_float(e2[u].y) * bx[x];
           const float next = F == kMax ? __builtin_fmaxf(s.best[t][x], product) : __builtin_fminf(s.best[t][x], product);
           s.where[t][x] = __float_as_int(next) != __float_as_int(s.best[t][x]) ? where_u : s.where[t][x];
           s.best[t][x] = next;
         }
+      }
     }
   }
 
@@ -519,7 +523,7 @@ __global__ void __launch_bounds__(kBlock) finish_split_rows(int32_t M, int32_t N
 // product has exactly the bits of C[i, j] is a candidate; the smallest entry index wins,
 // i.e. the first in storage order.  Rows inside one chunk are stored, split rows are
 // combined with an integer atomic min on a row preset to INT_MAX.
-template <int V, int T>
+template <int V, int T, class BT = float>
 struct ArgRows {
   static constexpr bool kCanSkipWholeRows = true;
   struct State { int best[T][V]; int want[T][V]; };
@@ -539,9 +543,10 @@ struct ArgRows {
   template <int U>
   __device__ static void pass(State& s, const KernelArgs& a, const int2* ka, int cs, int first, int stride, int left,
                               const int (&)[T], const int (&colc)[T]) {
+    using Load = BLoad<V, BT>;
     int2 e2[U];
     int where[U];
-    Vec<V> b[U][T];
+    typename Load::Raw b[U][T];
 #pragma unroll
     for (int u = 0; u < U; ++u) {          // a missing entry repeats an existing one: same index, harmless
       const int uu = u < left ? u : (left > 0 ? left - 1 : 0);
@@ -550,19 +555,22 @@ struct ArgRows {
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const float* brow = a.B + (int64_t)e2[u].x * a.N;
+      const BT* brow = reinterpret_cast<const BT*>(a.B) + (int64_t)e2[u].x * a.N;
 #pragma unroll
-      for (int t = 0; t < T; ++t) b[u][t] = Vec<V>::load(brow + colc[t]);
+      for (int t = 0; t < T; ++t) b[u][t] = Load::load(brow + colc[t]);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int t = 0; t < T; ++t)
+      for (int t = 0; t < T; ++t) {
+        float bx[V];
+        Load::unpack(b[u][t], bx);
 #pragma unroll
         for (int x = 0; x < V; ++x) {
-          const float prod = __int_as_float(e2[u].y) * b[u][t].v[x];
+          const float prod = __int_as_float(e2[u].y) * bx[x];
           if (__float_as_int(prod) == s.want[t][x] && where[u] < s.best[t][x]) s.best[t][x] = where[u];
         }
+      }
   }
 
   template <int G>
@@ -1040,6 +1048,7 @@ template <int V, int T> using MaxRows = FoldRows<kMax, V, T>;
 template <int V, int T> using MinRows = FoldRows<kMin, V, T>;
 template <int V, int T> using MaxArgRows = FoldArgRows<kMax, V, T>;
 template <int V, int T> using MinArgRows = FoldArgRows<kMin, V, T>;
+template <int V, int T> using PlainArgRows = ArgRows<V, T>;
 
 template <int V>
 MainKernel pick_job(int job, int G, int T) {
@@ -1047,7 +1056,7 @@ MainKernel pick_job(int job, int G, int T) {
     case kJobAdd: return pick_gt<AddRows, V>(G, T);
     case kJobMax: return pick_gt<MaxRows, V>(G, T);
     case kJobMin: return pick_gt<MinRows, V>(G, T);
-    case kJobArg: return pick_gt<ArgRows, V>(G, T);
+    case kJobArg: return pick_gt<PlainArgRows, V>(G, T);
     case kJobMaxWithArg: return pick_gt<MaxArgRows, V>(G, T);
     case kJobMinWithArg: return pick_gt<MinArgRows, V>(G, T);
     case kJobTransposed: return pick_gt<TransposedRows, V>(G, T);
@@ -1074,12 +1083,27 @@ MainKernel pick_b16_fold(int vec, int G, int T) {
   return nullptr;
 }
 
+template <class P4, class P1>
+MainKernel pick_b16_shapes(int vec, int G, int T) {      // P4 / P1: the policy for 4 columns / 1 column per lane
+  if (T != 1) return nullptr;
+#define GESPMM_CASE4(GG) if (vec == 4 && G == GG) return chunk_kernel<P4, 4, GG, 1>;
+#define GESPMM_CASE1(GG) if (vec == 1 && G == GG) return chunk_kernel<P1, 1, GG, 1>;
+  GESPMM_CASE4(1) GESPMM_CASE4(2) GESPMM_CASE4(4) GESPMM_CASE4(8) GESPMM_CASE4(16) GESPMM_CASE4(32)
+  GESPMM_CASE1(1) GESPMM_CASE1(2) GESPMM_CASE1(4) GESPMM_CASE1(8) GESPMM_CASE1(16) GESPMM_CASE1(32) GESPMM_CASE1(64)
+#undef GESPMM_CASE4
+#undef GESPMM_CASE1
+  return nullptr;
+}
+
 template <class BT>
 MainKernel pick_b16(int job, int vec, int G, int T) {
   switch (job) {
     case kJobAdd: return pick_b16_fold<kAdd, BT>(vec, G, T);
     case kJobMax: return pick_b16_fold<kMax, BT>(vec, G, T);
     case kJobMin: return pick_b16_fold<kMin, BT>(vec, G, T);
+    case kJobMaxWithArg: return pick_b16_shapes<FoldArgRows<kMax, 4, 1, BT>, FoldArgRows<kMax, 1, 1, BT>>(vec, G, T);
+    case kJobMinWithArg: return pick_b16_shapes<FoldArgRows<kMin, 4, 1, BT>, FoldArgRows<kMin, 1, 1, BT>>(vec, G, T);
+    case kJobArg: return pick_b16_shapes<ArgRows<4, 1, BT>, ArgRows<1, 1, BT>>(vec, G, T);
     default: return nullptr;
   }
 }

@@ -134,3 +134,29 @@ def test_sage_layer_matches_dense_pytorch(ag, aggregator):
     assert torch.allclose(out, ref, rtol=1e-5, atol=1e-5)
     for a, b in zip(got, want):
         assert torch.allclose(a, b, rtol=1e-4, atol=1e-5)
+
+
+@pytest.mark.parametrize("op", ["sum", "max"])
+def test_features_stored_in_16_bits(ag, op):
+    """B as bfloat16: forward equals the oracle on the stored values; the gradient (computed in fp32, rounded
+    to bfloat16 at the end) is within one bfloat16 rounding of the oracle's."""
+    rp, ci, v = graphgen.random_csr(500, 400, 8.0, 71, empty_frac=0.1, long_rows=((5, 2000),), duplicates=True)
+    Bn = torch.from_numpy(graphgen.random_dense(400, 32, 7)).to(torch.bfloat16)
+    Bw, dCh = Bn.float().numpy(), graphgen.random_dense(500, 32, 8)
+    print(f"  case autograd bf16 {op}", flush=True)
+    g = _graph(ag, rp, ci, v, 400)
+    B = Bn.cuda().requires_grad_(True)
+    C = ag.spmm(g, B, op)
+    assert C.dtype == torch.float32
+    C.backward(torch.from_numpy(dCh).cuda())
+    torch.cuda.synchronize()
+    ok, worst = oracle.compare(op, C.detach().cpu().numpy(), *oracle.spmm(rp, ci, v, Bw, op))
+    assert ok, worst
+    if op == "sum":
+        ref, sabs = oracle.spmm_transposed(rp, ci, v, dCh, op, 400)
+    else:
+        _, arg = oracle.spmm_arg(rp, ci, v, Bw, op)
+        ref, sabs = oracle.pool_backward(ci, v, arg, dCh, 400)
+    assert B.grad.dtype == torch.bfloat16
+    err = np.abs(B.grad.float().cpu().numpy().astype(np.float64) - ref)
+    assert (err <= 2.0 ** -8 * np.abs(ref) + 1e-5 * sabs + 1e-6).all()

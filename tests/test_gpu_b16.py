@@ -128,3 +128,42 @@ def test_workloads_at_full_size(gs, which, N, dt):
     for op in w.ops:
         C = check(gs, w.rowptr, w.colind, w.vals, B, dt, op, rows=rows, label=w.name, dA=dA)
         assert np.isfinite(C).all()
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+@pytest.mark.parametrize("N", [1, 4, 7, 12, 32, 64, 100, 128, 520, 1028])
+def test_value_and_position_with_16_bit_features(gs, N, dt):
+    """gespmm_csr_arg_b16: value bits and positions equal the oracle's on the stored (widened) values; few
+    distinct values so that ties are common; a row spanning many chunks; widths on both routes for split rows."""
+    rp, ci, v = graphgen.random_csr(600, 400, 8.0, 500 + N, empty_frac=0.1, long_rows=((77, 2500),),
+                                    duplicates=True, sort_cols=False)
+    B = np.round(graphgen.random_dense(400, N, N) * 4.0).astype(np.float32)
+    v = np.round(v * 2.0).astype(np.float32)
+    v[v == 0] = 1.0
+    B[5] = -0.0
+    Bn, Bw = narrow(B, dt)
+    for op in ("max", "min"):
+        for vv in (v, None):
+            say(f"  case arg-b16 {dt} N={N} op={op} vals={'yes' if vv is not None else 'NULL'}")
+            C, arg = gs.gespmm_csr_arg_b16(dev(rp), dev(ci), dev(vv), Bn.cuda(), op)
+            torch.cuda.synchronize()
+            Cref, aref = oracle.spmm_arg(rp, ci, vv, Bw, op)
+            assert np.array_equal(C.cpu().numpy().view(np.uint32), Cref.astype(np.float32).view(np.uint32))
+            assert np.array_equal(arg.cpu().numpy(), aref)
+
+
+def test_value_and_position_b16_on_a_workload(gs):
+    w = graphgen.workload(2)
+    N = 128
+    Bn, Bw = narrow(w.B(N), "bf16")
+    vals = graphgen.uniform_pm1(w.nnz, 98)
+    lens = np.diff(w.rowptr)
+    rows = np.unique(np.concatenate([np.argsort(lens)[-16:], np.flatnonzero(lens == 0)[:8],
+                                     np.random.default_rng(2).integers(0, w.M, 3000)])).astype(np.int64)
+    for op in ("max", "min"):
+        say(f"  case arg-b16 workload op={op}")
+        C, arg = gs.gespmm_csr_arg_b16(dev(w.rowptr), dev(w.colind), dev(vals), Bn.cuda(), op)
+        torch.cuda.synchronize()
+        Cref, aref = oracle.spmm_arg(w.rowptr, w.colind, vals, Bw, op, rows=rows)
+        assert np.array_equal(C.cpu().numpy()[rows].view(np.uint32), Cref.astype(np.float32).view(np.uint32))
+        assert np.array_equal(arg.cpu().numpy()[rows], aref)
