@@ -471,10 +471,13 @@ struct FoldArgRows {
 // than one chunk holds N packed words in its C and arg storage; one wavefront per such row
 // reads them all, then writes the row's values and positions over them.  N <= 64 * kFinishWords.
 constexpr int kFinishWords = 16;
-template <int F>
+// WORDS: packed words one lane holds per row (N <= 64 * WORDS); rows are taken kFinishWords / WORDS at
+// a time so that their loads are in flight together.
+template <int F, int WORDS>
 __global__ void __launch_bounds__(kBlock) finish_split_rows(int32_t M, int32_t N, const int32_t* __restrict__ rowptr,
                                                            float* C, int32_t* arg, int chunk_shift) {
   using Rows = FoldArgRows<F, 4, 1>;
+  constexpr int BATCH = kFinishWords / WORDS;
   const int lane = threadIdx.x & (kWave - 1);
   const int64_t base = ((int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)) * kWave;
   if (base >= M) return;
@@ -487,33 +490,48 @@ __global__ void __launch_bounds__(kBlock) finish_split_rows(int32_t M, int32_t N
   unsigned long long todo = __ballot(split);
   const int half = N >> 1;
   while (todo) {
-    const int i = __builtin_ctzll(todo);
-    todo &= todo - 1;
-    float* crow = C + (base + i) * (int64_t)N;
-    int32_t* arow = arg + (base + i) * (int64_t)N;
-    const unsigned long long* cslots = reinterpret_cast<const unsigned long long*>(crow);
-    const unsigned long long* aslots = reinterpret_cast<const unsigned long long*>(arow);
-    unsigned long long word[kFinishWords];
+    int64_t row[BATCH];
 #pragma unroll
-    for (int k = 0; k < kFinishWords; ++k) {
-      const int j = lane + k * kWave;
-      word[k] = j < N ? (j < half ? cslots[j] : aslots[j - half]) : 0ull;
+    for (int q = 0; q < BATCH; ++q) {                  // the next BATCH split rows (-1: none left)
+      row[q] = -1;
+      if (todo) {
+        row[q] = base + __builtin_ctzll(todo);
+        todo &= todo - 1;
+      }
     }
-    // every word of the row has been read (by all lanes) before any lane overwrites the row:
+    unsigned long long word[BATCH][WORDS];
+#pragma unroll
+    for (int q = 0; q < BATCH; ++q) {
+      if (row[q] < 0) continue;
+      const unsigned long long* cslots = reinterpret_cast<const unsigned long long*>(C + row[q] * (int64_t)N);
+      const unsigned long long* aslots = reinterpret_cast<const unsigned long long*>(arg + row[q] * (int64_t)N);
+#pragma unroll
+      for (int k = 0; k < WORDS; ++k) {
+        const int j = lane + k * kWave;
+        word[q][k] = j < N ? (j < half ? cslots[j] : aslots[j - half]) : 0ull;
+      }
+    }
+    // every word of these rows has been read (by all lanes) before any lane overwrites a row:
     // a workgroup-scope fence waits for this wavefront's outstanding loads and keeps the
     // compiler from moving memory operations across it (no cache maintenance is needed, the
-    // row belongs to this wavefront alone)
+    // rows belong to this wavefront alone)
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int k = 0; k < kFinishWords; ++k) {
-      const int j = lane + k * kWave;
-      if (j < N) {
-        float value;
-        int where;
-        Rows::unpack(word[k], value, where);
-        crow[j] = value;
-        arow[j] = where;
+    for (int q = 0; q < BATCH; ++q) {
+      if (row[q] < 0) continue;
+      float* crow = C + row[q] * (int64_t)N;
+      int32_t* arow = arg + row[q] * (int64_t)N;
+#pragma unroll
+      for (int k = 0; k < WORDS; ++k) {
+        const int j = lane + k * kWave;
+        if (j < N) {
+          float value;
+          int where;
+          Rows::unpack(word[q][k], value, where);
+          crow[j] = value;
+          arow[j] = where;
+        }
       }
     }
   }
@@ -1320,12 +1338,20 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
   }
   if (L.packed_split) {
     const unsigned blocks = (unsigned)((L.M + kBlock - 1) / kBlock);
-    if (L.job == kJobMaxWithArg)
-      hipLaunchKernelGGL(finish_split_rows<kMax>, dim3(blocks), dim3(kBlock), 0, stream, (int32_t)L.M, (int32_t)L.N, L.rowptr,
-                         L.dense_out, L.arg, shift);
-    else
-      hipLaunchKernelGGL(finish_split_rows<kMin>, dim3(blocks), dim3(kBlock), 0, stream, (int32_t)L.M, (int32_t)L.N, L.rowptr,
-                         L.dense_out, L.arg, shift);
+    int words = 1;
+    while (words * kWave < L.N) words *= 2;
+    const bool is_max = L.job == kJobMaxWithArg;
+#define GESPMM_FINISH(WW)                                                                                             \
+  if (words == WW) {                                                                                                  \
+    if (is_max)                                                                                                       \
+      hipLaunchKernelGGL((finish_split_rows<kMax, WW>), dim3(blocks), dim3(kBlock), 0, stream, (int32_t)L.M, (int32_t)L.N, \
+                         L.rowptr, L.dense_out, L.arg, shift);                                                        \
+    else                                                                                                              \
+      hipLaunchKernelGGL((finish_split_rows<kMin, WW>), dim3(blocks), dim3(kBlock), 0, stream, (int32_t)L.M, (int32_t)L.N, \
+                         L.rowptr, L.dense_out, L.arg, shift);                                                        \
+  }
+    GESPMM_FINISH(1) GESPMM_FINISH(2) GESPMM_FINISH(4) GESPMM_FINISH(8) GESPMM_FINISH(16)
+#undef GESPMM_FINISH
     if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
   }
   return GESPMM_OK;
