@@ -109,7 +109,7 @@ int gespmm_csr_b16(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* 
  *         smallest p (first in storage order); -1 for an empty row.
  * One fused pass carries (value, position) pairs through the reduction; rows that several
  * wavefronts share combine their pairs as packed 64-bit words held, during the call, in the
- * row's own C and arg storage, and a small kernel unpacks them at the end (1.1 to 1.7 times
+ * row's own C and arg storage, and a small kernel unpacks them at the end (1.1 to 1.45 times
  * the cost of gespmm_csr).  That route needs the vector kernels (N a multiple of 4; B, C and
  * arg 16-byte aligned) and N <= 1024; otherwise split rows get their positions from a second
  * pass over the matrix (up to 1.9 times the cost of gespmm_csr).  Same errors as gespmm_csr;

@@ -791,11 +791,17 @@ struct CustomRows {
   }
 };
 
+// The value+position fold carries twice the state per column; with half as many gathers in flight it
+// fits 76 registers (6 waves per SIMD instead of 4) and is 3-9 % faster.
+template <class P> struct FlightDivisor { static constexpr int value = 1; };
+template <int F, int V, int T, class BT> struct FlightDivisor<FoldArgRows<F, V, T, BT>> { static constexpr int value = 2; };
+
 // P: row policy; V: floats per lane per load; G: lanes per slot; T: column tiles per lane.
 template <class P, int V, int G, int T>
 __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
   constexpr int NS = kWave / G;                 // slots
-  constexpr int U = loads_in_flight(G) / T > 0 ? loads_in_flight(G) / T : 1;   // entries per lane per pass
+  constexpr int kFlight = loads_in_flight(G) / FlightDivisor<P>::value;
+  constexpr int U = kFlight / T > 0 ? kFlight / T : 1;   // entries per lane per pass
   extern __shared__ int2 s_dyn[];               // per wavefront: S entries (colind, val) + 64 row descriptors
 
   const int lane = threadIdx.x & (kWave - 1);
@@ -908,8 +914,17 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
           const int64_t row = rbase + (d.x & 63);
           typename P::State st;
           P::begin(st, a, row, d.y, colc);
-          for (int it = 0; __ballot(it < r_len) != 0ull; it += U)
-            P::template pass<U>(st, a, ka, cs, r_ps + (it < r_len ? it : 0), 1, r_len - it, col, colc);
+          // U entries per step; a last step with at most U / 2 entries left in every slot takes
+          // the half-size pass (fewer padded gathers: up to 7 % on matrices of short rows)
+          for (int it = 0; __ballot(it < r_len) != 0ull;) {
+            if (U >= 4 && __ballot(r_len - it > U / 2) == 0ull) {
+              P::template pass<(U >= 4 ? U / 2 : U)>(st, a, ka, cs, r_ps + (it < r_len ? it : 0), 1, r_len - it, col, colc);
+              it += U / 2;
+            } else {
+              P::template pass<U>(st, a, ka, cs, r_ps + (it < r_len ? it : 0), 1, r_len - it, col, colc);
+              it += U;
+            }
+          }
           if (have) P::end(st, a, row, (d.x >> 30) & 1, d.y, col);
         }
         wave_lds_fence();
