@@ -32,15 +32,15 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 # run and one WRITE_SIZE run, each scaled by the calibration copy kernel of known size;
 # the summaries are under profiles/).  Key: "<workload>/N<width>/<op>".  Missing = null.
 MEASURED_TRAFFIC_BYTES = {
-    "large_dense_degree/N64/sum": 22.989e9,   # profiles/chunk_kernel_large_dense_degree_N64_sum.md
-    "general_ops/N128/sum": 1.0068e9,         # profiles/chunk_kernel_general_ops_N128_sum.md
-    "skew_narrow/N8/sum": 0.63324e9,          # profiles/chunk_kernel_skew_narrow_N8_sum.md
-    "skew_narrow/N32/sum": 1.2064e9,          # profiles/chunk_kernel_skew_narrow_N32_sum.md
-    "width_sweep/N512/sum": 0.18092e9,        # profiles/chunk_kernel_width_sweep_N512_sum.md
-    "uniform_512k_d4/N128/sum": 1.4172e9,     # profiles/chunk_kernel_uniform_512k_d4_N128_sum.md
+    "large_dense_degree/N64/sum": 22.993e9,   # profiles/chunk_kernel_large_dense_degree_N64_sum.md
+    "general_ops/N128/sum": 1.0008e9,         # profiles/chunk_kernel_general_ops_N128_sum.md
+    "skew_narrow/N8/sum": 0.63337e9,          # profiles/chunk_kernel_skew_narrow_N8_sum.md
+    "skew_narrow/N32/sum": 1.2060e9,          # profiles/chunk_kernel_skew_narrow_N32_sum.md
+    "width_sweep/N512/sum": 0.19208e9,        # profiles/chunk_kernel_width_sweep_N512_sum.md
+    "uniform_512k_d4/N128/sum": 1.4153e9,     # profiles/chunk_kernel_uniform_512k_d4_N128_sum.md
 }
 MEASURED_TRAFFIC_BYTES_BF16 = {
-    "large_dense_degree/N64/sum": 11.679e9,   # profiles/chunk_kernel_large_dense_degree_N64_bf16_sum.md
+    "large_dense_degree/N64/sum": 11.680e9,   # profiles/chunk_kernel_large_dense_degree_N64_bf16_sum.md
 }
 
 
