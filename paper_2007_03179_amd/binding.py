@@ -36,13 +36,18 @@ _lib = None
 
 
 def lib():
-    """The loaded library (built by build.py; raises if it is not there)."""
+    """The loaded library.  It is built by build.py; if it is not there it is compiled now (hipcc,
+    gfx950), and if that is impossible this raises: there is no other code path."""
     global _lib
     if _lib is None:
         if not os.path.exists(LIB_PATH):
-            raise FileNotFoundError(
-                f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
-                "(or paper_2007_03179_amd/build.py) first; there is no fallback path")
+            try:
+                from . import build as _build
+                _build.build(force=True)
+            except Exception as exc:
+                raise FileNotFoundError(
+                    f"{LIB_PATH} is missing and could not be compiled ({exc}): run "
+                    "`python -c 'import __graft_entry__ as g; g.build()'`; there is no fallback path") from exc
         L = ctypes.CDLL(LIB_PATH)
         i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
         L.gespmm_csr.restype = ci
