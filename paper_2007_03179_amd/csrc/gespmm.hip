@@ -334,6 +334,10 @@ int gespmm_profile_begin(int capacity) {
   g_ev_stop.assign(capacity, nullptr);
   for (int i = 0; i < capacity; ++i) {
     if (hipEventCreate(&g_ev_start[i]) != hipSuccess || hipEventCreate(&g_ev_stop[i]) != hipSuccess) {
+      for (int j = 0; j <= i; ++j) {              // release what was created before the failure
+        if (g_ev_start[j]) (void)hipEventDestroy(g_ev_start[j]);
+        if (g_ev_stop[j]) (void)hipEventDestroy(g_ev_stop[j]);
+      }
       g_ev_start.clear();
       g_ev_stop.clear();
       return GESPMM_ERR_HIP;
