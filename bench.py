@@ -384,6 +384,29 @@ def tile_study(args, gs, torch, graphgen, dev):
     return rows
 
 
+def gather_ceiling(gs, torch, case, kernel_ms, plan, reps=10):
+    """Rate of the plain line-gather kernel on this workload's own index stream (colind, in storage order)
+    over a table shaped like the live slice of B (K lines of 128 bytes), next to the lines per second the
+    chunk kernel itself gathers.  fp32 only (one 128-byte line per entry and column block of 32 floats)."""
+    w = case.w
+    table = torch.empty((w.K, 32), dtype=torch.float32, device=case.B.device).uniform_(-1, 1)
+    out = gs.gespmm_calibration_gather(table, case.ci)
+    for _ in range(2):
+        gs.gespmm_calibration_gather(table, case.ci, out=out)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev[0].record()
+    for _ in range(reps):
+        gs.gespmm_calibration_gather(table, case.ci, out=out)
+    ev[1].record()
+    torch.cuda.synchronize()
+    ms = ev[0].elapsed_time(ev[1]) / reps
+    lines = w.nnz * plan["col_blocks"] * max(1, plan["vec"] * plan["lanes_per_row"] * plan["tiles_per_lane"] // 32)
+    return {"gather_only_G_lines_per_s": w.nnz / (ms * 1e-3) / 1e9,
+            "gather_only_GBps": w.nnz * 132 / (ms * 1e-3) / 1e9,          # 128-byte line + 4-byte index
+            "chunk_kernel_G_lines_per_s": lines / (kernel_ms * 1e-3) / 1e9,
+            "table_MB": w.K * 128 / 1e6}
+
+
 def geomean(xs):
     import math
     xs = [x for x in xs if x]
@@ -552,6 +575,9 @@ def main():
     if out["roofline"]["traffic"]:
         # what actually crossed the L2 / fabric boundary per second (Infinity Cache hits included)
         out["roofline"]["traffic_GBps"] = out["roofline"]["traffic"] / (r["main_kernel_ms"] * 1e-3) / 1e9
+    if args.b_dtype == "f32" and not args.no_cold:
+        # a plain gather of the same lines in the same order: the ceiling for the kernel's inner loop
+        out["roofline"]["gather_ceiling"] = gather_ceiling(gs, torch, case, r["main_kernel_ms"], plan)
     if evictor is not None:
         # outside the timed region: one call at a time, back to back and with L2 and Infinity Cache
         # flushed before each call, and the plain-copy bandwidth of this machine as a practical ceiling

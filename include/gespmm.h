@@ -247,6 +247,17 @@ int gespmm_profile_end(double* main_kernel_ms_sum, int* launches);
  */
 int gespmm_calibration_copy(const void* src, void* dst, int64_t bytes, void* stream);
 
+/*
+ * Second yardstick: a plain gather of 128-byte lines.  n times, 8 lanes read line idx[e]
+ * (0 <= idx[e] < table_lines) of `table` (table_lines * 128 bytes, 16-byte aligned), eight
+ * gathers in flight per lane: what the inner loop of gespmm_csr does to memory, and nothing
+ * else.  Its rate on a table of the size of the live slice of B is the ceiling for that loop.
+ * `out` receives one 16-byte value per launched lane (so the loads stay live): at least
+ * min(ceil(n / 256), 8192) * 4096 bytes.  Values in idx are not validated.
+ */
+int gespmm_calibration_gather(const void* table, int64_t table_lines, const int32_t* idx, int64_t n,
+                              void* out, int64_t out_bytes, void* stream);
+
 /* Static text for a status code (never NULL). */
 const char* gespmm_status_string(int status);
 

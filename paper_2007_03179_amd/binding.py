@@ -84,6 +84,8 @@ def lib():
         L.gespmm_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
         L.gespmm_calibration_copy.restype = ci
         L.gespmm_calibration_copy.argtypes = [vp, vp, i64, vp]
+        L.gespmm_calibration_gather.restype = ci
+        L.gespmm_calibration_gather.argtypes = [vp, i64, vp, i64, vp, i64, vp]
         L.gespmm_status_string.restype = ctypes.c_char_p
         L.gespmm_status_string.argtypes = [ci]
         L.gespmm_version.restype = ci
@@ -306,6 +308,22 @@ def gespmm_calibration_copy(src, dst, stream=None):
     assert dst.numel() * dst.element_size() == nbytes and src.is_contiguous() and dst.is_contiguous()
     _check(lib().gespmm_calibration_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)))
     return dst
+
+
+def gespmm_calibration_gather(table, idx, out=None, stream=None):
+    """n = idx.numel() gathers of 128-byte lines of `table` (any contiguous CUDA tensor whose size is a
+    multiple of 128 bytes); returns the scratch output tensor."""
+    import torch
+    nbytes = table.numel() * table.element_size()
+    assert table.is_cuda and table.is_contiguous() and nbytes % 128 == 0
+    assert idx.is_cuda and idx.dtype == torch.int32 and idx.is_contiguous()
+    n = idx.numel()
+    need = min((n + 255) // 256, 8192) * 4096
+    if out is None:
+        out = torch.empty(max(need // 4, 4), dtype=torch.float32, device=table.device)
+    _check(lib().gespmm_calibration_gather(_ptr(table), nbytes // 128, _ptr(idx), n, _ptr(out),
+                                           out.numel() * out.element_size(), _stream(stream)))
+    return out
 
 
 def gespmm_profile_begin(capacity: int):

@@ -385,6 +385,21 @@ int gespmm_calibration_copy(const void* src, void* dst, int64_t bytes, void* str
   return hipGetLastError() == hipSuccess ? GESPMM_OK : GESPMM_ERR_HIP;
 }
 
+int gespmm_calibration_gather(const void* table, int64_t table_lines, const int32_t* idx, int64_t n, void* out,
+                              int64_t out_bytes, void* stream_) {
+  if (table_lines < 0 || n < 0 || out_bytes < 0) return GESPMM_ERR_BAD_ARG;
+  if (n == 0) return GESPMM_OK;
+  if (!table || !idx || !out) return GESPMM_ERR_NULL;
+  if (table_lines == 0 || table_lines > INT32_MAX) return GESPMM_ERR_BAD_ARG;
+  if ((((uintptr_t)table | (uintptr_t)out) & 15u) != 0) return GESPMM_ERR_BAD_ARG;
+  int64_t blocks = (n + kBlock - 1) / kBlock;              // 8 lanes per gather, 8 gathers per step
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  if (out_bytes < blocks * kBlock * 16) return GESPMM_ERR_BAD_ARG;
+  hipLaunchKernelGGL(gather_lines, dim3((unsigned)blocks), dim3(kBlock), 0, (hipStream_t)stream_,
+                     (const float4*)table, idx, n, (float4*)out);
+  return hipGetLastError() == hipSuccess ? GESPMM_OK : GESPMM_ERR_HIP;
+}
+
 const char* gespmm_status_string(int status) {
   switch (status) {
     case GESPMM_OK: return "ok";

@@ -227,6 +227,31 @@ static __global__ void __launch_bounds__(kBlock) copy_f4(const float4* __restric
   for (; i < n4; i += stride) dst[i] = src[i];
 }
 
+// Plain gather of 128-byte lines: 8 lanes read line idx[e] of the table (16 bytes each), eight
+// gathers in flight per lane, indices read coalesced; every group of 8 lanes folds what it read
+// into one float4 so that the loads stay live.  It does what the chunk kernel's inner loop does
+// to memory and nothing else, so its rate is the ceiling for that loop on a table of that size.
+static __global__ void __launch_bounds__(kBlock) gather_lines(const float4* __restrict__ table, const int32_t* __restrict__ idx,
+                                                              int64_t n, float4* __restrict__ out) {
+  const int g = threadIdx.x & 7;
+  const int64_t group = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> 3;
+  const int64_t groups = ((int64_t)gridDim.x * kBlock) >> 3;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int64_t e = group * 8; e < n; e += groups * 8) {
+    int k[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) k[u] = idx[e + u < n ? e + u : n - 1];
+    float4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = table[(int64_t)k[u] * 8 + g];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (e + u < n) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }   // padded gathers do not count
+    }
+  }
+  out[(int64_t)blockIdx.x * kBlock + threadIdx.x] = acc;
+}
+
 // ------------------------------------------------------------ chunk kernel --
 // The walk over chunks, rows and row segments is the same for every job; what is done
 // with a row segment is a policy:

@@ -28,7 +28,7 @@ def test_every_declared_symbol_is_exported(L):
     names = _declared_functions()
     assert {"gespmm_csr", "gespmm_csr_simple", "gespmm_plan", "gespmm_set_tuning",
             "gespmm_profile_begin", "gespmm_profile_end", "gespmm_status_string",
-            "gespmm_calibration_copy", "gespmm_csr_arg", "gespmm_csr_transposed", "gespmm_pool_backward",
+            "gespmm_calibration_copy", "gespmm_calibration_gather", "gespmm_csr_arg", "gespmm_csr_transposed", "gespmm_pool_backward",
             "gespmm_csr_transpose", "gespmm_csr_transpose_workspace_bytes",
             "gespmm_csr_b16", "gespmm_plan_b16", "gespmm_csr_arg_b16", "gespmm_csr_transpose_sorted",
             "gespmm_csr_transpose_sorted_workspace_bytes", "gespmm_version"} <= set(names)

@@ -278,6 +278,17 @@ def test_calibration_copy_is_a_copy(gs, floats):
     assert bool((dst[:4] == -1).all()) and bool((dst[-4:] == -1).all())
 
 
+def test_calibration_gather_reads_every_requested_line(gs):
+    lines, n = 5000, 123_457
+    table = torch.arange(lines, dtype=torch.float32, device="cuda").repeat_interleave(32).view(lines, 32).contiguous()
+    idx = torch.from_numpy(np.random.default_rng(5).integers(0, lines, n).astype(np.int32)).cuda()
+    out = gs.gespmm_calibration_gather(table, idx)
+    torch.cuda.synchronize()
+    assert abs(float(out.double().sum()) - 32.0 * float(idx.double().sum())) <= 1e-6 * 32.0 * float(idx.double().sum())
+    with pytest.raises(gs.GespmmError):                       # scratch output too small
+        gs.gespmm_calibration_gather(table, idx, out=torch.empty(16, device="cuda"))
+
+
 # ------------------------------------------------------------ the workloads --
 @pytest.mark.parametrize("which", [0, 1, 2, "uniform_random_65k"])
 def test_workload_full_size_every_element(gs, which):
