@@ -107,8 +107,10 @@ def _csr(rowptr, colind, vals):
 
 
 def spmm_arg(rowptr, colind, vals, B, op, rows=None, threads=0, _lib_override=None):
-    """max / min and the position of the extreme: returns (Cref float64, arg int32); arg is the
-    index into colind/vals of the first stored entry that supplies the result, -1 for empty rows."""
+    """max / min and the position of the extreme: returns (Cref float64, arg int32); arg is the index
+    into colind/vals of the first stored entry whose product, rounded once to fp32, has the bits of
+    the result rounded once to fp32 (the position refers to the fp32 result the operator returns),
+    -1 for empty rows."""
     L = _lib_override or _load()
     rowptr, colind, vals = _csr(rowptr, colind, vals)
     B = np.ascontiguousarray(B, dtype=np.float32)

@@ -106,34 +106,48 @@ int spmm_oracle(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, const in
 }
 
 /*
- * max / min together with the position of the extreme: arg[i, j] is the index p (into
- * colind / vals) of the stored entry of row i whose product supplies C[i, j]; among
- * entries with the very same product it is the first in storage order; -1 for an empty
- * row.  This is what routes the gradient of a pooling aggregation (the GraphSAGE-pool
- * use of the SpMM-like operation, Section V-E; the operator has a gradient definition,
- * Section IV-B).  Same products, same zero rule as above.
+ * max / min together with the position of the extreme: what routes the gradient of a pooling
+ * aggregation (the GraphSAGE-pool use of the SpMM-like operation, Section V-E; the operator has
+ * a gradient definition, Section IV-B).  The paper does not say which entry wins among equals;
+ * the reading taken here refers to the fp32 result the operator returns: arg[i, j] is the index p
+ * (into colind / vals) of the FIRST stored entry of row i, in storage order, whose product
+ * vals[p] * B[colind[p], j], rounded once to fp32, has exactly the bits of C[i, j] rounded once to
+ * fp32; -1 for an empty row.  (Two entries whose exact products differ but round to the same fp32
+ * number are therefore equals, and the earlier one wins.)  The value is the same fold as above.
  */
+static int same_bits32(float x, float y) {
+  union { float f; uint32_t u; } ux, uy;
+  ux.f = x;
+  uy.f = y;
+  return ux.u == uy.u;
+}
+
 static void oracle_row_arg(int64_t i, int64_t N, const int32_t* rowptr, const int32_t* colind,
                            const float* vals, const float* B, int op, double* out_c, int32_t* out_arg) {
   const int64_t row_start = rowptr[i];
   const int64_t row_end = rowptr[i + 1];
   for (int64_t j = 0; j < N; ++j) {
-    double best = 0.0;
+    if (row_end == row_start) {
+      out_c[j] = 0.0;
+      out_arg[j] = -1;
+      continue;
+    }
+    double result = (op == OP_MAX) ? -INFINITY : INFINITY;
+    for (int64_t ptr = row_start; ptr < row_end; ++ptr) {
+      const int64_t k = colind[ptr];
+      const double a = vals ? (double)vals[ptr] : 1.0;
+      const double x = a * (double)B[k * N + j];
+      result = (op == OP_MAX) ? fold_max(result, x) : fold_min(result, x);
+    }
+    const float target = (float)result;
     int64_t where = -1;
     for (int64_t ptr = row_start; ptr < row_end; ++ptr) {
       const int64_t k = colind[ptr];
       const double a = vals ? (double)vals[ptr] : 1.0;
       const double x = a * (double)B[k * N + j];
-      int better;
-      if (where < 0) better = 1;
-      else if (op == OP_MAX) better = x > best || (x == best && signbit(best) && !signbit(x));
-      else better = x < best || (x == best && !signbit(best) && signbit(x));
-      if (better) {
-        best = x;
-        where = ptr;
-      }
+      if (where < 0 && same_bits32((float)x, target)) where = ptr;
     }
-    out_c[j] = best;
+    out_c[j] = result;
     out_arg[j] = (int32_t)where;
   }
 }

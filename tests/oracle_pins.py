@@ -285,20 +285,46 @@ PINS = (pin_brute_force_tiny, pin_dense_matmul, pin_identity, pin_all_ones_B,
 # These take the oracle module (or an object with the same functions):
 #   O.spmm, O.spmm_arg, O.spmm_transposed, O.pool_backward
 def _brute_arg(rowptr, colind, vals, B, op):
+    """Value: extreme of the exact products (Python floats), +0 above -0.  Position: the first stored entry
+    whose product, rounded once to fp32 (numpy's fp32 multiply of the two fp32 factors), has the bits of
+    the value rounded once to fp32."""
     M, N = len(rowptr) - 1, B.shape[1]
     C = np.zeros((M, N))
     arg = np.full((M, N), -1, dtype=np.int32)
+    one = np.float32(1.0)
     for i in range(M):
         for j in range(N):
-            best, where = 0.0, -1
-            for p in range(rowptr[i], rowptr[i + 1]):
-                x = (float(vals[p]) if vals is not None else 1.0) * float(B[colind[p], j])
-                key_x = (x, math.copysign(1.0, x))          # value, then +0 above -0
-                key_b = (best, math.copysign(1.0, best))
-                if where < 0 or (key_x > key_b if op == "max" else key_x < key_b):
-                    best, where = x, p
-            C[i, j], arg[i, j] = best, where
+            ps = range(rowptr[i], rowptr[i + 1])
+            if not len(ps):
+                continue
+            exact = [(float(vals[p]) if vals is not None else 1.0) * float(B[colind[p], j]) for p in ps]
+            keys = [(x, math.copysign(1.0, x)) for x in exact]
+            best = exact[keys.index(max(keys) if op == "max" else min(keys))]
+            target = np.float32(best).view(np.uint32)
+            rounded = [((vals[p] if vals is not None else one) * B[colind[p], j]).view(np.uint32) for p in ps]
+            C[i, j], arg[i, j] = best, ps[rounded.index(target)]
     return C, arg
+
+
+def pin_arg_ties_inside_one_fp32_rounding_interval(O):
+    """Two stored entries whose exact products differ by 2^-46 and round to the same fp32 number: they are
+    equals for the position (it refers to the fp32 result), so the one stored first wins, also when its
+    exact product is the smaller (max) or the larger (min) of the two."""
+    e = 2.0 ** -23
+    rp = np.array([0, 3, 3, 6], dtype=np.int32)
+    ci = np.array([0, 1, 2, 2, 1, 0], dtype=np.int32)
+    # row 0 stores (1 + 2e) * 1 first, then (1 + e) * (1 + e) = 1 + 2e + e^2, then a smaller term;
+    # row 2 stores them in the opposite order
+    B = np.array([[1.0], [1.0 + e], [0.5]], dtype=np.float32)
+    v = np.array([1.0 + 2 * e, 1.0 + e, 1.0, 1.0, 1.0 + e, 1.0 + 2 * e], dtype=np.float32)
+    assert float(v[0]) * float(B[0, 0]) < float(v[1]) * float(B[1, 0])            # exact products differ ...
+    assert v[0] * B[0, 0] == v[1] * B[1, 0]                                         # ... their fp32 roundings do not
+    c, a = O.spmm_arg(rp, ci, v, B, "max")
+    assert a[:, 0].tolist() == [0, -1, 4] and c[0, 0] == c[2, 0] == (1.0 + e) * (1.0 + e) and c[1, 0] == 0.0
+    c, a = O.spmm_arg(rp, ci, -v, B, "min")
+    assert a[:, 0].tolist() == [0, -1, 4] and c[0, 0] == -(1.0 + e) * (1.0 + e)
+    want_c, want_a = _brute_arg(rp, ci, v, B, "max")
+    assert np.array_equal(want_a, np.array([[0], [-1], [4]])) and want_c[0, 0] == (1.0 + e) * (1.0 + e)
 
 
 def pin_arg_brute_force_with_ties(O):
@@ -474,5 +500,5 @@ def pin_custom_fold(O):
                 assert got[i, j] == want
 
 
-GRAD_PINS = (pin_custom_fold, pin_csr_transpose, pin_arg_brute_force_with_ties, pin_arg_consistent_with_forward, pin_transposed_dense_and_scipy,
+GRAD_PINS = (pin_custom_fold, pin_csr_transpose, pin_arg_brute_force_with_ties, pin_arg_ties_inside_one_fp32_rounding_interval, pin_arg_consistent_with_forward, pin_transposed_dense_and_scipy,
              pin_transposed_is_the_adjoint, pin_pool_backward_numeric_gradient)

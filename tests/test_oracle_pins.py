@@ -46,10 +46,14 @@ MUTANTS = [
     ("next_row_start_as_end", "const int64_t row_end = rowptr[i + 1];",
      "const int64_t row_end = rowptr[i + 1] - (rowptr[i + 1] - rowptr[i] > 2);", 0),
     # gradient-side functions
-    ("arg_tie_goes_to_last", "better = x > best ||", "better = x >= best ||"),
-    ("arg_min_tie_goes_to_last", "else better = x < best ||", "else better = x <= best ||"),
+    ("arg_tie_goes_to_last", "if (where < 0 && same_bits32((float)x, target)) where = ptr;",
+     "if (same_bits32((float)x, target)) where = ptr;"),
+    ("arg_ties_on_exact_products", "if (where < 0 && same_bits32((float)x, target)) where = ptr;",
+     "if (where < 0 && x == result && signbit(x) == signbit(result)) where = ptr;"),
+    ("arg_value_from_the_wrong_fold", "result = (op == OP_MAX) ? fold_max(result, x) : fold_min(result, x);",
+     "result = (op == OP_MAX) ? fold_min(result, x) : fold_max(result, x);"),
     ("arg_relative_to_row", "out_arg[j] = (int32_t)where;", "out_arg[j] = (int32_t)(where < 0 ? where : where - row_start);"),
-    ("arg_zero_rule_dropped", "(x == best && signbit(best) && !signbit(x))", "0"),
+    ("arg_zero_sign_ignored", "return ux.u == uy.u;", "return x == y;"),
     ("transposed_mean_multiplies", "if (op == OP_MEAN) w /= (double)len;", "if (op == OP_MEAN) w *= (double)len;"),
     ("transposed_not_transposed", "dBref[k * N + j] += x;", "dBref[(k < M ? i % K : k) * N + j] += x;", 0),
     ("transposed_sabs_signed", "Sabs[k * N + j] += fabs(x);", "Sabs[k * N + j] += x;", 0),
