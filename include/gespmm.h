@@ -40,7 +40,10 @@ typedef enum {
   GESPMM_ERR_BAD_ARG = 1,   /* negative size, unknown op, nnz inconsistent       */
   GESPMM_ERR_NULL = 2,      /* a required pointer is NULL                         */
   GESPMM_ERR_TOO_LARGE = 3, /* M, K or nnz does not fit the 32-bit index arrays   */
-  GESPMM_ERR_HIP = 4        /* a HIP call (launch, event, copy) reported an error */
+  GESPMM_ERR_WORKSPACE = 4, /* the caller's workspace is too small or misaligned  */
+  GESPMM_ERR_HIP = 5,       /* a HIP call (launch, event, copy) reported an error */
+  GESPMM_ERR_SCRATCH_LIMIT = 6 /* beyond the built-in scratch buffer of the entry
+                                  point that allocates nothing                    */
 } gespmm_status_t;
 
 /*
@@ -158,13 +161,31 @@ int gespmm_csr_transposed(int64_t M, int64_t K, int64_t N, int64_t nnz, const in
  *   workspace  device memory of at least gespmm_csr_transpose_workspace_bytes(K) bytes,
  *   4-byte aligned, owned by the caller, contents destroyed; the library allocates nothing.
  * Errors: GESPMM_ERR_NULL (an output or the workspace is NULL), GESPMM_ERR_BAD_ARG
- * (negative size, workspace too small), GESPMM_ERR_TOO_LARGE, GESPMM_ERR_HIP.
+ * (negative size), GESPMM_ERR_WORKSPACE (workspace too small or misaligned),
+ * GESPMM_ERR_TOO_LARGE, GESPMM_ERR_HIP.
  */
 size_t gespmm_csr_transpose_workspace_bytes(int64_t K);   /* pure host function */
 int gespmm_csr_transpose(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr,
                          const int32_t* colind, const float* vals, int scale_by_row_length,
                          int32_t* rowptrT, int32_t* colindT, float* valsT, void* workspace,
                          size_t workspace_bytes, void* stream);
+
+/*
+ * gespmm_csr_transpose for callers that cannot allocate device memory or hand in a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results, ownership and errors as gespmm_csr_transpose, minus the workspace: the
+ * cursors and scan totals live in a buffer built into the library (static device memory,
+ * GESPMM_NOALLOC_TRANSPOSE_MAX_K * 4 bytes plus a few KB, held by every GPU the library runs on
+ * until the process ends).  The call allocates nothing, frees nothing and does not synchronise.
+ * K > GESPMM_NOALLOC_TRANSPOSE_MAX_K is rejected with GESPMM_ERR_SCRATCH_LIMIT before anything
+ * is launched.  All calls on one GPU share that one buffer: two calls of this function that
+ * overlap in time on the same GPU (different streams or threads) race; calls on one stream,
+ * or otherwise ordered, are fine, and so are calls on different GPUs.
+ */
+#define GESPMM_NOALLOC_TRANSPOSE_MAX_K 2097152
+int gespmm_csr_transpose_noalloc(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr,
+                                 const int32_t* colind, const float* vals, int scale_by_row_length,
+                                 int32_t* rowptrT, int32_t* colindT, float* valsT, void* stream);
 
 /*
  * The same transposed arrays by a stable radix sort on the column index instead of per-column

@@ -70,6 +70,8 @@ def lib():
         L.gespmm_csr_transpose_workspace_bytes.argtypes = [i64]
         L.gespmm_csr_transpose.restype = ci
         L.gespmm_csr_transpose.argtypes = [i64, i64, i64, vp, vp, vp, ci, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.gespmm_csr_transpose_noalloc.restype = ci
+        L.gespmm_csr_transpose_noalloc.argtypes = [i64, i64, i64, vp, vp, vp, ci, vp, vp, vp, vp]
         L.gespmm_csr_transpose_sorted_workspace_bytes.restype = ctypes.c_size_t
         L.gespmm_csr_transpose_sorted_workspace_bytes.argtypes = [i64, i64]
         L.gespmm_csr_transpose_sorted.restype = ci
@@ -246,6 +248,23 @@ def gespmm_csr_transpose(rowptr, colind, vals, K, scale_by_row_length=False, str
     _check(lib().gespmm_csr_transpose(M, K, nnz, _ptr(rowptr), _ptr(colind), _ptr(vals),
                                       int(bool(scale_by_row_length)), _ptr(rowptrT), _ptr(colindT),
                                       _ptr(valsT), _ptr(work), nbytes, _stream(stream)))
+    return rowptrT, colindT, valsT
+
+
+def gespmm_csr_transpose_noalloc(rowptr, colind, vals, K, rowptrT, colindT, valsT, scale_by_row_length=False, stream=None):
+    """gespmm_csr_transpose on the library's built-in scratch buffer: the caller passes inputs and the three
+    output arrays (int32[K+1], int32[nnz], float32[nnz]); nothing is allocated, here or in the library."""
+    import torch
+    M, nnz = rowptr.numel() - 1, colind.numel()
+    assert rowptr.is_cuda and rowptr.dtype == torch.int32 and rowptr.is_contiguous()
+    assert colind.is_cuda and colind.dtype == torch.int32 and colind.is_contiguous()
+    assert vals is None or (vals.is_cuda and vals.dtype == torch.float32 and vals.numel() == nnz)
+    assert rowptrT.is_cuda and rowptrT.dtype == torch.int32 and rowptrT.is_contiguous() and rowptrT.numel() == K + 1
+    assert colindT.is_cuda and colindT.dtype == torch.int32 and colindT.is_contiguous() and colindT.numel() == nnz
+    assert valsT.is_cuda and valsT.dtype == torch.float32 and valsT.is_contiguous() and valsT.numel() == nnz
+    _check(lib().gespmm_csr_transpose_noalloc(M, K, nnz, _ptr(rowptr), _ptr(colind), _ptr(vals),
+                                              int(bool(scale_by_row_length)), _ptr(rowptrT), _ptr(colindT),
+                                              _ptr(valsT), _stream(stream)))
     return rowptrT, colindT, valsT
 
 

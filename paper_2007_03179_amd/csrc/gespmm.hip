@@ -4,6 +4,8 @@
 #include "gespmm_kernels.hpp"
 #include "gespmm_sort.hpp"
 
+#include <mutex>
+
 using namespace gespmm_detail;
 
 extern "C" {
@@ -172,18 +174,24 @@ size_t gespmm_csr_transpose_workspace_bytes(int64_t K) {
   return (size_t)(K + tiles + 4) * sizeof(int32_t);
 }
 
-int gespmm_csr_transpose(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
-                         const float* vals, int scale_by_row_length, int32_t* rowptrT, int32_t* colindT,
-                         float* valsT, void* workspace, size_t workspace_bytes, void* stream_) {
+// Argument checks shared by the two counter-based transpose entry points (everything but the scratch memory).
+static int check_transpose_args(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+                                int32_t* rowptrT, int32_t* colindT, float* valsT) {
   if (M < 0 || K < 0 || nnz < 0) return GESPMM_ERR_BAD_ARG;
   if (M >= INT32_MAX || K >= INT32_MAX || nnz > INT32_MAX - (1 << kMaxChunkShift)) return GESPMM_ERR_TOO_LARGE;
   if (nnz > 0 && (M == 0 || K == 0)) return GESPMM_ERR_BAD_ARG;
   if (!rowptrT) return GESPMM_ERR_NULL;
   if (nnz > 0 && (!rowptr || !colind || !colindT || !valsT)) return GESPMM_ERR_NULL;
-  if (!workspace) return GESPMM_ERR_NULL;
-  if (workspace_bytes < gespmm_csr_transpose_workspace_bytes(K)) return GESPMM_ERR_BAD_ARG;
-  hipStream_t stream = (hipStream_t)stream_;
-  int32_t* cursor = static_cast<int32_t*>(workspace);          // K entries
+  return GESPMM_OK;
+}
+
+// The counter-based transpose on a scratch buffer of gespmm_csr_transpose_workspace_bytes(K) bytes
+// (cursors, then one total per scan tile).  Every word of the scratch that is read was written earlier
+// in the same call, so stale contents do no harm.
+static int transpose_with_counters(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+                                   const float* vals, int scale_by_row_length, int32_t* rowptrT, int32_t* colindT,
+                                   float* valsT, void* scratch_memory, hipStream_t stream) {
+  int32_t* cursor = static_cast<int32_t*>(scratch_memory);     // K entries
   int32_t* sums = cursor + K;                                  // one per scan tile
   const int64_t n = K + 1;
   const int64_t tiles = (n + kScanTile - 1) / kScanTile;
@@ -217,6 +225,58 @@ int gespmm_csr_transpose(int64_t M, int64_t K, int64_t nnz, const int32_t* rowpt
   return launch_chunks(L, stream);
 }
 
+int gespmm_csr_transpose(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+                         const float* vals, int scale_by_row_length, int32_t* rowptrT, int32_t* colindT,
+                         float* valsT, void* workspace, size_t workspace_bytes, void* stream_) {
+  const int st = check_transpose_args(M, K, nnz, rowptr, colind, rowptrT, colindT, valsT);
+  if (st != GESPMM_OK) return st;
+  if (!workspace) return GESPMM_ERR_NULL;
+  if (workspace_bytes < gespmm_csr_transpose_workspace_bytes(K) || ((uintptr_t)workspace & 3u) != 0) return GESPMM_ERR_WORKSPACE;
+  return transpose_with_counters(M, K, nnz, rowptr, colind, vals, scale_by_row_length, rowptrT, colindT, valsT,
+                                 workspace, (hipStream_t)stream_);
+}
+
+// ---- the entry point that allocates nothing ---------------------------------------------------
+// Scratch memory of the counter-based transpose for up to GESPMM_NOALLOC_TRANSPOSE_MAX_K columns, held
+// by every GPU the library runs on until the process ends.  In host code the array's name is only a
+// stand-in for the symbol; its device address comes from hipGetSymbolAddress, once per device.
+constexpr int64_t kNoAllocMaxK = GESPMM_NOALLOC_TRANSPOSE_MAX_K;
+constexpr size_t kNoAllocScratchBytes =
+    (size_t)(kNoAllocMaxK + (kNoAllocMaxK + 1 + kScanTile - 1) / kScanTile + 4) * sizeof(int32_t);
+static __device__ __align__(256) unsigned char scratch[(kNoAllocScratchBytes + 255) / 256 * 256];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_address[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call on that device).
+static int scratch_of_current_device(void** out) {
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return GESPMM_ERR_HIP;
+  std::lock_guard<std::mutex> hold(g_scratch_mutex);
+  if (!g_scratch_address[device]) {
+    void* address = nullptr;
+    if (hipGetSymbolAddress(&address, HIP_SYMBOL(scratch)) != hipSuccess || !address) return GESPMM_ERR_HIP;
+    g_scratch_address[device] = address;
+  }
+  *out = g_scratch_address[device];
+  return GESPMM_OK;
+}
+
+int gespmm_csr_transpose_noalloc(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+                                 const float* vals, int scale_by_row_length, int32_t* rowptrT, int32_t* colindT,
+                                 float* valsT, void* stream_) {
+  const int st = check_transpose_args(M, K, nnz, rowptr, colind, rowptrT, colindT, valsT);
+  if (st != GESPMM_OK) return st;
+  if (K > kNoAllocMaxK) return GESPMM_ERR_SCRATCH_LIMIT;
+  static_assert(sizeof(scratch) >= kNoAllocScratchBytes, "scratch array too small for the stated maximum");
+  void* memory = nullptr;
+  const int found = scratch_of_current_device(&memory);
+  if (found != GESPMM_OK) return found;
+  return transpose_with_counters(M, K, nnz, rowptr, colind, vals, scale_by_row_length, rowptrT, colindT, valsT,
+                                 memory, (hipStream_t)stream_);
+}
+
 size_t gespmm_csr_transpose_sorted_workspace_bytes(int64_t K, int64_t nnz) {
   if (K < 0 || nnz < 0) return 0;
   return make_sort_plan(K, nnz).bytes;
@@ -232,7 +292,7 @@ int gespmm_csr_transpose_sorted(int64_t M, int64_t K, int64_t nnz, const int32_t
   if (nnz > 0 && (!rowptr || !colind || !colindT || !valsT)) return GESPMM_ERR_NULL;
   if (!workspace) return GESPMM_ERR_NULL;
   const SortPlan plan = make_sort_plan(K, nnz);
-  if (workspace_bytes < plan.bytes || ((uintptr_t)workspace & 3u) != 0) return GESPMM_ERR_BAD_ARG;
+  if (workspace_bytes < plan.bytes || ((uintptr_t)workspace & 3u) != 0) return GESPMM_ERR_WORKSPACE;
   hipStream_t stream = (hipStream_t)stream_;
   if (nnz == 0) return launch_fill(reinterpret_cast<float*>(rowptrT), K + 1, 0.0f, stream);
 
@@ -406,7 +466,10 @@ const char* gespmm_status_string(int status) {
     case GESPMM_ERR_BAD_ARG: return "bad argument (negative size, unknown op, or no kernel for the forced tuning)";
     case GESPMM_ERR_NULL: return "a required pointer is NULL";
     case GESPMM_ERR_TOO_LARGE: return "M, K or nnz does not fit 32-bit indices";
+    case GESPMM_ERR_WORKSPACE: return "the workspace is too small or misaligned";
     case GESPMM_ERR_HIP: return "a HIP call failed";
+    case GESPMM_ERR_SCRATCH_LIMIT:
+      return "the problem needs more scratch memory than the built-in buffer of the no-allocation entry point holds";
     default: return "unknown status";
   }
 }

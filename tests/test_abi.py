@@ -29,7 +29,7 @@ def test_every_declared_symbol_is_exported(L):
     assert {"gespmm_csr", "gespmm_csr_simple", "gespmm_plan", "gespmm_set_tuning",
             "gespmm_profile_begin", "gespmm_profile_end", "gespmm_status_string",
             "gespmm_calibration_copy", "gespmm_calibration_gather", "gespmm_csr_arg", "gespmm_csr_transposed", "gespmm_pool_backward",
-            "gespmm_csr_transpose", "gespmm_csr_transpose_workspace_bytes",
+            "gespmm_csr_transpose", "gespmm_csr_transpose_workspace_bytes", "gespmm_csr_transpose_noalloc",
             "gespmm_csr_b16", "gespmm_plan_b16", "gespmm_csr_arg_b16", "gespmm_csr_transpose_sorted",
             "gespmm_csr_transpose_sorted_workspace_bytes", "gespmm_version"} <= set(names)
     for n in names:
@@ -101,12 +101,14 @@ def test_argument_errors_come_before_any_device_work(L):
     assert L.gespmm_pool_backward(4, 4, 0, 8, p, p, p, p, p, None) == 0
     need = gs.gespmm_csr_transpose_workspace_bytes(4)
     assert need >= 4 * 4 and gs.gespmm_csr_transpose_workspace_bytes(10**6) >= 4 * 10**6
-    assert L.gespmm_csr_transpose(4, 4, 8, p, p, p, 0, p, p, p, p, need - 1, None) == 1    # workspace too small
+    assert L.gespmm_csr_transpose(4, 4, 8, p, p, p, 0, p, p, p, p, need - 1, None) == 4    # workspace too small
     assert L.gespmm_csr_transpose(4, 4, 8, p, p, p, 0, p, p, p, None, need, None) == 2
     assert L.gespmm_csr_transpose(4, 4, 8, p, p, p, 0, None, p, p, p, need, None) == 2
     assert L.gespmm_csr_transpose(4, 4, 8, p, p, p, 0, p, None, p, p, need, None) == 2
     assert L.gespmm_csr_transpose(4, -4, 8, p, p, p, 0, p, p, p, p, need, None) == 1
     assert L.gespmm_csr_transpose(4, 2**31, 8, p, p, p, 0, p, p, p, p, 2**40, None) == 3
+    assert L.gespmm_csr_transpose_noalloc(4, 2097153, 8, p, p, p, 0, p, p, p, None) == 6    # beyond the built-in scratch
+    assert L.gespmm_csr_transpose_noalloc(4, 4, 8, p, p, p, 0, p, None, p, None) == 2
     assert L.gespmm_plan(4, 4, 4, 1, None) == 2
     assert L.gespmm_profile_end(None, None) == 1                  # not profiling
     assert L.gespmm_calibration_copy(p, p, 24, None) == 1         # not a multiple of 16
