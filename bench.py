@@ -65,20 +65,25 @@ def forward(gs):
     return gs.gespmm_csr if B_ELEM_BYTES == 4 else gs.gespmm_csr_b16
 
 
-def cpu_baseline(w, B, op, budget_s=12.0, max_passes=60):
-    """The oracle as it stands, all rows of the same workload, repeated for ~budget_s."""
+def cpu_baseline(w, B, op, C_gpu, budget_s=12.0, max_passes=60):
+    """The oracle as it stands, all rows of the same workload, repeated for ~budget_s; its result is
+    also what the output of the timed GPU run (C_gpu, a host array) is checked against, element by
+    element.  Returns (cpu_baseline, parity)."""
     import oracle
     times = []
     t_all = time.perf_counter()
     while len(times) < max_passes and (not times or time.perf_counter() - t_all < budget_s):
         t0 = time.perf_counter()
-        oracle.spmm(w.rowptr, w.colind, w.vals, B, op)
+        Cref, Sabs = oracle.spmm(w.rowptr, w.colind, w.vals, B, op)
         times.append(time.perf_counter() - t0)
     mean = sum(times) / len(times)
-    return {"value": 2.0 * w.nnz * B.shape[1] / mean / 1e9, "unit": "GFLOP/s",
-            "cores": oracle.max_threads(), "kind": "oracle",
-            "sample": f"all {w.M} rows of the same workload, {len(times)} full passes, "
-                      f"mean {mean:.3f} s per pass"}
+    ok, worst = oracle.compare(op, C_gpu, Cref, Sabs)
+    parity = {"ok": bool(ok), "elements": int(C_gpu.size), "against": "oracle, every element of the timed run's output"}
+    parity["worst_ratio" if op in ("sum", "mean") else "mismatches"] = worst
+    return ({"value": 2.0 * w.nnz * B.shape[1] / mean / 1e9, "unit": "GFLOP/s",
+             "cores": oracle.max_threads(), "kind": "oracle",
+             "sample": f"all {w.M} rows of the same workload, {len(times)} full passes, "
+                       f"mean {mean:.3f} s per pass"}, parity)
 
 
 def time_graph_replay(gs, torch, case, op, steps, calls_per_graph=20):
@@ -547,6 +552,7 @@ def main():
     op = args.op
     case = DeviceCase(w, N, torch, dev)
     r = case.time(gs, torch, op, args.steps, args.warmup)
+    C_timed = case.C.cpu().numpy()                       # what the last timed step left in C
     plan = gs.gespmm_plan_b16(w.M, N, w.nnz, args.b_dtype)
     desc = w.describe()
     achieved = r["model_GBps_kernel"]
@@ -587,7 +593,7 @@ def main():
         out["roofline"]["frac_of_measured_copy"] = achieved / copy
         out["single_call"]["cold_model_GBps"] = r["model_bytes"] / (out["single_call"]["cold_mean_ms"] * 1e-3) / 1e9
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(w, case.B_host, op)
+        out["cpu_baseline"], out["parity"] = cpu_baseline(w, case.B_host, op, C_timed)
     if sweep_rows is not None:
         out["sweep"] = [{k: row[k] for k in ("workload", "N", "op", "ms_per_step", "gflops", "model_GBps_step",
                                              "warm_min_ms", "cold_mean_ms")}
@@ -601,6 +607,9 @@ def main():
     if tile_rows is not None:
         out["tile_study"] = tile_rows
     print(json.dumps(out), flush=True)
+    if "parity" in out and not out["parity"]["ok"]:
+        print("bench.py: the timed run's output does NOT match the oracle", file=sys.stderr)
+        sys.exit(1)
 
 
 if __name__ == "__main__":

@@ -118,15 +118,9 @@ def test_workloads_at_full_size(gs, which, N, dt):
     w = graphgen.workload(which)
     say(" ", w.describe())
     dA = dev(w.rowptr), dev(w.colind), dev(w.vals)
-    rows = None
-    if w.nnz > 3_000_000:
-        lens = np.diff(w.rowptr)
-        rng = np.random.default_rng(which)
-        rows = np.unique(np.concatenate([np.argsort(lens)[-16:], np.flatnonzero(lens == 0)[:8],
-                                         rng.integers(0, w.M, size=2000), [0, w.M - 1]])).astype(np.int64)
     B = w.B(N)
-    for op in w.ops:
-        C = check(gs, w.rowptr, w.colind, w.vals, B, dt, op, rows=rows, label=w.name, dA=dA)
+    for op in w.ops:                                    # every element against the oracle
+        C = check(gs, w.rowptr, w.colind, w.vals, B, dt, op, label=w.name, dA=dA)
         assert np.isfinite(C).all()
 
 
@@ -157,13 +151,10 @@ def test_value_and_position_b16_on_a_workload(gs):
     N = 128
     Bn, Bw = narrow(w.B(N), "bf16")
     vals = graphgen.uniform_pm1(w.nnz, 98)
-    lens = np.diff(w.rowptr)
-    rows = np.unique(np.concatenate([np.argsort(lens)[-16:], np.flatnonzero(lens == 0)[:8],
-                                     np.random.default_rng(2).integers(0, w.M, 3000)])).astype(np.int64)
-    for op in ("max", "min"):
+    for op in ("max", "min"):                           # every value and position
         say(f"  case arg-b16 workload op={op}")
         C, arg = gs.gespmm_csr_arg_b16(dev(w.rowptr), dev(w.colind), dev(vals), Bn.cuda(), op)
         torch.cuda.synchronize()
-        Cref, aref = oracle.spmm_arg(w.rowptr, w.colind, vals, Bw, op, rows=rows)
-        assert np.array_equal(C.cpu().numpy()[rows].view(np.uint32), Cref.astype(np.float32).view(np.uint32))
-        assert np.array_equal(arg.cpu().numpy()[rows], aref)
+        Cref, aref = oracle.spmm_arg(w.rowptr, w.colind, vals, Bw, op)
+        assert np.array_equal(C.cpu().numpy().view(np.uint32), Cref.astype(np.float32).view(np.uint32))
+        assert np.array_equal(arg.cpu().numpy(), aref)

@@ -260,10 +260,8 @@ def test_gradient_side_on_workloads(gs, which):
     vals = graphgen.uniform_pm1(w.nnz, 98)              # signed weights: max and min both non-trivial
     dA = dev(w.rowptr), dev(w.colind), dev(vals)
     lens = np.diff(w.rowptr)
-    rows = np.unique(np.concatenate([np.argsort(lens)[-16:], np.flatnonzero(lens == 0)[:8],
-                                     np.random.default_rng(which).integers(0, w.M, 4000)])).astype(np.int64)
-    for op in ("max", "min"):
-        C, arg = check_arg(gs, w.rowptr, w.colind, vals, B, op, rows=rows, label=w.name, dA=dA)
+    for op in ("max", "min"):                           # every value and every position against the oracle
+        C, arg = check_arg(gs, w.rowptr, w.colind, vals, B, op, label=w.name, dA=dA)
         # properties at full size: the position lies in its row and reproduces the value bit for bit
         i, j = np.nonzero(arg >= 0)
         p = arg[i, j]
