@@ -31,17 +31,30 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 # HBM bytes per launch of the chunk kernel, measured with rocprofv3 --pmc (one FETCH_SIZE
 # run and one WRITE_SIZE run, each scaled by the calibration copy kernel of known size;
 # the summaries are under profiles/).  Key: "<workload>/N<width>/<op>".  Missing = null.
+# Each entry: (bytes per CALL summed over the call's main-kernel launches, the launch shape it was measured
+# with).  A run whose shape differs reports traffic null: the number would describe another kernel.
 MEASURED_TRAFFIC_BYTES = {
-    "large_dense_degree/N64/sum": 22.993e9,   # profiles/chunk_kernel_large_dense_degree_N64_sum.md
-    "general_ops/N128/sum": 1.0008e9,         # profiles/chunk_kernel_general_ops_N128_sum.md
-    "skew_narrow/N8/sum": 0.63337e9,          # profiles/chunk_kernel_skew_narrow_N8_sum.md
-    "skew_narrow/N32/sum": 1.2060e9,          # profiles/chunk_kernel_skew_narrow_N32_sum.md
-    "width_sweep/N512/sum": 0.19208e9,        # profiles/chunk_kernel_width_sweep_N512_sum.md
-    "uniform_512k_d4/N128/sum": 1.4153e9,     # profiles/chunk_kernel_uniform_512k_d4_N128_sum.md
 }
 MEASURED_TRAFFIC_BYTES_BF16 = {
-    "large_dense_degree/N64/sum": 11.680e9,   # profiles/chunk_kernel_large_dense_degree_N64_bf16_sum.md
 }
+
+
+def plan_string(plan):
+    return (f"vec={plan['vec']} G={plan['lanes_per_row']} T={plan['tiles_per_lane']} S={plan['chunk_nnz']} "
+            f"col_blocks={plan['col_blocks']} k_parts={plan['k_parts']}")
+
+
+def measured_traffic(table, key, plan):
+    """Bytes per call from the committed counter profile of this workload, or None when there is none or
+    when it was measured with another launch shape than today's plan."""
+    if key not in table:
+        return None
+    nbytes, shape = table[key]
+    if shape != plan_string(plan):
+        print(f"bench.py: the traffic profile of {key} was measured with [{shape}], today's plan is "
+              f"[{plan_string(plan)}]: traffic reported as null", file=sys.stderr)
+        return None
+    return nbytes
 
 
 B_ELEM_BYTES = 4                # 2 with --b-dtype bf16 / f16 (B stored in 16 bits; arithmetic and C stay fp32)
@@ -59,10 +72,16 @@ def compulsory_bytes(M, K, N, nnz, has_vals=True):
 
 
 B_TORCH_DTYPE = None
+B_DTYPE_NAME = "f32"
+TUNING = None                   # --tuning: per-call overrides handed to every forward call
+USE_WORKSPACE = True            # --no-workspace: never hand the forward call a workspace (no K-phased path)
 
 
 def forward(gs):
-    return gs.gespmm_csr if B_ELEM_BYTES == 4 else gs.gespmm_csr_b16
+    """The forward call as benchmarked: gespmm_csr_ex with the case's workspace and the --tuning overrides."""
+    def call(rp, ci, v, B, op, C=None, stream=None, workspace=None, profiler=None):
+        return gs.gespmm_csr_ex(rp, ci, v, B, op, C=C, workspace=workspace, tuning=TUNING, profiler=profiler, stream=stream)
+    return call
 
 
 def cpu_baseline(w, B, op, C_gpu, budget_s=12.0, max_passes=60):
@@ -94,7 +113,7 @@ def time_graph_replay(gs, torch, case, op, steps, calls_per_graph=20):
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=side):
         for _ in range(calls_per_graph):
-            forward(gs)(case.rp, case.ci, case.v, case.B, op, C=case.C)
+            forward(gs)(case.rp, case.ci, case.v, case.B, op, C=case.C, workspace=case.work)
     replays = max(1, steps // calls_per_graph)
     graph.replay()
     torch.cuda.synchronize()
@@ -119,6 +138,12 @@ class DeviceCase:
             self.B = self.B.to(B_TORCH_DTYPE)
             self.B_host = self.B.float().cpu().numpy()
         self.C = torch.empty((w.M, N), dtype=torch.float32, device=dev)
+        self.work = None                                 # workspace of the K-phased path, when the plan wants one
+        import paper_2007_03179_amd as gs
+        need = gs.gespmm_csr_workspace_bytes(w.M, w.K, N, w.nnz, B_DTYPE_NAME, tuning=TUNING) if USE_WORKSPACE else 0
+        if need:
+            self.work = torch.empty(need // 4 + 1, dtype=torch.int32, device=dev)
+        self.plan = gs.gespmm_plan_ex(w.M, w.K, N, w.nnz, B_DTYPE_NAME, workspace_bytes=need, tuning=TUNING)
 
     def time(self, gs, torch, op, steps, warmup, bracket_kernel=True):
         """Time `steps` whole calls.  With bracket_kernel the library also records a HIP event
@@ -127,21 +152,23 @@ class DeviceCase:
         only matters for microsecond-scale workloads)."""
         stream = torch.cuda.current_stream()
         for _ in range(warmup):
-            forward(gs)(self.rp, self.ci, self.v, self.B, op, C=self.C, stream=stream)
+            forward(gs)(self.rp, self.ci, self.v, self.B, op, C=self.C, stream=stream, workspace=self.work)
         torch.cuda.synchronize()
-        if bracket_kernel:
-            gs.gespmm_profile_begin(steps)
+        launches_per_call = self.plan["k_parts"]         # main-kernel launches one call makes
+        prof = gs.gespmm_profiler_create(steps * launches_per_call) if bracket_kernel else None
         t0 = time.perf_counter()
         for _ in range(steps):
-            forward(gs)(self.rp, self.ci, self.v, self.B, op, C=self.C, stream=stream)
+            forward(gs)(self.rp, self.ci, self.v, self.B, op, C=self.C, stream=stream, workspace=self.work, profiler=prof)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        main_ms_sum, launches = gs.gespmm_profile_end() if bracket_kernel else (float("nan"), 0)
+        main_ms_sum, launches = gs.gespmm_profiler_finish(prof) if bracket_kernel else (float("nan"), 0)
         w, N = self.w, self.N
         ms = (t1 - t0) * 1e3 / steps
-        main_ms = main_ms_sum / max(launches, 1)
+        launch_ms = main_ms_sum / max(launches, 1)       # average duration of one main-kernel launch
+        main_ms = launch_ms * launches_per_call          # main-kernel time of one call
         mb = model_bytes(w.M, N, w.nnz)
         return {"workload": w.name, "N": N, "op": op, "ms_per_step": ms, "main_kernel_ms": main_ms,
+                "launch_ms": launch_ms, "launches_per_call": launches_per_call,
                 "launches_timed": launches, "gflops": 2.0 * w.nnz * N / (ms * 1e-3) / 1e9,
                 "model_bytes": mb, "model_GBps_step": mb / (ms * 1e-3) / 1e9,
                 "model_GBps_kernel": mb / (main_ms * 1e-3) / 1e9,
@@ -186,7 +213,7 @@ def per_call_times(gs, torch, case, op, calls, before_each=None):
             before_each()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record(stream)
-        forward(gs)(case.rp, case.ci, case.v, case.B, op, C=case.C, stream=stream)
+        forward(gs)(case.rp, case.ci, case.v, case.B, op, C=case.C, stream=stream, workspace=case.work)
         b.record(stream)
         pairs.append((a, b))
     torch.cuda.synchronize()
@@ -360,7 +387,9 @@ def tile_study(args, gs, torch, graphgen, dev):
     cases = (("uniform_random_65k", 512), ("general_ops", 128), ("grid3d_64", 128), ("large_dense_degree", 64))
     for name, N in cases:
         w = graphgen.suite_matrix(name) if name in graphgen.SUITE_NAMES else graphgen.workload(name, args.scale)
-        case = DeviceCase(w, N, torch, dev)
+        global TUNING, USE_WORKSPACE
+        saved = TUNING, USE_WORKSPACE
+        USE_WORKSPACE = False                            # the study is about the plain kernel's shape
         auto = gs.gespmm_plan(w.M, N, w.nnz)
         steps = max(20, min(args.steps, int(2e11 / (w.nnz * N))))
         try:
@@ -368,13 +397,14 @@ def tile_study(args, gs, torch, graphgen, dev):
                 for T in (1, 2, 4):
                     if 4 * G * T > max(N, 16) * 1 or 4 * G * T < 32:      # no wider than the row, no narrower than 128 bytes
                         continue
+                    TUNING = (G, T)
                     try:
-                        gs.gespmm_set_tuning(G, T)
+                        case = DeviceCase(w, N, torch, dev)
                         case.time(gs, torch, "sum", 5, 2)
                     except gs.GespmmError:                                # this shape is not instantiated
                         continue
                     r = case.time(gs, torch, "sum", steps, 3)
-                    p = gs.gespmm_plan(w.M, N, w.nnz)
+                    p = case.plan
                     is_auto = (G, T) == (auto["lanes_per_row"], auto["tiles_per_lane"])
                     rows.append({"workload": name, "N": N, "lanes_per_row": G, "tiles_per_lane": T,
                                  "col_blocks": p["col_blocks"], "kernel_ms": r["main_kernel_ms"],
@@ -382,9 +412,9 @@ def tile_study(args, gs, torch, graphgen, dev):
                     print(f"{name:20s} N={N:4d} lanes/row {G:2d} tiles/lane {T}  column blocks {p['col_blocks']:2d}  kernel "
                           f"{r['main_kernel_ms']*1e3:9.1f} us {rows[-1]['gflops_kernel']:8.1f} GFLOP/s"
                           + ("   <- automatic" if is_auto else ""), file=sys.stderr, flush=True)
+                    del case
         finally:
-            gs.gespmm_set_tuning()
-        del case
+            TUNING, USE_WORKSPACE = saved
         torch.cuda.empty_cache()
     return rows
 
@@ -497,8 +527,10 @@ def main():
     ap.add_argument("--b-dtype", default="f32", choices=("f32", "bf16", "f16"),
                     help="storage type of the dense input B (arithmetic and C stay fp32); f32 is the paper's setting")
     ap.add_argument("--tuning", default="",
-                    help="lanes_per_row,tiles_per_lane,xcd_remap,chunk_nnz,short_len override, e.g. "
-                         "--tuning=-1,-1,0,512,16 (each -1 = automatic)")
+                    help="lanes_per_row,tiles_per_lane,xcd_remap,chunk_nnz,short_len,k_parts override, e.g. "
+                         "--tuning=-1,-1,0,512,16,8 (each -1 = automatic)")
+    ap.add_argument("--no-workspace", action="store_true",
+                    help="never hand the forward call a workspace: the K-phased path stays off")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -510,14 +542,16 @@ def main():
     import paper_2007_03179_amd as gs
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    global B_ELEM_BYTES, B_TORCH_DTYPE
+    global B_ELEM_BYTES, B_TORCH_DTYPE, B_DTYPE_NAME, TUNING, USE_WORKSPACE
     if args.b_dtype != "f32":
         B_ELEM_BYTES, B_TORCH_DTYPE = 2, {"bf16": torch.bfloat16, "f16": torch.float16}[args.b_dtype]
+        B_DTYPE_NAME = args.b_dtype
         assert not (args.gradients or args.gcn or args.tile_study or args.vendor), "--b-dtype applies to the forward call only"
     gs.lib()
     dev = torch.device("cuda:0")
     if args.tuning:
-        gs.gespmm_set_tuning(*[int(x) for x in args.tuning.split(",")])
+        TUNING = tuple(int(x) for x in args.tuning.split(","))
+    USE_WORKSPACE = not args.no_workspace
 
     if args.copy_gib > 0:
         n = int(args.copy_gib * (1 << 30)) // 16 * 4
@@ -551,11 +585,20 @@ def main():
     N = args.width or w.widths[0]
     op = args.op
     case = DeviceCase(w, N, torch, dev)
-    r = case.time(gs, torch, op, args.steps, args.warmup)
+    # the timed region: K whole calls, nothing else on the stream (this is ms_per_step and value) ...
+    clean = case.time(gs, torch, op, args.steps, args.warmup, bracket_kernel=False)
     C_timed = case.C.cpu().numpy()                       # what the last timed step left in C
-    plan = gs.gespmm_plan_b16(w.M, N, w.nnz, args.b_dtype)
+    # ... then the same K calls again with an event pair around every main-kernel launch, for the roofline
+    r = case.time(gs, torch, op, args.steps, 0)
+    r["bracketed_ms_per_step"] = r["ms_per_step"]
+    for key in ("ms_per_step", "gflops", "model_GBps_step"):
+        r[key] = clean[key]
+    plan = case.plan
     desc = w.describe()
     achieved = r["model_GBps_kernel"]
+    launches = r["launches_per_call"]
+    table = MEASURED_TRAFFIC_BYTES if args.b_dtype == "f32" else MEASURED_TRAFFIC_BYTES_BF16 if args.b_dtype == "bf16" else {}
+    traffic_call = measured_traffic(table, f"{w.name}/N{N}/{op}", plan)
     out = {
         "metric": "fp32 CSR SpMM GFLOP/s (2*nnz*N) and achieved HBM GB/s vs peak, 1 MI355X",
         "value": r["gflops"], "unit": "GFLOP/s",
@@ -566,21 +609,31 @@ def main():
         "config": {"workload": f"{w.name}: M=K={w.M}, nnz={w.nnz}, N={N}, reduce={op}, seed={w.seed}"
                                + ("" if args.b_dtype == "f32" else f", B stored as {args.b_dtype}"),
                    "csr_hash": desc["csr_hash"], "max_row": desc["max_row"],
-                   "kernel": f"chunk_kernel<FoldRows> vec={plan['vec']} G={plan['lanes_per_row']} "
-                             f"T={plan['tiles_per_lane']} S={plan['chunk_nnz']} col_blocks={plan['col_blocks']}"},
+                   "kernel": f"chunk_kernel<FoldRows> {plan_string(plan)}"
+                             + (f" (K-phased path: {launches} launches per call, workspace "
+                                f"{plan['workspace_bytes']} bytes)" if launches > 1 else "")},
         "model_GBps_whole_step": r["model_GBps_step"],
         "frac_of_hbm_peak_whole_step": r["model_GBps_step"] / HBM_PEAK_GBPS,
         "compulsory_bytes": r["compulsory_bytes"],
-        "roofline": {"bound": "hbm", "kernel": "chunk_kernel<FoldRows>", "achieved": achieved,
+        # achieved = algorithmic bytes of one launch / average duration of one launch of the dominant kernel.
+        # The byte model bills every gathered row of B as memory traffic although the caches serve most of
+        # them, so the fraction can exceed 1; frac_compulsory counts B once and is a lower bound on what
+        # must cross HBM.  What actually bounds the kernel is the rate at which L2 and fabric deliver
+        # 128-byte lines (see gather_ceiling and the design doc).
+        "roofline": {"bound": "hbm", "bound_note": "byte model; B is served from L2 / Infinity Cache, not HBM",
+                     "kernel": "chunk_kernel<FoldRows>", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": (MEASURED_TRAFFIC_BYTES if args.b_dtype == "f32" else
-                                 MEASURED_TRAFFIC_BYTES_BF16 if args.b_dtype == "bf16" else {}).get(f"{w.name}/N{N}/{op}"),
-                     "algorithmic_bytes_per_launch": r["model_bytes"],
-                     "avg_launch_ms": r["main_kernel_ms"], "launches_timed": r["launches_timed"]},
+                     "traffic": traffic_call / launches if traffic_call else None,
+                     "algorithmic_bytes_per_launch": r["model_bytes"] / launches,
+                     "avg_launch_ms": r["launch_ms"], "launches_timed": r["launches_timed"],
+                     "launches_per_call": launches,
+                     "frac_compulsory": r["compulsory_bytes"] / (r["main_kernel_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS},
     }
-    if out["roofline"]["traffic"]:
+    if traffic_call:
         # what actually crossed the L2 / fabric boundary per second (Infinity Cache hits included)
-        out["roofline"]["traffic_GBps"] = out["roofline"]["traffic"] / (r["main_kernel_ms"] * 1e-3) / 1e9
+        out["roofline"]["traffic_GBps"] = traffic_call / (r["main_kernel_ms"] * 1e-3) / 1e9
+        out["roofline"]["traffic_over_algorithmic"] = traffic_call / r["model_bytes"]
+        out["roofline"]["traffic_over_compulsory"] = traffic_call / r["compulsory_bytes"]
     if args.b_dtype == "f32" and not args.no_cold:
         # a plain gather of the same lines in the same order: the ceiling for the kernel's inner loop
         out["roofline"]["gather_ceiling"] = gather_ceiling(gs, torch, case, r["main_kernel_ms"], plan)

@@ -16,7 +16,9 @@
  * owns every buffer.  The library allocates no device memory, frees nothing,
  * and never synchronises (except gespmm_csr_simple, see below): all work is
  * enqueued on the given stream.  Inputs are only read.  C is fully overwritten
- * and need not be initialised; C must not overlap any input.
+ * and need not be initialised; C must not overlap any input.  There is no
+ * process-wide mutable state: tuning overrides and timing brackets are arguments
+ * of the call they apply to, so calls from several threads do not interact.
  *
  * Every function returns a gespmm_status_t (0 = success) unless stated.
  * Argument errors are detected on the host before any HIP call is made.
@@ -50,7 +52,7 @@ typedef enum {
  * The SpMM / SpMM-like operation (Algorithm 1; Eq. 1; Section IV-A).
  *
  *   M, K, N   matrix sizes, >= 0.  M < 2^31 - 1, K < 2^31.
- *   nnz       number of stored entries, 0 <= nnz < 2^31; must equal rowptr[M].
+ *   nnz       number of stored entries, 0 <= nnz <= 2^31 - 1025; must equal rowptr[M].
  *   rowptr    device, int32[M+1], rowptr[0] == 0, non-decreasing, rowptr[M] == nnz.
  *   colind    device, int32[nnz], 0 <= colind[p] < K, any order inside a row,
  *             repeated columns allowed (each stored entry is its own term).
@@ -216,49 +218,95 @@ int gespmm_pool_backward(int64_t M, int64_t K, int64_t N, int64_t nnz, const int
                          void* stream);
 
 /*
+ * Per-call overrides of the automatic launch shape, for tests, benchmarks and callers who know
+ * their matrix.  Every field: -1 = automatic.  lanes_per_row in {1,2,4,...,64}, tiles_per_lane
+ * in {1,2,4}, xcd_remap in {0,1}, chunk_nnz a power of two in [16, 1024], short_len in
+ * [0, 1024] (0 = every row is handled by all slots together), k_parts in [0, 64] (parts the
+ * column range is cut into by the K-phased path of gespmm_csr_ex; 0 or 1 = off).  A value that
+ * has no kernel makes the call return GESPMM_ERR_BAD_ARG.
+ */
+typedef struct {
+  int32_t lanes_per_row;
+  int32_t tiles_per_lane;
+  int32_t xcd_remap;
+  int32_t chunk_nnz;
+  int32_t short_len;
+  int32_t k_parts;
+} gespmm_tuning_t;
+
+/*
  * The kernel selection of Section IV-A ("GE-SpMM for different matrix sizes"),
- * redone for 64-lane wavefronts: pure host function, touches no device.
- * Fills the launch shape gespmm_csr would use for these sizes.
+ * redone for 64-lane wavefronts: pure host functions, they touch no device.
+ * They fill the launch shape the forward call would use for these sizes.
  */
 typedef struct {
   int32_t vec;            /* columns per lane per load: 4 (vectorised) or 1 (scalar)      */
   int32_t lanes_per_row;  /* G: lanes that cover one column block of a sparse row         */
   int32_t tiles_per_lane; /* T: column tiles each lane accumulates (row loaded once)      */
   int32_t slots;          /* 64 / G: non-zeros of a row consumed per wavefront step       */
-  int32_t chunk_nnz;      /* S: stored entries assigned to one wavefront                  */
+  int32_t chunk_nnz;      /* S: items (stored entries + row ends) assigned to one wavefront */
   int32_t col_blocks;     /* grid.y: ceil(N / (vec * G * T))                              */
-  int64_t chunks;         /* ceil(nnz / S)                                                */
-  int64_t grid_x;         /* workgroups along x of the main kernel                        */
+  int64_t chunks;         /* ceil((nnz + M) / S)                                          */
+  int64_t grid_x;         /* workgroups along x of one main-kernel launch                 */
   int32_t block_threads;  /* threads per workgroup                                        */
   int32_t xcd_remap;      /* 1: consecutive chunks are kept on one XCD                    */
   int32_t short_len;      /* row segments up to this length are handled one per slot      */
   int32_t lds_bytes;      /* dynamic LDS per workgroup                                    */
+  int32_t k_parts;        /* main-kernel launches per call: 1, or the parts of the K-phased path */
+  int32_t reserved;
+  int64_t workspace_bytes; /* workspace the K-phased path needs for this shape (0 when k_parts == 1) */
 } gespmm_plan_t;
 
 int gespmm_plan(int64_t M, int64_t N, int64_t nnz, int aligned16, gespmm_plan_t* out);
 /* The same for gespmm_csr_b16. */
 int gespmm_plan_b16(int64_t M, int64_t N, int64_t nnz, int aligned16, int b_dtype, gespmm_plan_t* out);
+/* The same for gespmm_csr_ex: K, the workspace the caller will pass and the tuning overrides count. */
+int gespmm_plan_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, int aligned16, int b_dtype,
+                   size_t workspace_bytes, const gespmm_tuning_t* tuning, gespmm_plan_t* out);
 
 /*
- * Tuning override for tests and benchmarks (process-wide, not thread-safe):
- * lanes_per_row in {1,2,4,...,64}, tiles_per_lane in {1,2,4}, xcd_remap in {0,1},
- * chunk_nnz a power of two in [16, 1024], short_len in [0, 1024] (0 = every row is
- * handled by all slots together); -1 restores the automatic choice for that field.
- * Returns GESPMM_ERR_BAD_ARG for a value that has no kernel.
+ * Timing brackets for benchmarks: an object that owns `capacity` HIP event pairs.  A forward call
+ * that is given the object records one pair around every main-kernel launch it makes, on the call's
+ * stream, while pairs are left.  gespmm_profiler_finish waits for the recorded events, returns the
+ * summed main-kernel time in milliseconds and the number of bracketed launches, and destroys the
+ * object (also on error).  One object must not be used by two threads at once.
  */
-int gespmm_set_tuning(int lanes_per_row, int tiles_per_lane, int xcd_remap, int chunk_nnz,
-                      int short_len);
+typedef struct gespmm_profiler gespmm_profiler_t;
+int gespmm_profiler_create(int capacity, gespmm_profiler_t** out);
+int gespmm_profiler_finish(gespmm_profiler_t* profiler, double* main_kernel_ms_sum, int* launches);
 
 /*
- * Per-kernel timing for the benchmark.  gespmm_profile_begin creates `capacity`
- * event pairs; while profiling is on, each gespmm_csr call brackets its main
- * kernel with one pair on the call's stream (calls beyond capacity are not
- * bracketed).  gespmm_profile_end waits for the recorded events, returns the
- * summed main-kernel time in milliseconds and the number of bracketed launches,
- * and destroys the events.  Not thread-safe.
+ * The forward operation with everything optional spelled out (Algorithm 1; Eq. 1; Sections III,
+ * IV-A): gespmm_csr / gespmm_csr_b16 are this call with no workspace, tuning or profiler.
+ *   b_dtype          element type of B (gespmm_dtype_t).
+ *   workspace        device memory, 4-byte aligned, owned by the caller, contents destroyed, or NULL.
+ *   workspace_bytes  its size.  With at least gespmm_csr_workspace_bytes(...) bytes the call may take
+ *                    the K-PHASED path: the column range [0, K) is cut into k_parts equal parts and
+ *                    the operation runs once per part, launch after launch, each launch folding into
+ *                    C; every launch then gathers from K / k_parts rows of B only, which stay in the
+ *                    L2 caches (Section III observes that the loads of B dominate; on this chip a B
+ *                    that does not fit the L2s is what bounds the kernel).  The path is chosen when B
+ *                    is several times larger than the L2s and the rows of A are long (mean >= 128
+ *                    stored entries); it pays when columns are sorted inside the rows, as CSR builders
+ *                    produce them, and is correct for any order.  No state survives the call: the
+ *                    workspace is rebuilt every time (about 0.1 ms for 10^8 entries).
+ *   tuning           overrides or NULL.  k_parts >= 2 forces the phased path (GESPMM_ERR_WORKSPACE if
+ *                    the workspace is NULL or too small), 0 or 1 forbids it.
+ *   profiler         timing brackets or NULL.
+ * Everything else, including accuracy and errors, as gespmm_csr; sum and mean add one rounding per
+ * part to every output.
  */
-int gespmm_profile_begin(int capacity);
-int gespmm_profile_end(double* main_kernel_ms_sum, int* launches);
+size_t gespmm_csr_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t nnz, int b_dtype,
+                                  const gespmm_tuning_t* tuning);   /* pure host function */
+int gespmm_csr_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                  const int32_t* colind, const float* vals, const void* B, int b_dtype, float* C, int op,
+                  void* workspace, size_t workspace_bytes, const gespmm_tuning_t* tuning,
+                  gespmm_profiler_t* profiler, void* stream);
+
+/* gespmm_csr_arg_b16 with tuning overrides (NULL = automatic; k_parts is ignored). */
+int gespmm_csr_arg_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                      const int32_t* colind, const float* vals, const void* B, int b_dtype, float* C,
+                      int32_t* arg, int op, const gespmm_tuning_t* tuning, void* stream);
 
 /*
  * Measurement helper, not part of the method: copies `bytes` (a multiple of 16, both

@@ -17,8 +17,9 @@
 // element, and step(acc, a, b) == merge(acc, step(identity(), a, b)).  Arguments, layout,
 // ownership and error codes are those of gespmm_csr (include/gespmm.h); an empty row yields 0;
 // rows that are split across wavefronts are combined with a compare-and-swap loop around merge.
-// Compile with hipcc --offload-arch=gfx950 and the include paths of this repository's
-// `include/` and `paper_2007_03179_amd/csrc/` directories.
+// A last argument `const gespmm_tuning_t* tuning` (default NULL = automatic) overrides the launch shape
+// for this call, as in gespmm_csr_ex.  Compile with hipcc --offload-arch=gfx950 -I <this directory>:
+// everything needed (this file, gespmm_kernels.hpp, gespmm.h) lies here.
 #pragma once
 
 #include "gespmm_kernels.hpp"

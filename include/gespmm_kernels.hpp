@@ -1,16 +1,21 @@
 // CSR SpMM / SpMM-like kernels for gfx950 (MI355X): device code and launch helpers.
-// (The C ABI over them is in gespmm.hip; user-defined reduce operations include this
-// file through include/gespmm_custom.hpp.)
+// (The C ABI over them is in paper_2007_03179_amd/csrc/gespmm.hip; user-defined reduce
+// operations include this file through gespmm_custom.hpp, which is why it lives beside
+// the public headers.)
 //
 // Result computed (paper: Algorithm 1, Section III-A; general reduce: Eq. 1, Section IV-A):
 //     C[i, j] = reduce_p  vals[p] * B[colind[p], j],   p over the stored entries of row i.
 //
 // How the work is laid out (what is kept from the paper and what is not):
 //  * The paper gives one thread block to each sparse row (Algorithms 2 and 3).  Here the
-//    unit of work is a CHUNK of S consecutive stored entries, one per 64-lane wavefront,
-//    so every wavefront has the same amount of gather work whatever the row lengths are.
-//    A row that crosses a chunk border is finished with atomics (add, or integer
-//    max/min on the ordered bit pattern of the float); rows inside one chunk are
+//    unit of work is a CHUNK of S consecutive ITEMS, one per 64-lane wavefront, where the
+//    items are the stored entries and the row ends merged into one sequence: row r
+//    contributes its entries and then one row-end item, so entry p of row r is item p + r.
+//    A wavefront therefore never has more than S entries to gather NOR more than S rows to
+//    walk, whatever the row lengths are (a stretch of thousands of empty or one-entry rows
+//    is spread over many wavefronts instead of trailing behind one).
+//    A row whose entries fall into more than one chunk is finished with atomics (add, or
+//    integer max/min on the ordered bit pattern of the float); rows inside one chunk are
 //    written with plain stores by exactly one wavefront.
 //  * Kept from Coalesced Row Caching (Section III-B): a wavefront first pulls its chunk
 //    of (colind, val) with fully coalesced loads into LDS, then every lane reads the
@@ -44,6 +49,7 @@ constexpr int kBlock = kWave * kWavesPerBlock;
 constexpr int kMinChunkShift = 4;               // chunks hold 16 .. 1024 stored entries
 constexpr int kMaxChunkShift = 10;
 constexpr int kXcds = 8;
+constexpr int kMaxParts = 64;                     // most parts the K-phased path cuts the column range into
 // 16-byte gathers a lane issues before it waits (measured: 8 beats 4 and 16 for slots of
 // up to 16 lanes; wider slots already move 512 B and more per load instruction)
 constexpr int loads_in_flight(int G) { return G <= 16 ? 8 : 4; }
@@ -60,7 +66,8 @@ struct KernelArgs {
   int32_t xcd_remap;
   int32_t chunk_shift;    // log2(S), S = stored entries per wavefront
   int32_t short_len;      // row segments up to this length are handled one per slot
-  const int32_t* rowptr;
+  const int32_t* rowptr;  // row starts; in a phase of the K-phased path: the phase's virtual row starts
+  const int32_t* delta;   // K-phased path: stored position = virtual position + delta[row]; otherwise nullptr
   const int32_t* colind;
   const float* vals;
   const float* B;         // dense input (the gradient dC for the transposed job)
@@ -70,7 +77,16 @@ struct KernelArgs {
   int32_t* cursor;        // next free place of every transposed row (structure-transpose job)
   int32_t only_split;     // position job: rows inside one chunk were already done by the fused pass
   int32_t packed_split;   // fused value+position pass: split rows collect (value, position) pairs in 64-bit slots
+  int32_t accumulate;     // K-phased path: fold the row's result into what C already holds
+  int32_t taper_chunks;   // K-phased path: this many chunks at the end of a launch hold S / 4 items only
 };
+
+// Entry p of row r is item p + r of the merged sequence of entries and row ends; chunk c owns the
+// items [c * S, (c + 1) * S).  A non-empty row [s, e) is shared by several chunks exactly when its
+// first and its last entry are owned by different chunks.
+__device__ __forceinline__ bool row_is_shared(int s, int e, int64_t r, int chunk_shift) {
+  return (((int64_t)s + r) >> chunk_shift) != (((int64_t)e - 1 + r) >> chunk_shift);
+}
 
 // ------------------------------------------------------------------ vectors --
 template <int V> struct Vec;
@@ -134,6 +150,9 @@ template <> struct BLoad<1, f16_t> {
   __device__ static void unpack(const Raw& r, float (&o)[1]) { o[0] = (float)__builtin_bit_cast(_Float16, r); }
 };
 
+// Zeros: what the sum's gathers read for entries that do not exist.
+__device__ float4 kZeroLine[4] = {};      // never written (not const: a const array would live in another address space than B)
+
 template <int F> __device__ __forceinline__ float fold_identity() {
   return F == kAdd ? 0.0f : (F == kMax ? -__builtin_inff() : __builtin_inff());
 }
@@ -180,6 +199,8 @@ __device__ __forceinline__ int64_t logical_block(int64_t b, int64_t nb, int rema
 // empty rows get `empty_value` (0 for the result, the bits of -1 for positions); rows whose
 // entries lie in more than one chunk get `split_value` (the reduce identity, or the bits
 // of INT_MAX for positions): they are completed by atomics in the chunk kernel.
+// chunk_shift < 0: every non-empty row gets `split_value` (the K-phased path, whose phases
+// all fold into what C holds).
 template <int V>
 __global__ void __launch_bounds__(kBlock) init_rows(int32_t M, int32_t N, const int32_t* __restrict__ rowptr,
                                                    float* __restrict__ C, float empty_value, float split_value,
@@ -192,7 +213,7 @@ __global__ void __launch_bounds__(kBlock) init_rows(int32_t M, int32_t N, const 
   if (r < M) {
     const int s = rowptr[r], e = rowptr[r + 1];
     if (s == e) flag = 1;
-    else if ((s >> chunk_shift) != ((e - 1) >> chunk_shift)) flag = 2;
+    else if (chunk_shift < 0 || row_is_shared(s, e, r, chunk_shift)) flag = 2;
   }
   const unsigned long long todo = __ballot(flag != 0);
   if (todo == 0ull) return;
@@ -285,15 +306,17 @@ struct FoldRows {
       for (int x = 0; x < V; ++x) s.acc[t].v[x] = fold_identity<F>();
   }
 
-  // An entry that does not exist re-reads the last one that does: harmless for max/min
-  // (idempotent) and given weight 0 for the sum, so the pass is straight-line code with
-  // all gathers issued before the first use.
+  // All gathers of a pass are issued before the first use, in straight-line code.  An entry that
+  // does not exist: max / min re-read the last one that does (idempotent, whatever the values
+  // are); the sum reads a line of zeros instead of B and gives it weight 0, so that a non-finite
+  // element of B reaches exactly the rows that store an entry for it, as in Algorithm 1.
   template <int U>
   __device__ static void pass(State& s, const KernelArgs& a, const int2* ka, int, int first, int stride, int left,
                               const int (&)[T], const int (&colc)[T]) {
     using Load = BLoad<V, BT>;
     int2 e2[U];
     typename Load::Raw b[U][T];
+    const BT* nothing = reinterpret_cast<const BT*>(kZeroLine);      // the same 16 bytes for every lane: a uniform address
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int uu = u < left ? u : (left > 0 ? left - 1 : 0);
@@ -304,7 +327,7 @@ struct FoldRows {
     for (int u = 0; u < U; ++u) {
       const BT* brow = reinterpret_cast<const BT*>(a.B) + (int64_t)e2[u].x * a.N;
 #pragma unroll
-      for (int t = 0; t < T; ++t) b[u][t] = Load::load(brow + colc[t]);
+      for (int t = 0; t < T; ++t) b[u][t] = Load::load(F == kAdd && u >= left ? nothing : brow + colc[t]);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
@@ -328,7 +351,9 @@ struct FoldRows {
   }
 
   // Plain store when the whole row lay in this chunk, atomics otherwise (the row was
-  // preset to the identity by init_rows).
+  // preset to the identity by init_rows).  In a phase of the K-phased path the row's part
+  // of this phase is folded into what the earlier phases left in C: by this wavefront
+  // alone when the part lay in one chunk (nobody else touches the row during the launch).
   __device__ static void end(State& s, const KernelArgs& a, int64_t row, bool whole, int row_len, const int (&col)[T]) {
     float* crow = a.C + row * (int64_t)a.N;
     const float len = (float)row_len;
@@ -336,7 +361,11 @@ struct FoldRows {
     for (int t = 0; t < T; ++t) {
       if (col[t] < a.N) {
         if (whole) {
-          if (a.is_mean) {
+          if (a.accumulate) {
+            const Vec<V> before = Vec<V>::load(crow + col[t]);
+#pragma unroll
+            for (int x = 0; x < V; ++x) s.acc[t].v[x] = fold2<F>(before.v[x], s.acc[t].v[x]);
+          } else if (a.is_mean) {
 #pragma unroll
             for (int x = 0; x < V; ++x) s.acc[t].v[x] = s.acc[t].v[x] / len;
           }
@@ -510,7 +539,7 @@ __global__ void __launch_bounds__(kBlock) finish_split_rows(int32_t M, int32_t N
   bool split = false;
   if (r < M) {
     const int s = rowptr[r], e = rowptr[r + 1];
-    split = e > s && (s >> chunk_shift) != ((e - 1) >> chunk_shift);
+    split = e > s && row_is_shared(s, e, r, chunk_shift);
   }
   unsigned long long todo = __ballot(split);
   const int half = N >> 1;
@@ -822,80 +851,26 @@ template <class P> struct FlightDivisor { static constexpr int value = 1; };
 template <int F, int V, int T, class BT> struct FlightDivisor<FoldArgRows<F, V, T, BT>> { static constexpr int value = 2; };
 
 // P: row policy; V: floats per lane per load; G: lanes per slot; T: column tiles per lane.
-template <class P, int V, int G, int T>
+// kPhased: the kernel runs one phase of the K-phased path (see launch_phased): `rowptr` holds the
+// phase's virtual row starts (consecutive numbers for the entries the phase owns, row after row),
+// `delta[r]` turns a virtual position of row r into the stored position, the number of chunks is
+// read from the device, a wavefront takes chunks c, c + (wavefronts launched), ... and the result
+// of a row is folded into C.
+template <class P, int V, int G, int T, bool kPhased>
 __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
   constexpr int NS = kWave / G;                 // slots
   constexpr int kFlight = loads_in_flight(G) / FlightDivisor<P>::value;
   constexpr int U = kFlight / T > 0 ? kFlight / T : 1;   // entries per lane per pass
-  extern __shared__ int2 s_dyn[];               // per wavefront: S entries (colind, val) + 64 row descriptors
+  extern __shared__ int2 s_dyn[];               // per wavefront: S entries (colind, val) + 64 row descriptors (+ 64 row records)
 
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x >> 6;
   const int slot = lane / G;
   const int g = lane % G;
   const int S = 1 << a.chunk_shift;
-
-  const int64_t chunk = logical_block(blockIdx.x, a.chunk_blocks, a.xcd_remap) * kWavesPerBlock + wave;
-  if (chunk >= a.chunks) return;                // whole wavefront leaves; no block barrier is used
-  const int cs = (int)(chunk << a.chunk_shift); // first stored entry of this chunk (< 2^31)
-  const int cnt = (a.nnz - cs) < S ? (a.nnz - cs) : S;
-  const int ce = cs + cnt;
-  int2* ka = s_dyn + wave * (S + kWave);
+  int2* ka = s_dyn + wave * (S + (kPhased ? 2 : 1) * kWave);
   int2* short_rows = ka + S;
-
-  // (1) coalesced load of the chunk's (colind, val) into this wavefront's LDS slice, in groups
-  //     of four loads per array (indices past the end repeat the last entry; those copies
-  //     are never consumed).  The first group is issued before the row search below and
-  //     written to LDS after it, so its latency overlaps the search's.
-  auto load_group = [&](int u0, int (&k)[4], float (&v)[4]) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int idx = u0 + u * kWave + lane;
-      k[u] = a.colind[cs + (idx < cnt ? idx : cnt - 1)];
-    }
-    if (a.vals) {
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int idx = u0 + u * kWave + lane;
-        v[u] = a.vals[cs + (idx < cnt ? idx : cnt - 1)];
-      }
-    } else {
-#pragma unroll
-      for (int u = 0; u < 4; ++u) v[u] = 1.0f;
-    }
-  };
-  auto store_group = [&](int u0, const int (&k)[4], const float (&v)[4]) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int idx = u0 + u * kWave + lane;
-      if (idx < S) ka[idx] = make_int2(k[u], __float_as_int(v[u]));
-    }
-  };
-  int k0[4];
-  float v0[4];
-  load_group(0, k0, v0);
-
-  // (2) first row of the chunk: the last r with rowptr[r] <= cs, found by a 64-way search
-  int lo = 0, hi = a.M;                          // rowptr[lo] <= cs < rowptr[hi]
-  while (hi - lo > 1) {
-    const int64_t step = ((int64_t)(hi - lo) + kWave - 1) / kWave;
-    int64_t probe = lo + (int64_t)(lane + 1) * step;
-    if (probe > hi) probe = hi;
-    const int below = __builtin_popcountll(__ballot(a.rowptr[probe] <= cs));   // probes are monotone
-    const int64_t nlo = lo + below * step;       // below <= 63 because rowptr[hi] > cs
-    int64_t nhi = nlo + step;
-    if (nhi > hi) nhi = hi;
-    lo = (int)nlo;
-    hi = (int)nhi;
-  }
-
-  store_group(0, k0, v0);
-  for (int u0 = 4 * kWave; u0 < cnt; u0 += 4 * kWave) {
-    int k[4];
-    float v[4];
-    load_group(u0, k, v);
-    store_group(u0, k, v);
-  }
+  int2* row_info = short_rows + kWave;          // kPhased only: (row start relative to the chunk's first entry, delta)
 
   // column tiles of this lane (loads use a clamped column so they are never masked)
   const int colbase = blockIdx.y * (V * G * T);
@@ -907,77 +882,202 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
     colc[t] = col[t] < a.N ? col[t] : a.N - V;
   }
 
-  wave_lds_fence();
+  // Items are numbered from `first_item`; a phase's entries carry the numbers rowptr[0] .. rowptr[M].
+  const int64_t first_item = kPhased ? (int64_t)a.rowptr[0] : 0;
+  const int64_t end_entry = kPhased ? (int64_t)a.rowptr[a.M] : (int64_t)a.nnz;
+  const int64_t end_item = end_entry + a.M;
+  // A phase ends with chunks of S / 4 items (at most a quarter of its items): the wavefronts that are
+  // dispatched last finish four times sooner, which shortens the time the launch spends draining.
+  const int small_shift = a.chunk_shift - 2;
+  int64_t small_items = kPhased ? (int64_t)a.taper_chunks << small_shift : 0;
+  if (small_items > (end_item - first_item) >> 2) small_items = (end_item - first_item) >> 2;
+  const int64_t big_chunks = kPhased ? (end_item - first_item - small_items) >> a.chunk_shift : 0;   // chunks of S items
+  const int64_t first_small_item = first_item + (big_chunks << a.chunk_shift);
+  const int64_t nchunks = kPhased ? big_chunks + ((end_item - first_small_item + (S >> 2) - 1) >> small_shift) : a.chunks;
+  const int64_t wave_stride = a.chunk_blocks * kWavesPerBlock;
 
-  // (3) walk the rows that have entries in [cs, ce), 64 row bounds at a time (lane <-> row)
-  for (int64_t rbase = lo;; rbase += kWave) {
-    int64_t rr = rbase + lane;
-    if (rr > a.M) rr = a.M;
-    const int my_s = a.rowptr[rr];
-    const int my_e = a.rowptr[rr < a.M ? rr + 1 : a.M];
-    const bool my_whole = my_s >= cs && my_e <= ce;
-    const bool valid = rbase + lane < a.M && my_e > my_s && my_s < ce &&
-                       !(P::kCanSkipWholeRows && a.only_split && my_whole);
-    const int my_ps = (my_s > cs ? my_s : cs) - cs;     // the row's segment inside the chunk,
-    const int my_pe = (my_e < ce ? my_e : ce) - cs;     // as offsets into the LDS slice
-    const bool is_short = NS > 1 && valid && (my_pe - my_ps) <= a.short_len;
+  for (int64_t chunk = logical_block(blockIdx.x, a.chunk_blocks, a.xcd_remap) * kWavesPerBlock + wave; chunk < nchunks;
+       chunk += wave_stride) {
+    const bool small = kPhased && chunk >= big_chunks;
+    const int64_t d0 = small ? first_small_item + ((chunk - big_chunks) << small_shift)
+                             : first_item + (chunk << a.chunk_shift);    // items [d0, d1) are this chunk's
+    const int64_t span = small ? S >> 2 : S;
+    const int64_t d1 = d0 + span < end_item ? d0 + span : end_item;
 
-    // (3a) short segments: one per slot, 64/G rows at a time, no cross-lane exchange
-    if (NS > 1) {
-      const unsigned long long smask = __ballot(is_short);
-      const int nshort = __builtin_popcountll(smask);
-      if (nshort > 0) {
-        const int rank = __builtin_amdgcn_mbcnt_hi((unsigned)(smask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)smask, 0u));
-        if (is_short)   // lane | offset << 6 | length << 18 | whole << 30 ; full row length
-          short_rows[rank] = make_int2(lane | (my_ps << 6) | ((my_pe - my_ps) << 18) | ((int)my_whole << 30), my_e - my_s);
-        wave_lds_fence();
-        for (int t0 = 0; t0 < nshort; t0 += NS) {
-          const bool have = t0 + slot < nshort;
-          const int2 d = short_rows[have ? t0 + slot : nshort - 1];   // an idle slot shadows the last row
-          const int r_ps = (d.x >> 6) & 4095;
-          const int r_len = have ? (d.x >> 18) & 4095 : 0;
-          const int64_t row = rbase + (d.x & 63);
-          typename P::State st;
-          P::begin(st, a, row, d.y, colc);
-          // U entries per step; a last step with at most U / 2 entries left in every slot takes
-          // the half-size pass (fewer padded gathers: up to 7 % on matrices of short rows)
-          for (int it = 0; __ballot(it < r_len) != 0ull;) {
-            if (U >= 4 && __ballot(r_len - it > U / 2) == 0ull) {
-              P::template pass<(U >= 4 ? U / 2 : U)>(st, a, ka, cs, r_ps + (it < r_len ? it : 0), 1, r_len - it, col, colc);
-              it += U / 2;
-            } else {
-              P::template pass<U>(st, a, ka, cs, r_ps + (it < r_len ? it : 0), 1, r_len - it, col, colc);
-              it += U;
+    // (1) first row of the chunk: the last r with rowptr[r] + r <= d0 (that function of r is strictly
+    //     increasing), found by a 64-way search
+    int lo = 0, hi = a.M;                          // rowptr[lo] + lo <= d0 < rowptr[hi] + hi
+    while (hi - lo > 1) {
+      const int64_t step = ((int64_t)(hi - lo) + kWave - 1) / kWave;
+      int64_t probe = lo + (int64_t)(lane + 1) * step;
+      if (probe > hi) probe = hi;
+      const int below = __builtin_popcountll(__ballot((int64_t)a.rowptr[probe] + probe <= d0));   // probes are monotone
+      const int64_t nlo = lo + below * step;       // below <= 63 because the item of row `hi` lies beyond d0
+      int64_t nhi = nlo + step;
+      if (nhi > hi) nhi = hi;
+      lo = (int)nlo;
+      hi = (int)nhi;
+    }
+    const int64_t r0 = lo;
+    const int cs = (int)(d0 - r0);                 // first entry the chunk can own (rowptr[r0] <= cs <= rowptr[r0 + 1])
+    const int cnt = (int)(end_entry - cs < S ? end_entry - cs : S);   // entries [cs, cs + cnt) cover everything it owns
+    if (cnt <= 0) {                                // only the ends of trailing empty rows: nothing to compute
+      if (!kPhased) break;
+      continue;
+    }
+
+    // row bounds, 64 rows at a time (lane <-> row); the next batch is requested before the current one is worked on
+    auto load_bounds = [&](int64_t rbase, int& s, int& e, int& dl) {
+      int64_t rr = rbase + lane;
+      if (rr > a.M) rr = a.M;
+      s = a.rowptr[rr];
+      e = a.rowptr[rr < a.M ? rr + 1 : a.M];
+      if (kPhased) dl = a.delta[rr < a.M ? rr : a.M - 1];
+    };
+    int next_s, next_e, next_delta = 0;
+    load_bounds(r0, next_s, next_e, next_delta);
+
+    // (2) plain path: coalesced load of the entries [cs, cs + cnt) into this wavefront's LDS slice, in
+    //     groups of four loads per array (indices past the end repeat the last entry; those copies are
+    //     never consumed).  The K-phased path stages its entries batch by batch below.
+    if (!kPhased) {
+      for (int u0 = 0; u0 < cnt; u0 += 4 * kWave) {
+        int k[4];
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int idx = u0 + u * kWave + lane;
+          k[u] = a.colind[cs + (idx < cnt ? idx : cnt - 1)];
+        }
+        if (a.vals) {
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int idx = u0 + u * kWave + lane;
+            v[u] = a.vals[cs + (idx < cnt ? idx : cnt - 1)];
+          }
+        } else {
+#pragma unroll
+          for (int u = 0; u < 4; ++u) v[u] = 1.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int idx = u0 + u * kWave + lane;
+          if (idx < S) ka[idx] = make_int2(k[u], __float_as_int(v[u]));
+        }
+      }
+      wave_lds_fence();
+    }
+
+    // (3) walk the rows that have entries among the chunk's items
+    for (int64_t rbase = r0;; rbase += kWave) {
+      const int my_s = next_s, my_e = next_e, my_delta = next_delta;
+      // another batch follows if its first row still starts inside the chunk
+      const bool more = rbase + kWave < a.M && (int64_t)__builtin_amdgcn_readlane(my_e, kWave - 1) + rbase + kWave < d1;
+      if (more) load_bounds(rbase + kWave, next_s, next_e, next_delta);
+
+      const int64_t rr = rbase + lane;
+      const int64_t limit = d1 - rr;                       // the chunk owns the row's entries below this number ...
+      const int own_s = my_s > cs ? my_s : cs;             // ... and from this one on
+      const int own_e = (int64_t)my_e <= limit ? my_e : (limit > own_s ? (int)limit : own_s);
+      const bool my_whole = own_s == my_s && own_e == my_e;
+      const bool valid = rr < a.M && own_e > own_s && !(P::kCanSkipWholeRows && a.only_split && my_whole);
+      const int my_ps = own_s - cs;                        // the row's segment inside the chunk,
+      const int my_pe = own_e - cs;                        // as offsets into the LDS slice
+      const bool is_short = NS > 1 && valid && (my_pe - my_ps) <= a.short_len;
+
+      if (kPhased) {
+        // stage the entries of this batch's segments: they are consecutive virtual positions [bs, be);
+        // a lane finds the row of its position by a search over the batch's row starts, then reads
+        // the stored entry at position + delta[row]
+        const unsigned long long vmask = __ballot(valid);
+        if (vmask) {
+          const int bs = __builtin_amdgcn_readlane(my_ps, __builtin_ctzll(vmask));
+          const int be = __builtin_amdgcn_readlane(my_pe, 63 - __builtin_clzll(vmask));
+          row_info[lane] = make_int2(rr < a.M ? my_s - cs : INT32_MAX, my_delta);
+          wave_lds_fence();
+          for (int x0 = bs; x0 < be; x0 += 4 * kWave) {
+            int k[4];
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              const int x = x0 + u * kWave + lane;
+              const int xc = x < be ? x : be - 1;
+              int pos = 0;                                 // last row of the batch that starts at or before xc
+#pragma unroll
+              for (int step = kWave / 2; step > 0; step >>= 1)
+                if (row_info[pos + step].x <= xc) pos += step;
+              const int p = xc + cs + row_info[pos].y;
+              k[u] = a.colind[p];
+              v[u] = a.vals ? a.vals[p] : 1.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              const int x = x0 + u * kWave + lane;
+              if (x < be) ka[x] = make_int2(k[u], __float_as_int(v[u]));
             }
           }
-          if (have) P::end(st, a, row, (d.x >> 30) & 1, d.y, col);
+          wave_lds_fence();
         }
-        wave_lds_fence();
       }
-    }
 
-    // (3b) long segments: all slots work on one row, slot s takes entries s, s+NS, ...
-    unsigned long long todo = __ballot(valid && !is_short);
-    while (todo) {
-      const int i = __builtin_ctzll(todo);
-      todo &= todo - 1;
-      const int ps = __builtin_amdgcn_readlane(my_ps, i);
-      const int pe = __builtin_amdgcn_readlane(my_pe, i);
-      const int s = __builtin_amdgcn_readlane(my_s, i);
-      const int e = __builtin_amdgcn_readlane(my_e, i);
-      typename P::State st;
-      P::begin(st, a, rbase + i, e - s, colc);
-      for (int base = ps; base < pe; base += U * NS) {
-        const int first = base + slot;
-        const int left = (pe - first + NS - 1) / NS;       // entries first, first+NS, ... below pe
-        P::template pass<U>(st, a, ka, cs, left > 0 ? first : pe - 1, NS, left, col, colc);
+      // (3a) short segments: one per slot, 64/G rows at a time, no cross-lane exchange
+      if (NS > 1) {
+        const unsigned long long smask = __ballot(is_short);
+        const int nshort = __builtin_popcountll(smask);
+        if (nshort > 0) {
+          const int rank = __builtin_amdgcn_mbcnt_hi((unsigned)(smask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)smask, 0u));
+          if (is_short)   // lane | offset << 6 | length << 18 | whole << 30 ; full row length
+            short_rows[rank] = make_int2(lane | (my_ps << 6) | ((my_pe - my_ps) << 18) | ((int)my_whole << 30), my_e - my_s);
+          wave_lds_fence();
+          for (int t0 = 0; t0 < nshort; t0 += NS) {
+            const bool have = t0 + slot < nshort;
+            const int2 d = short_rows[have ? t0 + slot : nshort - 1];   // an idle slot shadows the last row
+            const int r_ps = (d.x >> 6) & 4095;
+            const int r_len = have ? (d.x >> 18) & 4095 : 0;
+            const int64_t row = rbase + (d.x & 63);
+            typename P::State st;
+            P::begin(st, a, row, d.y, colc);
+            // U entries per step; a last step with at most U / 2 entries left in every slot takes
+            // the half-size pass (fewer padded gathers: up to 7 % on matrices of short rows)
+            for (int it = 0; __ballot(it < r_len) != 0ull;) {
+              if (U >= 4 && __ballot(r_len - it > U / 2) == 0ull) {
+                P::template pass<(U >= 4 ? U / 2 : U)>(st, a, ka, cs, r_ps + (it < r_len ? it : 0), 1, r_len - it, col, colc);
+                it += U / 2;
+              } else {
+                P::template pass<U>(st, a, ka, cs, r_ps + (it < r_len ? it : 0), 1, r_len - it, col, colc);
+                it += U;
+              }
+            }
+            if (have) P::end(st, a, row, (d.x >> 30) & 1, d.y, col);
+          }
+          wave_lds_fence();
+        }
       }
-      P::template combine<G>(st);
-      if (slot == 0) P::end(st, a, rbase + i, s >= cs && e <= ce, e - s, col);
+
+      // (3b) long segments: all slots work on one row, slot s takes entries s, s+NS, ...
+      unsigned long long todo = __ballot(valid && !is_short);
+      while (todo) {
+        const int i = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        const int ps = __builtin_amdgcn_readlane(my_ps, i);
+        const int pe = __builtin_amdgcn_readlane(my_pe, i);
+        const int s = __builtin_amdgcn_readlane(my_s, i);
+        const int e = __builtin_amdgcn_readlane(my_e, i);
+        const bool whole = __builtin_amdgcn_readlane((int)my_whole, i) != 0;
+        typename P::State st;
+        P::begin(st, a, rbase + i, e - s, colc);
+        for (int base = ps; base < pe; base += U * NS) {
+          const int first = base + slot;
+          const int left = (pe - first + NS - 1) / NS;       // entries first, first+NS, ... below pe
+          P::template pass<U>(st, a, ka, cs, left > 0 ? first : pe - 1, NS, left, col, colc);
+        }
+        P::template combine<G>(st);
+        if (slot == 0) P::end(st, a, rbase + i, whole, e - s, col);
+      }
+      if (!more) break;
     }
-    // the next batch of rows is needed only if it still starts inside the chunk
-    const int next_start = __builtin_amdgcn_readlane(my_e, kWave - 1);
-    if (rbase + kWave >= a.M || next_start >= ce) break;
+    if (!kPhased) break;
+    wave_lds_fence();                              // the LDS slice is reused by the next chunk
   }
 }
 
@@ -1084,6 +1184,73 @@ static __global__ void __launch_bounds__(kBlock) add_tile_offsets(int32_t* __res
   }
 }
 
+// ----------------------------------------------- kernels of the K-phased path --
+// The K-phased path (launch_phased) cuts the column range [0, K) into Q equal parts and runs the
+// whole operation once per part, one launch after the other, so that at any time the gathers touch
+// only K / Q rows of B.  For that every row is cut into Q consecutive pieces: piece q of row r
+// starts at the first stored position of the row whose column is >= q * cols_per_part.  With
+// columns sorted inside the rows (what CSR builders produce) piece q holds exactly the entries of
+// part q; with any other order the pieces still partition the row, so the result is the same and
+// only the locality is lost.
+//   piece_start[q * M + r]        = that stored position
+//   piece_len[q * (M + 1) + r]    = length of the piece (entry M of every part is 0), which an
+//                                    exclusive scan over all Q * (M + 1) numbers turns into the
+//                                    virtual row starts of part q
+// Lanes that sit side by side search the SAME row for consecutive parts (their probes fall into the
+// same few cache lines); a wavefront takes 64 / lanes_per_row rows, lanes_per_row = Q rounded up to a
+// power of two.
+static __global__ void __launch_bounds__(kBlock) phase_pieces(int32_t M, int32_t Q, int32_t lanes_shift, int32_t cols_per_part,
+                                                             const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colind,
+                                                             int32_t* __restrict__ piece_start, int32_t* __restrict__ piece_len) {
+  const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  const int64_t row = t >> lanes_shift;
+  const int q = (int)(t & ((1 << lanes_shift) - 1));
+  const bool live = row < M && q < Q;
+  const int r = (int)(row < M ? row : M - 1);
+  const int s = rowptr[r], e = rowptr[r + 1];
+  // Binary search over the whole row.  For any data, sorted or not, the result is monotone in the
+  // column searched for as long as every search starts from the same interval, which is what makes
+  // the pieces a partition of the row: the end of piece q IS the start of piece q + 1.
+  int lo = s, hi = e;
+  const int64_t column = (int64_t)q * cols_per_part;
+  if (q == 0 || !live) hi = lo;                     // piece 0 starts where the row starts
+  while (lo < hi) {
+    const int mid = lo + ((hi - lo) >> 1);
+    if (colind[mid] < column) lo = mid + 1;
+    else hi = mid;
+  }
+  const int begin = lo;
+  const int next_begin = __shfl_down(begin, 1, kWave);    // the lane to the right holds part q + 1 of the same row
+  const int end = q == Q - 1 ? e : next_begin;
+  if (live) {
+    piece_start[(int64_t)q * M + r] = begin;
+    piece_len[(int64_t)q * (M + 1) + r] = end - begin;
+    if (r == 0) piece_len[(int64_t)q * (M + 1) + M] = 0;
+  }
+}
+
+// piece_start[q * M + r] -= virtual_start[q * (M + 1) + r]: what is left is the number a virtual
+// position of row r in part q needs added to become the stored position.
+static __global__ void __launch_bounds__(kBlock) phase_deltas(int32_t M, int32_t Q, const int32_t* __restrict__ virtual_start,
+                                                             int32_t* __restrict__ piece_start) {
+  const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (t >= (int64_t)Q * M) return;
+  const int64_t q = t / M, r = t % M;
+  piece_start[t] -= virtual_start[q * (M + 1) + r];
+}
+
+// C[r, :] /= stored length of row r (the mean, after the phases have summed); empty rows stay 0.
+static __global__ void __launch_bounds__(kBlock) divide_rows_by_length(int32_t M, int32_t N, const int32_t* __restrict__ rowptr,
+                                                                      float* __restrict__ C) {
+  const int64_t total = (int64_t)M * N;
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total; i += stride) {
+    const int64_t r = i / N;
+    const int len = rowptr[r + 1] - rowptr[r];
+    if (len > 1) C[i] = C[i] / (float)len;
+  }
+}
+
 // --------------------------------------------------------------- host side --
 using MainKernel = void (*)(const KernelArgs);
 
@@ -1092,7 +1259,7 @@ enum Job { kJobAdd = kAdd, kJobMax = kMax, kJobMin = kMin, kJobArg = 3, kJobTran
 
 template <template <int, int> class P, int V>
 MainKernel pick_gt(int G, int T) {
-#define GESPMM_CASE(GG, TT) if (G == GG && T == TT) return chunk_kernel<P<V, TT>, V, GG, TT>;
+#define GESPMM_CASE(GG, TT) if (G == GG && T == TT) return chunk_kernel<P<V, TT>, V, GG, TT, false>;
   GESPMM_CASE(1, 1) GESPMM_CASE(2, 1) GESPMM_CASE(4, 1) GESPMM_CASE(8, 1)
   GESPMM_CASE(16, 1) GESPMM_CASE(32, 1) GESPMM_CASE(64, 1)
   GESPMM_CASE(4, 2) GESPMM_CASE(8, 2) GESPMM_CASE(16, 2) GESPMM_CASE(32, 2) GESPMM_CASE(64, 2)
@@ -1118,7 +1285,7 @@ MainKernel pick_job(int job, int G, int T) {
     case kJobMaxWithArg: return pick_gt<MaxArgRows, V>(G, T);
     case kJobMinWithArg: return pick_gt<MinArgRows, V>(G, T);
     case kJobTransposed: return pick_gt<TransposedRows, V>(G, T);
-    case kJobScatter: return (V == 1 && G == 1 && T == 1) ? chunk_kernel<ScatterRows<1, 1>, 1, 1, 1> : nullptr;
+    case kJobScatter: return (V == 1 && G == 1 && T == 1) ? chunk_kernel<ScatterRows<1, 1>, 1, 1, 1, false> : nullptr;
     default: return nullptr;
   }
 }
@@ -1134,7 +1301,7 @@ inline MainKernel pick_kernel(int job, int vec, int G, int T) {
 template <int F, class BT>
 MainKernel pick_b16_fold(int vec, int G, int T) {
   if (T != 1) return nullptr;
-#define GESPMM_CASE(VV, GG) if (vec == VV && G == GG) return chunk_kernel<FoldRows<F, VV, 1, BT>, VV, GG, 1>;
+#define GESPMM_CASE(VV, GG) if (vec == VV && G == GG) return chunk_kernel<FoldRows<F, VV, 1, BT>, VV, GG, 1, false>;
   GESPMM_CASE(4, 1) GESPMM_CASE(4, 2) GESPMM_CASE(4, 4) GESPMM_CASE(4, 8) GESPMM_CASE(4, 16) GESPMM_CASE(4, 32)
   GESPMM_CASE(1, 1) GESPMM_CASE(1, 2) GESPMM_CASE(1, 4) GESPMM_CASE(1, 8) GESPMM_CASE(1, 16) GESPMM_CASE(1, 32) GESPMM_CASE(1, 64)
 #undef GESPMM_CASE
@@ -1144,8 +1311,8 @@ MainKernel pick_b16_fold(int vec, int G, int T) {
 template <class P4, class P1>
 MainKernel pick_b16_shapes(int vec, int G, int T) {      // P4 / P1: the policy for 4 columns / 1 column per lane
   if (T != 1) return nullptr;
-#define GESPMM_CASE4(GG) if (vec == 4 && G == GG) return chunk_kernel<P4, 4, GG, 1>;
-#define GESPMM_CASE1(GG) if (vec == 1 && G == GG) return chunk_kernel<P1, 1, GG, 1>;
+#define GESPMM_CASE4(GG) if (vec == 4 && G == GG) return chunk_kernel<P4, 4, GG, 1, false>;
+#define GESPMM_CASE1(GG) if (vec == 1 && G == GG) return chunk_kernel<P1, 1, GG, 1, false>;
   GESPMM_CASE4(1) GESPMM_CASE4(2) GESPMM_CASE4(4) GESPMM_CASE4(8) GESPMM_CASE4(16) GESPMM_CASE4(32)
   GESPMM_CASE1(1) GESPMM_CASE1(2) GESPMM_CASE1(4) GESPMM_CASE1(8) GESPMM_CASE1(16) GESPMM_CASE1(32) GESPMM_CASE1(64)
 #undef GESPMM_CASE4
@@ -1166,6 +1333,21 @@ MainKernel pick_b16(int job, int vec, int G, int T) {
   }
 }
 
+// Kernels of the K-phased path: the three folds with four columns per lane; slots of 8, 16 or 32
+// lanes with one tile per lane, slots of 8 or 16 lanes with two.
+inline bool has_phased_kernel(int G, int T) { return (T == 1 && (G == 8 || G == 16 || G == 32)) || (T == 2 && (G == 8 || G == 16)); }
+
+template <class BT>
+MainKernel pick_phased(int job, int vec, int G, int T) {
+  if (vec != 4) return nullptr;
+#define GESPMM_CASE(FF, GG, TT) if (job == FF && G == GG && T == TT) return chunk_kernel<FoldRows<FF, 4, TT, BT>, 4, GG, TT, true>;
+  GESPMM_CASE(kAdd, 8, 1) GESPMM_CASE(kAdd, 16, 1) GESPMM_CASE(kAdd, 32, 1) GESPMM_CASE(kAdd, 8, 2) GESPMM_CASE(kAdd, 16, 2)
+  GESPMM_CASE(kMax, 8, 1) GESPMM_CASE(kMax, 16, 1) GESPMM_CASE(kMax, 32, 1) GESPMM_CASE(kMax, 8, 2) GESPMM_CASE(kMax, 16, 2)
+  GESPMM_CASE(kMin, 8, 1) GESPMM_CASE(kMin, 16, 1) GESPMM_CASE(kMin, 32, 1) GESPMM_CASE(kMin, 8, 2) GESPMM_CASE(kMin, 16, 2)
+#undef GESPMM_CASE
+  return nullptr;
+}
+
 inline bool has_kernel(int G, int T) { return pick_gt<AddRows, 4>(G, T) != nullptr; }
 
 inline int next_pow2(int64_t x) {
@@ -1174,23 +1356,79 @@ inline int next_pow2(int64_t x) {
   return p;
 }
 
-// process-wide tuning overrides (-1 = automatic)
-inline int g_force_g = -1, g_force_t = -1, g_force_remap = -1, g_force_shift = -1, g_force_short = -1;
+// Per-call overrides of the automatic launch shape (-1 = automatic), checked copy of gespmm_tuning_t.
+struct Tuning {
+  int g = -1, t = -1, remap = -1, shift = -1, short_len = -1, k_parts = -1;
+};
+
+inline int parse_tuning(const gespmm_tuning_t* in, Tuning* out) {
+  *out = Tuning{};
+  if (!in) return GESPMM_OK;
+  const int G = in->lanes_per_row, T = in->tiles_per_lane;
+  if (G > 0 && (G > kWave || (G & (G - 1)) != 0)) return GESPMM_ERR_BAD_ARG;
+  if (T > 0 && T != 1 && T != 2 && T != 4) return GESPMM_ERR_BAD_ARG;
+  if (G > 0 && T > 0 && !has_kernel(G, T)) return GESPMM_ERR_BAD_ARG;
+  if (in->xcd_remap > 1) return GESPMM_ERR_BAD_ARG;
+  int shift = -1;
+  if (in->chunk_nnz > 0) {
+    for (int sh = kMinChunkShift; sh <= kMaxChunkShift; ++sh)
+      if (in->chunk_nnz == (1 << sh)) shift = sh;
+    if (shift < 0) return GESPMM_ERR_BAD_ARG;
+  }
+  if (in->short_len > (1 << kMaxChunkShift)) return GESPMM_ERR_BAD_ARG;
+  if (in->k_parts > kMaxParts) return GESPMM_ERR_BAD_ARG;
+  out->g = G > 0 ? G : -1;
+  out->t = T > 0 ? T : -1;
+  out->remap = in->xcd_remap >= 0 ? in->xcd_remap : -1;
+  out->shift = shift;
+  out->short_len = in->short_len >= 0 ? in->short_len : -1;
+  out->k_parts = in->k_parts >= 0 ? (in->k_parts < 2 ? 1 : in->k_parts) : -1;
+  return GESPMM_OK;
+}
 
 // A problem that yields fewer wavefronts than this (8 per compute unit) gets smaller chunks,
 // so that its rows are spread over more of the chip.  Measured on matrices of 10^4 .. 10^6
 // entries: below this count halving the chunk pays; above it the extra split rows (finished
 // by atomics) and the extra row searches cost more than the added parallelism brings.
 constexpr int64_t kMinWaves = 2048;
+// chunks of a quarter of the size at the end of every phase of the K-phased path: two per wavefront the chip holds
+constexpr int kTaperChunks = 2 * 256 * 20;
+
+// Workspace of the K-phased path for Q parts: virtual row starts Q * (M + 1), deltas Q * M, scan totals.
+inline size_t phased_workspace_bytes(int64_t M, int Q) {
+  const int64_t n = (int64_t)Q * (M + 1);
+  const int64_t tiles = (n + kScanTile - 1) / kScanTile;
+  return (size_t)(n + (int64_t)Q * M + tiles + 4) * sizeof(int32_t);
+}
+
+// Number of parts the K range is cut into (1 = the plain path).  The phases pay when the rows of B
+// a column block touches (K x block bytes) are several times larger than one L2 (4 MB per XCD) and
+// the rows of A are long enough that a piece of a row still holds a few dozen entries.  A part is
+// sized to about 7.5 MB of B rows: measured on the 233k-vertex workload (60 MB of B), 8 parts beat
+// 6, 10, 14, 20 and 28; smaller parts raise the L2 hit rate further (65 % -> 84 %) but every phase
+// re-reads and re-writes C and walks all rows again, which costs more than the hits bring.  Needs
+// the vector kernels and, unless forced, a workspace that is large enough.
+inline int choose_parts(int64_t M, int64_t K, int64_t nnz, int vec, int block_bytes, const Tuning& tune,
+                        size_t workspace_bytes) {
+  if (vec != 4 || M <= 0 || K <= 0 || nnz <= 0) return 1;
+  if (tune.k_parts >= 0) return tune.k_parts < 2 ? 1 : (int)(tune.k_parts < K ? tune.k_parts : (K < 2 ? 1 : K));
+  const int64_t live = K * block_bytes;
+  const int64_t mean_row = nnz / M;
+  if (live < (12ll << 20) || mean_row < 128) return 1;
+  int64_t q = (live + (15ll << 18)) / (15ll << 19);        // nearest multiple of 7.5 MB
+  while (q > 2 && mean_row / q < 32) --q;
+  if (q > kMaxParts) q = kMaxParts;
+  if (q < 2) return 1;
+  if (workspace_bytes < phased_workspace_bytes(M, (int)q)) return 1;
+  return (int)q;
+}
 
 // elem_bytes: size of one element of the dense input (4, or 2 for the 16-bit formats); a lane
 // loads four columns at once when the width and the alignment allow it, one otherwise.
-inline void make_plan(int64_t M, int64_t N, int64_t nnz, bool aligned16, gespmm_plan_t* p, int elem_bytes = 4) {
+inline void make_plan(int64_t M, int64_t K, int64_t N, int64_t nnz, bool aligned16, int elem_bytes, const Tuning& tune,
+                      size_t workspace_bytes, gespmm_plan_t* p) {
   int vec = 1;
-  if (aligned16 && N > 0) {
-    if (elem_bytes == 4) vec = N % 4 == 0 ? 4 : 1;
-    else vec = N % 4 == 0 ? 4 : 1;              // 16-bit elements: 8-byte loads
-  }
+  if (aligned16 && N > 0) vec = N % 4 == 0 ? 4 : 1;        // 16-byte loads of fp32, 8-byte loads of 16-bit elements
   const int64_t ncv = N > 0 ? (N + vec - 1) / vec : 1;     // vector columns to cover
   // Column blocks of one 128-byte line (8 lanes x 16 bytes) up to N = 128, of two lines
   // beyond; wider N is covered by grid.y.  The blocks of one grid.y index run together in
@@ -1198,9 +1436,14 @@ inline void make_plan(int64_t M, int64_t N, int64_t nnz, bool aligned16, gespmm_
   // L2s keep far better than whole rows of B; the sparse arrays are re-read per block,
   // which costs 8 bytes per entry against 128 gathered.
   int G = next_pow2(ncv), T = 1;
+  int parts = 1;
   if (vec > 1) {
     const int line = 128 / (vec * elem_bytes);  // lanes that cover one 128-byte line of a row of B
-    if (G > line) G = ncv <= 4 * line ? line : 2 * line;   // one line; two lines for wide N
+    // the K-phased path keeps B in L2 by its own means and takes two lines per block
+    const int wide = G > 2 * line ? 2 * line : G;
+    parts = choose_parts(M, K, nnz, vec, wide * vec * elem_bytes, tune, workspace_bytes);
+    if (parts > 1) G = wide < 8 ? 8 : wide;
+    else if (G > line) G = ncv <= 4 * line ? line : 2 * line;   // one line; two lines for wide N
   } else if (elem_bytes == 2) {
     if (G > 64) G = 64;                         // one column per lane, one tile: up to 64 columns per block
   } else if (G > 16) {
@@ -1208,44 +1451,61 @@ inline void make_plan(int64_t M, int64_t N, int64_t nnz, bool aligned16, gespmm_
     T = 2;
     if (ncv > 64 && G * T < 128) { G = 64; T = 2; }
   }
-  if (g_force_g > 0) G = g_force_g;
-  if (g_force_t > 0) T = g_force_t;
-  // chunk size: 256 stored entries; 512 for column blocks of up to 64 bytes (less data
-  // per entry) and for matrices with long rows (fewer split rows); halved while the
-  // problem has too few chunks to fill the chip
+  if (tune.g > 0) G = tune.g;
+  if (tune.t > 0) T = tune.t;
+  if (parts > 1 && !has_phased_kernel(G, T)) parts = 1;   // no phased kernel of that shape
+  // chunk size: 256 items (stored entries and row ends); 512 for column blocks of up to 64
+  // bytes (less data per entry) and for matrices with long rows (fewer split rows); halved
+  // while the problem has too few chunks to fill the chip
   const int64_t col_blocks = (ncv + (int64_t)G * T - 1) / ((int64_t)G * T);
+  const int64_t items = nnz + M;
   int shift = ((int64_t)vec * G * T * elem_bytes <= 64 || (M > 0 && nnz / M >= 128)) ? 9 : 8;
-  while (shift > 6 && ((nnz + (1ll << shift) - 1) >> shift) * col_blocks < kMinWaves) --shift;
-  if (g_force_shift >= kMinChunkShift) shift = g_force_shift;
+  if (parts > 1) shift = 9;                     // measured: 512 and 1024 within 1 %, 256 is 10 % slower
+  while (shift > 6 && ((items / parts + (1ll << shift) - 1) >> shift) * col_blocks < kMinWaves) --shift;
+  if (tune.shift >= kMinChunkShift) shift = tune.shift;
   p->vec = vec;
   p->lanes_per_row = G;
   p->tiles_per_lane = T;
   p->slots = kWave / G;
   p->chunk_nnz = 1 << shift;
   p->col_blocks = (int32_t)col_blocks;
-  p->chunks = (nnz + p->chunk_nnz - 1) >> shift;
+  p->chunks = (items + p->chunk_nnz - 1) >> shift;
   p->grid_x = (p->chunks + kWavesPerBlock - 1) / kWavesPerBlock;
   p->block_threads = kBlock;
   // rows much longer than a chunk are finished by atomics from many consecutive chunks:
   // keep those chunks on one XCD (one L2); otherwise deal the chunks round-robin
   const bool long_rows = M > 0 && nnz / M >= p->chunk_nnz / 2;
-  p->xcd_remap = g_force_remap >= 0 ? g_force_remap : (long_rows ? 1 : 0);
+  p->xcd_remap = tune.remap >= 0 ? tune.remap : (long_rows && parts == 1 ? 1 : 0);
   // Rows up to short_len entries are walked one per slot, longer ones by all slots together
   // (with a cross-slot combine per row).  Where the mean row has 17 .. 48 entries, as in
   // stencil and finite-element matrices whose rows all have about that length, one slot per
   // row up to 32 entries avoids that combine for most rows (measured: up to 22 % on a
   // 27-point stencil, within 3 % either way on power-law graphs of the same mean).
-  const int64_t mean_row = M > 0 ? nnz / M : 0;
+  const int64_t mean_row = M > 0 ? nnz / M / parts : 0;
   int auto_short = 2 * p->slots < 16 ? 2 * p->slots : 16;
   if (mean_row > 16 && mean_row <= 48) auto_short = 32;
-  p->short_len = g_force_short >= 0 ? g_force_short : auto_short;
-  p->lds_bytes = (int32_t)(kWavesPerBlock * (p->chunk_nnz + kWave) * sizeof(int2));
+  p->short_len = tune.short_len >= 0 ? tune.short_len : auto_short;
+  p->lds_bytes = (int32_t)(kWavesPerBlock * (p->chunk_nnz + (parts > 1 ? 2 : 1) * kWave) * sizeof(int2));
+  p->k_parts = parts;
+  p->workspace_bytes = parts > 1 ? (int64_t)phased_workspace_bytes(M, parts) : 0;
+  if (parts > 1) {
+    // a phase is launched with 5/4 of the wavefronts it needs when the parts hold equal shares of
+    // the entries (counting the small chunks at its end); a part that holds more is finished by
+    // the same wavefronts taking further chunks
+    const int64_t phase_items = (nnz / parts) * 5 / 4 + M;
+    int64_t small_items = (int64_t)kTaperChunks << (shift - 2);
+    if (small_items > phase_items / 4) small_items = phase_items / 4;
+    const int64_t phase_chunks = ((phase_items - small_items) >> shift) + ((small_items + (p->chunk_nnz >> 2) - 1) >> (shift - 2)) + 1;
+    p->grid_x = (phase_chunks + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (p->grid_x < 1) p->grid_x = 1;
+  }
 }
 
-// profiling state
-inline std::vector<hipEvent_t> g_ev_start, g_ev_stop;
-inline int g_ev_used = 0;
-inline bool g_profiling = false;
+// Event pairs around main-kernel launches, owned by the caller through an opaque handle.
+struct Profiler {
+  std::vector<hipEvent_t> start, stop;
+  int used = 0;
+};
 
 inline int validate(int64_t M, int64_t K, int64_t N, int64_t nnz, const void* rowptr, const void* colind,
              const void* B, const void* C, int op) {
@@ -1273,11 +1533,22 @@ inline int launch_fill(float* dst, int64_t n, float value, hipStream_t stream) {
   return hipGetLastError() == hipSuccess ? GESPMM_OK : GESPMM_ERR_HIP;
 }
 
+// In-place exclusive scan of data[0 .. n) on the device; sums: scratch of ceil(n / kScanTile) numbers.
+inline int launch_exclusive_scan(int32_t* data, int64_t n, int32_t* sums, hipStream_t stream) {
+  const int64_t tiles = (n + kScanTile - 1) / kScanTile;
+  hipLaunchKernelGGL(scan_tiles, dim3((unsigned)tiles), dim3(kBlock), 0, stream, data, n, sums);
+  hipLaunchKernelGGL(scan_sums, dim3(1), dim3(kBlock), 0, stream, sums, tiles);
+  int64_t blocks = (n + kBlock - 1) / kBlock;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  hipLaunchKernelGGL(add_tile_offsets, dim3((unsigned)blocks), dim3(kBlock), 0, stream, data, n, sums, (int32_t*)nullptr, (int64_t)0);
+  return hipGetLastError() == hipSuccess ? GESPMM_OK : GESPMM_ERR_HIP;
+}
+
 // One pass of the chunk kernel over the matrix, preceded (when init_target is set) by the
 // row-initialisation kernel for that output.
 struct ChunkLaunch {
   int job = kJobAdd;
-  int64_t M = 0, N = 0, nnz = 0;
+  int64_t M = 0, K = 0, N = 0, nnz = 0;
   const int32_t* rowptr = nullptr;
   const int32_t* colind = nullptr;
   const float* vals = nullptr;
@@ -1293,18 +1564,127 @@ struct ChunkLaunch {
   float empty2_value = 0.0f, split2_value = 0.0f;
   bool only_split = false;             // position job: leave rows that lie inside one chunk alone
   bool packed_split = false;           // fused value+position job: packed words for split rows, unpacked at the end
-  bool timed = false;                  // bracket the chunk kernel with profiling events
   MainKernel (*picker)(int vec, int G, int T) = nullptr;   // user-defined reduce: its own kernel table
   int32_t* cursor = nullptr;           // structure-transpose job only
   bool one_lane_per_entry = false;     // use the <V=1, G=1, T=1> instance whatever N is
   int b_dtype = GESPMM_F32;            // element type of dense_in (16-bit types: fold jobs only)
+  Tuning tuning;                       // the caller's overrides
+  Profiler* profiler = nullptr;        // brackets every main-kernel launch with an event pair while it has pairs left
+  void* workspace = nullptr;           // enables the K-phased path (fold jobs only)
+  size_t workspace_bytes = 0;
 };
+
+inline bool record_start(Profiler* prof, hipStream_t stream, bool* timed, int* status) {
+  *timed = prof && prof->used < (int)prof->start.size();
+  if (*timed && hipEventRecord(prof->start[prof->used], stream) != hipSuccess) {
+    *status = GESPMM_ERR_HIP;
+    return false;
+  }
+  return true;
+}
+
+inline bool record_stop(Profiler* prof, hipStream_t stream, bool timed, int* status) {
+  if (!timed) return true;
+  if (hipEventRecord(prof->stop[prof->used], stream) != hipSuccess) {
+    *status = GESPMM_ERR_HIP;
+    return false;
+  }
+  ++prof->used;
+  return true;
+}
+
+inline void launch_init_rows(int vec, int64_t M, int64_t N, const int32_t* rowptr, float* target, float empty_value,
+                             float split_value, int shift, hipStream_t stream) {
+  int lanes_shift = 0;                          // lanes that write one row in init_rows
+  while ((1 << lanes_shift) < kWave && ((int64_t)vec << lanes_shift) < N) ++lanes_shift;
+  const unsigned init_blocks = (unsigned)((M + kBlock - 1) / kBlock);
+  if (vec == 4)
+    hipLaunchKernelGGL(init_rows<4>, dim3(init_blocks), dim3(kBlock), 0, stream, (int32_t)M, (int32_t)N, rowptr, target,
+                       empty_value, split_value, shift, lanes_shift);
+  else
+    hipLaunchKernelGGL(init_rows<1>, dim3(init_blocks), dim3(kBlock), 0, stream, (int32_t)M, (int32_t)N, rowptr, target,
+                       empty_value, split_value, shift, lanes_shift);
+}
+
+// The K-phased path: C = A (x) B as plan.k_parts launches, part q of the column range after part q - 1.
+// Every launch gathers from K / k_parts rows of B only, which the L2s hold, instead of from all of B.
+//   1. every non-empty row of C is preset to the reduce identity (empty rows to 0);
+//   2. phase_pieces cuts every row into k_parts pieces, an exclusive scan numbers the entries of every
+//      part consecutively (its virtual row starts), phase_deltas keeps what leads back to the stored
+//      positions: Q * (2 M + 1) numbers in the caller's workspace;
+//   3. one launch of the chunk kernel per part on that part's virtual CSR, folding into C; launches on
+//      one stream run one after the other, so no two wavefronts that may touch the same row with plain
+//      loads and stores are ever in flight together;
+//   4. mean: the phases sum, a last kernel divides the rows by their stored length.
+inline int launch_phased(const ChunkLaunch& L, const gespmm_plan_t& plan, MainKernel kernel, int shift, hipStream_t stream) {
+  const int Q = plan.k_parts;
+  const int64_t M = L.M;
+  if (((uintptr_t)L.workspace & 3u) != 0 || L.workspace_bytes < phased_workspace_bytes(M, Q)) return GESPMM_ERR_WORKSPACE;
+  int32_t* virtual_start = static_cast<int32_t*>(L.workspace);          // Q * (M + 1)
+  int32_t* delta = virtual_start + (int64_t)Q * (M + 1);                // Q * M
+  int32_t* sums = delta + (int64_t)Q * M;
+  const int cols_per_part = (int)((L.K + Q - 1) / Q);
+
+  launch_init_rows(plan.vec, M, L.N, L.rowptr, L.dense_out, L.empty_value, L.split_value, -1, stream);
+  const unsigned piece_blocks = (unsigned)(((int64_t)Q * M + kBlock - 1) / kBlock);
+  int lanes_shift = 0;                              // lanes that share a row in phase_pieces
+  while ((1 << lanes_shift) < Q) ++lanes_shift;
+  const unsigned search_blocks = (unsigned)(((M << lanes_shift) + kBlock - 1) / kBlock);
+  hipLaunchKernelGGL(phase_pieces, dim3(search_blocks), dim3(kBlock), 0, stream, (int32_t)M, Q, lanes_shift, cols_per_part, L.rowptr,
+                     L.colind, delta, virtual_start);
+  if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
+  const int scanned = launch_exclusive_scan(virtual_start, (int64_t)Q * (M + 1), sums, stream);
+  if (scanned != GESPMM_OK) return scanned;
+  hipLaunchKernelGGL(phase_deltas, dim3(piece_blocks), dim3(kBlock), 0, stream, (int32_t)M, Q, virtual_start, delta);
+  if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
+
+  KernelArgs a{};
+  a.M = (int32_t)M;
+  a.N = (int32_t)L.N;
+  a.nnz = (int32_t)L.nnz;
+  a.is_mean = 0;
+  a.chunks = 0;
+  a.chunk_blocks = plan.grid_x;
+  a.xcd_remap = plan.xcd_remap;
+  a.chunk_shift = shift;
+  a.short_len = plan.short_len;
+  a.colind = L.colind;
+  a.vals = L.vals;
+  a.B = L.dense_in;
+  a.C = L.dense_out;
+  a.accumulate = 1;
+  a.taper_chunks = kTaperChunks;
+  int status = GESPMM_OK;
+  for (int q = 0; q < Q; ++q) {
+    a.rowptr = virtual_start + (int64_t)q * (M + 1);
+    a.delta = delta + (int64_t)q * M;
+    bool timed = false;
+    if (!record_start(L.profiler, stream, &timed, &status)) return status;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)plan.grid_x, (unsigned)plan.col_blocks), dim3(kBlock), (size_t)plan.lds_bytes, stream, a);
+    if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
+    if (!record_stop(L.profiler, stream, timed, &status)) return status;
+  }
+  if (L.is_mean) {
+    int64_t blocks = (M * L.N + kBlock - 1) / kBlock;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(divide_rows_by_length, dim3((unsigned)blocks), dim3(kBlock), 0, stream, (int32_t)M, (int32_t)L.N, L.rowptr,
+                       L.dense_out);
+    if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
+  }
+  return GESPMM_OK;
+}
 
 inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
   const bool aligned16 = (((uintptr_t)L.dense_in | (uintptr_t)L.dense_out | (uintptr_t)L.result_in |
                            (uintptr_t)L.also_aligned) & 15u) == 0;
+  const bool fold_job = !L.picker && (L.job == kJobAdd || L.job == kJobMax || L.job == kJobMin) && !L.one_lane_per_entry;
+  Tuning tune = L.tuning;
+  if (!fold_job || !L.workspace) {
+    if (tune.k_parts > 1 && fold_job) return GESPMM_ERR_WORKSPACE;   // phases were asked for but there is nowhere to put their row starts
+    tune.k_parts = 1;
+  }
   gespmm_plan_t plan;
-  make_plan(L.M, L.N, L.nnz, aligned16, &plan, L.b_dtype == GESPMM_F32 ? 4 : 2);
+  make_plan(L.M, L.K, L.N, L.nnz, aligned16, L.b_dtype == GESPMM_F32 ? 4 : 2, tune, L.workspace_bytes, &plan);
   if (L.one_lane_per_entry) {
     plan.vec = 1;
     plan.lanes_per_row = 1;
@@ -1313,41 +1693,37 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
     plan.col_blocks = 1;
     plan.short_len = 16;
   }
+  if (plan.col_blocks > 65535) return GESPMM_ERR_TOO_LARGE;   // grid.y limit (N beyond ~33 million)
+  int shift = 0;
+  while ((1 << shift) < plan.chunk_nnz) ++shift;
+
+  if (plan.k_parts > 1 && L.nnz > 0) {
+    MainKernel phased = nullptr;
+    if (L.b_dtype == GESPMM_BF16) phased = pick_phased<bf16_t>(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
+    else if (L.b_dtype == GESPMM_F16) phased = pick_phased<f16_t>(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
+    else phased = pick_phased<float>(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
+    if (!phased) return GESPMM_ERR_BAD_ARG;
+    return launch_phased(L, plan, phased, shift, stream);
+  }
+
   MainKernel kernel = nullptr;
   if (L.picker) kernel = L.picker(plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
   else if (L.b_dtype == GESPMM_BF16) kernel = pick_b16<bf16_t>(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
   else if (L.b_dtype == GESPMM_F16) kernel = pick_b16<f16_t>(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
   else kernel = pick_kernel(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
   if (!kernel) return GESPMM_ERR_BAD_ARG;
-  if (plan.col_blocks > 65535) return GESPMM_ERR_TOO_LARGE;   // grid.y limit (N beyond ~33 million)
-  int shift = 0;
-  while ((1 << shift) < plan.chunk_nnz) ++shift;
 
   // (a) empty rows and rows shared by several chunks are preset
   if (L.init_target) {
-    int lanes_shift = 0;                          // lanes that write one row in init_rows
-    while ((1 << lanes_shift) < kWave && ((int64_t)plan.vec << lanes_shift) < L.N) ++lanes_shift;
-    const unsigned init_blocks = (unsigned)((L.M + kBlock - 1) / kBlock);
-    if (plan.vec == 4)
-      hipLaunchKernelGGL(init_rows<4>, dim3(init_blocks), dim3(kBlock), 0, stream, (int32_t)L.M, (int32_t)L.N, L.rowptr,
-                         L.init_target, L.empty_value, L.split_value, shift, lanes_shift);
-    else
-      hipLaunchKernelGGL(init_rows<1>, dim3(init_blocks), dim3(kBlock), 0, stream, (int32_t)L.M, (int32_t)L.N, L.rowptr,
-                         L.init_target, L.empty_value, L.split_value, shift, lanes_shift);
-    if (L.init2_target) {
-      if (plan.vec == 4)
-        hipLaunchKernelGGL(init_rows<4>, dim3(init_blocks), dim3(kBlock), 0, stream, (int32_t)L.M, (int32_t)L.N, L.rowptr,
-                           L.init2_target, L.empty2_value, L.split2_value, shift, lanes_shift);
-      else
-        hipLaunchKernelGGL(init_rows<1>, dim3(init_blocks), dim3(kBlock), 0, stream, (int32_t)L.M, (int32_t)L.N, L.rowptr,
-                           L.init2_target, L.empty2_value, L.split2_value, shift, lanes_shift);
-    }
+    launch_init_rows(plan.vec, L.M, L.N, L.rowptr, L.init_target, L.empty_value, L.split_value, shift, stream);
+    if (L.init2_target)
+      launch_init_rows(plan.vec, L.M, L.N, L.rowptr, L.init2_target, L.empty2_value, L.split2_value, shift, stream);
     if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
   }
   if (L.nnz == 0) return GESPMM_OK;
 
   // (b) the chunks
-  KernelArgs a;
+  KernelArgs a{};
   a.M = (int32_t)L.M;
   a.N = (int32_t)L.N;
   a.nnz = (int32_t)L.nnz;
@@ -1358,6 +1734,7 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
   a.chunk_shift = shift;
   a.short_len = plan.short_len;
   a.rowptr = L.rowptr;
+  a.delta = nullptr;
   a.colind = L.colind;
   a.vals = L.vals;
   a.B = L.dense_in;
@@ -1367,15 +1744,14 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
   a.cursor = L.cursor;
   a.only_split = L.only_split ? 1 : 0;
   a.packed_split = L.packed_split ? 1 : 0;
+  a.accumulate = 0;
   if (L.packed_split && (plan.vec != 4 || L.N > kWave * kFinishWords || !L.arg)) return GESPMM_ERR_BAD_ARG;
-  const bool timed = L.timed && g_profiling && g_ev_used < (int)g_ev_start.size();
-  if (timed && hipEventRecord(g_ev_start[g_ev_used], stream) != hipSuccess) return GESPMM_ERR_HIP;
+  int status = GESPMM_OK;
+  bool timed = false;
+  if (!record_start(L.profiler, stream, &timed, &status)) return status;
   hipLaunchKernelGGL(kernel, dim3((unsigned)plan.grid_x, (unsigned)plan.col_blocks), dim3(kBlock), (size_t)plan.lds_bytes, stream, a);
   if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
-  if (timed) {
-    if (hipEventRecord(g_ev_stop[g_ev_used], stream) != hipSuccess) return GESPMM_ERR_HIP;
-    ++g_ev_used;
-  }
+  if (!record_stop(L.profiler, stream, timed, &status)) return status;
   if (L.packed_split) {
     const unsigned blocks = (unsigned)((L.M + kBlock - 1) / kBlock);
     int words = 1;
@@ -1412,16 +1788,19 @@ MainKernel pick_custom(int vec, int G, int T) {
 namespace gespmm {
 
 // C = A (x) B with the user-defined reduce R (see CustomRows for what R must provide).
-// Same arguments, layout, ownership and errors as gespmm_csr; an empty row yields 0.
+// Same arguments, layout, ownership and errors as gespmm_csr; an empty row yields 0;
+// `tuning` as in gespmm_csr_ex (NULL = automatic).
 template <class R>
 int csr_custom(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
-               const float* vals, const float* B, float* C, hipStream_t stream) {
+               const float* vals, const float* B, float* C, hipStream_t stream, const gespmm_tuning_t* tuning = nullptr) {
   using namespace gespmm_detail;
   const int st = validate(M, K, N, nnz, rowptr, colind, B, C, GESPMM_SUM);
   if (st != GESPMM_OK || M == 0 || N == 0) return st;
   ChunkLaunch L;
+  const int parsed = parse_tuning(tuning, &L.tuning);
+  if (parsed != GESPMM_OK) return parsed;
   L.picker = &pick_custom<R>;
-  L.M = M; L.N = N; L.nnz = nnz;
+  L.M = M; L.K = K; L.N = N; L.nnz = nnz;
   L.rowptr = rowptr; L.colind = colind; L.vals = vals;
   L.dense_in = B; L.dense_out = C;
   L.init_target = C; L.empty_value = 0.0f; L.split_value = R::identity();

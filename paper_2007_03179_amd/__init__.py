@@ -7,12 +7,14 @@ from .binding import (GespmmError, OPS, gespmm_calibration_copy, gespmm_calibrat
                       gespmm_plan_b16, gespmm_csr_arg_b16, gespmm_csr_transpose_sorted, gespmm_csr_transpose_sorted_workspace_bytes,
                       gespmm_csr_simple, gespmm_csr_transpose, gespmm_csr_transpose_noalloc, gespmm_csr_transpose_workspace_bytes,
                       gespmm_csr_transposed, gespmm_plan, gespmm_pool_backward,
-                      gespmm_profile_begin, gespmm_profile_end, gespmm_set_tuning,
+                      gespmm_csr_ex, gespmm_csr_arg_ex, gespmm_csr_workspace_bytes, gespmm_plan_ex,
+                      gespmm_profiler_create, gespmm_profiler_finish, gespmm_tuning_t,
                       gespmm_status_string, gespmm_version, lib)
 
 __all__ = ["GespmmError", "OPS", "gespmm_calibration_copy", "gespmm_calibration_gather", "gespmm_csr", "gespmm_csr_arg", "gespmm_csr_b16",
            "gespmm_plan_b16", "gespmm_csr_arg_b16", "gespmm_csr_transpose_sorted", "gespmm_csr_transpose_sorted_workspace_bytes",
            "gespmm_csr_simple", "gespmm_csr_transpose", "gespmm_csr_transpose_noalloc", "gespmm_csr_transpose_workspace_bytes",
            "gespmm_csr_transposed", "gespmm_plan", "gespmm_pool_backward",
-           "gespmm_profile_begin", "gespmm_profile_end", "gespmm_set_tuning",
+           "gespmm_csr_ex", "gespmm_csr_arg_ex", "gespmm_csr_workspace_bytes", "gespmm_plan_ex",
+           "gespmm_profiler_create", "gespmm_profiler_finish", "gespmm_tuning_t",
            "gespmm_status_string", "gespmm_version", "lib"]

@@ -29,7 +29,35 @@ class gespmm_plan_t(ctypes.Structure):
                 ("chunk_nnz", ctypes.c_int32), ("col_blocks", ctypes.c_int32),
                 ("chunks", ctypes.c_int64), ("grid_x", ctypes.c_int64),
                 ("block_threads", ctypes.c_int32), ("xcd_remap", ctypes.c_int32),
-                ("short_len", ctypes.c_int32), ("lds_bytes", ctypes.c_int32)]
+                ("short_len", ctypes.c_int32), ("lds_bytes", ctypes.c_int32),
+                ("k_parts", ctypes.c_int32), ("reserved", ctypes.c_int32), ("workspace_bytes", ctypes.c_int64)]
+
+
+class gespmm_tuning_t(ctypes.Structure):
+    _fields_ = [("lanes_per_row", ctypes.c_int32), ("tiles_per_lane", ctypes.c_int32),
+                ("xcd_remap", ctypes.c_int32), ("chunk_nnz", ctypes.c_int32),
+                ("short_len", ctypes.c_int32), ("k_parts", ctypes.c_int32)]
+
+
+def _tuning(t):
+    """None, a gespmm_tuning_t, a dict of field names, or up to six numbers in field order (-1 = automatic)."""
+    if t is None or isinstance(t, gespmm_tuning_t):
+        return t
+    out = gespmm_tuning_t(-1, -1, -1, -1, -1, -1)
+    if isinstance(t, dict):
+        for name, value in t.items():
+            if name not in dict(gespmm_tuning_t._fields_):
+                raise KeyError(name)
+            setattr(out, name, int(value))
+    else:
+        for (name, _), value in zip(gespmm_tuning_t._fields_, t):
+            setattr(out, name, int(value))
+    return out
+
+
+def _tuning_ref(t):
+    t = _tuning(t)
+    return None if t is None else ctypes.byref(t)
 
 
 _lib = None
@@ -78,12 +106,19 @@ def lib():
         L.gespmm_csr_transpose_sorted.argtypes = [i64, i64, i64, vp, vp, vp, ci, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.gespmm_plan.restype = ci
         L.gespmm_plan.argtypes = [i64, i64, i64, ci, ctypes.POINTER(gespmm_plan_t)]
-        L.gespmm_set_tuning.restype = ci
-        L.gespmm_set_tuning.argtypes = [ci, ci, ci, ci, ci]
-        L.gespmm_profile_begin.restype = ci
-        L.gespmm_profile_begin.argtypes = [ci]
-        L.gespmm_profile_end.restype = ci
-        L.gespmm_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
+        tp = ctypes.POINTER(gespmm_tuning_t)
+        L.gespmm_plan_ex.restype = ci
+        L.gespmm_plan_ex.argtypes = [i64, i64, i64, i64, ci, ci, ctypes.c_size_t, tp, ctypes.POINTER(gespmm_plan_t)]
+        L.gespmm_csr_workspace_bytes.restype = ctypes.c_size_t
+        L.gespmm_csr_workspace_bytes.argtypes = [i64, i64, i64, i64, ci, tp]
+        L.gespmm_csr_ex.restype = ci
+        L.gespmm_csr_ex.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, ci, vp, ci, vp, ctypes.c_size_t, tp, vp, vp]
+        L.gespmm_csr_arg_ex.restype = ci
+        L.gespmm_csr_arg_ex.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, ci, vp, vp, ci, tp, vp]
+        L.gespmm_profiler_create.restype = ci
+        L.gespmm_profiler_create.argtypes = [ci, ctypes.POINTER(vp)]
+        L.gespmm_profiler_finish.restype = ci
+        L.gespmm_profiler_finish.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
         L.gespmm_calibration_copy.restype = ci
         L.gespmm_calibration_copy.argtypes = [vp, vp, i64, vp]
         L.gespmm_calibration_gather.restype = ci
@@ -180,7 +215,7 @@ def gespmm_csr_arg_b16(rowptr, colind, vals, B, op, C=None, arg=None, stream=Non
 def gespmm_plan_b16(M, N, nnz, b_dtype="bf16", aligned16=True) -> dict:
     p = gespmm_plan_t()
     _check(lib().gespmm_plan_b16(M, N, nnz, int(bool(aligned16)), DTYPES[b_dtype], ctypes.byref(p)))
-    return {name: int(getattr(p, name)) for name, _ in p._fields_}
+    return {name: int(getattr(p, name)) for name, _ in p._fields_ if name != "reserved"}
 
 
 def gespmm_csr_simple(rowptr, colind, vals, B, op, C=None, stream=None):
@@ -313,12 +348,68 @@ def gespmm_pool_backward(colind, vals, arg, dC, K, dB=None, stream=None):
 def gespmm_plan(M, N, nnz, aligned16=True) -> dict:
     p = gespmm_plan_t()
     _check(lib().gespmm_plan(M, N, nnz, int(bool(aligned16)), ctypes.byref(p)))
-    return {name: int(getattr(p, name)) for name, _ in p._fields_}
+    return {name: int(getattr(p, name)) for name, _ in p._fields_ if name != "reserved"}
 
 
-def gespmm_set_tuning(lanes_per_row=-1, tiles_per_lane=-1, xcd_remap=-1, chunk_nnz=-1, short_len=-1):
-    _check(lib().gespmm_set_tuning(int(lanes_per_row), int(tiles_per_lane), int(xcd_remap),
-                                   int(chunk_nnz), int(short_len)))
+def gespmm_plan_ex(M, K, N, nnz, b_dtype="f32", aligned16=True, workspace_bytes=0, tuning=None) -> dict:
+    """The launch shape gespmm_csr_ex would use (workspace_bytes: what the caller will pass)."""
+    p = gespmm_plan_t()
+    _check(lib().gespmm_plan_ex(M, K, N, nnz, int(bool(aligned16)), DTYPES[b_dtype], int(workspace_bytes),
+                                _tuning_ref(tuning), ctypes.byref(p)))
+    return {name: int(getattr(p, name)) for name, _ in p._fields_ if name != "reserved"}
+
+
+def gespmm_csr_workspace_bytes(M, K, N, nnz, b_dtype="f32", tuning=None) -> int:
+    return int(lib().gespmm_csr_workspace_bytes(M, K, N, nnz, DTYPES[b_dtype], _tuning_ref(tuning)))
+
+
+def gespmm_csr_ex(rowptr, colind, vals, B, op, C=None, workspace=None, tuning=None, profiler=None, stream=None):
+    """The forward call with its optional arguments: B float32 / bfloat16 / float16, `workspace` a CUDA tensor
+    (enables the K-phased path), `tuning` overrides, `profiler` a handle from gespmm_profiler_create."""
+    import torch
+    M, (K, N) = rowptr.numel() - 1, B.shape
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.float32, device=B.device)
+    code_b = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}[B.dtype]
+    _check_tensors(rowptr, colind, vals, B, C, b_dtype=B.dtype)
+    assert workspace is None or (workspace.is_cuda and workspace.is_contiguous())
+    code = OPS[op] if isinstance(op, str) else int(op)
+    _check(lib().gespmm_csr_ex(M, K, N, colind.numel(), _ptr(rowptr), _ptr(colind), _ptr(vals), _ptr(B), code_b,
+                               _ptr(C), code, _ptr(workspace),
+                               0 if workspace is None else workspace.numel() * workspace.element_size(),
+                               _tuning_ref(tuning), profiler, _stream(stream)))
+    return C
+
+
+def gespmm_csr_arg_ex(rowptr, colind, vals, B, op, C=None, arg=None, tuning=None, stream=None):
+    """gespmm_csr_arg / gespmm_csr_arg_b16 with tuning overrides; returns (C fp32, arg int32)."""
+    import torch
+    M, (K, N) = rowptr.numel() - 1, B.shape
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.float32, device=B.device)
+    if arg is None:
+        arg = torch.empty((M, N), dtype=torch.int32, device=B.device)
+    code_b = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}[B.dtype]
+    _check_tensors(rowptr, colind, vals, B, C, b_dtype=B.dtype)
+    assert arg.is_cuda and arg.dtype == torch.int32 and arg.is_contiguous() and arg.shape == C.shape
+    code = OPS[op] if isinstance(op, str) else int(op)
+    _check(lib().gespmm_csr_arg_ex(M, K, N, colind.numel(), _ptr(rowptr), _ptr(colind), _ptr(vals), _ptr(B), code_b,
+                                   _ptr(C), _ptr(arg), code, _tuning_ref(tuning), _stream(stream)))
+    return C, arg
+
+
+def gespmm_profiler_create(capacity: int):
+    """A handle that owns `capacity` event pairs; pass it to gespmm_csr_ex, then to gespmm_profiler_finish."""
+    handle = ctypes.c_void_p()
+    _check(lib().gespmm_profiler_create(int(capacity), ctypes.byref(handle)))
+    return handle
+
+
+def gespmm_profiler_finish(handle):
+    """Returns (summed main-kernel milliseconds, number of bracketed launches) and destroys the handle."""
+    ms, n = ctypes.c_double(0.0), ctypes.c_int(0)
+    _check(lib().gespmm_profiler_finish(handle, ctypes.byref(ms), ctypes.byref(n)))
+    return float(ms.value), int(n.value)
 
 
 def gespmm_calibration_copy(src, dst, stream=None):
@@ -343,14 +434,3 @@ def gespmm_calibration_gather(table, idx, out=None, stream=None):
     _check(lib().gespmm_calibration_gather(_ptr(table), nbytes // 128, _ptr(idx), n, _ptr(out),
                                            out.numel() * out.element_size(), _stream(stream)))
     return out
-
-
-def gespmm_profile_begin(capacity: int):
-    _check(lib().gespmm_profile_begin(int(capacity)))
-
-
-def gespmm_profile_end():
-    """Returns (summed main-kernel milliseconds, number of bracketed launches)."""
-    ms, n = ctypes.c_double(0.0), ctypes.c_int(0)
-    _check(lib().gespmm_profile_end(ctypes.byref(ms), ctypes.byref(n)))
-    return float(ms.value), int(n.value)

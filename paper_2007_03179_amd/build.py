@@ -14,7 +14,6 @@ HIPCC_FLAGS = [
     "-munsafe-fp-atomics",                                   # hardware fp32 atomic add
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-I", os.path.join(ROOT, "include"),
-    "-I", os.path.join(HERE, "csrc"),
 ]
 
 

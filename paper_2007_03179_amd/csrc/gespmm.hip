@@ -5,100 +5,137 @@
 #include "gespmm_sort.hpp"
 
 #include <mutex>
+#include <new>
 
 using namespace gespmm_detail;
 
 extern "C" {
 
-int gespmm_plan(int64_t M, int64_t N, int64_t nnz, int aligned16, gespmm_plan_t* out) {
+struct gespmm_profiler : gespmm_detail::Profiler {};
+
+static int element_bytes(int b_dtype) { return b_dtype == GESPMM_F32 ? 4 : 2; }
+static bool known_dtype(int b_dtype) { return b_dtype == GESPMM_F32 || b_dtype == GESPMM_BF16 || b_dtype == GESPMM_F16; }
+
+int gespmm_plan_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, int aligned16, int b_dtype, size_t workspace_bytes,
+                   const gespmm_tuning_t* tuning, gespmm_plan_t* out) {
   if (!out) return GESPMM_ERR_NULL;
-  if (M < 0 || N < 0 || nnz < 0) return GESPMM_ERR_BAD_ARG;
-  make_plan(M, N, nnz, aligned16 != 0, out);
+  if (M < 0 || K < 0 || N < 0 || nnz < 0 || !known_dtype(b_dtype)) return GESPMM_ERR_BAD_ARG;
+  Tuning tune;
+  const int parsed = parse_tuning(tuning, &tune);
+  if (parsed != GESPMM_OK) return parsed;
+  make_plan(M, K, N, nnz, aligned16 != 0, element_bytes(b_dtype), tune, workspace_bytes, out);
   return GESPMM_OK;
+}
+
+int gespmm_plan(int64_t M, int64_t N, int64_t nnz, int aligned16, gespmm_plan_t* out) {
+  return gespmm_plan_ex(M, 0, N, nnz, aligned16, GESPMM_F32, 0, nullptr, out);
 }
 
 int gespmm_plan_b16(int64_t M, int64_t N, int64_t nnz, int aligned16, int b_dtype, gespmm_plan_t* out) {
+  return gespmm_plan_ex(M, 0, N, nnz, aligned16, b_dtype, 0, nullptr, out);
+}
+
+size_t gespmm_csr_workspace_bytes(int64_t M, int64_t K, int64_t N, int64_t nnz, int b_dtype, const gespmm_tuning_t* tuning) {
+  gespmm_plan_t plan;
+  if (gespmm_plan_ex(M, K, N, nnz, 1, b_dtype, (size_t)-1, tuning, &plan) != GESPMM_OK) return 0;
+  return (size_t)plan.workspace_bytes;
+}
+
+int gespmm_profiler_create(int capacity, gespmm_profiler_t** out) {
   if (!out) return GESPMM_ERR_NULL;
-  if (M < 0 || N < 0 || nnz < 0) return GESPMM_ERR_BAD_ARG;
-  if (b_dtype != GESPMM_F32 && b_dtype != GESPMM_BF16 && b_dtype != GESPMM_F16) return GESPMM_ERR_BAD_ARG;
-  make_plan(M, N, nnz, aligned16 != 0, out, b_dtype == GESPMM_F32 ? 4 : 2);
+  *out = nullptr;
+  if (capacity <= 0) return GESPMM_ERR_BAD_ARG;
+  gespmm_profiler* p = new (std::nothrow) gespmm_profiler();
+  if (!p) return GESPMM_ERR_HIP;
+  p->start.assign(capacity, nullptr);
+  p->stop.assign(capacity, nullptr);
+  for (int i = 0; i < capacity; ++i) {
+    if (hipEventCreate(&p->start[i]) != hipSuccess || hipEventCreate(&p->stop[i]) != hipSuccess) {
+      for (int j = 0; j <= i; ++j) {              // release what was created before the failure
+        if (p->start[j]) (void)hipEventDestroy(p->start[j]);
+        if (p->stop[j]) (void)hipEventDestroy(p->stop[j]);
+      }
+      delete p;
+      return GESPMM_ERR_HIP;
+    }
+  }
+  *out = p;
   return GESPMM_OK;
 }
 
-int gespmm_set_tuning(int lanes_per_row, int tiles_per_lane, int xcd_remap, int chunk_nnz, int short_len) {
-  const int G = lanes_per_row, T = tiles_per_lane;
-  if (G > 0 && (G > kWave || (G & (G - 1)) != 0)) return GESPMM_ERR_BAD_ARG;
-  if (T > 0 && T != 1 && T != 2 && T != 4) return GESPMM_ERR_BAD_ARG;
-  if (G > 0 && T > 0 && !has_kernel(G, T)) return GESPMM_ERR_BAD_ARG;
-  if (xcd_remap > 1) return GESPMM_ERR_BAD_ARG;
-  int shift = -1;
-  if (chunk_nnz > 0) {
-    for (int sh = kMinChunkShift; sh <= kMaxChunkShift; ++sh)
-      if (chunk_nnz == (1 << sh)) shift = sh;
-    if (shift < 0) return GESPMM_ERR_BAD_ARG;
+int gespmm_profiler_finish(gespmm_profiler_t* p, double* main_kernel_ms_sum, int* launches) {
+  if (!p) return GESPMM_ERR_NULL;
+  double total = 0.0;
+  int status = GESPMM_OK;
+  for (int i = 0; i < p->used; ++i) {
+    float ms = 0.0f;
+    if (hipEventSynchronize(p->stop[i]) != hipSuccess || hipEventElapsedTime(&ms, p->start[i], p->stop[i]) != hipSuccess)
+      status = GESPMM_ERR_HIP;
+    total += ms;
   }
-  if (short_len > (1 << kMaxChunkShift)) return GESPMM_ERR_BAD_ARG;
-  g_force_g = G > 0 ? G : -1;
-  g_force_t = T > 0 ? T : -1;
-  g_force_remap = xcd_remap >= 0 ? xcd_remap : -1;
-  g_force_shift = shift;
-  g_force_short = short_len >= 0 ? short_len : -1;
-  return GESPMM_OK;
+  for (size_t i = 0; i < p->start.size(); ++i) {
+    (void)hipEventDestroy(p->start[i]);
+    (void)hipEventDestroy(p->stop[i]);
+  }
+  if (main_kernel_ms_sum) *main_kernel_ms_sum = total;
+  if (launches) *launches = p->used;
+  delete p;
+  return status;
+}
+
+int gespmm_csr_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+                  const float* vals, const void* B, int b_dtype, float* C, int op, void* workspace,
+                  size_t workspace_bytes, const gespmm_tuning_t* tuning, gespmm_profiler_t* profiler, void* stream_) {
+  if (!known_dtype(b_dtype)) return GESPMM_ERR_BAD_ARG;
+  const int st = validate(M, K, N, nnz, rowptr, colind, B, C, op);
+  if (st != GESPMM_OK || M == 0 || N == 0) return st;
+  ChunkLaunch L;
+  const int parsed = parse_tuning(tuning, &L.tuning);
+  if (parsed != GESPMM_OK) return parsed;
+  const int job = op == GESPMM_MAX ? kJobMax : (op == GESPMM_MIN ? kJobMin : kJobAdd);
+  float identity = 0.0f;
+  if (job == kJobMax) identity = -__builtin_inff();
+  if (job == kJobMin) identity = __builtin_inff();
+  L.job = job;
+  L.b_dtype = b_dtype;
+  L.M = M; L.K = K; L.N = N; L.nnz = nnz;
+  L.rowptr = rowptr; L.colind = colind; L.vals = vals;
+  L.dense_in = static_cast<const float*>(B); L.dense_out = C;
+  L.is_mean = op == GESPMM_MEAN;
+  L.init_target = C; L.empty_value = 0.0f; L.split_value = identity;
+  L.profiler = profiler;
+  L.workspace = workspace; L.workspace_bytes = workspace ? workspace_bytes : 0;
+  return launch_chunks(L, (hipStream_t)stream_);
 }
 
 int gespmm_csr(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
                const int32_t* colind, const float* vals, const float* B, float* C, int op,
                void* stream_) {
-  const int st = validate(M, K, N, nnz, rowptr, colind, B, C, op);
-  if (st != GESPMM_OK || M == 0 || N == 0) return st;
-  const int job = op == GESPMM_MAX ? kJobMax : (op == GESPMM_MIN ? kJobMin : kJobAdd);
-  float identity = 0.0f;
-  if (job == kJobMax) identity = -__builtin_inff();
-  if (job == kJobMin) identity = __builtin_inff();
-  ChunkLaunch L;
-  L.job = job;
-  L.M = M; L.N = N; L.nnz = nnz;
-  L.rowptr = rowptr; L.colind = colind; L.vals = vals;
-  L.dense_in = B; L.dense_out = C;
-  L.is_mean = op == GESPMM_MEAN;
-  L.init_target = C; L.empty_value = 0.0f; L.split_value = identity;
-  L.timed = true;
-  return launch_chunks(L, (hipStream_t)stream_);
+  return gespmm_csr_ex(M, K, N, nnz, rowptr, colind, vals, B, GESPMM_F32, C, op, nullptr, 0, nullptr, nullptr, stream_);
 }
 
 int gespmm_csr_b16(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
                    const int32_t* colind, const float* vals, const void* B, int b_dtype, float* C,
                    int op, void* stream_) {
-  if (b_dtype == GESPMM_F32) return gespmm_csr(M, K, N, nnz, rowptr, colind, vals, (const float*)B, C, op, stream_);
-  if (b_dtype != GESPMM_BF16 && b_dtype != GESPMM_F16) return GESPMM_ERR_BAD_ARG;
-  const int st = validate(M, K, N, nnz, rowptr, colind, B, C, op);
-  if (st != GESPMM_OK || M == 0 || N == 0) return st;
-  const int job = op == GESPMM_MAX ? kJobMax : (op == GESPMM_MIN ? kJobMin : kJobAdd);
-  float identity = 0.0f;
-  if (job == kJobMax) identity = -__builtin_inff();
-  if (job == kJobMin) identity = __builtin_inff();
-  ChunkLaunch L;
-  L.job = job;
-  L.b_dtype = b_dtype;
-  L.M = M; L.N = N; L.nnz = nnz;
-  L.rowptr = rowptr; L.colind = colind; L.vals = vals;
-  L.dense_in = (const float*)B; L.dense_out = C;
-  L.is_mean = op == GESPMM_MEAN;
-  L.init_target = C; L.empty_value = 0.0f; L.split_value = identity;
-  L.timed = true;
-  return launch_chunks(L, (hipStream_t)stream_);
+  return gespmm_csr_ex(M, K, N, nnz, rowptr, colind, vals, B, b_dtype, C, op, nullptr, 0, nullptr, nullptr, stream_);
 }
 
 int gespmm_csr_arg(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
                    const int32_t* colind, const float* vals, const float* B, float* C, int32_t* arg,
                    int op, void* stream_) {
-  return gespmm_csr_arg_b16(M, K, N, nnz, rowptr, colind, vals, B, GESPMM_F32, C, arg, op, stream_);
+  return gespmm_csr_arg_ex(M, K, N, nnz, rowptr, colind, vals, B, GESPMM_F32, C, arg, op, nullptr, stream_);
 }
 
 int gespmm_csr_arg_b16(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
-                       const int32_t* colind, const float* vals, const void* B_, int b_dtype, float* C,
+                       const int32_t* colind, const float* vals, const void* B, int b_dtype, float* C,
                        int32_t* arg, int op, void* stream_) {
-  if (b_dtype != GESPMM_F32 && b_dtype != GESPMM_BF16 && b_dtype != GESPMM_F16) return GESPMM_ERR_BAD_ARG;
+  return gespmm_csr_arg_ex(M, K, N, nnz, rowptr, colind, vals, B, b_dtype, C, arg, op, nullptr, stream_);
+}
+
+int gespmm_csr_arg_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                      const int32_t* colind, const float* vals, const void* B_, int b_dtype, float* C,
+                      int32_t* arg, int op, const gespmm_tuning_t* tuning, void* stream_) {
+  if (!known_dtype(b_dtype)) return GESPMM_ERR_BAD_ARG;
   const float* B = static_cast<const float*>(B_);
   if (op != GESPMM_MAX && op != GESPMM_MIN) return GESPMM_ERR_BAD_ARG;
   const int st = validate(M, K, N, nnz, rowptr, colind, B, C, op);
@@ -107,8 +144,11 @@ int gespmm_csr_arg_b16(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32
   // One fused pass gives value and position for every row that lies inside one chunk.
   hipStream_t stream = (hipStream_t)stream_;
   ChunkLaunch L;
+  const int parsed = parse_tuning(tuning, &L.tuning);
+  if (parsed != GESPMM_OK) return parsed;
+  L.tuning.k_parts = 1;
   L.job = op == GESPMM_MAX ? kJobMaxWithArg : kJobMinWithArg;
-  L.M = M; L.N = N; L.nnz = nnz;
+  L.M = M; L.K = K; L.N = N; L.nnz = nnz;
   L.rowptr = rowptr; L.colind = colind; L.vals = vals;
   L.dense_in = B; L.dense_out = C; L.arg = arg;
   L.b_dtype = b_dtype;
@@ -117,7 +157,6 @@ int gespmm_csr_arg_b16(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32
   L.init2_target = reinterpret_cast<float*>(arg);
   L.empty_value = 0.0f;
   L.empty2_value = bits_as_float(-1);
-  L.timed = true;
   // Rows split across chunks.  Vector kernels, N <= 1024: their (value, position) pairs are
   // combined as packed 64-bit words kept in the row's own C and arg storage (preset to zero)
   // and unpacked by a small kernel after the pass.  Otherwise: values by atomics in this pass
@@ -136,8 +175,9 @@ int gespmm_csr_arg_b16(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32
   // Second pass, split rows only (their values are final once the first kernel has ended):
   // entries whose product has the bits of C[i, j] compete by atomic min on their index.
   ChunkLaunch S;
+  S.tuning = L.tuning;
   S.job = kJobArg;
-  S.M = M; S.N = N; S.nnz = nnz;
+  S.M = M; S.K = K; S.N = N; S.nnz = nnz;
   S.rowptr = rowptr; S.colind = colind; S.vals = vals;
   S.dense_in = B; S.result_in = C; S.arg = arg;
   S.b_dtype = b_dtype;
@@ -161,7 +201,7 @@ int gespmm_csr_transposed(int64_t M, int64_t K, int64_t N, int64_t nnz, const in
   if (fill != GESPMM_OK || nnz == 0) return fill;
   ChunkLaunch L;
   L.job = kJobTransposed;
-  L.M = M; L.N = N; L.nnz = nnz;
+  L.M = M; L.K = K; L.N = N; L.nnz = nnz;
   L.rowptr = rowptr; L.colind = colind; L.vals = vals;
   L.dense_in = dC; L.dense_out = dB;
   L.is_mean = op == GESPMM_MEAN;
@@ -217,7 +257,7 @@ static int transpose_with_counters(int64_t M, int64_t K, int64_t nnz, const int3
   // every stored entry takes the next free place of its column's row
   ChunkLaunch L;
   L.job = kJobScatter;
-  L.M = M; L.N = 1; L.nnz = nnz;
+  L.M = M; L.K = K; L.N = 1; L.nnz = nnz;
   L.rowptr = rowptr; L.colind = colind; L.vals = vals;
   L.dense_out = valsT; L.arg = colindT; L.cursor = cursor;
   L.is_mean = scale_by_row_length != 0;
@@ -309,7 +349,7 @@ int gespmm_csr_transpose_sorted(int64_t M, int64_t K, int64_t nnz, const int32_t
   // (1) row index and weight of every stored entry, in entry order (the chunk walk, one lane per entry)
   ChunkLaunch L;
   L.job = kJobScatter;
-  L.M = M; L.N = 1; L.nnz = nnz;
+  L.M = M; L.K = K; L.N = 1; L.nnz = nnz;
   L.rowptr = rowptr; L.colind = colind; L.vals = vals;
   L.dense_out = weight; L.arg = rowid; L.cursor = nullptr;
   L.is_mean = scale_by_row_length != 0;
@@ -386,50 +426,6 @@ int gespmm_csr_simple(int64_t M, int64_t K, int64_t N, const int32_t* rowptr, co
   if (hipMemcpyAsync(&nnz, rowptr + M, sizeof(nnz), hipMemcpyDeviceToHost, stream) != hipSuccess) return GESPMM_ERR_HIP;
   if (hipStreamSynchronize(stream) != hipSuccess) return GESPMM_ERR_HIP;
   return gespmm_csr(M, K, N, nnz, rowptr, colind, vals, B, C, op, stream_);
-}
-
-int gespmm_profile_begin(int capacity) {
-  if (capacity <= 0 || g_profiling) return GESPMM_ERR_BAD_ARG;
-  g_ev_start.assign(capacity, nullptr);
-  g_ev_stop.assign(capacity, nullptr);
-  for (int i = 0; i < capacity; ++i) {
-    if (hipEventCreate(&g_ev_start[i]) != hipSuccess || hipEventCreate(&g_ev_stop[i]) != hipSuccess) {
-      for (int j = 0; j <= i; ++j) {              // release what was created before the failure
-        if (g_ev_start[j]) (void)hipEventDestroy(g_ev_start[j]);
-        if (g_ev_stop[j]) (void)hipEventDestroy(g_ev_stop[j]);
-      }
-      g_ev_start.clear();
-      g_ev_stop.clear();
-      return GESPMM_ERR_HIP;
-    }
-  }
-  g_ev_used = 0;
-  g_profiling = true;
-  return GESPMM_OK;
-}
-
-int gespmm_profile_end(double* main_kernel_ms_sum, int* launches) {
-  if (!g_profiling) return GESPMM_ERR_BAD_ARG;
-  g_profiling = false;
-  double total = 0.0;
-  int status = GESPMM_OK;
-  for (int i = 0; i < g_ev_used; ++i) {
-    float ms = 0.0f;
-    if (hipEventSynchronize(g_ev_stop[i]) != hipSuccess ||
-        hipEventElapsedTime(&ms, g_ev_start[i], g_ev_stop[i]) != hipSuccess)
-      status = GESPMM_ERR_HIP;
-    total += ms;
-  }
-  for (size_t i = 0; i < g_ev_start.size(); ++i) {
-    (void)hipEventDestroy(g_ev_start[i]);
-    (void)hipEventDestroy(g_ev_stop[i]);
-  }
-  if (main_kernel_ms_sum) *main_kernel_ms_sum = total;
-  if (launches) *launches = g_ev_used;
-  g_ev_start.clear();
-  g_ev_stop.clear();
-  g_ev_used = 0;
-  return status;
 }
 
 int gespmm_calibration_copy(const void* src, void* dst, int64_t bytes, void* stream_) {

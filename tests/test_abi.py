@@ -26,8 +26,8 @@ def _declared_functions():
 
 def test_every_declared_symbol_is_exported(L):
     names = _declared_functions()
-    assert {"gespmm_csr", "gespmm_csr_simple", "gespmm_plan", "gespmm_set_tuning",
-            "gespmm_profile_begin", "gespmm_profile_end", "gespmm_status_string",
+    assert {"gespmm_csr", "gespmm_csr_simple", "gespmm_plan", "gespmm_plan_ex", "gespmm_csr_ex", "gespmm_csr_arg_ex",
+            "gespmm_csr_workspace_bytes", "gespmm_profiler_create", "gespmm_profiler_finish", "gespmm_status_string",
             "gespmm_calibration_copy", "gespmm_calibration_gather", "gespmm_csr_arg", "gespmm_csr_transposed", "gespmm_pool_backward",
             "gespmm_csr_transpose", "gespmm_csr_transpose_workspace_bytes", "gespmm_csr_transpose_noalloc",
             "gespmm_csr_b16", "gespmm_plan_b16", "gespmm_csr_arg_b16", "gespmm_csr_transpose_sorted",
@@ -110,7 +110,20 @@ def test_argument_errors_come_before_any_device_work(L):
     assert L.gespmm_csr_transpose_noalloc(4, 2097153, 8, p, p, p, 0, p, p, p, None) == 6    # beyond the built-in scratch
     assert L.gespmm_csr_transpose_noalloc(4, 4, 8, p, p, p, 0, p, None, p, None) == 2
     assert L.gespmm_plan(4, 4, 4, 1, None) == 2
-    assert L.gespmm_profile_end(None, None) == 1                  # not profiling
+    assert L.gespmm_profiler_finish(None, None, None) == 2        # no profiler
+    assert L.gespmm_profiler_create(0, ctypes.byref(ctypes.c_void_p())) == 1
+    assert L.gespmm_profiler_create(4, None) == 2
+    ex = L.gespmm_csr_ex
+    assert ex(4, 4, 4, 8, p, p, p, p, 7, p, 0, None, 0, None, None, None) == 1       # unknown element type
+    assert ex(4, 4, 4, 8, p, p, p, None, 0, p, 0, None, 0, None, None, None) == 2    # B NULL
+    assert ex(-4, 4, 4, 8, p, p, p, p, 0, p, 0, None, 0, None, None, None) == 1
+    bad = gs.gespmm_tuning_t(3, -1, -1, -1, -1, -1)                                    # 3 lanes per row: no such kernel
+    assert ex(4, 4, 4, 8, p, p, p, p, 0, p, 0, None, 0, ctypes.byref(bad), None, None) == 1
+    forced = gs.gespmm_tuning_t(-1, -1, -1, -1, -1, 4)                                 # phases forced without a workspace
+    assert ex(4, 4, 4, 8, p, p, p, p, 0, p, 0, None, 0, ctypes.byref(forced), None, None) == 4
+    assert ex(4, 4, 4, 8, p, p, p, p, 0, p, 0, p, 8, ctypes.byref(forced), None, None) == 4   # workspace too small
+    assert L.gespmm_csr_arg_ex(4, 4, 4, 8, p, p, p, p, 0, p, p, 0, None, None) == 1     # sum has no position
+    assert L.gespmm_csr_arg_ex(4, 4, 4, 8, p, p, p, p, 0, p, p, 2, ctypes.byref(bad), None) == 1
     assert L.gespmm_calibration_copy(p, p, 24, None) == 1         # not a multiple of 16
     assert L.gespmm_calibration_copy(None, p, 32, None) == 2
     assert L.gespmm_calibration_copy(p, ctypes.c_void_p(0x1004), 32, None) == 1
@@ -124,7 +137,7 @@ def test_plan_covers_all_columns_vectorised(N, G, T, blocks):
     p = gs.gespmm_plan(1000, N, 10_000)
     assert p["vec"] == 4 and (p["lanes_per_row"], p["tiles_per_lane"], p["col_blocks"]) == (G, T, blocks)
     assert p["vec"] * G * T * blocks >= N and p["slots"] * G == 64
-    assert p["chunks"] == -(-10_000 // p["chunk_nnz"])
+    assert p["chunks"] == -(-(10_000 + 1000) // p["chunk_nnz"])      # items: stored entries + row ends
     assert p["grid_x"] * (p["block_threads"] // 64) >= p["chunks"]
 
 
@@ -136,26 +149,57 @@ def test_plan_scalar_path(N, aligned):
 
 
 def test_tuning_override_is_validated():
-    with pytest.raises(gs.GespmmError):
-        gs.gespmm_set_tuning(3, -1, -1)
-    with pytest.raises(gs.GespmmError):
-        gs.gespmm_set_tuning(-1, 3, -1)
-    with pytest.raises(gs.GespmmError):
-        gs.gespmm_set_tuning(2, 4, -1)        # no such kernel
-    try:
-        gs.gespmm_set_tuning(32, 1, 0)
-        p = gs.gespmm_plan(1000, 64, 10_000)
-        assert (p["lanes_per_row"], p["tiles_per_lane"], p["xcd_remap"], p["col_blocks"]) == (32, 1, 0, 1)
-        gs.gespmm_set_tuning(chunk_nnz=1024, short_len=5)
-        p = gs.gespmm_plan(1000, 64, 10_000)
-        assert (p["lanes_per_row"], p["chunk_nnz"], p["short_len"], p["chunks"]) == (8, 1024, 5, 10)
-        assert p["lds_bytes"] == 4 * (1024 + 64) * 8
-        for bad in (dict(chunk_nnz=100), dict(chunk_nnz=2048), dict(chunk_nnz=8), dict(short_len=5000)):
-            with pytest.raises(gs.GespmmError):
-                gs.gespmm_set_tuning(**bad)
-    finally:
-        gs.gespmm_set_tuning()
-    assert gs.gespmm_plan(1000, 64, 10_000)["lanes_per_row"] == 8
+    plan = lambda **t: gs.gespmm_plan_ex(1000, 1000, 64, 10_000, tuning=t)
+    for bad in (dict(lanes_per_row=3), dict(tiles_per_lane=3), dict(lanes_per_row=2, tiles_per_lane=4),   # no such kernel
+                dict(chunk_nnz=100), dict(chunk_nnz=2048), dict(chunk_nnz=8), dict(short_len=5000), dict(xcd_remap=2),
+                dict(k_parts=65)):
+        with pytest.raises(gs.GespmmError):
+            plan(**bad)
+    p = plan(lanes_per_row=32, tiles_per_lane=1, xcd_remap=0)
+    assert (p["lanes_per_row"], p["tiles_per_lane"], p["xcd_remap"], p["col_blocks"]) == (32, 1, 0, 1)
+    p = plan(chunk_nnz=1024, short_len=5)
+    assert (p["lanes_per_row"], p["chunk_nnz"], p["short_len"], p["chunks"]) == (8, 1024, 5, 11)
+    assert p["lds_bytes"] == 4 * (1024 + 64) * 8
+    assert gs.gespmm_plan(1000, 64, 10_000)["lanes_per_row"] == 8           # nothing sticks between calls
+
+
+def test_two_threads_with_different_tunings_get_their_own_plans():
+    """Tuning is an argument of the call, not process-wide state: plans computed at the same time from
+    several threads with different overrides never see each other's values."""
+    import threading
+    wrong = []
+
+    def worker(G, chunk):
+        for _ in range(3000):
+            p = gs.gespmm_plan_ex(5000, 5000, 256, 400_000, tuning=dict(lanes_per_row=G, chunk_nnz=chunk))
+            if (p["lanes_per_row"], p["chunk_nnz"]) != (G, chunk):
+                wrong.append((G, chunk, p))
+            q = gs.gespmm_plan_ex(5000, 5000, 256, 400_000)
+            if (q["lanes_per_row"], q["chunk_nnz"]) != (16, 256):
+                wrong.append(("auto", q))
+
+    threads = [threading.Thread(target=worker, args=a) for a in ((8, 64), (32, 1024), (64, 128), (4, 512))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not wrong, wrong[:3]
+
+
+def test_k_phased_path_is_planned_for_large_features_and_long_rows():
+    big = dict(workspace_bytes=1 << 40)
+    p = gs.gespmm_plan_ex(232_965, 232_965, 64, 114_693_532, **big)             # workload 4: B is 60 MB, mean row 492
+    assert p["k_parts"] >= 8 and p["lanes_per_row"] == 16 and p["col_blocks"] == 1 and p["workspace_bytes"] > 0
+    assert p["workspace_bytes"] == gs.gespmm_csr_workspace_bytes(232_965, 232_965, 64, 114_693_532)
+    assert p["workspace_bytes"] >= 4 * p["k_parts"] * (2 * 232_965 + 1)
+    assert gs.gespmm_plan_ex(232_965, 232_965, 64, 114_693_532)["k_parts"] == 1     # no workspace, no phases
+    assert gs.gespmm_plan_ex(232_965, 232_965, 64, 114_693_532, workspace_bytes=1000)["k_parts"] == 1
+    assert gs.gespmm_plan_ex(232_965, 232_965, 64, 114_693_532, tuning=dict(k_parts=1), **big)["k_parts"] == 1
+    assert gs.gespmm_plan_ex(232_965, 232_965, 64, 114_693_532, tuning=dict(k_parts=5), **big)["k_parts"] == 5
+    # short rows or a B that fits the caches: the plain path
+    assert gs.gespmm_plan_ex(1_000_000, 1_000_000, 32, 15_357_733, **big)["k_parts"] == 1
+    assert gs.gespmm_plan_ex(20_000, 20_000, 64, 10_000_000, **big)["k_parts"] == 1
+    assert gs.gespmm_csr_workspace_bytes(1_000_000, 1_000_000, 32, 15_357_733) == 0
 
 
 def test_chunk_size_follows_width_and_problem_size():
@@ -166,6 +210,7 @@ def test_chunk_size_follows_width_and_problem_size():
     # long rows (mean length >= 128): larger chunks, fewer split rows
     assert gs.gespmm_plan(232_965, 64, 114_693_532)["chunk_nnz"] == 512
     assert all(p["lds_bytes"] == 4 * (p["chunk_nnz"] + 64) * 8 for p in plans)
+    assert all(p["chunks"] == -(-(big + 10**6) // p["chunk_nnz"]) for p in plans)
     # small problems: smaller chunks, so the rows spread over more wavefronts
     # (fewer than 2048 wavefronts over all column blocks -> halve, down to 64 entries)
     assert [gs.gespmm_plan(19717, N, 88_648)["chunk_nnz"] for N in (32, 64, 128, 256, 512)] == [64, 64, 128, 128, 256]

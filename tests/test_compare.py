@@ -60,6 +60,20 @@ def test_sum_rejects_non_finite_results(op, poison):
     assert not oracle.compare(op, C, Cref, np.full((3, 4), np.inf))[0]
 
 
+def test_sum_non_finite_references_must_be_matched_exactly():
+    Cref = np.array([[np.inf, -np.inf, np.nan, 1.0]])
+    Sabs = np.array([[np.inf, np.inf, np.inf, 1.0]])
+    good = np.array([[np.inf, -np.inf, np.nan, 1.0]], dtype=np.float32)
+    assert oracle.compare("sum", good, Cref, Sabs) == (True, 0.0)
+    for j, wrong in ((0, -np.inf), (0, np.nan), (0, 3.0e38), (1, np.inf), (1, np.nan), (2, np.inf), (2, 0.0)):
+        bad = good.copy()
+        bad[0, j] = wrong
+        assert not oracle.compare("sum", bad, Cref, Sabs)[0], (j, wrong)
+    bad = good.copy()
+    bad[0, 3] = 1.1                                        # the finite elements are still checked
+    assert not oracle.compare("sum", bad, Cref, Sabs)[0]
+
+
 def test_mean_bound_uses_the_row_length():
     """A row of four entries (1, 2, 3, 4) against ones: sum of magnitudes 10, mean 2.5, and the scale
     of the mean's bound is 10 / 4, so an error of 2.0e-5 passes for sum's scale but fails for mean's."""

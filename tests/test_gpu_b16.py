@@ -23,8 +23,7 @@ def gs():
     import paper_2007_03179_amd as gs
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     gs.lib()
-    yield gs
-    gs.gespmm_set_tuning()
+    return gs
 
 
 def say(*a):
@@ -42,11 +41,14 @@ def narrow(B, dt):
     return Bn, Bn.float().numpy()
 
 
-def check(gs, rp, ci, v, B, dt, op, rows=None, label="", dA=None, dB=None):
+def check(gs, rp, ci, v, B, dt, op, rows=None, label="", dA=None, dB=None, tuning=None, workspace=None):
     say(f"  case {label} {dt} op={op} M={len(rp) - 1} K={B.shape[0]} N={B.shape[1]} nnz={len(ci)}")
     Bn, Bw = narrow(B, dt)
     d_rp, d_ci, d_v = dA if dA is not None else (dev(rp), dev(ci), dev(v))
-    C = gs.gespmm_csr_b16(d_rp, d_ci, d_v, dB if dB is not None else Bn.cuda(), op)
+    if tuning is None and workspace is None:
+        C = gs.gespmm_csr_b16(d_rp, d_ci, d_v, dB if dB is not None else Bn.cuda(), op)
+    else:
+        C = gs.gespmm_csr_ex(d_rp, d_ci, d_v, dB if dB is not None else Bn.cuda(), op, tuning=tuning, workspace=workspace)
     torch.cuda.synchronize()
     C = C.cpu().numpy()
     Cref, Sabs = oracle.spmm(rp, ci, v, Bw, op, rows=rows)
@@ -68,19 +70,32 @@ def test_widths_all_ops(gs, N, dt):
 def test_every_kernel_shape(gs, dt):
     rp, ci, v = graphgen.random_csr(300, 260, 7.0, 56, empty_frac=0.1, long_rows=((11, 900), (12, 300)))
     dA = dev(rp), dev(ci), dev(v)
-    try:
-        for N, vec, shapes in ((136, 4, (1, 2, 4, 8, 16, 32)), (37, 1, (1, 2, 4, 8, 16, 32, 64))):
-            B = graphgen.random_dense(260, N, 56)
-            dB = narrow(B, dt)[0].cuda()
-            for G in shapes:
-                for chunk, short in ((16, 0), (256, -1), (1024, 1024)):
-                    gs.gespmm_set_tuning(G, 1, -1, chunk, short)
-                    plan = gs.gespmm_plan_b16(300, N, len(ci), dt)
-                    assert (plan["vec"], plan["lanes_per_row"], plan["chunk_nnz"]) == (vec, G, chunk)
-                    for op in OPS:
-                        check(gs, rp, ci, v, B, dt, op, dA=dA, dB=dB, label=f"G={G} S={chunk} short={short}")
-    finally:
-        gs.gespmm_set_tuning()
+    for N, vec, shapes in ((136, 4, (1, 2, 4, 8, 16, 32)), (37, 1, (1, 2, 4, 8, 16, 32, 64))):
+        B = graphgen.random_dense(260, N, 56)
+        dB = narrow(B, dt)[0].cuda()
+        for G in shapes:
+            for chunk, short in ((16, 0), (256, -1), (1024, 1024)):
+                tuning = (G, 1, -1, chunk, short)
+                plan = gs.gespmm_plan_ex(300, 260, N, len(ci), dt, tuning=tuning)
+                assert (plan["vec"], plan["lanes_per_row"], plan["chunk_nnz"]) == (vec, G, chunk)
+                for op in OPS:
+                    check(gs, rp, ci, v, B, dt, op, dA=dA, dB=dB, tuning=tuning, label=f"G={G} S={chunk} short={short}")
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+def test_k_phased_path_with_16_bit_features(gs, dt):
+    rp, ci, v = graphgen.random_csr(500, 700, 30.0, 57, empty_frac=0.1, long_rows=((11, 2500),))
+    dA = dev(rp), dev(ci), dev(v)
+    for N in (64, 136):
+        B = graphgen.random_dense(700, N, 57)
+        dB = narrow(B, dt)[0].cuda()
+        for parts, G in ((3, 8), (16, 16), (5, 32)):
+            tuning = dict(k_parts=parts, lanes_per_row=G)
+            need = gs.gespmm_csr_workspace_bytes(500, 700, N, len(ci), dt, tuning=tuning)
+            assert need > 0
+            work = torch.empty(need // 4, dtype=torch.int32, device="cuda")
+            for op in OPS:
+                check(gs, rp, ci, v, B, dt, op, dA=dA, dB=dB, tuning=tuning, workspace=work, label=f"phased parts={parts} G={G}")
 
 
 def test_unaligned_and_special_values(gs):

@@ -21,8 +21,7 @@ def gs():
     import paper_2007_03179_amd as gs
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     gs.lib()
-    yield gs
-    gs.gespmm_set_tuning()
+    return gs
 
 
 def say(*a):
@@ -34,10 +33,13 @@ def dev(x):
     return None if x is None else torch.from_numpy(np.ascontiguousarray(x)).cuda()
 
 
-def check_arg(gs, rp, ci, v, B, op, rows=None, label="", dA=None, dB=None):
+def check_arg(gs, rp, ci, v, B, op, rows=None, label="", dA=None, dB=None, tuning=None):
     say(f"  case arg {label} op={op} M={len(rp) - 1} N={B.shape[1]} nnz={len(ci)}")
     d_rp, d_ci, d_v = dA if dA is not None else (dev(rp), dev(ci), dev(v))
-    C, arg = gs.gespmm_csr_arg(d_rp, d_ci, d_v, dB if dB is not None else dev(B), op)
+    if tuning is None:
+        C, arg = gs.gespmm_csr_arg(d_rp, d_ci, d_v, dB if dB is not None else dev(B), op)
+    else:
+        C, arg = gs.gespmm_csr_arg_ex(d_rp, d_ci, d_v, dB if dB is not None else dev(B), op, tuning=tuning)
     torch.cuda.synchronize()
     C, arg = C.cpu().numpy(), arg.cpu().numpy()
     Cref, aref = oracle.spmm_arg(rp, ci, v, B, op, rows=rows)
@@ -90,14 +92,11 @@ def test_positions_every_launch_shape(gs):
     B = np.round(graphgen.random_dense(260, 72, 56) * 8.0).astype(np.float32)
     dA, dB = (dev(rp), dev(ci), dev(v)), dev(B)
     shapes = [(1, 1), (2, 1), (8, 1), (16, 1), (64, 1), (4, 2), (16, 2), (64, 2), (8, 4), (64, 4)]
-    try:
-        for G, T in shapes:
-            for remap, chunk, short in ((0, 16, 0), (1, 256, -1), (1, 1024, 1024)):
-                gs.gespmm_set_tuning(G, T, remap, chunk, short)
-                for op in ("max", "min"):
-                    check_arg(gs, rp, ci, v, B, op, label=f"G={G} T={T} S={chunk} short={short}", dA=dA, dB=dB)
-    finally:
-        gs.gespmm_set_tuning()
+    for G, T in shapes:
+        for remap, chunk, short in ((0, 16, 0), (1, 256, -1), (1, 1024, 1024)):
+            for op in ("max", "min"):
+                check_arg(gs, rp, ci, v, B, op, label=f"G={G} T={T} S={chunk} short={short}", dA=dA, dB=dB,
+                          tuning=(G, T, remap, chunk, short))
 
 
 def test_positions_unaligned_outputs_take_the_two_pass_route(gs):

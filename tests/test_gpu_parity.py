@@ -28,8 +28,7 @@ def gs():
     import paper_2007_03179_amd as gs
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     gs.lib()                                   # raises if the HIP library was not built
-    yield gs
-    gs.gespmm_set_tuning()
+    return gs
 
 
 # largest error / bound seen for sum and mean in this session: over all cases, and over the
@@ -46,12 +45,17 @@ def dev(x):
     return None if x is None else torch.from_numpy(np.ascontiguousarray(x)).cuda()
 
 
-def check(gs, rowptr, colind, vals, B, op, rows=None, label="", entry="gespmm_csr", dB=None, dA=None):
-    """Run one call on the GPU and compare with the oracle (all rows, or the sampled rows)."""
+def check(gs, rowptr, colind, vals, B, op, rows=None, label="", entry="gespmm_csr", dB=None, dA=None, tuning=None,
+          workspace=None):
+    """Run one call on the GPU and compare with the oracle (all rows, or the sampled rows).  With tuning
+    overrides or a workspace the call goes through gespmm_csr_ex."""
     say(f"  case {label} op={op} M={len(rowptr) - 1} K={B.shape[0]} N={B.shape[1]} nnz={len(colind)}")
     d_rp, d_ci, d_v = dA if dA is not None else (dev(rowptr), dev(colind), dev(vals))
     d_B = dB if dB is not None else dev(B)
-    C = getattr(gs, entry)(d_rp, d_ci, d_v, d_B, op)
+    if tuning is not None or workspace is not None:
+        C = gs.gespmm_csr_ex(d_rp, d_ci, d_v, d_B, op, tuning=tuning, workspace=workspace)
+    else:
+        C = getattr(gs, entry)(d_rp, d_ci, d_v, d_B, op)
     torch.cuda.synchronize()
     C = C.cpu().numpy()
     Cref, Sabs = oracle.spmm(rowptr, colind, vals, B, op, rows=rows)
@@ -152,18 +156,15 @@ def test_every_kernel_shape(gs, vec_n):
     rp, ci, v = graphgen.random_csr(300, 260, 7.0, 55, empty_frac=0.1, long_rows=((11, 900), (12, 300)))
     B = graphgen.random_dense(260, N, 55)
     dA, dB = (dev(rp), dev(ci), dev(v)), dev(B)
-    try:
-        for G, T in KERNEL_SHAPES:
-            for remap, chunk, short in LAUNCH_VARIANTS:
-                gs.gespmm_set_tuning(G, T, remap, chunk, short)
-                plan = gs.gespmm_plan(300, N, len(ci))
-                assert plan["vec"] == vec and plan["lanes_per_row"] == G and plan["tiles_per_lane"] == T
-                assert plan["chunk_nnz"] == chunk and plan["xcd_remap"] == remap
-                for op in ("sum", "mean", "max", "min"):
-                    check(gs, rp, ci, v, B, op, dA=dA, dB=dB,
-                          label=f"G={G} T={T} remap={remap} S={chunk} short={short}")
-    finally:
-        gs.gespmm_set_tuning()
+    for G, T in KERNEL_SHAPES:
+        for remap, chunk, short in LAUNCH_VARIANTS:
+            tuning = (G, T, remap, chunk, short)
+            plan = gs.gespmm_plan_ex(300, 260, N, len(ci), tuning=tuning)
+            assert plan["vec"] == vec and plan["lanes_per_row"] == G and plan["tiles_per_lane"] == T
+            assert plan["chunk_nnz"] == chunk and plan["xcd_remap"] == remap
+            for op in ("sum", "mean", "max", "min"):
+                check(gs, rp, ci, v, B, op, dA=dA, dB=dB, tuning=tuning,
+                      label=f"G={G} T={T} remap={remap} S={chunk} short={short}")
 
 
 def test_unaligned_buffers_take_scalar_path(gs):
@@ -261,11 +262,18 @@ def test_results_do_not_depend_on_what_C_held(gs):
 def test_profile_brackets_main_kernel(gs):
     rp, ci, v = graphgen.random_csr(2000, 2000, 20.0, 2)
     d = dev(rp), dev(ci), dev(v), dev(graphgen.random_dense(2000, 64, 2))
-    gs.gespmm_profile_begin(3)
+    prof = gs.gespmm_profiler_create(3)
     for _ in range(5):
-        gs.gespmm_csr(*d, "sum")
-    ms, n = gs.gespmm_profile_end()
+        gs.gespmm_csr_ex(*d, "sum", profiler=prof)
+    ms, n = gs.gespmm_profiler_finish(prof)
     assert n == 3 and 0 < ms < 1000
+    # the K-phased path brackets every one of its launches
+    prof = gs.gespmm_profiler_create(10)
+    work = torch.empty(gs.gespmm_csr_workspace_bytes(2000, 2000, 64, len(ci), tuning={"k_parts": 4}) // 4,
+                       dtype=torch.int32, device="cuda")
+    gs.gespmm_csr_ex(*d, "sum", workspace=work, tuning={"k_parts": 4}, profiler=prof)
+    ms, n = gs.gespmm_profiler_finish(prof)
+    assert n == 4 and 0 < ms < 1000
 
 
 @pytest.mark.parametrize("floats", [4, 1020, 4 * 256 * 8192 * 4 + 4 * 77, 4 * 256 * 8192 * 9 + 4])
@@ -287,6 +295,84 @@ def test_calibration_gather_reads_every_requested_line(gs):
     assert abs(float(out.double().sum()) - 32.0 * float(idx.double().sum())) <= 1e-6 * 32.0 * float(idx.double().sum())
     with pytest.raises(gs.GespmmError):                       # scratch output too small
         gs.gespmm_calibration_gather(table, idx, out=torch.empty(16, device="cuda"))
+
+
+def _workspace(gs, M, K, N, nnz, tuning, dtype="f32"):
+    need = gs.gespmm_csr_workspace_bytes(M, K, N, nnz, dtype, tuning=tuning)
+    assert need > 0
+    return torch.full((need // 4 + 1,), -12345, dtype=torch.int32, device="cuda")
+
+
+@pytest.mark.parametrize("N", [4, 32, 64, 72, 128, 260])
+def test_k_phased_path_forced_on_small_matrices(gs, N):
+    """The path that runs the operation once per part of the column range, forced on matrices of a few
+    chunks: sorted columns (what it is made for), unsorted columns with repeats (the pieces still
+    partition every row), NULL values, empty rows, rows much longer than a chunk, M != K, parts that hold
+    no entry at all, more parts than columns per row; every op, every slot width it has kernels for."""
+    cases = (graphgen.random_csr(700, 500, 9.0, 300 + N, empty_frac=0.1, long_rows=((350, 3000),)),
+             graphgen.random_csr(400, 900, 40.0, 301 + N, empty_frac=0.05, duplicates=True, sort_cols=False,
+                                 long_rows=((7, 2000), (8, 1))),
+             graphgen.random_csr(50, 30, 2.0, 302 + N, empty_frac=0.5))
+    for which, (rp, ci, v) in enumerate(cases):
+        M, K = len(rp) - 1, (500, 900, 30)[which]
+        if which == 0:                                           # entries only in the lower half of the columns
+            ci = (ci // 2).astype(np.int32)
+        B = graphgen.random_dense(K, N, N + which)
+        dA, dB = (dev(rp), dev(ci), dev(v)), dev(B)
+        for parts, G, chunk in ((2, -1, -1), (3, 8, 64), (7, 16, 256), (64, 32, 16), (5, 16, 1024)):
+            if G > 0 and 4 * G > max(N, 32) * 2:
+                G = -1
+            tuning = dict(k_parts=parts, lanes_per_row=G, chunk_nnz=chunk)
+            plan = gs.gespmm_plan_ex(M, K, N, len(ci), workspace_bytes=1 << 30, tuning=tuning)
+            assert plan["k_parts"] == min(parts, K) and plan["workspace_bytes"] > 0
+            work = _workspace(gs, M, K, N, len(ci), tuning)
+            for op in OPS:
+                check(gs, rp, ci, v, B, op, dA=dA, dB=dB, tuning=tuning, workspace=work,
+                      label=f"phased case={which} parts={parts} G={G} S={chunk}")
+            check(gs, rp, ci, None, B, "sum", dA=(dA[0], dA[1], None), dB=dB, tuning=tuning, workspace=work,
+                  label=f"phased vals=NULL case={which} parts={parts}")
+
+
+def test_k_phased_path_arguments(gs):
+    rp, ci, v = graphgen.random_csr(300, 200, 20.0, 5)
+    d = dev(rp), dev(ci), dev(v), dev(graphgen.random_dense(200, 64, 5))
+    with pytest.raises(gs.GespmmError) as e:                     # phases forced, nowhere to put their row starts
+        gs.gespmm_csr_ex(*d, "sum", tuning={"k_parts": 4})
+    assert e.value.status == 4
+    small = torch.empty(16, dtype=torch.int32, device="cuda")
+    with pytest.raises(gs.GespmmError) as e:
+        gs.gespmm_csr_ex(*d, "sum", tuning={"k_parts": 4}, workspace=small)
+    assert e.value.status == 4
+    # automatic choice on a small problem: the workspace is ignored, the plain path runs
+    assert gs.gespmm_plan_ex(300, 200, 64, len(ci), workspace_bytes=1 << 30)["k_parts"] == 1
+    C = gs.gespmm_csr_ex(*d, "sum", workspace=small)
+    torch.cuda.synchronize()
+    ok, worst = oracle.compare("sum", C.cpu().numpy(), *oracle.spmm(rp, ci, v, graphgen.random_dense(200, 64, 5), "sum"))
+    assert ok, worst
+    # N not a multiple of 4: no phased kernel, the plain path runs whatever is forced
+    assert gs.gespmm_plan_ex(300, 200, 30, len(ci), workspace_bytes=1 << 30, tuning={"k_parts": 4})["k_parts"] == 1
+
+
+def test_non_finite_features_reach_exactly_the_rows_that_use_them(gs):
+    """Algorithm 1 in IEEE arithmetic: an infinite element of B makes the outputs of the rows that store an
+    entry for it infinite (NaN where +inf and -inf meet or a stored zero multiplies it), and no other."""
+    rp, ci, v = graphgen.random_csr(600, 400, 9.0, 88, empty_frac=0.1, long_rows=((30, 2500),))
+    v = np.abs(v) + 0.5                                           # positive weights: inf stays inf
+    B = graphgen.random_dense(400, 40, 88)
+    B[17, :] = np.inf
+    B[200, 3] = -np.inf
+    B[399, 39] = np.inf
+    for op in OPS:
+        C = check(gs, rp, ci, v, B, op, label="inf in B")
+        touched = np.zeros(600, dtype=bool)
+        touched[np.repeat(np.arange(600), np.diff(rp))[np.isin(ci, (17, 200, 399))]] = True
+        assert np.isfinite(C[~touched]).all()
+        assert not np.isfinite(C[touched]).all()
+    v2 = v.copy()
+    v2[rp[30]:rp[30] + 5] = 0.0                                   # stored zeros: 0 * inf = NaN where they meet row 17 of B
+    ci2 = ci.copy()
+    ci2[rp[30]] = 17
+    check(gs, rp, ci2, v2, B, "sum", label="0 * inf")
 
 
 # ------------------------------------------------------------ the workloads --
