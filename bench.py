@@ -442,6 +442,113 @@ def gather_ceiling(gs, torch, case, kernel_ms, plan, reps=10):
             "table_MB": w.K * 128 / 1e6}
 
 
+def gather_sweep(args, gs, torch, graphgen, dev):
+    """What the chip delivers to a plain gather, as a function of the size of the table, the access shape
+    (lanes per row x bytes per lane x rows in flight), the cache policy of the loads and the order of the
+    index stream: uniform random indices, and the colind streams of workloads 4 and 5 in storage order and
+    with the column range cut into parts that are visited one after the other (what the K-phased path does).
+    Rates in G rows per second; table on stderr."""
+    rows = []
+    out = torch.empty(2048 * 256, dtype=torch.float32, device=dev)
+
+    def rate(table, row_bytes, idx, lanes=8, load=16, flight=8, policy=0, reps=5):
+        call = lambda: gs.gespmm_calibration_gather_shape(table, row_bytes, idx, lanes, load, flight, policy, out=out)
+        call(); call()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ev[0].record()
+        for _ in range(reps):
+            call()
+        ev[1].record()
+        torch.cuda.synchronize()
+        return idx.numel() / (ev[0].elapsed_time(ev[1]) / reps * 1e-3) / 1e9
+
+    def note(stream, table_mb, row_bytes, lanes, load, flight, policy, g):
+        rows.append({"stream": stream, "table_MB": table_mb, "row_bytes": row_bytes, "lanes": lanes, "load_bytes": load,
+                     "in_flight": flight, "policy": ("plain", "bypass L1", "non-temporal")[policy], "G_rows_per_s": g})
+
+    def table_of(nrows, row_bytes):
+        return torch.empty(nrows * row_bytes // 4, dtype=torch.float32, device=dev).uniform_(-1, 1)
+
+    def say(text):
+        print(text, file=sys.stderr, flush=True)
+
+    torch.manual_seed(0)
+    n = 32 << 20
+    say("== uniform random indices, rows of 128 bytes, 8 lanes x 16 bytes, 8 in flight: table size x cache policy (G rows/s)")
+    for mb in (1, 2, 3, 4, 6, 8, 16, 32, 64, 128, 256, 512, 1024):
+        nrows = (mb << 20) // 128
+        t, idx = table_of(nrows, 128), torch.randint(0, nrows, (n,), dtype=torch.int32, device=dev)
+        res = [rate(t, 128, idx, policy=p) for p in (0, 1, 2)]
+        for p, g in enumerate(res):
+            note("uniform", mb, 128, 8, 16, 8, p, g)
+        say(f"table {mb:5d} MB: plain {res[0]:7.1f}   bypass L1 {res[1]:7.1f}   non-temporal {res[2]:7.1f}")
+        del t, idx
+    say("== uniform random indices, rows of 128 bytes: lanes x bytes per lane, in flight 2 / 4 / 8 / 16 (G rows/s)")
+    for mb in (2, 32, 512):
+        nrows = (mb << 20) // 128
+        t, idx = table_of(nrows, 128), torch.randint(0, nrows, (n,), dtype=torch.int32, device=dev)
+        for lanes, load in ((8, 16), (16, 8), (32, 4), (4, 16), (2, 16), (4, 8), (8, 4)):
+            res = [rate(t, 128, idx, lanes, load, f) for f in (2, 4, 8, 16)]
+            for f, g in zip((2, 4, 8, 16), res):
+                note("uniform", mb, 128, lanes, load, f, 0, g)
+            say(f"table {mb:4d} MB, {lanes:2d} lanes x {load:2d} B ({lanes*load:3d} B of the row): " + " ".join(f"{g:7.1f}" for g in res))
+        del t, idx
+    for row_bytes, lanes in ((256, 16), (512, 32), (1024, 64)):
+        nrows = (32 << 20) // row_bytes
+        t, idx = table_of(nrows, row_bytes), torch.randint(0, nrows, (n // 2,), dtype=torch.int32, device=dev)
+        res = [rate(t, row_bytes, idx, lanes, 16, f) for f in (2, 4, 8)]
+        for f, g in zip((2, 4, 8), res):
+            note("uniform", 32, row_bytes, lanes, 16, f, 0, g)
+        say(f"table   32 MB, rows of {row_bytes:4d} B, {lanes} lanes x 16 B, in flight 2 / 4 / 8: " + " ".join(f"{g:7.1f}" for g in res))
+        del t, idx
+
+    def cut(colind, K, parts):                          # the stream with part 0 of the column range first, then part 1, ...
+        part = (colind.long() * parts // K).to(torch.int32)
+        return colind[torch.sort(part, stable=True).indices].contiguous()
+
+    w = graphgen.workload("large_dense_degree", args.scale)
+    ci = torch.from_numpy(w.colind).to(dev)
+    say(f"== colind of {w.name} (K = {w.K}, {w.nnz} entries) as the index stream")
+    for row_bytes, lanes in ((128, 8), (256, 16)):
+        t = table_of(w.K, row_bytes)
+        mb = w.K * row_bytes / 1e6
+        for policy in ((0, 1, 2) if row_bytes == 128 else (0,)):
+            res = [rate(t, row_bytes, ci, lanes, 16, f, policy, reps=3) for f in (4, 8, 16)]
+            for f, g in zip((4, 8, 16), res):
+                note(f"{w.name} storage order", mb, row_bytes, lanes, 16, f, policy, g)
+            say(f"rows of {row_bytes} B ({mb:.1f} MB), storage order, {('plain', 'bypass L1', 'non-temporal')[policy]:12s} in flight 4 / 8 / 16: "
+                + " ".join(f"{g:7.1f}" for g in res))
+        for parts in (2, 4, 8, 16, 32, 64):
+            stream = cut(ci, w.K, parts)
+            res = [rate(t, row_bytes, stream, lanes, 16, f, reps=3) for f in (8, 16)]
+            for f, g in zip((8, 16), res):
+                note(f"{w.name} cut in {parts} parts", mb, row_bytes, lanes, 16, f, 0, g)
+            say(f"rows of {row_bytes} B, column range cut in {parts:2d} parts of {mb/parts:6.2f} MB, in flight 8 / 16: "
+                + " ".join(f"{g:7.1f}" for g in res))
+            del stream
+        del t
+    del ci
+    w = graphgen.workload("skew_narrow", args.scale)
+    ci = torch.from_numpy(w.colind).to(dev)
+    say(f"== colind of {w.name} (K = {w.K}, {w.nnz} entries) as the index stream")
+    for row_bytes, shapes in ((32, ((2, 16), (4, 8), (8, 4))), (128, ((8, 16),))):
+        t = table_of(w.K, row_bytes)
+        mb = w.K * row_bytes / 1e6
+        for lanes, load in shapes:
+            res = [rate(t, row_bytes, ci, lanes, load, f) for f in (4, 8, 16)]
+            for f, g in zip((4, 8, 16), res):
+                note(f"{w.name} storage order", mb, row_bytes, lanes, load, f, 0, g)
+            say(f"rows of {row_bytes:3d} B ({mb:.0f} MB), storage order, {lanes} lanes x {load:2d} B, in flight 4 / 8 / 16: "
+                + " ".join(f"{g:7.1f}" for g in res))
+        for parts in (4, 16, 64):
+            g = rate(t, row_bytes, cut(ci, w.K, parts), shapes[0][0], shapes[0][1], 8)
+            note(f"{w.name} cut in {parts} parts", mb, row_bytes, shapes[0][0], shapes[0][1], 8, 0, g)
+            say(f"rows of {row_bytes:3d} B, column range cut in {parts:2d} parts, in flight 8: {g:7.1f}")
+        del t
+    return rows
+
+
 def geomean(xs):
     import math
     xs = [x for x in xs if x]
@@ -520,6 +627,8 @@ def main():
                     help="with --suite: time torch's CSR matmul (vendor sparse library) beside each case")
     ap.add_argument("--tile-study", action="store_true",
                     help="also time every lanes-per-row x tiles-per-lane kernel shape on four matrices (Table VI's question)")
+    ap.add_argument("--gather-sweep", action="store_true",
+                    help="also map out the rate of plain gathers over table size, access shape, cache policy and index order")
     ap.add_argument("--gradients", action="store_true",
                     help="also time the gradient-side entry points (positions, transposed, pooling gradient)")
     ap.add_argument("--copy-gib", type=float, default=0.0,
@@ -575,6 +684,7 @@ def main():
     gcn_rows = gcn_share(args, gs, torch, graphgen, dev) if args.gcn else None
     suite_out = shape_suite(args, gs, torch, graphgen, dev) if args.suite else None
     tile_rows = tile_study(args, gs, torch, graphgen, dev) if args.tile_study else None
+    gather_rows = gather_sweep(args, gs, torch, graphgen, dev) if args.gather_sweep else None
 
     if args.mtx:
         w = graphgen.workload_from_matrix_market(args.mtx)
@@ -659,6 +769,8 @@ def main():
         out["suite"] = suite_out
     if tile_rows is not None:
         out["tile_study"] = tile_rows
+    if gather_rows is not None:
+        out["gather_sweep"] = gather_rows
     print(json.dumps(out), flush=True)
     if "parity" in out and not out["parity"]["ok"]:
         print("bench.py: the timed run's output does NOT match the oracle", file=sys.stderr)

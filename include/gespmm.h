@@ -327,6 +327,18 @@ int gespmm_calibration_copy(const void* src, void* dst, int64_t bytes, void* str
 int gespmm_calibration_gather(const void* table, int64_t table_lines, const int32_t* idx, int64_t n,
                               void* out, int64_t out_bytes, void* stream);
 
+/*
+ * The same yardstick with its shape as arguments, for mapping out what the chip delivers: n times,
+ * lanes_per_row lanes read load_bytes (4, 8 or 16) each of row idx[e] of `table` (rows row_bytes apart,
+ * table_bytes in all, below 4 GB, 16-byte aligned; lanes_per_row * load_bytes <= row_bytes), in_flight
+ * (2, 4, 8 or 16) rows in flight per lane.  cache_policy: 0 plain loads; 1 loads that bypass the L1;
+ * 2 non-temporal loads (1 and 2 exist for 8 lanes x 16 bytes only).  `out`: 2048 * 256 * 4 bytes of scratch
+ * output.  GESPMM_ERR_BAD_ARG for a shape that is not instantiated.  Values in idx are not validated.
+ */
+int gespmm_calibration_gather_shape(const void* table, int64_t table_bytes, int row_bytes, const int32_t* idx,
+                                    int64_t n, int lanes_per_row, int load_bytes, int in_flight,
+                                    int cache_policy, void* out, int64_t out_bytes, void* stream);
+
 /* Static text for a status code (never NULL). */
 const char* gespmm_status_string(int status);
 

@@ -235,44 +235,6 @@ __global__ void __launch_bounds__(kBlock) init_rows(int32_t M, int32_t N, const 
   }
 }
 
-// ------------------------------------------------------- calibration copy --
-// Plain 16-byte-per-lane copy of a known size: the yardstick that hardware traffic
-// counters (FETCH_SIZE / WRITE_SIZE) are scaled by.
-static __global__ void __launch_bounds__(kBlock) copy_f4(const float4* __restrict__ src, float4* __restrict__ dst, int64_t n4) {
-  const int64_t stride = (int64_t)gridDim.x * kBlock;
-  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  for (; i + 3 * stride < n4; i += 4 * stride) {   // four independent 16-byte loads in flight per lane
-    const float4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-    dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
-  }
-  for (; i < n4; i += stride) dst[i] = src[i];
-}
-
-// Plain gather of 128-byte lines: 8 lanes read line idx[e] of the table (16 bytes each), eight
-// gathers in flight per lane, indices read coalesced; every group of 8 lanes folds what it read
-// into one float4 so that the loads stay live.  It does what the chunk kernel's inner loop does
-// to memory and nothing else, so its rate is the ceiling for that loop on a table of that size.
-static __global__ void __launch_bounds__(kBlock) gather_lines(const float4* __restrict__ table, const int32_t* __restrict__ idx,
-                                                              int64_t n, float4* __restrict__ out) {
-  const int g = threadIdx.x & 7;
-  const int64_t group = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> 3;
-  const int64_t groups = ((int64_t)gridDim.x * kBlock) >> 3;
-  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int64_t e = group * 8; e < n; e += groups * 8) {
-    int k[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) k[u] = idx[e + u < n ? e + u : n - 1];
-    float4 v[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = table[(int64_t)k[u] * 8 + g];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      if (e + u < n) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }   // padded gathers do not count
-    }
-  }
-  out[(int64_t)blockIdx.x * kBlock + threadIdx.x] = acc;
-}
-
 // ------------------------------------------------------------ chunk kernel --
 // The walk over chunks, rows and row segments is the same for every job; what is done
 // with a row segment is a policy:

@@ -123,6 +123,8 @@ def lib():
         L.gespmm_calibration_copy.argtypes = [vp, vp, i64, vp]
         L.gespmm_calibration_gather.restype = ci
         L.gespmm_calibration_gather.argtypes = [vp, i64, vp, i64, vp, i64, vp]
+        L.gespmm_calibration_gather_shape.restype = ci
+        L.gespmm_calibration_gather_shape.argtypes = [vp, i64, ci, vp, i64, ci, ci, ci, ci, vp, i64, vp]
         L.gespmm_status_string.restype = ctypes.c_char_p
         L.gespmm_status_string.argtypes = [ci]
         L.gespmm_version.restype = ci
@@ -349,6 +351,21 @@ def gespmm_plan(M, N, nnz, aligned16=True) -> dict:
     p = gespmm_plan_t()
     _check(lib().gespmm_plan(M, N, nnz, int(bool(aligned16)), ctypes.byref(p)))
     return {name: int(getattr(p, name)) for name, _ in p._fields_ if name != "reserved"}
+
+
+def gespmm_calibration_gather_shape(table, row_bytes, idx, lanes_per_row=8, load_bytes=16, in_flight=8, cache_policy=0,
+                                    out=None, stream=None):
+    """idx.numel() gathers of rows of `table` (a contiguous CUDA tensor cut into rows of row_bytes) with the
+    given access shape; returns the scratch output tensor."""
+    import torch
+    nbytes = table.numel() * table.element_size()
+    assert table.is_cuda and table.is_contiguous() and idx.is_cuda and idx.dtype == torch.int32 and idx.is_contiguous()
+    if out is None:
+        out = torch.empty(2048 * 256, dtype=torch.float32, device=table.device)
+    _check(lib().gespmm_calibration_gather_shape(_ptr(table), nbytes, int(row_bytes), _ptr(idx), idx.numel(),
+                                                 int(lanes_per_row), int(load_bytes), int(in_flight), int(cache_policy),
+                                                 _ptr(out), out.numel() * out.element_size(), _stream(stream)))
+    return out
 
 
 def gespmm_plan_ex(M, K, N, nnz, b_dtype="f32", aligned16=True, workspace_bytes=0, tuning=None) -> dict:

@@ -3,6 +3,7 @@
 // fills the launch descriptions and owns no device code of its own.
 #include "gespmm_kernels.hpp"
 #include "gespmm_sort.hpp"
+#include "gespmm_calibration.hpp"
 
 #include <mutex>
 #include <new>
@@ -453,6 +454,25 @@ int gespmm_calibration_gather(const void* table, int64_t table_lines, const int3
   if (out_bytes < blocks * kBlock * 16) return GESPMM_ERR_BAD_ARG;
   hipLaunchKernelGGL(gather_lines, dim3((unsigned)blocks), dim3(kBlock), 0, (hipStream_t)stream_,
                      (const float4*)table, idx, n, (float4*)out);
+  return hipGetLastError() == hipSuccess ? GESPMM_OK : GESPMM_ERR_HIP;
+}
+
+int gespmm_calibration_gather_shape(const void* table, int64_t table_bytes, int row_bytes, const int32_t* idx, int64_t n,
+                                    int lanes_per_row, int load_bytes, int in_flight, int cache_policy, void* out,
+                                    int64_t out_bytes, void* stream_) {
+  if (table_bytes < 0 || n < 0 || out_bytes < 0 || row_bytes <= 0 || row_bytes % 4 != 0) return GESPMM_ERR_BAD_ARG;
+  if (n == 0) return GESPMM_OK;
+  if (!table || !idx || !out) return GESPMM_ERR_NULL;
+  if (load_bytes != 4 && load_bytes != 8 && load_bytes != 16) return GESPMM_ERR_BAD_ARG;
+  if (lanes_per_row <= 0 || (int64_t)lanes_per_row * load_bytes > row_bytes) return GESPMM_ERR_BAD_ARG;
+  if (table_bytes < row_bytes || table_bytes % row_bytes != 0 || table_bytes >= (4ll << 30)) return GESPMM_ERR_BAD_ARG;
+  if ((((uintptr_t)table | (uintptr_t)out) & 15u) != 0 || row_bytes % load_bytes != 0) return GESPMM_ERR_BAD_ARG;
+  GatherKernel kernel = pick_gather(lanes_per_row, load_bytes / 4, in_flight, cache_policy);
+  if (!kernel) return GESPMM_ERR_BAD_ARG;
+  const int64_t blocks = 256 * 8;                  // eight workgroups per compute unit
+  if (out_bytes < blocks * kBlock * 4) return GESPMM_ERR_BAD_ARG;
+  hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(kBlock), 0, (hipStream_t)stream_, (const char*)table,
+                     (uint32_t)table_bytes, row_bytes, idx, n, (float*)out);
   return hipGetLastError() == hipSuccess ? GESPMM_OK : GESPMM_ERR_HIP;
 }
 
