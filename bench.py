@@ -632,7 +632,10 @@ def main():
     ap.add_argument("--gradients", action="store_true",
                     help="also time the gradient-side entry points (positions, transposed, pooling gradient)")
     ap.add_argument("--copy-gib", type=float, default=0.0,
-                    help="launch the calibration copy kernel once on this many GiB (traffic-counter yardstick)")
+                    help="launch the calibration copy kernel on this many GiB (traffic-counter yardstick)")
+    ap.add_argument("--copy-reps", type=int, default=1,
+                    help="with --copy-gib: launch the copy this many times on the same buffers (a small buffer copied "
+                         "repeatedly stays in the Infinity Cache: tells cache hits from HBM accesses in the counters)")
     ap.add_argument("--b-dtype", default="f32", choices=("f32", "bf16", "f16"),
                     help="storage type of the dense input B (arithmetic and C stay fp32); f32 is the paper's setting")
     ap.add_argument("--tuning", default="",
@@ -667,9 +670,10 @@ def main():
         src = torch.ones(n, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
-        gs.gespmm_calibration_copy(src, dst)
+        for _ in range(max(1, args.copy_reps)):
+            gs.gespmm_calibration_copy(src, dst)
         torch.cuda.synchronize()
-        print(f"# calibration copy: {n * 4} bytes read, {n * 4} bytes written", file=sys.stderr)
+        print(f"# calibration copy: {n * 4} bytes read, {n * 4} bytes written, {max(1, args.copy_reps)} time(s)", file=sys.stderr)
         del src, dst
 
     evictor = None if args.no_cold else Evictor(gs, torch, dev)
