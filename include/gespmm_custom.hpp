@@ -12,8 +12,8 @@
 //   };
 //   int status = gespmm::csr_custom<SumOfSquares>(M, K, N, nnz, rowptr, colind, vals, B, C, stream);
 //
-// Requirements (Section IV-A: "the parallel execution requires the reduction function to be
-// associative and commutative"): merge is associative and commutative, identity() is its neutral
+// Requirements (Section IV-A asks for an associative and commutative reduce, because partial results are
+// combined in parallel): merge is associative and commutative, identity() is its neutral
 // element, and step(acc, a, b) == merge(acc, step(identity(), a, b)).  Arguments, layout,
 // ownership and error codes are those of gespmm_csr (include/gespmm.h); an empty row yields 0;
 // rows that are split across wavefronts are combined with a compare-and-swap loop around merge.

@@ -261,8 +261,8 @@ int spmm_oracle_csr_transpose(int64_t M, int64_t K, const int32_t* rowptr, const
 }
 
 /*
- * The general SpMM-like operation with a user-supplied initial value and fold (Eq. 1 and
- * Section IV-A: "an initialization function and a reduce function"): for every output,
+ * The general SpMM-like operation with a user-supplied initial value and fold (Eq. 1; Section
+ * IV-A lets the user supply the initial value and the reduce step): for every output,
  * start from `init` and fold the stored entries of the row in storage order with
  * `step(acc, stored value, B element)`, all in double.  An empty row yields 0.  Serial:
  * the fold may be a callback into an interpreter.

@@ -1,5 +1,6 @@
-"""The SpMM-like operation as a PyTorch autograd function (paper: Section IV-B, "wrap the kernel
-inside a custom autograd function ... an aggregation step on the graph").
+"""The SpMM-like operation as a PyTorch autograd function: the paper embeds its kernel in the framework
+as an operator that carries its own gradient definition and is used as the aggregation step of a GNN layer
+(Section IV-B).
 
 Thin glue over the C ABI: the forward pass is gespmm_csr (sum, mean) or gespmm_csr_arg (max, min);
 the backward pass with respect to the dense features is gespmm_csr on the transposed arrays

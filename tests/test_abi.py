@@ -216,6 +216,8 @@ def test_chunk_size_follows_width_and_problem_size():
     assert [gs.gespmm_plan(19717, N, 88_648)["chunk_nnz"] for N in (32, 64, 128, 256, 512)] == [64, 64, 128, 128, 256]
     assert gs.gespmm_plan(2708, 16, 10_556)["chunk_nnz"] == 64
     assert gs.gespmm_plan(65_536, 512, 649_959)["chunk_nnz"] == 256
+    # ... unless the rows are long: every chunk a row crosses costs its outputs one more rounding
+    assert gs.gespmm_plan(2, 8, 100_000)["chunk_nnz"] == 512
     # mean row of 17 .. 48 entries: one slot per row up to 32 entries
     assert [gs.gespmm_plan(262_144, N, 6_859_000)["short_len"] for N in (32, 128, 512)] == [32, 32, 32]
     assert gs.gespmm_plan(100_000, 128, 1_600_000)["short_len"] == 16
