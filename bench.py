@@ -32,10 +32,21 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 # run and one WRITE_SIZE run, each scaled by the calibration copy kernel of known size;
 # the summaries are under profiles/).  Key: "<workload>/N<width>/<op>".  Missing = null.
 # Each entry: (bytes per CALL summed over the call's main-kernel launches, the launch shape it was measured
-# with).  A run whose shape differs reports traffic null: the number would describe another kernel.
+# with, the summary under profiles/).  A run whose shape matches none of a workload's entries reports traffic
+# null: the number would describe another kernel.
 MEASURED_TRAFFIC_BYTES = {
+    "large_dense_degree/N64/sum": [
+        (12.0637e9, "vec=4 G=16 T=1 S=512 col_blocks=1 k_parts=8", "chunk_kernel_large_dense_degree_N64_sum.md"),
+        (23.0407e9, "vec=4 G=8 T=1 S=512 col_blocks=2 k_parts=1", "chunk_kernel_large_dense_degree_N64_sum_plain_path.md")],
+    "general_ops/N128/sum": [(1.00217e9, "vec=4 G=8 T=1 S=256 col_blocks=4 k_parts=1", "chunk_kernel_general_ops_N128_sum.md")],
+    "skew_narrow/N8/sum": [(0.638577e9, "vec=4 G=2 T=1 S=512 col_blocks=1 k_parts=1", "chunk_kernel_skew_narrow_N8_sum.md")],
+    "skew_narrow/N32/sum": [(1.21140e9, "vec=4 G=8 T=1 S=256 col_blocks=1 k_parts=1", "chunk_kernel_skew_narrow_N32_sum.md")],
+    "width_sweep/N512/sum": [(0.189019e9, "vec=4 G=16 T=1 S=256 col_blocks=8 k_parts=1", "chunk_kernel_width_sweep_N512_sum.md")],
+    "uniform_512k_d4/N128/sum": [(1.41339e9, "vec=4 G=8 T=1 S=256 col_blocks=4 k_parts=1", "chunk_kernel_uniform_512k_d4_N128_sum.md")],
 }
 MEASURED_TRAFFIC_BYTES_BF16 = {
+    "large_dense_degree/N64/sum": [
+        (6.97594e9, "vec=4 G=16 T=1 S=512 col_blocks=1 k_parts=4", "chunk_kernel_large_dense_degree_N64_bf16_sum.md")],
 }
 
 
@@ -49,12 +60,12 @@ def measured_traffic(table, key, plan):
     when it was measured with another launch shape than today's plan."""
     if key not in table:
         return None
-    nbytes, shape = table[key]
-    if shape != plan_string(plan):
-        print(f"bench.py: the traffic profile of {key} was measured with [{shape}], today's plan is "
-              f"[{plan_string(plan)}]: traffic reported as null", file=sys.stderr)
-        return None
-    return nbytes
+    for nbytes, shape, _ in table[key]:
+        if shape == plan_string(plan):
+            return nbytes
+    print(f"bench.py: the traffic profiles of {key} were measured with {[e[1] for e in table[key]]}, today's plan is "
+          f"[{plan_string(plan)}]: traffic reported as null", file=sys.stderr)
+    return None
 
 
 B_ELEM_BYTES = 4                # 2 with --b-dtype bf16 / f16 (B stored in 16 bits; arithmetic and C stay fp32)

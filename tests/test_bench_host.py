@@ -34,13 +34,22 @@ def test_every_profile_names_its_command_and_measured_traffic_agrees():
     import bench
     import re
     prof = os.path.join(ROOT, "profiles")
-    for key, value in {**bench.MEASURED_TRAFFIC_BYTES,
-                       **{k + "/bf16": v for k, v in bench.MEASURED_TRAFFIC_BYTES_BF16.items()}}.items():
-        name, width, op = key.split("/")[:3]
-        fname = f"chunk_kernel_{name}_{width}{'_bf16' if key.endswith('/bf16') else ''}_{op}.md"
-        text = open(os.path.join(prof, fname)).read()
-        assert "rocprofv3 --kernel-trace --stats" in text and "rocprofv3 --pmc FETCH_SIZE" in text
-        total = float(re.search(r"total ([0-9.]+) GB", text).group(1)) * 1e9
-        assert abs(total - value) <= 0.002 * value, (key, total, value)
+    for table in (bench.MEASURED_TRAFFIC_BYTES, bench.MEASURED_TRAFFIC_BYTES_BF16):
+        for key, entries in table.items():
+            for value, shape, fname in entries:
+                text = open(os.path.join(prof, fname)).read()
+                assert "rocprofv3 --kernel-trace --stats" in text and "rocprofv3 --pmc FETCH_SIZE" in text
+                assert shape in text, (key, shape)                      # the summary was made with this launch shape
+                total = float(re.search(r"total ([0-9.]+) GB", text).group(1)) * 1e9
+                assert abs(total - value) <= 0.002 * value, (key, total, value)
     for f in os.listdir(prof):
         assert f.endswith((".md", ".txt")) and os.path.getsize(os.path.join(prof, f)) < 20_000
+
+
+def test_traffic_is_null_for_a_launch_shape_without_a_profile():
+    import bench
+    plan = dict(vec=4, lanes_per_row=16, tiles_per_lane=1, chunk_nnz=512, col_blocks=1, k_parts=8)
+    assert bench.measured_traffic(bench.MEASURED_TRAFFIC_BYTES, "large_dense_degree/N64/sum", plan) == 12.0637e9
+    plan["k_parts"] = 9
+    assert bench.measured_traffic(bench.MEASURED_TRAFFIC_BYTES, "large_dense_degree/N64/sum", plan) is None
+    assert bench.measured_traffic(bench.MEASURED_TRAFFIC_BYTES, "no_such_workload/N1/sum", plan) is None
