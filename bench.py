@@ -431,26 +431,34 @@ def tile_study(args, gs, torch, graphgen, dev):
 
 
 def gather_ceiling(gs, torch, case, kernel_ms, plan, reps=10):
-    """Rate of the plain line-gather kernel on this workload's own index stream (colind, in storage order)
-    over a table shaped like the live slice of B (K lines of 128 bytes), next to the lines per second the
-    chunk kernel itself gathers.  fp32 only (one 128-byte line per entry and column block of 32 floats)."""
+    """Rate of the plain gather yardstick on this workload's own index stream (colind, in storage order) with
+    the kernel's own access shape (rows of one column block of B, the slot's lanes, 16 bytes per lane, eight
+    in flight), next to the rows per second the chunk kernel itself gathers.  fp32 with the vector kernels only."""
     w = case.w
-    table = torch.empty((w.K, 32), dtype=torch.float32, device=case.B.device).uniform_(-1, 1)
-    out = gs.gespmm_calibration_gather(table, case.ci)
+    if plan["vec"] != 4:
+        return None
+    lanes = plan["lanes_per_row"]
+    row_bytes = 16 * lanes * plan["tiles_per_lane"]                      # one column block of a row of B
+    lanes = min(lanes, 64)
+    table = torch.empty((w.K, row_bytes // 4), dtype=torch.float32, device=case.B.device).uniform_(-1, 1)
+    try:
+        out = gs.gespmm_calibration_gather_shape(table, row_bytes, case.ci, lanes, 16, 8)
+    except gs.GespmmError:                                               # no yardstick of that shape
+        return None
     for _ in range(2):
-        gs.gespmm_calibration_gather(table, case.ci, out=out)
+        gs.gespmm_calibration_gather_shape(table, row_bytes, case.ci, lanes, 16, 8, out=out)
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     ev[0].record()
     for _ in range(reps):
-        gs.gespmm_calibration_gather(table, case.ci, out=out)
+        gs.gespmm_calibration_gather_shape(table, row_bytes, case.ci, lanes, 16, 8, out=out)
     ev[1].record()
     torch.cuda.synchronize()
     ms = ev[0].elapsed_time(ev[1]) / reps
-    lines = w.nnz * plan["col_blocks"] * max(1, plan["vec"] * plan["lanes_per_row"] * plan["tiles_per_lane"] // 32)
-    return {"gather_only_G_lines_per_s": w.nnz / (ms * 1e-3) / 1e9,
-            "gather_only_GBps": w.nnz * 132 / (ms * 1e-3) / 1e9,          # 128-byte line + 4-byte index
-            "chunk_kernel_G_lines_per_s": lines / (kernel_ms * 1e-3) / 1e9,
-            "table_MB": w.K * 128 / 1e6}
+    rows = w.nnz * plan["col_blocks"]
+    return {"row_bytes": row_bytes, "gather_only_G_rows_per_s": w.nnz / (ms * 1e-3) / 1e9,
+            "chunk_kernel_G_rows_per_s": rows / (kernel_ms * 1e-3) / 1e9,
+            "index_order": "colind as stored (the K-phased path visits it part by part; see profiles/gather_ceiling_sweep.md)",
+            "table_MB": w.K * row_bytes / 1e6}
 
 
 def gather_sweep(args, gs, torch, graphgen, dev):
@@ -744,7 +752,7 @@ def main():
         # The byte model bills every gathered row of B as memory traffic although the caches serve most of
         # them, so the fraction can exceed 1; frac_compulsory counts B once and is a lower bound on what
         # must cross HBM.  What actually bounds the kernel is the rate at which L2 and fabric deliver
-        # 128-byte lines (see gather_ceiling and the design doc).
+        # 128-byte lines (gather_ceiling below gives the rate of a plain gather of the same rows).
         "roofline": {"bound": "hbm", "bound_note": "byte model; B is served from L2 / Infinity Cache, not HBM",
                      "kernel": "chunk_kernel<FoldRows>", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
