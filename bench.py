@@ -22,6 +22,8 @@ import os
 import sys
 import time
 
+import numpy as np
+
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
@@ -52,7 +54,8 @@ MEASURED_TRAFFIC_BYTES_BF16 = {
 
 def plan_string(plan):
     return (f"vec={plan['vec']} G={plan['lanes_per_row']} T={plan['tiles_per_lane']} S={plan['chunk_nnz']} "
-            f"col_blocks={plan['col_blocks']} k_parts={plan['k_parts']}")
+            f"col_blocks={plan['col_blocks']} k_parts={plan['k_parts']}"
+            + (f" row_window={plan['row_window']}" if plan.get("row_window") else ""))
 
 
 def measured_traffic(table, key, plan):
@@ -86,12 +89,25 @@ B_TORCH_DTYPE = None
 B_DTYPE_NAME = "f32"
 TUNING = None                   # --tuning: per-call overrides handed to every forward call
 USE_WORKSPACE = True            # --no-workspace: never hand the forward call a workspace (no K-phased path)
+ROW_BOUND = True                # --no-row-bound: do not tell the forward call how long the longest row of the matrix is
+
+TUNING_FIELDS = ("lanes_per_row", "tiles_per_lane", "xcd_remap", "chunk_nnz", "short_len", "k_parts", "longest_row")
 
 
-def forward(gs):
-    """The forward call as benchmarked: gespmm_csr_ex with the case's workspace and the --tuning overrides."""
+def case_tuning(w):
+    """The --tuning overrides plus what a caller knows about its graph: the length of the longest row (a
+    property GNN frameworks keep with the graph, like the degrees; it lets short-row matrices take the
+    single-launch whole-row path)."""
+    t = dict(zip(TUNING_FIELDS, TUNING)) if TUNING else {}
+    if ROW_BOUND and t.get("longest_row", -1) < 0 and w.M:
+        t["longest_row"] = int(np.diff(w.rowptr).max())
+    return t or None
+
+
+def forward(gs, tuning=None):
+    """The forward call as benchmarked: gespmm_csr_ex with the case's workspace and tuning."""
     def call(rp, ci, v, B, op, C=None, stream=None, workspace=None, profiler=None):
-        return gs.gespmm_csr_ex(rp, ci, v, B, op, C=C, workspace=workspace, tuning=TUNING, profiler=profiler, stream=stream)
+        return gs.gespmm_csr_ex(rp, ci, v, B, op, C=C, workspace=workspace, tuning=tuning, profiler=profiler, stream=stream)
     return call
 
 
@@ -124,7 +140,7 @@ def time_graph_replay(gs, torch, case, op, steps, calls_per_graph=20):
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=side):
         for _ in range(calls_per_graph):
-            forward(gs)(case.rp, case.ci, case.v, case.B, op, C=case.C, workspace=case.work)
+            forward(gs, case.tuning)(case.rp, case.ci, case.v, case.B, op, C=case.C, workspace=case.work)
     replays = max(1, steps // calls_per_graph)
     graph.replay()
     torch.cuda.synchronize()
@@ -151,10 +167,11 @@ class DeviceCase:
         self.C = torch.empty((w.M, N), dtype=torch.float32, device=dev)
         self.work = None                                 # workspace of the K-phased path, when the plan wants one
         import paper_2007_03179_amd as gs
-        need = gs.gespmm_csr_workspace_bytes(w.M, w.K, N, w.nnz, B_DTYPE_NAME, tuning=TUNING) if USE_WORKSPACE else 0
+        self.tuning = case_tuning(w)
+        need = gs.gespmm_csr_workspace_bytes(w.M, w.K, N, w.nnz, B_DTYPE_NAME, tuning=self.tuning) if USE_WORKSPACE else 0
         if need:
             self.work = torch.empty(need // 4 + 1, dtype=torch.int32, device=dev)
-        self.plan = gs.gespmm_plan_ex(w.M, w.K, N, w.nnz, B_DTYPE_NAME, workspace_bytes=need, tuning=TUNING)
+        self.plan = gs.gespmm_plan_ex(w.M, w.K, N, w.nnz, B_DTYPE_NAME, workspace_bytes=need, tuning=self.tuning)
 
     def time(self, gs, torch, op, steps, warmup, bracket_kernel=True):
         """Time `steps` whole calls.  With bracket_kernel the library also records a HIP event
@@ -163,13 +180,13 @@ class DeviceCase:
         only matters for microsecond-scale workloads)."""
         stream = torch.cuda.current_stream()
         for _ in range(warmup):
-            forward(gs)(self.rp, self.ci, self.v, self.B, op, C=self.C, stream=stream, workspace=self.work)
+            forward(gs, self.tuning)(self.rp, self.ci, self.v, self.B, op, C=self.C, stream=stream, workspace=self.work)
         torch.cuda.synchronize()
         launches_per_call = self.plan["k_parts"]         # main-kernel launches one call makes
         prof = gs.gespmm_profiler_create(steps * launches_per_call) if bracket_kernel else None
         t0 = time.perf_counter()
         for _ in range(steps):
-            forward(gs)(self.rp, self.ci, self.v, self.B, op, C=self.C, stream=stream, workspace=self.work, profiler=prof)
+            forward(gs, self.tuning)(self.rp, self.ci, self.v, self.B, op, C=self.C, stream=stream, workspace=self.work, profiler=prof)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         main_ms_sum, launches = gs.gespmm_profiler_finish(prof) if bracket_kernel else (float("nan"), 0)
@@ -224,7 +241,7 @@ def per_call_times(gs, torch, case, op, calls, before_each=None):
             before_each()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record(stream)
-        forward(gs)(case.rp, case.ci, case.v, case.B, op, C=case.C, stream=stream, workspace=case.work)
+        forward(gs, case.tuning)(case.rp, case.ci, case.v, case.B, op, C=case.C, stream=stream, workspace=case.work)
         b.record(stream)
         pairs.append((a, b))
     torch.cuda.synchronize()
@@ -398,9 +415,9 @@ def tile_study(args, gs, torch, graphgen, dev):
     cases = (("uniform_random_65k", 512), ("general_ops", 128), ("grid3d_64", 128), ("large_dense_degree", 64))
     for name, N in cases:
         w = graphgen.suite_matrix(name) if name in graphgen.SUITE_NAMES else graphgen.workload(name, args.scale)
-        global TUNING, USE_WORKSPACE
-        saved = TUNING, USE_WORKSPACE
-        USE_WORKSPACE = False                            # the study is about the plain kernel's shape
+        global TUNING, USE_WORKSPACE, ROW_BOUND
+        saved = TUNING, USE_WORKSPACE, ROW_BOUND
+        USE_WORKSPACE = ROW_BOUND = False                # the study is about the plain kernel's shape
         auto = gs.gespmm_plan(w.M, N, w.nnz)
         steps = max(20, min(args.steps, int(2e11 / (w.nnz * N))))
         try:
@@ -425,7 +442,7 @@ def tile_study(args, gs, torch, graphgen, dev):
                           + ("   <- automatic" if is_auto else ""), file=sys.stderr, flush=True)
                     del case
         finally:
-            TUNING, USE_WORKSPACE = saved
+            TUNING, USE_WORKSPACE, ROW_BOUND = saved
         torch.cuda.empty_cache()
     return rows
 
@@ -658,10 +675,13 @@ def main():
     ap.add_argument("--b-dtype", default="f32", choices=("f32", "bf16", "f16"),
                     help="storage type of the dense input B (arithmetic and C stay fp32); f32 is the paper's setting")
     ap.add_argument("--tuning", default="",
-                    help="lanes_per_row,tiles_per_lane,xcd_remap,chunk_nnz,short_len,k_parts override, e.g. "
+                    help="lanes_per_row,tiles_per_lane,xcd_remap,chunk_nnz,short_len,k_parts,longest_row override, e.g. "
                          "--tuning=-1,-1,0,512,16,8 (each -1 = automatic)")
     ap.add_argument("--no-workspace", action="store_true",
                     help="never hand the forward call a workspace: the K-phased path stays off")
+    ap.add_argument("--no-row-bound", action="store_true",
+                    help="do not pass the length of the matrix's longest row (tuning.longest_row): the whole-row "
+                         "path stays off and every call is init_rows + chunk kernel")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -673,7 +693,7 @@ def main():
     import paper_2007_03179_amd as gs
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    global B_ELEM_BYTES, B_TORCH_DTYPE, B_DTYPE_NAME, TUNING, USE_WORKSPACE
+    global B_ELEM_BYTES, B_TORCH_DTYPE, B_DTYPE_NAME, TUNING, USE_WORKSPACE, ROW_BOUND
     if args.b_dtype != "f32":
         B_ELEM_BYTES, B_TORCH_DTYPE = 2, {"bf16": torch.bfloat16, "f16": torch.float16}[args.b_dtype]
         B_DTYPE_NAME = args.b_dtype
@@ -683,6 +703,7 @@ def main():
     if args.tuning:
         TUNING = tuple(int(x) for x in args.tuning.split(","))
     USE_WORKSPACE = not args.no_workspace
+    ROW_BOUND = not args.no_row_bound
 
     if args.copy_gib > 0:
         n = int(args.copy_gib * (1 << 30)) // 16 * 4

@@ -224,6 +224,13 @@ int gespmm_pool_backward(int64_t M, int64_t K, int64_t N, int64_t nnz, const int
  * [0, 1024] (0 = every row is handled by all slots together), k_parts in [0, 64] (parts the
  * column range is cut into by the K-phased path of gespmm_csr_ex; 0 or 1 = off).  A value that
  * has no kernel makes the call return GESPMM_ERR_BAD_ARG.
+ * longest_row is not an override but something the caller may know about the matrix: an upper
+ * bound on the stored entries of any row (-1 or 0 = not known).  With it the forward call on fp32
+ * features can take the WHOLE-ROW path when rows are short against a chunk (or the problem is
+ * small): every row is computed by one wavefront and written once, so the call is a single kernel
+ * launch without presetting and without atomics, and sum / mean become independent of the order in
+ * which wavefronts finish.  The bound only selects the path: the result is right whatever it says;
+ * a row much longer than stated is walked by one wavefront alone and is slow.
  */
 typedef struct {
   int32_t lanes_per_row;
@@ -232,6 +239,7 @@ typedef struct {
   int32_t chunk_nnz;
   int32_t short_len;
   int32_t k_parts;
+  int32_t longest_row;
 } gespmm_tuning_t;
 
 /*
@@ -253,7 +261,7 @@ typedef struct {
   int32_t short_len;      /* row segments up to this length are handled one per slot      */
   int32_t lds_bytes;      /* dynamic LDS per workgroup                                    */
   int32_t k_parts;        /* main-kernel launches per call: 1, or the parts of the K-phased path */
-  int32_t reserved;
+  int32_t row_window;     /* whole-row path: entries a wavefront stages at once (S + longest row); 0 = rows are split among chunks */
   int64_t workspace_bytes; /* workspace the K-phased path needs for this shape (0 when k_parts == 1) */
 } gespmm_plan_t;
 

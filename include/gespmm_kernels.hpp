@@ -79,6 +79,7 @@ struct KernelArgs {
   int32_t packed_split;   // fused value+position pass: split rows collect (value, position) pairs in 64-bit slots
   int32_t accumulate;     // K-phased path: fold the row's result into what C already holds
   int32_t taper_chunks;   // K-phased path: this many chunks at the end of a launch hold S / 4 items only
+  int32_t row_window;     // whole-row path: entries one wavefront's LDS slice holds (>= S)
 };
 
 // Entry p of row r is item p + r of the merged sequence of entries and row ends; chunk c owns the
@@ -310,6 +311,17 @@ struct FoldRows {
       for (int t = 0; t < T; ++t)
 #pragma unroll
         for (int x = 0; x < V; ++x) s.acc[t].v[x] = fold2<F>(s.acc[t].v[x], __shfl_xor(s.acc[t].v[x], off, kWave));
+  }
+
+  // A row without stored entries yields 0 (whole-row path, where no other kernel presets it).
+  __device__ static void store_empty(const KernelArgs& a, int64_t row, const int (&col)[T]) {
+    float* crow = a.C + row * (int64_t)a.N;
+    Vec<V> zero;
+#pragma unroll
+    for (int x = 0; x < V; ++x) zero.v[x] = 0.0f;
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+      if (col[t] < a.N) zero.store(crow + col[t]);
   }
 
   // Plain store when the whole row lay in this chunk, atomics otherwise (the row was
@@ -818,8 +830,17 @@ template <int F, int V, int T, class BT> struct FlightDivisor<FoldArgRows<F, V, 
 // `delta[r]` turns a virtual position of row r into the stored position, the number of chunks is
 // read from the device, a wavefront takes chunks c, c + (wavefronts launched), ... and the result
 // of a row is folded into C.
-template <class P, int V, int G, int T, bool kPhased>
+// kOwned: the whole-row path.  A row belongs to the chunk that owns its FIRST item (its first entry, or
+// its end when it stores nothing) and that chunk's wavefront walks all of it, also the part that lies
+// beyond the chunk's own items: every row is written exactly once, by plain stores, empty rows
+// included, so nothing has to be preset and nothing is combined by atomics: one launch per call.
+// The LDS slice holds `row_window` >= S entries; with the longest row L of the matrix, S + L entries
+// cover everything a chunk can own.  A row that still reaches beyond the slice is necessarily the
+// last one the chunk owns and is walked in windows, each staged over the slice: correct for any
+// matrix, fast when rows are short against S.
+template <class P, int V, int G, int T, bool kPhased, bool kOwned = false>
 __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
+  static_assert(!(kPhased && kOwned), "a phase folds into C; the whole-row path writes every row once");
   constexpr int NS = kWave / G;                 // slots
   constexpr int kFlight = loads_in_flight(G) / FlightDivisor<P>::value;
   constexpr int U = kFlight / T > 0 ? kFlight / T : 1;   // entries per lane per pass
@@ -830,8 +851,9 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
   const int slot = lane / G;
   const int g = lane % G;
   const int S = 1 << a.chunk_shift;
-  int2* ka = s_dyn + wave * (S + (kPhased ? 2 : 1) * kWave);
-  int2* short_rows = ka + S;
+  const int slice = kOwned ? a.row_window : S;  // entries the LDS slice of this wavefront holds
+  int2* ka = s_dyn + wave * (slice + (kPhased ? 2 : 1) * kWave);
+  int2* short_rows = ka + slice;
   int2* row_info = short_rows + kWave;          // kPhased only: (row start relative to the chunk's first entry, delta)
 
   // column tiles of this lane (loads use a clamped column so they are never masked)
@@ -882,8 +904,8 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
     }
     const int64_t r0 = lo;
     const int cs = (int)(d0 - r0);                 // first entry the chunk can own (rowptr[r0] <= cs <= rowptr[r0 + 1])
-    const int cnt = (int)(end_entry - cs < S ? end_entry - cs : S);   // entries [cs, cs + cnt) cover everything it owns
-    if (cnt <= 0) {                                // only the ends of trailing empty rows: nothing to compute
+    const int cnt = (int)(end_entry - cs < slice ? end_entry - cs : slice);   // entries [cs, cs + cnt) cover everything it owns
+    if (!kOwned && cnt <= 0) {                     // only the ends of trailing empty rows: nothing to compute
       if (!kPhased) break;
       continue;
     }
@@ -899,36 +921,35 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
     int next_s, next_e, next_delta = 0;
     load_bounds(r0, next_s, next_e, next_delta);
 
-    // (2) plain path: coalesced load of the entries [cs, cs + cnt) into this wavefront's LDS slice, in
-    //     groups of four loads per array (indices past the end repeat the last entry; those copies are
-    //     never consumed).  The K-phased path stages its entries batch by batch below.
-    if (!kPhased) {
-      for (int u0 = 0; u0 < cnt; u0 += 4 * kWave) {
-        int k[4];
-        float v[4];
+    // (2) plain path: coalesced load of the entries [cs, cs + cnt) into this wavefront's LDS slice.
+    //     The K-phased path stages its entries batch by batch below.
+    auto stage = [&](int from, int count) {        // entries [from, from + count) -> ka[0 .. count), count <= slice
+      // up to eight loads per array are issued before the first is waited for (a whole chunk of 512 in one
+      // round trip); a group of 64 that lies wholly beyond `count` is skipped (the test is wave-uniform)
+      for (int u0 = 0; u0 < count; u0 += 8 * kWave) {
+        int k[8];
+        float v[8];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < 8; ++u) {
           const int idx = u0 + u * kWave + lane;
-          k[u] = a.colind[cs + (idx < cnt ? idx : cnt - 1)];
-        }
-        if (a.vals) {
-#pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            const int idx = u0 + u * kWave + lane;
-            v[u] = a.vals[cs + (idx < cnt ? idx : cnt - 1)];
-          }
-        } else {
-#pragma unroll
-          for (int u = 0; u < 4; ++u) v[u] = 1.0f;
+          k[u] = 0;
+          if (u0 + u * kWave < count) k[u] = a.colind[from + (idx < count ? idx : count - 1)];
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < 8; ++u) {
           const int idx = u0 + u * kWave + lane;
-          if (idx < S) ka[idx] = make_int2(k[u], __float_as_int(v[u]));
+          v[u] = 1.0f;
+          if (a.vals && u0 + u * kWave < count) v[u] = a.vals[from + (idx < count ? idx : count - 1)];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int idx = u0 + u * kWave + lane;
+          if (idx < count) ka[idx] = make_int2(k[u], __float_as_int(v[u]));
         }
       }
       wave_lds_fence();
-    }
+    };
+    if (!kPhased) stage(cs, cnt);
 
     // (3) walk the rows that have entries among the chunk's items
     for (int64_t rbase = r0;; rbase += kWave) {
@@ -939,13 +960,24 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
 
       const int64_t rr = rbase + lane;
       const int64_t limit = d1 - rr;                       // the chunk owns the row's entries below this number ...
-      const int own_s = my_s > cs ? my_s : cs;             // ... and from this one on
-      const int own_e = (int64_t)my_e <= limit ? my_e : (limit > own_s ? (int)limit : own_s);
-      const bool my_whole = own_s == my_s && own_e == my_e;
-      const bool valid = rr < a.M && own_e > own_s && !(P::kCanSkipWholeRows && a.only_split && my_whole);
+      int own_s = my_s > cs ? my_s : cs;                   // ... and from this one on
+      int own_e = (int64_t)my_e <= limit ? my_e : (limit > own_s ? (int)limit : own_s);
+      bool my_whole = own_s == my_s && own_e == my_e;
+      bool valid = rr < a.M && own_e > own_s && !(P::kCanSkipWholeRows && a.only_split && my_whole);
+      bool is_empty = false;                               // whole-row path: a row of this chunk without entries
+      if (kOwned) {
+        const int64_t first_item_of_row = (int64_t)my_s + rr;
+        const bool mine = rr < a.M && first_item_of_row >= d0 && first_item_of_row < d1;
+        own_s = my_s;
+        own_e = my_e;
+        my_whole = true;
+        valid = mine && my_e > my_s;
+        is_empty = mine && my_e == my_s;
+      }
       const int my_ps = own_s - cs;                        // the row's segment inside the chunk,
       const int my_pe = own_e - cs;                        // as offsets into the LDS slice
-      const bool is_short = NS > 1 && valid && (my_pe - my_ps) <= a.short_len;
+      // (whole-row path: a row counts as short only when the slice holds all of it; an empty one is a short row of length 0)
+      const bool is_short = NS > 1 && ((valid && (my_pe - my_ps) <= a.short_len && (!kOwned || my_pe <= slice)) || is_empty);
 
       if (kPhased) {
         // stage the entries of this batch's segments: they are consecutive virtual positions [bs, be);
@@ -988,8 +1020,10 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
         const int nshort = __builtin_popcountll(smask);
         if (nshort > 0) {
           const int rank = __builtin_amdgcn_mbcnt_hi((unsigned)(smask >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)smask, 0u));
+          // an empty row's offset is only ever used for padded gathers: it is moved onto a staged entry
+          const int desc_ps = is_empty ? (my_ps < cnt ? my_ps : (cnt > 0 ? cnt - 1 : 0)) : my_ps;
           if (is_short)   // lane | offset << 6 | length << 18 | whole << 30 ; full row length
-            short_rows[rank] = make_int2(lane | (my_ps << 6) | ((my_pe - my_ps) << 18) | ((int)my_whole << 30), my_e - my_s);
+            short_rows[rank] = make_int2(lane | (desc_ps << 6) | ((my_pe - my_ps) << 18) | ((int)my_whole << 30), my_e - my_s);
           wave_lds_fence();
           for (int t0 = 0; t0 < nshort; t0 += NS) {
             const bool have = t0 + slot < nshort;
@@ -1010,14 +1044,19 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
                 it += U;
               }
             }
-            if (have) P::end(st, a, row, (d.x >> 30) & 1, d.y, col);
+            if constexpr (kOwned) {
+              if (have && r_len == 0) P::store_empty(a, row, col);
+              else if (have) P::end(st, a, row, true, d.y, col);
+            } else {
+              if (have) P::end(st, a, row, (d.x >> 30) & 1, d.y, col);
+            }
           }
           wave_lds_fence();
         }
       }
 
       // (3b) long segments: all slots work on one row, slot s takes entries s, s+NS, ...
-      unsigned long long todo = __ballot(valid && !is_short);
+      unsigned long long todo = __ballot((valid || is_empty) && !is_short);
       while (todo) {
         const int i = __builtin_ctzll(todo);
         todo &= todo - 1;
@@ -1027,6 +1066,30 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
         const int e = __builtin_amdgcn_readlane(my_e, i);
         const bool whole = __builtin_amdgcn_readlane((int)my_whole, i) != 0;
         typename P::State st;
+        if constexpr (kOwned) {
+          if (e == s) {                                      // (only reached when a slot is the whole wavefront)
+            if (slot == 0) P::store_empty(a, rbase + i, col);
+            continue;
+          }
+          if (pe > slice) {
+            // the row reaches beyond the staged entries: it is the last row of this chunk (every later row
+            // starts beyond the chunk's items), so the slice can be reused for windows of the row
+            P::begin(st, a, rbase + i, e - s, colc);
+            for (int w = s; w < e; w += slice) {
+              const int wn = e - w < slice ? e - w : slice;
+              wave_lds_fence();                              // earlier reads of the slice are done
+              stage(w, wn);
+              for (int base = 0; base < wn; base += U * NS) {
+                const int first = base + slot;
+                const int left = (wn - first + NS - 1) / NS;
+                P::template pass<U>(st, a, ka, w, left > 0 ? first : wn - 1, NS, left, col, colc);
+              }
+            }
+            P::template combine<G>(st);
+            if (slot == 0) P::end(st, a, rbase + i, true, e - s, col);
+            continue;
+          }
+        }
         P::begin(st, a, rbase + i, e - s, colc);
         for (int base = ps; base < pe; base += U * NS) {
           const int first = base + slot;
@@ -1310,6 +1373,23 @@ MainKernel pick_phased(int job, int vec, int G, int T) {
   return nullptr;
 }
 
+// Kernels of the whole-row path: the three folds on fp32 features, one tile per lane.
+inline bool has_owned_kernel(int G, int T) { return T == 1 && G >= 1 && G <= kWave; }
+
+inline MainKernel pick_owned(int job, int vec, int G, int T) {
+  if (T != 1) return nullptr;
+#define GESPMM_CASE(FF, VV, GG) if (job == FF && vec == VV && G == GG) return chunk_kernel<FoldRows<FF, VV, 1, float>, VV, GG, 1, false, true>;
+#define GESPMM_SHAPES(FF)                                                                              \
+  GESPMM_CASE(FF, 4, 1) GESPMM_CASE(FF, 4, 2) GESPMM_CASE(FF, 4, 4) GESPMM_CASE(FF, 4, 8) GESPMM_CASE(FF, 4, 16) \
+  GESPMM_CASE(FF, 4, 32) GESPMM_CASE(FF, 4, 64)                                                        \
+  GESPMM_CASE(FF, 1, 1) GESPMM_CASE(FF, 1, 2) GESPMM_CASE(FF, 1, 4) GESPMM_CASE(FF, 1, 8) GESPMM_CASE(FF, 1, 16) \
+  GESPMM_CASE(FF, 1, 32) GESPMM_CASE(FF, 1, 64)
+  GESPMM_SHAPES(kAdd) GESPMM_SHAPES(kMax) GESPMM_SHAPES(kMin)
+#undef GESPMM_SHAPES
+#undef GESPMM_CASE
+  return nullptr;
+}
+
 inline bool has_kernel(int G, int T) { return pick_gt<AddRows, 4>(G, T) != nullptr; }
 
 inline int next_pow2(int64_t x) {
@@ -1321,6 +1401,7 @@ inline int next_pow2(int64_t x) {
 // Per-call overrides of the automatic launch shape (-1 = automatic), checked copy of gespmm_tuning_t.
 struct Tuning {
   int g = -1, t = -1, remap = -1, shift = -1, short_len = -1, k_parts = -1;
+  int longest_row = -1;       // the caller's upper bound on the stored entries of a row; -1 = not known
 };
 
 inline int parse_tuning(const gespmm_tuning_t* in, Tuning* out) {
@@ -1345,6 +1426,7 @@ inline int parse_tuning(const gespmm_tuning_t* in, Tuning* out) {
   out->shift = shift;
   out->short_len = in->short_len >= 0 ? in->short_len : -1;
   out->k_parts = in->k_parts >= 0 ? (in->k_parts < 2 ? 1 : in->k_parts) : -1;
+  out->longest_row = in->longest_row > 0 ? in->longest_row : -1;
   return GESPMM_OK;
 }
 
@@ -1387,8 +1469,9 @@ inline int choose_parts(int64_t M, int64_t K, int64_t nnz, int vec, int block_by
 
 // elem_bytes: size of one element of the dense input (4, or 2 for the 16-bit formats); a lane
 // loads four columns at once when the width and the alignment allow it, one otherwise.
+// whole_rows_allowed: the job has kernels of the whole-row path (the forward folds on fp32 features).
 inline void make_plan(int64_t M, int64_t K, int64_t N, int64_t nnz, bool aligned16, int elem_bytes, const Tuning& tune,
-                      size_t workspace_bytes, gespmm_plan_t* p) {
+                      size_t workspace_bytes, gespmm_plan_t* p, bool whole_rows_allowed = true) {
   int vec = 1;
   if (aligned16 && N > 0) vec = N % 4 == 0 ? 4 : 1;        // 16-byte loads of fp32, 8-byte loads of 16-bit elements
   const int64_t ncv = N > 0 ? (N + vec - 1) / vec : 1;     // vector columns to cover
@@ -1453,7 +1536,24 @@ inline void make_plan(int64_t M, int64_t K, int64_t N, int64_t nnz, bool aligned
   int auto_short = 2 * p->slots < 16 ? 2 * p->slots : 16;
   if (mean_row > 16 && mean_row <= 48) auto_short = 32;
   p->short_len = tune.short_len >= 0 ? tune.short_len : auto_short;
-  p->lds_bytes = (int32_t)(kWavesPerBlock * (p->chunk_nnz + (parts > 1 ? 2 : 1) * kWave) * sizeof(int2));
+  // The whole-row path (one launch, no presetting, no atomics) when the caller has said how long the
+  // longest row is and that is short against a chunk: a wavefront then walks at most S + L entries
+  // instead of S.  For problems that do not fill the chip anyway (where the second launch is a large
+  // share of the call) rows of up to 1024 entries are accepted.  The hint only selects the path and
+  // sizes the LDS slice; the result is right whatever it says.
+  p->row_window = 0;
+  if (whole_rows_allowed && parts == 1 && tune.longest_row > 0 && has_owned_kernel(G, T)) {
+    const int64_t waves = ((items + p->chunk_nnz - 1) >> shift) * col_blocks;
+    const bool small = waves <= 2 * kMinWaves;
+    const int64_t accepted = small ? (p->chunk_nnz > 1024 ? p->chunk_nnz : 1024) : p->chunk_nnz;
+    // (a large matrix whose mean row is below 8 has so few rows on chunk borders that nothing is gained: measured
+    //  -3 % on a 5-point stencil of 10^6 rows, +-1 % on a uniform graph of mean degree 4, against +5 .. +14 % on
+    //  27-point stencils and graphs of mean degree 10)
+    if (tune.longest_row <= accepted && (small || nnz / M >= 8)) p->row_window = p->chunk_nnz + tune.longest_row;
+    if (p->row_window > 1984) p->row_window = 0;   // 64 KB of LDS per workgroup; offsets into the slice are kept in 12 bits
+  }
+  const int slice = p->row_window > 0 ? p->row_window : p->chunk_nnz;
+  p->lds_bytes = (int32_t)(kWavesPerBlock * (slice + (parts > 1 ? 2 : 1) * kWave) * sizeof(int2));
   p->k_parts = parts;
   p->workspace_bytes = parts > 1 ? (int64_t)phased_workspace_bytes(M, parts) : 0;
   if (parts > 1) {
@@ -1652,7 +1752,8 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
     tune.k_parts = 1;
   }
   gespmm_plan_t plan;
-  make_plan(L.M, L.K, L.N, L.nnz, aligned16, L.b_dtype == GESPMM_F32 ? 4 : 2, tune, L.workspace_bytes, &plan);
+  const bool whole_rows_allowed = fold_job && L.b_dtype == GESPMM_F32 && L.init_target == L.dense_out && !L.init2_target;
+  make_plan(L.M, L.K, L.N, L.nnz, aligned16, L.b_dtype == GESPMM_F32 ? 4 : 2, tune, L.workspace_bytes, &plan, whole_rows_allowed);
   if (L.one_lane_per_entry) {
     plan.vec = 1;
     plan.lanes_per_row = 1;
@@ -1679,16 +1780,17 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
   else if (L.b_dtype == GESPMM_BF16) kernel = pick_b16<bf16_t>(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
   else if (L.b_dtype == GESPMM_F16) kernel = pick_b16<f16_t>(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
   else kernel = pick_kernel(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
+  if (plan.row_window > 0) kernel = pick_owned(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
   if (!kernel) return GESPMM_ERR_BAD_ARG;
 
-  // (a) empty rows and rows shared by several chunks are preset
-  if (L.init_target) {
+  // (a) empty rows and rows shared by several chunks are preset (the whole-row path writes every row itself)
+  if (L.init_target && plan.row_window == 0) {
     launch_init_rows(plan.vec, L.M, L.N, L.rowptr, L.init_target, L.empty_value, L.split_value, shift, stream);
     if (L.init2_target)
       launch_init_rows(plan.vec, L.M, L.N, L.rowptr, L.init2_target, L.empty2_value, L.split2_value, shift, stream);
     if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
   }
-  if (L.nnz == 0) return GESPMM_OK;
+  if (L.nnz == 0 && plan.row_window == 0) return GESPMM_OK;
 
   // (b) the chunks
   KernelArgs a{};
@@ -1713,6 +1815,7 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
   a.only_split = L.only_split ? 1 : 0;
   a.packed_split = L.packed_split ? 1 : 0;
   a.accumulate = 0;
+  a.row_window = plan.row_window;
   if (L.packed_split && (plan.vec != 4 || L.N > kWave * kFinishWords || !L.arg)) return GESPMM_ERR_BAD_ARG;
   int status = GESPMM_OK;
   bool timed = false;

@@ -2,10 +2,13 @@
 as an operator that carries its own gradient definition and is used as the aggregation step of a GNN layer
 (Section IV-B).
 
-Thin glue over the C ABI: the forward pass is gespmm_csr (sum, mean) or gespmm_csr_arg (max, min);
-the backward pass with respect to the dense features is gespmm_csr on the transposed arrays
+Thin glue over the C ABI: the forward pass is gespmm_csr_ex (sum, mean) or gespmm_csr_arg (max, min);
+the backward pass with respect to the dense features is gespmm_csr_ex on the transposed arrays
 (built once per graph by gespmm_csr_transpose_sorted and cached) or gespmm_pool_backward.  The edge
-values are treated as constants (no gradient), as in the paper's operator.
+values are treated as constants (no gradient), as in the paper's operator.  The graph object keeps what a
+framework knows about its graph anyway and the library can use: the length of the longest row of either
+orientation (read back once; it selects the single-launch whole-row path on graphs of short rows) and a
+workspace per feature width (it enables the K-phased path on graphs of long rows and wide feature tables).
 """
 from __future__ import annotations
 
@@ -24,6 +27,8 @@ class CsrGraph:
         self.rowptr, self.colind, self.vals = rowptr.contiguous(), colind.contiguous(), vals
         self.M, self.K = rowptr.numel() - 1, int(K)
         self._transposed = {}
+        self._longest = {}
+        self._workspaces = {}
 
     def transposed(self, mean: bool):
         """(rowptrT, colindT, valsT); with mean weights val / row length when `mean`."""
@@ -31,6 +36,23 @@ class CsrGraph:
             self._transposed[mean] = _b.gespmm_csr_transpose_sorted(self.rowptr, self.colind, self.vals, self.K,
                                                                     scale_by_row_length=mean)
         return self._transposed[mean]
+
+    def aggregate(self, B, op, transposed=False):
+        """The forward call on A (or, for the gradient of sum / mean, on the transposed arrays) with the hints
+        and the workspace this graph keeps.  The workspace of one (orientation, width, type) is reused by every
+        call: calls on one graph are assumed to be issued on one stream, as autograd issues them."""
+        rowptr, colind, vals = self.transposed(op == "mean") if transposed else (self.rowptr, self.colind, self.vals)
+        rows, cols = (self.K, self.M) if transposed else (self.M, self.K)
+        if transposed not in self._longest:            # one read-back per orientation
+            self._longest[transposed] = int((rowptr[1:] - rowptr[:-1]).max().item()) if rows else 0
+        tuning = {"longest_row": self._longest[transposed]}
+        dtype = {torch.float32: "f32", torch.bfloat16: "bf16", torch.float16: "f16"}[B.dtype]
+        key = (transposed, B.shape[1], dtype)
+        if key not in self._workspaces:
+            need = _b.gespmm_csr_workspace_bytes(rows, cols, B.shape[1], colind.numel(), dtype, tuning=tuning)
+            self._workspaces[key] = torch.empty(need // 4 + 1, dtype=torch.int32, device=B.device) if need else None
+        return _b.gespmm_csr_ex(rowptr, colind, vals, B, "sum" if transposed else op, workspace=self._workspaces[key],
+                                tuning=tuning)
 
 
 class _SpMM(torch.autograd.Function):
@@ -43,7 +65,7 @@ class _SpMM(torch.autograd.Function):
             ctx.save_for_backward(arg)
             ctx.mark_non_differentiable(arg)
             return C
-        return _b.gespmm_csr_b16(graph.rowptr, graph.colind, graph.vals, B, op)
+        return graph.aggregate(B, op)
 
     @staticmethod
     def backward(ctx, dC):
@@ -53,8 +75,7 @@ class _SpMM(torch.autograd.Function):
             (arg,) = ctx.saved_tensors
             dB = _b.gespmm_pool_backward(graph.colind, graph.vals, arg, dC, graph.K)
         else:
-            rowptrT, colindT, valsT = graph.transposed(op == "mean")
-            dB = _b.gespmm_csr(rowptrT, colindT, valsT, dC, "sum")
+            dB = graph.aggregate(dC, op, transposed=True)
         return dB.to(ctx.b_dtype), None, None
 
 

@@ -30,20 +30,20 @@ class gespmm_plan_t(ctypes.Structure):
                 ("chunks", ctypes.c_int64), ("grid_x", ctypes.c_int64),
                 ("block_threads", ctypes.c_int32), ("xcd_remap", ctypes.c_int32),
                 ("short_len", ctypes.c_int32), ("lds_bytes", ctypes.c_int32),
-                ("k_parts", ctypes.c_int32), ("reserved", ctypes.c_int32), ("workspace_bytes", ctypes.c_int64)]
+                ("k_parts", ctypes.c_int32), ("row_window", ctypes.c_int32), ("workspace_bytes", ctypes.c_int64)]
 
 
 class gespmm_tuning_t(ctypes.Structure):
     _fields_ = [("lanes_per_row", ctypes.c_int32), ("tiles_per_lane", ctypes.c_int32),
                 ("xcd_remap", ctypes.c_int32), ("chunk_nnz", ctypes.c_int32),
-                ("short_len", ctypes.c_int32), ("k_parts", ctypes.c_int32)]
+                ("short_len", ctypes.c_int32), ("k_parts", ctypes.c_int32), ("longest_row", ctypes.c_int32)]
 
 
 def _tuning(t):
-    """None, a gespmm_tuning_t, a dict of field names, or up to six numbers in field order (-1 = automatic)."""
+    """None, a gespmm_tuning_t, a dict of field names, or up to seven numbers in field order (-1 = automatic)."""
     if t is None or isinstance(t, gespmm_tuning_t):
         return t
-    out = gespmm_tuning_t(-1, -1, -1, -1, -1, -1)
+    out = gespmm_tuning_t(-1, -1, -1, -1, -1, -1, -1)
     if isinstance(t, dict):
         for name, value in t.items():
             if name not in dict(gespmm_tuning_t._fields_):
@@ -217,7 +217,7 @@ def gespmm_csr_arg_b16(rowptr, colind, vals, B, op, C=None, arg=None, stream=Non
 def gespmm_plan_b16(M, N, nnz, b_dtype="bf16", aligned16=True) -> dict:
     p = gespmm_plan_t()
     _check(lib().gespmm_plan_b16(M, N, nnz, int(bool(aligned16)), DTYPES[b_dtype], ctypes.byref(p)))
-    return {name: int(getattr(p, name)) for name, _ in p._fields_ if name != "reserved"}
+    return {name: int(getattr(p, name)) for name, _ in p._fields_}
 
 
 def gespmm_csr_simple(rowptr, colind, vals, B, op, C=None, stream=None):
@@ -350,7 +350,7 @@ def gespmm_pool_backward(colind, vals, arg, dC, K, dB=None, stream=None):
 def gespmm_plan(M, N, nnz, aligned16=True) -> dict:
     p = gespmm_plan_t()
     _check(lib().gespmm_plan(M, N, nnz, int(bool(aligned16)), ctypes.byref(p)))
-    return {name: int(getattr(p, name)) for name, _ in p._fields_ if name != "reserved"}
+    return {name: int(getattr(p, name)) for name, _ in p._fields_}
 
 
 def gespmm_calibration_gather_shape(table, row_bytes, idx, lanes_per_row=8, load_bytes=16, in_flight=8, cache_policy=0,
@@ -373,7 +373,7 @@ def gespmm_plan_ex(M, K, N, nnz, b_dtype="f32", aligned16=True, workspace_bytes=
     p = gespmm_plan_t()
     _check(lib().gespmm_plan_ex(M, K, N, nnz, int(bool(aligned16)), DTYPES[b_dtype], int(workspace_bytes),
                                 _tuning_ref(tuning), ctypes.byref(p)))
-    return {name: int(getattr(p, name)) for name, _ in p._fields_ if name != "reserved"}
+    return {name: int(getattr(p, name)) for name, _ in p._fields_}
 
 
 def gespmm_csr_workspace_bytes(M, K, N, nnz, b_dtype="f32", tuning=None) -> int:

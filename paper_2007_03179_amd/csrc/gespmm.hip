@@ -24,7 +24,7 @@ int gespmm_plan_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, int aligned16, 
   Tuning tune;
   const int parsed = parse_tuning(tuning, &tune);
   if (parsed != GESPMM_OK) return parsed;
-  make_plan(M, K, N, nnz, aligned16 != 0, element_bytes(b_dtype), tune, workspace_bytes, out);
+  make_plan(M, K, N, nnz, aligned16 != 0, element_bytes(b_dtype), tune, workspace_bytes, out, b_dtype == GESPMM_F32);
   return GESPMM_OK;
 }
 

@@ -202,6 +202,26 @@ def test_k_phased_path_is_planned_for_large_features_and_long_rows():
     assert gs.gespmm_csr_workspace_bytes(1_000_000, 1_000_000, 32, 15_357_733) == 0
 
 
+def test_whole_row_path_is_planned_only_from_a_bound_on_the_longest_row():
+    plan = gs.gespmm_plan_ex
+    assert plan(19_717, 19_717, 128, 88_648)["row_window"] == 0                       # nothing known: rows are split
+    assert plan(19_717, 19_717, 128, 88_648, tuning=dict(longest_row=0))["row_window"] == 0
+    p = plan(19_717, 19_717, 128, 88_648, tuning=dict(longest_row=173))               # a small problem: up to 1024
+    assert p["row_window"] == p["chunk_nnz"] + 173 and p["lds_bytes"] == 4 * (p["row_window"] + 64) * 8
+    assert plan(19_717, 19_717, 128, 88_648, tuning=dict(longest_row=1025))["row_window"] == 0
+    # a problem that fills the chip: only rows that are short against a chunk, and a mean row of at least 8
+    p = plan(1_000_000, 1_000_000, 128, 10_000_000, tuning=dict(longest_row=27))
+    assert p["chunk_nnz"] == 256 and p["row_window"] == 256 + 27
+    assert plan(1_000_000, 1_000_000, 128, 10_000_000, tuning=dict(longest_row=256))["row_window"] == 512
+    assert plan(1_000_000, 1_000_000, 128, 10_000_000, tuning=dict(longest_row=257))["row_window"] == 0
+    assert plan(1_000_000, 1_000_000, 128, 5_000_000, tuning=dict(longest_row=5))["row_window"] == 0
+    # the K-phased path and 16-bit features keep their own kernels; LDS per workgroup stays within 64 KB
+    assert plan(232_965, 232_965, 64, 114_693_532, workspace_bytes=1 << 40, tuning=dict(longest_row=100))["row_window"] == 0
+    assert plan(19_717, 19_717, 128, 88_648, "bf16", tuning=dict(longest_row=173))["row_window"] == 0
+    assert plan(1000, 1000, 64, 10_000, tuning=dict(longest_row=1000, chunk_nnz=1024))["row_window"] == 0
+    assert plan(1000, 1000, 64, 10_000, tuning=dict(longest_row=960, chunk_nnz=1024))["row_window"] == 1984
+
+
 def test_chunk_size_follows_width_and_problem_size():
     big = 100_000_000
     plans = [gs.gespmm_plan(10**6, N, big) for N in (8, 16, 32, 64, 128, 512)]

@@ -375,6 +375,82 @@ def test_non_finite_features_reach_exactly_the_rows_that_use_them(gs):
     check(gs, rp, ci2, v2, B, "sum", label="0 * inf")
 
 
+# --------------------------------------------------------- whole-row path --
+@pytest.mark.parametrize("N", [1, 4, 7, 16, 32, 64, 72, 128, 256, 260, 512])
+def test_whole_row_path_on_small_matrices(gs, N):
+    """The single-launch path chosen through tuning.longest_row: every row is written once by the chunk that
+    owns its first item.  True bounds and bounds that understate the longest row (then the row is walked in
+    windows), runs of empty rows inside, before and after the entries, rows far longer than a chunk, unsorted
+    repeated columns, NULL values, every op, every chunk size and slot width, and a C that held garbage."""
+    cases = (graphgen.random_csr(700, 500, 9.0, 500 + N, empty_frac=0.1, long_rows=((350, 900),)),
+             graphgen.random_csr(400, 900, 40.0, 501 + N, empty_frac=0.05, duplicates=True, sort_cols=False,
+                                 long_rows=((7, 3000), (8, 1), (399, 1500))),
+             graphgen.random_csr(3000, 64, 1.0, 502 + N, empty_frac=0.9),
+             graphgen.random_csr(300, 300, 5.0, 503 + N))
+    for which, (rp, ci, v) in enumerate(cases):
+        M, K = len(rp) - 1, (500, 900, 64, 300)[which]
+        longest = int(np.diff(rp).max())
+        B = graphgen.random_dense(K, N, N + which)
+        dA, dB = (dev(rp), dev(ci), dev(v)), dev(B)
+        for hint, G, chunk, short_len in ((longest, -1, -1, -1), (1, -1, 16, 0), (longest, 64, 64, -1), (70, 4, 256, 1024),
+                                          (3, 1, 1024, 3), (200, 32, 128, -1), (1024, 16, 512, -1)):
+            tuning = dict(longest_row=hint, lanes_per_row=G, chunk_nnz=chunk, short_len=short_len)
+            plan = gs.gespmm_plan_ex(M, K, N, len(ci), tuning=tuning)
+            if hint == longest and longest > 1024:
+                assert plan["row_window"] == 0                  # too long for the path: the two-launch path runs
+            else:
+                assert plan["row_window"] >= plan["chunk_nnz"] + hint, plan
+            for op in OPS:
+                check(gs, rp, ci, v, B, op, dA=dA, dB=dB, tuning=tuning,
+                      label=f"whole-row case={which} hint={hint} longest={longest} G={G} S={chunk}")
+            check(gs, rp, ci, None, B, "mean", dA=(dA[0], dA[1], None), dB=dB, tuning=tuning,
+                  label=f"whole-row vals=NULL case={which} hint={hint}")
+
+
+def test_whole_row_path_degenerate_and_deterministic(gs):
+    B = graphgen.random_dense(5, 8, 1)
+    hint = dict(longest_row=1000)
+    rp = np.zeros(4, dtype=np.int32)                                # no entries at all: zeros from the one launch
+    for op in OPS:
+        C = check(gs, rp, np.zeros(0, np.int32), np.zeros(0, np.float32), B, op, tuning=hint, label="whole-row nnz=0")
+        assert not C.any()
+    rp = np.array([0, 0, 0, 1000, 1000, 1000], dtype=np.int32)      # empty rows around one long row
+    rng = np.random.default_rng(3)
+    ci = rng.integers(0, 5, size=1000).astype(np.int32)
+    v = (rng.random(1000) - 0.5).astype(np.float32)
+    for op in OPS:
+        check(gs, rp, ci, v, B, op, tuning=hint, label="whole-row empty-around-long")
+        check(gs, rp, ci, v, B, op, tuning=dict(longest_row=5, chunk_nnz=64), label="whole-row windows")
+    # nothing is combined by atomics: two runs give the same bits, also for sum, whatever C held before
+    rp, ci, v = graphgen.random_csr(5000, 4000, 12.0, 9, empty_frac=0.05, long_rows=((77, 800),))
+    Bn = graphgen.random_dense(4000, 64, 9)
+    d = dev(rp), dev(ci), dev(v), dev(Bn)
+    tuning = dict(longest_row=int(np.diff(rp).max()))
+    assert gs.gespmm_plan_ex(5000, 4000, 64, len(ci), tuning=tuning)["row_window"] > 0
+    first = gs.gespmm_csr_ex(*d, "sum", tuning=tuning, C=torch.full((5000, 64), float("nan"), device="cuda"))
+    second = gs.gespmm_csr_ex(*d, "sum", tuning=tuning, C=torch.full((5000, 64), 7.0, device="cuda"))
+    torch.cuda.synchronize()
+    assert torch.equal(first, second)
+    ok, worst = oracle.compare("sum", first.cpu().numpy(), *oracle.spmm(rp, ci, v, Bn, "sum"))
+    assert ok, worst
+
+
+@pytest.mark.parametrize("which", [0, 1, 2, "uniform_random_65k"])
+def test_whole_row_path_on_workloads(gs, which):
+    """The workloads whose longest row is short enough, full size, every element, with the true bound."""
+    w = graphgen.workload(which)
+    longest = int(np.diff(w.rowptr).max())
+    tuning = dict(longest_row=longest)
+    dA = dev(w.rowptr), dev(w.colind), dev(w.vals)
+    for N in w.widths:
+        plan = gs.gespmm_plan_ex(w.M, w.K, N, w.nnz, tuning=tuning)
+        say(f"  {w.name} N={N} longest row {longest}: row_window {plan['row_window']} S {plan['chunk_nnz']}")
+        B = w.B(N)
+        dB = dev(B)
+        for op in w.ops:
+            check(gs, w.rowptr, w.colind, w.vals, B, op, label=w.name + " whole-row", dA=dA, dB=dB, tuning=tuning)
+
+
 # ------------------------------------------------------------ the workloads --
 @pytest.mark.parametrize("which", [0, 1, 2, "uniform_random_65k"])
 def test_workload_full_size_every_element(gs, which):
