@@ -311,7 +311,8 @@ int gespmm_csr_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* r
                   void* workspace, size_t workspace_bytes, const gespmm_tuning_t* tuning,
                   gespmm_profiler_t* profiler, void* stream);
 
-/* gespmm_csr_arg_b16 with tuning overrides (NULL = automatic; k_parts is ignored). */
+/* gespmm_csr_arg_b16 with tuning overrides (NULL = automatic; k_parts is ignored; with longest_row and fp32
+ * features the call can take the whole-row path: one launch instead of four). */
 int gespmm_csr_arg_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
                       const int32_t* colind, const float* vals, const void* B, int b_dtype, float* C,
                       int32_t* arg, int op, const gespmm_tuning_t* tuning, void* stream);

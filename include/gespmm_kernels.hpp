@@ -448,6 +448,24 @@ struct FoldArgRows {
         }
   }
 
+  // A row without stored entries: value 0, position -1 (whole-row path).
+  __device__ static void store_empty(const KernelArgs& a, int64_t row, const int (&col)[T]) {
+    float* crow = a.C + row * (int64_t)a.N;
+    int32_t* arow = a.arg + row * (int64_t)a.N;
+    Vec<V> value, place;
+#pragma unroll
+    for (int x = 0; x < V; ++x) {
+      value.v[x] = 0.0f;
+      place.v[x] = __int_as_float(-1);
+    }
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+      if (col[t] < a.N) {
+        value.store(crow + col[t]);
+        place.store(reinterpret_cast<float*>(arow + col[t]));
+      }
+  }
+
   __device__ static void end(State& s, const KernelArgs& a, int64_t row, bool whole, int, const int (&col)[T]) {
     float* crow = a.C + row * (int64_t)a.N;
     int32_t* arow = a.arg + row * (int64_t)a.N;
@@ -1373,21 +1391,29 @@ MainKernel pick_phased(int job, int vec, int G, int T) {
   return nullptr;
 }
 
-// Kernels of the whole-row path: the three folds on fp32 features, one tile per lane.
+// Kernels of the whole-row path: the three folds and max / min with positions, on fp32 features, one tile per lane.
 inline bool has_owned_kernel(int G, int T) { return T == 1 && G >= 1 && G <= kWave; }
+
+template <class P4, class P1>
+MainKernel pick_owned_shapes(int vec, int G) {      // P4 / P1: the policy for 4 columns / 1 column per lane
+#define GESPMM_CASE(GG)                                                         \
+  if (vec == 4 && G == GG) return chunk_kernel<P4, 4, GG, 1, false, true>;      \
+  if (vec == 1 && G == GG) return chunk_kernel<P1, 1, GG, 1, false, true>;
+  GESPMM_CASE(1) GESPMM_CASE(2) GESPMM_CASE(4) GESPMM_CASE(8) GESPMM_CASE(16) GESPMM_CASE(32) GESPMM_CASE(64)
+#undef GESPMM_CASE
+  return nullptr;
+}
 
 inline MainKernel pick_owned(int job, int vec, int G, int T) {
   if (T != 1) return nullptr;
-#define GESPMM_CASE(FF, VV, GG) if (job == FF && vec == VV && G == GG) return chunk_kernel<FoldRows<FF, VV, 1, float>, VV, GG, 1, false, true>;
-#define GESPMM_SHAPES(FF)                                                                              \
-  GESPMM_CASE(FF, 4, 1) GESPMM_CASE(FF, 4, 2) GESPMM_CASE(FF, 4, 4) GESPMM_CASE(FF, 4, 8) GESPMM_CASE(FF, 4, 16) \
-  GESPMM_CASE(FF, 4, 32) GESPMM_CASE(FF, 4, 64)                                                        \
-  GESPMM_CASE(FF, 1, 1) GESPMM_CASE(FF, 1, 2) GESPMM_CASE(FF, 1, 4) GESPMM_CASE(FF, 1, 8) GESPMM_CASE(FF, 1, 16) \
-  GESPMM_CASE(FF, 1, 32) GESPMM_CASE(FF, 1, 64)
-  GESPMM_SHAPES(kAdd) GESPMM_SHAPES(kMax) GESPMM_SHAPES(kMin)
-#undef GESPMM_SHAPES
-#undef GESPMM_CASE
-  return nullptr;
+  switch (job) {
+    case kJobAdd: return pick_owned_shapes<FoldRows<kAdd, 4, 1>, FoldRows<kAdd, 1, 1>>(vec, G);
+    case kJobMax: return pick_owned_shapes<FoldRows<kMax, 4, 1>, FoldRows<kMax, 1, 1>>(vec, G);
+    case kJobMin: return pick_owned_shapes<FoldRows<kMin, 4, 1>, FoldRows<kMin, 1, 1>>(vec, G);
+    case kJobMaxWithArg: return pick_owned_shapes<FoldArgRows<kMax, 4, 1>, FoldArgRows<kMax, 1, 1>>(vec, G);
+    case kJobMinWithArg: return pick_owned_shapes<FoldArgRows<kMin, 4, 1>, FoldArgRows<kMin, 1, 1>>(vec, G);
+    default: return nullptr;
+  }
 }
 
 inline bool has_kernel(int G, int T) { return pick_gt<AddRows, 4>(G, T) != nullptr; }
@@ -1742,7 +1768,9 @@ inline int launch_phased(const ChunkLaunch& L, const gespmm_plan_t& plan, MainKe
   return GESPMM_OK;
 }
 
-inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
+// took_whole_rows (optional): set when the whole-row path ran, i.e. every row is final and nothing is left to combine.
+inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream, bool* took_whole_rows = nullptr) {
+  if (took_whole_rows) *took_whole_rows = false;
   const bool aligned16 = (((uintptr_t)L.dense_in | (uintptr_t)L.dense_out | (uintptr_t)L.result_in |
                            (uintptr_t)L.also_aligned) & 15u) == 0;
   const bool fold_job = !L.picker && (L.job == kJobAdd || L.job == kJobMax || L.job == kJobMin) && !L.one_lane_per_entry;
@@ -1752,7 +1780,8 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
     tune.k_parts = 1;
   }
   gespmm_plan_t plan;
-  const bool whole_rows_allowed = fold_job && L.b_dtype == GESPMM_F32 && L.init_target == L.dense_out && !L.init2_target;
+  const bool arg_job = !L.picker && (L.job == kJobMaxWithArg || L.job == kJobMinWithArg) && L.arg && !L.one_lane_per_entry;
+  const bool whole_rows_allowed = (fold_job || arg_job) && L.b_dtype == GESPMM_F32 && L.init_target == L.dense_out;
   make_plan(L.M, L.K, L.N, L.nnz, aligned16, L.b_dtype == GESPMM_F32 ? 4 : 2, tune, L.workspace_bytes, &plan, whole_rows_allowed);
   if (L.one_lane_per_entry) {
     plan.vec = 1;
@@ -1816,13 +1845,18 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream) {
   a.packed_split = L.packed_split ? 1 : 0;
   a.accumulate = 0;
   a.row_window = plan.row_window;
-  if (L.packed_split && (plan.vec != 4 || L.N > kWave * kFinishWords || !L.arg)) return GESPMM_ERR_BAD_ARG;
+  if (plan.row_window > 0) a.packed_split = 0;    // no row is split
+  else if (L.packed_split && (plan.vec != 4 || L.N > kWave * kFinishWords || !L.arg)) return GESPMM_ERR_BAD_ARG;
   int status = GESPMM_OK;
   bool timed = false;
   if (!record_start(L.profiler, stream, &timed, &status)) return status;
   hipLaunchKernelGGL(kernel, dim3((unsigned)plan.grid_x, (unsigned)plan.col_blocks), dim3(kBlock), (size_t)plan.lds_bytes, stream, a);
   if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
   if (!record_stop(L.profiler, stream, timed, &status)) return status;
+  if (plan.row_window > 0) {
+    if (took_whole_rows) *took_whole_rows = true;
+    return GESPMM_OK;
+  }
   if (L.packed_split) {
     const unsigned blocks = (unsigned)((L.M + kBlock - 1) / kBlock);
     int words = 1;

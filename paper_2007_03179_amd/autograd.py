@@ -39,13 +39,16 @@ class CsrGraph:
 
     def aggregate(self, B, op, transposed=False):
         """The forward call on A (or, for the gradient of sum / mean, on the transposed arrays) with the hints
-        and the workspace this graph keeps.  The workspace of one (orientation, width, type) is reused by every
-        call: calls on one graph are assumed to be issued on one stream, as autograd issues them."""
+        and the workspace this graph keeps; for max / min it returns (C, positions).  The workspace of one
+        (orientation, width, type) is reused by every call: calls on one graph are assumed to be issued on one
+        stream, as autograd issues them."""
         rowptr, colind, vals = self.transposed(op == "mean") if transposed else (self.rowptr, self.colind, self.vals)
         rows, cols = (self.K, self.M) if transposed else (self.M, self.K)
         if transposed not in self._longest:            # one read-back per orientation
             self._longest[transposed] = int((rowptr[1:] - rowptr[:-1]).max().item()) if rows else 0
         tuning = {"longest_row": self._longest[transposed]}
+        if op in ("max", "min"):                       # value and position (forward pass of the pooling aggregation)
+            return _b.gespmm_csr_arg_ex(rowptr, colind, vals, B, op, tuning=tuning)
         dtype = {torch.float32: "f32", torch.bfloat16: "bf16", torch.float16: "f16"}[B.dtype]
         key = (transposed, B.shape[1], dtype)
         if key not in self._workspaces:
@@ -61,7 +64,7 @@ class _SpMM(torch.autograd.Function):
         B = B.contiguous()
         ctx.graph, ctx.op, ctx.b_dtype = graph, op, B.dtype
         if op in ("max", "min"):          # (the *_b16 calls take fp32 as well)
-            C, arg = _b.gespmm_csr_arg_b16(graph.rowptr, graph.colind, graph.vals, B, op)
+            C, arg = graph.aggregate(B, op)
             ctx.save_for_backward(arg)
             ctx.mark_non_differentiable(arg)
             return C

@@ -171,8 +171,9 @@ int gespmm_csr_arg_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_
   }
   L.split_value = op == GESPMM_MAX ? -__builtin_inff() : __builtin_inff();
   L.split2_value = bits_as_float(INT32_MAX);
-  const int fused = launch_chunks(L, stream);
-  if (fused != GESPMM_OK || nnz == 0) return fused;
+  bool whole_rows = false;
+  const int fused = launch_chunks(L, stream, &whole_rows);
+  if (fused != GESPMM_OK || nnz == 0 || whole_rows) return fused;
   // Second pass, split rows only (their values are final once the first kernel has ended):
   // entries whose product has the bits of C[i, j] compete by atomic min on their index.
   ChunkLaunch S;

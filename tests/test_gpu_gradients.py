@@ -87,6 +87,26 @@ def test_positions_widths_ties_and_split_rows(gs, N):
             check_arg(gs, rp, ci, vv, B, op, label=f"ties N={N}")
 
 
+@pytest.mark.parametrize("N", [1, 4, 7, 32, 72, 128, 520])
+def test_positions_whole_row_path(gs, N):
+    """Value and position from the single-launch path (tuning.longest_row): ties, repeated and unsorted columns, empty
+    rows at both ends, true and understated bounds (the long row is then walked in windows), every slot width."""
+    rp, ci, v = graphgen.random_csr(600, 400, 8.0, 700 + N, empty_frac=0.15, long_rows=((77, 900), (599, 0), (0, 0)),
+                                    duplicates=True, sort_cols=False)
+    B = np.round(graphgen.random_dense(400, N, N) * 4.0).astype(np.float32)
+    v = np.round(v * 2.0).astype(np.float32)
+    dA, dB = (dev(rp), dev(ci), dev(v)), dev(B)
+    longest = int(np.diff(rp).max())
+    for hint, G, chunk in ((longest, -1, -1), (5, -1, 64), (longest, 64, 128), (100, 1, 1024), (longest, 4, 16)):
+        tuning = dict(longest_row=hint, lanes_per_row=G, chunk_nnz=chunk)
+        for op in ("max", "min"):
+            check_arg(gs, rp, ci, v, B, op, dA=dA, dB=dB, tuning=tuning, label=f"whole-row hint={hint} G={G} S={chunk}")
+    rp0 = np.zeros(5, dtype=np.int32)                               # nothing stored: zeros and -1 from the one launch
+    C, arg = check_arg(gs, rp0, np.zeros(0, np.int32), np.zeros(0, np.float32), B, "max", tuning=dict(longest_row=3),
+                       label="whole-row nnz=0")
+    assert not C.any() and (arg == -1).all()
+
+
 def test_positions_every_launch_shape(gs):
     rp, ci, v = graphgen.random_csr(300, 260, 7.0, 56, empty_frac=0.1, long_rows=((11, 900), (12, 300)))
     B = np.round(graphgen.random_dense(260, 72, 56) * 8.0).astype(np.float32)
