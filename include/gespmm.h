@@ -44,8 +44,10 @@ typedef enum {
   GESPMM_ERR_TOO_LARGE = 3, /* M, K or nnz does not fit the 32-bit index arrays   */
   GESPMM_ERR_WORKSPACE = 4, /* the caller's workspace is too small or misaligned  */
   GESPMM_ERR_HIP = 5,       /* a HIP call (launch, event, copy) reported an error */
-  GESPMM_ERR_SCRATCH_LIMIT = 6 /* beyond the built-in scratch buffer of the entry
-                                  point that allocates nothing                    */
+  GESPMM_ERR_SCRATCH_LIMIT = 6, /* beyond the built-in scratch buffer of the entry
+                                   point that allocates nothing                   */
+  GESPMM_ERR_COMPILE = 7,   /* the text of a user-defined reduce did not compile   */
+  GESPMM_ERR_NO_RTC = 8     /* the run-time compiler library cannot be loaded      */
 } gespmm_status_t;
 
 /*
@@ -316,6 +318,41 @@ int gespmm_csr_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* r
 int gespmm_csr_arg_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
                       const int32_t* colind, const float* vals, const void* B, int b_dtype, float* C,
                       int32_t* arg, int op, const gespmm_tuning_t* tuning, void* stream);
+
+/*
+ * User-defined reduce operations compiled at run time (Eq. 1; Section IV-A: the user supplies an
+ * initialisation and a reduce function, which are compiled into the kernel).  include/gespmm_custom.hpp is
+ * the same mechanism at build time, for C++ callers; this one needs no compiler on the caller's side.
+ *   source   HIP C++ text that defines a struct `name` with three static functions
+ *                static __device__ float identity();                        initial value of a row
+ *                static __device__ float step(float acc, float a, float b); acc joined with the entry (a = vals[p], b = B[colind[p], j])
+ *                static __device__ float merge(float x, float y);           two partial results
+ *            merge must be associative and commutative with identity() as neutral element, and
+ *            step(acc, a, b) == merge(acc, step(identity(), a, b)): partial results of a row are combined
+ *            in parallel.  The text may contain helpers of its own; it sees the HIP device runtime only.
+ *   name     the struct (an identifier, optionally qualified).
+ *   out      receives the operation; the caller destroys it with gespmm_custom_op_destroy once no call
+ *            that uses it is in flight.
+ *   log      host buffer for the compiler's messages (NUL-terminated, truncated to log_bytes) or NULL.
+ * gespmm_custom_op_create compiles on the calling thread (about a second), runs a one-thread kernel on the
+ * current device to read identity() and synchronises with it; kernels for further launch shapes are
+ * compiled on first use inside gespmm_csr_custom (a fraction of a second each, once).  The operation is
+ * bound to the device that was current at creation.  It may be used from several threads.
+ * Errors: GESPMM_ERR_NULL, GESPMM_ERR_BAD_ARG (name is not an identifier; another device is current),
+ * GESPMM_ERR_COMPILE (see log), GESPMM_ERR_NO_RTC, GESPMM_ERR_HIP.
+ *
+ * gespmm_csr_custom: C[i, j] = merge over the stored entries p of row i of step(identity(), vals[p],
+ * B[colind[p], j]), 0 for a row that stores nothing.  Arguments, layout, ownership, stream semantics and
+ * errors as gespmm_csr (fp32 features); tuning as in gespmm_csr_ex (longest_row and k_parts are ignored).
+ * Rows that lie in several chunks are combined by a compare-and-swap loop around merge.
+ */
+typedef struct gespmm_custom_op gespmm_custom_op_t;
+int gespmm_custom_op_create(const char* source, const char* name, gespmm_custom_op_t** out, char* log,
+                            size_t log_bytes);
+int gespmm_custom_op_destroy(gespmm_custom_op_t* op);
+int gespmm_csr_custom(gespmm_custom_op_t* op, int64_t M, int64_t K, int64_t N, int64_t nnz,
+                      const int32_t* rowptr, const int32_t* colind, const float* vals, const float* B,
+                      float* C, const gespmm_tuning_t* tuning, void* stream);
 
 /*
  * Measurement helper, not part of the method: copies `bytes` (a multiple of 16, both

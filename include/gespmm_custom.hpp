@@ -19,7 +19,8 @@
 // rows that are split across wavefronts are combined with a compare-and-swap loop around merge.
 // A last argument `const gespmm_tuning_t* tuning` (default NULL = automatic) overrides the launch shape
 // for this call, as in gespmm_csr_ex.  Compile with hipcc --offload-arch=gfx950 -I <this directory>:
-// everything needed (this file, gespmm_kernels.hpp, gespmm.h) lies here.
+// everything needed (this file, gespmm_kernels.hpp, gespmm_device.hpp, gespmm.h) lies here.  The same struct
+// can be compiled at run time from source text instead: gespmm_custom_op_create in gespmm.h.
 #pragma once
 
 #include "gespmm_kernels.hpp"

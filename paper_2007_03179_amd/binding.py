@@ -125,6 +125,12 @@ def lib():
         L.gespmm_calibration_gather.argtypes = [vp, i64, vp, i64, vp, i64, vp]
         L.gespmm_calibration_gather_shape.restype = ci
         L.gespmm_calibration_gather_shape.argtypes = [vp, i64, ci, vp, i64, ci, ci, ci, ci, vp, i64, vp]
+        L.gespmm_custom_op_create.restype = ci
+        L.gespmm_custom_op_create.argtypes = [ctypes.c_char_p, ctypes.c_char_p, ctypes.POINTER(vp), ctypes.c_char_p, ctypes.c_size_t]
+        L.gespmm_custom_op_destroy.restype = ci
+        L.gespmm_custom_op_destroy.argtypes = [vp]
+        L.gespmm_csr_custom.restype = ci
+        L.gespmm_csr_custom.argtypes = [vp, i64, i64, i64, i64, vp, vp, vp, vp, vp, tp, vp]
         L.gespmm_status_string.restype = ctypes.c_char_p
         L.gespmm_status_string.argtypes = [ci]
         L.gespmm_version.restype = ci
@@ -413,6 +419,35 @@ def gespmm_csr_arg_ex(rowptr, colind, vals, B, op, C=None, arg=None, tuning=None
     _check(lib().gespmm_csr_arg_ex(M, K, N, colind.numel(), _ptr(rowptr), _ptr(colind), _ptr(vals), _ptr(B), code_b,
                                    _ptr(C), _ptr(arg), code, _tuning_ref(tuning), _stream(stream)))
     return C, arg
+
+
+def gespmm_custom_op_create(source: str, name: str):
+    """A user-defined reduce operation compiled at run time from HIP C++ text that defines the struct `name`
+    (identity / step / merge).  Returns a handle for gespmm_csr_custom; a GespmmError carries the compiler's log."""
+    handle = ctypes.c_void_p()
+    log = ctypes.create_string_buffer(1 << 16)
+    status = lib().gespmm_custom_op_create(source.encode(), name.encode(), ctypes.byref(handle), log, len(log))
+    if status != GESPMM_OK:
+        err = GespmmError(status, gespmm_status_string(status) + "\n" + log.value.decode(errors="replace"))
+        err.log = log.value.decode(errors="replace")
+        raise err
+    return handle
+
+
+def gespmm_custom_op_destroy(op):
+    _check(lib().gespmm_custom_op_destroy(op))
+
+
+def gespmm_csr_custom(op, rowptr, colind, vals, B, C=None, tuning=None, stream=None):
+    """C = A (x) B with the reduce operation `op` (from gespmm_custom_op_create); fp32 tensors on the GPU."""
+    import torch
+    M, (K, N) = rowptr.numel() - 1, B.shape
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.float32, device=B.device)
+    _check_tensors(rowptr, colind, vals, B, C)
+    _check(lib().gespmm_csr_custom(op, M, K, N, colind.numel(), _ptr(rowptr), _ptr(colind), _ptr(vals), _ptr(B), _ptr(C),
+                                   _tuning_ref(tuning), _stream(stream)))
+    return C
 
 
 def gespmm_profiler_create(capacity: int):

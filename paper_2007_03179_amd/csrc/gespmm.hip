@@ -4,6 +4,7 @@
 #include "gespmm_kernels.hpp"
 #include "gespmm_sort.hpp"
 #include "gespmm_calibration.hpp"
+#include "gespmm_rtc.hpp"
 
 #include <mutex>
 #include <new>
@@ -477,6 +478,96 @@ int gespmm_calibration_gather_shape(const void* table, int64_t table_bytes, int 
   return hipGetLastError() == hipSuccess ? GESPMM_OK : GESPMM_ERR_HIP;
 }
 
+static void copy_log(const std::string& text, char* log, size_t log_bytes) {
+  if (!log || log_bytes == 0) return;
+  const size_t n = text.size() < log_bytes - 1 ? text.size() : log_bytes - 1;
+  std::memcpy(log, text.data(), n);
+  log[n] = '\0';
+}
+
+int gespmm_custom_op_create(const char* source, const char* name, gespmm_custom_op_t** out, char* log, size_t log_bytes) {
+  if (log && log_bytes > 0) log[0] = '\0';
+  if (!source || !name || !out) return GESPMM_ERR_NULL;
+  *out = nullptr;
+  if (!is_identifier(name)) return GESPMM_ERR_BAD_ARG;
+  gespmm_custom_op* op = new (std::nothrow) gespmm_custom_op;
+  if (!op) return GESPMM_ERR_HIP;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&op->device) != hipSuccess || hipGetDeviceProperties(&prop, op->device) != hipSuccess) {
+    delete op;
+    return GESPMM_ERR_HIP;
+  }
+  op->arch = prop.gcnArchName;
+  op->name = name;
+  op->source = std::string("#include \"gespmm_device.hpp\"\n#line 1 \"user_reduce\"\n") + source + "\n";
+  // identity(): read back once through a one-thread kernel (also the first check that the text compiles)
+  std::string text;
+  std::vector<char> code;
+  std::string symbol;
+  const std::string probe = op->source + "extern \"C\" __global__ void gespmm_identity_of(float* out) { *out = " + op->name +
+                            "::identity(); }\n";
+  int status = rtc_compile(probe, op->arch, "", "gespmm_identity_of", &code, &symbol, &text);
+  if (status == GESPMM_OK) {
+    hipModule_t module = nullptr;
+    hipFunction_t function = nullptr;
+    float* device_value = nullptr;
+    status = GESPMM_ERR_HIP;
+    if (hipModuleLoadData(&module, code.data()) == hipSuccess) {
+      if (hipModuleGetFunction(&function, module, symbol.c_str()) == hipSuccess &&
+          hipMalloc(reinterpret_cast<void**>(&device_value), sizeof(float)) == hipSuccess) {
+        void* params[] = {&device_value};
+        if (hipModuleLaunchKernel(function, 1, 1, 1, 1, 1, 1, 0, nullptr, params, nullptr) == hipSuccess &&
+            hipMemcpy(&op->identity, device_value, sizeof(float), hipMemcpyDeviceToHost) == hipSuccess)
+          status = GESPMM_OK;
+        (void)hipFree(device_value);
+      }
+      (void)hipModuleUnload(module);
+    }
+  }
+  // step() and merge(): build the most common kernel shape now, so that a mistake in them is reported here
+  if (status == GESPMM_OK) {
+    hipFunction_t function = nullptr;
+    status = op->kernel_for(4, 8, 1, &function, &text);
+  }
+  copy_log(text, log, log_bytes);
+  if (status != GESPMM_OK) {
+    gespmm_custom_op_destroy(op);
+    return status;
+  }
+  *out = op;
+  return GESPMM_OK;
+}
+
+int gespmm_custom_op_destroy(gespmm_custom_op_t* op) {
+  if (!op) return GESPMM_OK;
+  int status = GESPMM_OK;
+  for (auto& entry : op->kernels)
+    if (hipModuleUnload(entry.second.module) != hipSuccess) status = GESPMM_ERR_HIP;
+  delete op;
+  return status;
+}
+
+int gespmm_csr_custom(gespmm_custom_op_t* op, int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                      const int32_t* colind, const float* vals, const float* B, float* C,
+                      const gespmm_tuning_t* tuning, void* stream_) {
+  if (!op) return GESPMM_ERR_NULL;
+  const int st = validate(M, K, N, nnz, rowptr, colind, B, C, GESPMM_SUM);
+  if (st != GESPMM_OK || M == 0 || N == 0) return st;
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess) return GESPMM_ERR_HIP;
+  if (device != op->device) return GESPMM_ERR_BAD_ARG;      // its kernels are loaded on the device it was created on
+  ChunkLaunch L;
+  const int parsed = parse_tuning(tuning, &L.tuning);
+  if (parsed != GESPMM_OK) return parsed;
+  L.launcher = &rtc_launch;
+  L.launcher_context = op;
+  L.M = M; L.K = K; L.N = N; L.nnz = nnz;
+  L.rowptr = rowptr; L.colind = colind; L.vals = vals;
+  L.dense_in = B; L.dense_out = C;
+  L.init_target = C; L.empty_value = 0.0f; L.split_value = op->identity;
+  return launch_chunks(L, (hipStream_t)stream_);
+}
+
 const char* gespmm_status_string(int status) {
   switch (status) {
     case GESPMM_OK: return "ok";
@@ -487,6 +578,8 @@ const char* gespmm_status_string(int status) {
     case GESPMM_ERR_HIP: return "a HIP call failed";
     case GESPMM_ERR_SCRATCH_LIMIT:
       return "the problem needs more scratch memory than the built-in buffer of the no-allocation entry point holds";
+    case GESPMM_ERR_COMPILE: return "the source of a user-defined reduce operation did not compile (see the log)";
+    case GESPMM_ERR_NO_RTC: return "the run-time compiler library (libhiprtc.so) could not be loaded";
     default: return "unknown status";
   }
 }

@@ -257,3 +257,29 @@ def test_header_is_plain_c_and_cxx():
         assert r.returncode == 0, r.stderr
     text = open(HEADER).read()
     assert "hip/" not in text and "torch" not in text.lower()
+
+
+def test_run_time_reduce_host_side_argument_checks(L):
+    handle = ctypes.c_void_p()
+    log = ctypes.create_string_buffer(64)
+    src = b"struct A { static __device__ float identity() { return 0.0f; } };"
+    assert L.gespmm_custom_op_create(None, b"A", ctypes.byref(handle), log, 64) == 2
+    assert L.gespmm_custom_op_create(src, None, ctypes.byref(handle), log, 64) == 2
+    assert L.gespmm_custom_op_create(src, b"A", None, log, 64) == 2
+    for bad in (b"", b"1A", b"A B", b"A;", b"A<int>", b":A"):
+        assert L.gespmm_custom_op_create(src, bad, ctypes.byref(handle), None, 0) == 1, bad
+        assert not handle.value
+    assert L.gespmm_custom_op_destroy(None) == 0
+    assert L.gespmm_csr_custom(None, 1, 1, 1, 0, None, None, None, None, None, None, None) == 2
+    assert "compile" in gs.gespmm_status_string(7) and "libhiprtc" in gs.gespmm_status_string(8)
+
+
+def test_embedded_device_header_is_the_header():
+    """The text handed to the run-time compiler is include/gespmm_device.hpp, byte for byte."""
+    path = hip_build.embed_device_header()
+    pieces = re.findall(r'R"GESPMM_TEXT\((.*?)\)GESPMM_TEXT"\n', open(path).read(), flags=re.S)
+    assert "".join(pieces) == open(os.path.join(ROOT, "include", "gespmm_device.hpp")).read()
+    # device code only: nothing in it may need a host header when the run-time compiler reads it
+    device = open(os.path.join(ROOT, "include", "gespmm_device.hpp")).read()
+    includes = re.findall(r"#include\s*[<\"]([^>\"]+)[>\"]", device)
+    assert sorted(includes) == ["cstdint", "hip/hip_runtime.h"], includes

@@ -62,3 +62,98 @@ def test_user_defined_reduce_argument_errors(custom):
     assert custom.custom_sum_of_squares(-1, 4, 4, 0, p, p, p, p, p, None) == 1
     assert custom.custom_sum_of_squares(4, 4, 4, 8, None, p, p, p, p, None) == 2
     assert custom.custom_max_magnitude(0, 4, 4, 0, p, p, p, p, p, None) == 0
+
+
+# --------------------------------------------- the same mechanism at run time --
+RTC_SOURCE = """
+// C[i, j] = sum_p (vals[p] * B[colind[p], j])^2
+struct SumOfSquares {
+  static __device__ float identity() { return 0.0f; }
+  static __device__ float step(float acc, float a, float b) { const float x = a * b; return acc + x * x; }
+  static __device__ float merge(float x, float y) { return x + y; }
+};
+// C[i, j] = max_p |vals[p] * B[colind[p], j]|
+struct MaxMagnitude {
+  static __device__ float identity() { return 0.0f; }
+  static __device__ float step(float acc, float a, float b) { return __builtin_fmaxf(acc, __builtin_fabsf(a * b)); }
+  static __device__ float merge(float x, float y) { return __builtin_fmaxf(x, y); }
+};
+// C[i, j] = number of stored entries whose product is positive; identity is not zero-like on purpose
+namespace mine {
+__device__ float positive(float x) { return x > 0.0f ? 1.0f : 0.0f; }
+struct CountPositivePlusSeven {
+  static __device__ float identity() { return 7.0f; }          // merge(x, y) = x + y - 7 has 7 as neutral element
+  static __device__ float step(float acc, float a, float b) { return acc + positive(a * b); }
+  static __device__ float merge(float x, float y) { return x + y - 7.0f; }
+};
+}
+"""
+
+
+@pytest.fixture(scope="module")
+def gs():
+    import paper_2007_03179_amd as gs
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    gs.lib()
+    return gs
+
+
+@pytest.fixture(scope="module")
+def rtc_ops(gs):
+    ops = {name: gs.gespmm_custom_op_create(RTC_SOURCE, name) for name in ("SumOfSquares", "MaxMagnitude", "mine::CountPositivePlusSeven")}
+    yield ops
+    for op in ops.values():
+        gs.gespmm_custom_op_destroy(op)
+
+
+def run_rtc(gs, op, rp, ci, v, B, tuning=None):
+    d = lambda x: None if x is None else torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    C = torch.full((len(rp) - 1, B.shape[1]), float("nan"), dtype=torch.float32, device="cuda")
+    gs.gespmm_csr_custom(op, d(rp), d(ci), d(v), d(B), C=C, tuning=tuning)
+    torch.cuda.synchronize()
+    return C.cpu().numpy()
+
+
+@pytest.mark.parametrize("N", [1, 3, 8, 37, 64, 160, 512])
+def test_reduce_compiled_at_run_time_matches_general_fold(gs, rtc_ops, N):
+    """Source text in, kernels out: vector and scalar kernels (aligned widths and not), one and two tiles per lane,
+    every slot width the plan picks, empty rows, a row spanning many chunks (compare-and-swap combine)."""
+    rp, ci, v = graphgen.random_csr(400, 300, 6.0, 900 + N, empty_frac=0.1, long_rows=((33, 1500),), duplicates=True)
+    B = graphgen.random_dense(300, N, N)
+    for vv in (v, None):
+        print(f"  case rtc N={N} vals={'given' if vv is not None else 'NULL'}", flush=True)
+        got = run_rtc(gs, rtc_ops["SumOfSquares"], rp, ci, vv, B)
+        ref = oracle.spmm_custom(rp, ci, vv, B, 0.0, lambda acc, a, b: acc + (a * b) ** 2)
+        assert np.all(np.abs(got - ref) <= 1e-5 * ref + 1e-6), float(np.abs(got - ref).max())
+        got = run_rtc(gs, rtc_ops["MaxMagnitude"], rp, ci, vv, B)
+        ref = oracle.spmm_custom(rp, ci, vv, B, 0.0, lambda acc, a, b: max(acc, abs(a * b)))
+        assert np.array_equal(got.view(np.uint32), ref.astype(np.float32).view(np.uint32))
+        got = run_rtc(gs, rtc_ops["mine::CountPositivePlusSeven"], rp, ci, vv, B)
+        ref = oracle.spmm_custom(rp, ci, vv, B, 7.0, lambda acc, a, b: acc + (1.0 if np.float32(a) * np.float32(b) > 0 else 0.0))
+        assert np.array_equal(got, ref.astype(np.float32))          # small integers (+7; 0 for an empty row): exact
+
+
+def test_reduce_compiled_at_run_time_launch_shapes_and_reuse(gs, rtc_ops):
+    rp, ci, v = graphgen.random_csr(300, 200, 9.0, 31, empty_frac=0.1, long_rows=((5, 700),))
+    B = graphgen.random_dense(200, 72, 31)
+    ref = oracle.spmm_custom(rp, ci, v, B, 0.0, lambda acc, a, b: acc + (a * b) ** 2)
+    for G, T, chunk in ((1, 1, 16), (2, 1, 64), (4, 2, 256), (8, 4, 1024), (16, 1, 128), (32, 2, 64), (64, 1, 256)):
+        for _ in range(2):                                            # the second call reuses the loaded kernel
+            got = run_rtc(gs, rtc_ops["SumOfSquares"], rp, ci, v, B, tuning=dict(lanes_per_row=G, tiles_per_lane=T, chunk_nnz=chunk))
+            assert np.all(np.abs(got - ref) <= 1e-5 * ref + 1e-6), (G, T, chunk)
+    # degenerate: nothing stored
+    got = run_rtc(gs, rtc_ops["MaxMagnitude"], np.zeros(4, np.int32), np.zeros(0, np.int32), None, B[:5])
+    assert got.shape == (3, 72) and not got.any()
+
+
+def test_reduce_compiled_at_run_time_reports_compile_errors(gs):
+    with pytest.raises(gs.GespmmError) as e:
+        gs.gespmm_custom_op_create("struct Broken { static __device__ float identity() { return 0.0f } };", "Broken")
+    assert e.value.status == 7 and "error" in e.value.log
+    with pytest.raises(gs.GespmmError) as e:                          # compiles, but step() has the wrong shape
+        gs.gespmm_custom_op_create("""struct NoStep { static __device__ float identity() { return 0.0f; }
+                                      static __device__ float merge(float x, float y) { return x + y; } };""", "NoStep")
+    assert e.value.status == 7 and "step" in e.value.log
+    with pytest.raises(gs.GespmmError) as e:
+        gs.gespmm_custom_op_create("struct A {};", "not an identifier")
+    assert e.value.status == 1
