@@ -91,7 +91,7 @@ TUNING = None                   # --tuning: per-call overrides handed to every f
 USE_WORKSPACE = True            # --no-workspace: never hand the forward call a workspace (no K-phased path)
 ROW_BOUND = True                # --no-row-bound: do not tell the forward call how long the longest row of the matrix is
 
-TUNING_FIELDS = ("lanes_per_row", "tiles_per_lane", "xcd_remap", "chunk_nnz", "short_len", "k_parts", "longest_row")
+TUNING_FIELDS = ("lanes_per_row", "tiles_per_lane", "xcd_remap", "chunk_nnz", "short_len", "k_parts", "longest_row", "wide_addresses")
 
 
 def case_tuning(w):
@@ -675,7 +675,7 @@ def main():
     ap.add_argument("--b-dtype", default="f32", choices=("f32", "bf16", "f16"),
                     help="storage type of the dense input B (arithmetic and C stay fp32); f32 is the paper's setting")
     ap.add_argument("--tuning", default="",
-                    help="lanes_per_row,tiles_per_lane,xcd_remap,chunk_nnz,short_len,k_parts,longest_row override, e.g. "
+                    help="lanes_per_row,tiles_per_lane,xcd_remap,chunk_nnz,short_len,k_parts,longest_row,wide_addresses override, e.g. "
                          "--tuning=-1,-1,0,512,16,8 (each -1 = automatic)")
     ap.add_argument("--no-workspace", action="store_true",
                     help="never hand the forward call a workspace: the K-phased path stays off")

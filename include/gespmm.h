@@ -233,6 +233,9 @@ int gespmm_pool_backward(int64_t M, int64_t K, int64_t N, int64_t nnz, const int
  * launch without presetting and without atomics, and sum / mean become independent of the order in
  * which wavefronts finish.  The bound only selects the path: the result is right whatever it says;
  * a row much longer than stated is walked by one wavefront alone and is slow.
+ * wide_addresses = 1 makes the forward kernels compute 64-bit addresses for their gathers also when B
+ * is smaller than 2 GiB, where they otherwise gather through a buffer descriptor with 32-bit offsets
+ * (-1 or 0 = automatic; same results either way; for tests and comparisons).
  */
 typedef struct {
   int32_t lanes_per_row;
@@ -242,6 +245,7 @@ typedef struct {
   int32_t short_len;
   int32_t k_parts;
   int32_t longest_row;
+  int32_t wide_addresses;
 } gespmm_tuning_t;
 
 /*

@@ -91,6 +91,9 @@ struct KernelArgs {
   int32_t accumulate;     // K-phased path: fold the row's result into what C already holds
   int32_t taper_chunks;   // K-phased path: this many chunks at the end of a launch hold S / 4 items only
   int32_t row_window;     // whole-row path: entries one wavefront's LDS slice holds (>= S)
+  uint32_t b_row_bytes;   // fold jobs on a B below 2 GiB: bytes of one row of B (the staged key of an entry is then
+                          // the byte offset of its row of B, and the gathers are buffer loads); 0 = 64-bit addresses
+  uint32_t b_bytes;       // ... and the size of B in bytes
 };
 
 // Entry p of row r is item p + r of the merged sequence of entries and row ends; chunk c owns the
@@ -120,17 +123,33 @@ template <> struct Vec<1> {
 struct bf16_t { uint16_t bits; };               // 1 sign, 8 exponent, 7 fraction bits: the top half of an fp32
 struct f16_t { uint16_t bits; };                // IEEE binary16
 
+// Gathers through a buffer descriptor of B (base, size): the address of a load is base + a 32-bit byte
+// offset, which costs one 32-bit add per gather where a 64-bit address costs a 64-bit multiply-add and a
+// 64-bit shift-add, and a load whose offset lies beyond the size returns zeros instead of faulting - the
+// sum uses that for entries that do not exist (kPastTheEnd).  Limited to 2 GiB of B by the 32-bit offsets.
+using BufferOfB = __amdgpu_buffer_rsrc_t;
+constexpr uint32_t kPastTheEnd = 0x80000000u;     // plus any offset inside a row: still beyond every B this path takes
+__device__ __forceinline__ BufferOfB buffer_of(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);   // untyped 32-bit data, no swizzle
+}
+
 // BLoad<V, BT>: one load of V consecutive elements of type BT, kept as loaded (Raw) until
 // it is used, so that all loads of a pass can be in flight together; unpack widens to fp32.
+// load_at is the same load through the buffer descriptor, at a byte offset.
 template <int V, class BT> struct BLoad;
 template <> struct BLoad<4, float> {
   using Raw = float4;
   __device__ static Raw load(const float* p) { return *reinterpret_cast<const float4*>(p); }
+  __device__ static Raw load_at(BufferOfB b, uint32_t offset) {
+    const auto w = __builtin_amdgcn_raw_buffer_load_b128(b, (int)offset, 0, 0);
+    return make_float4(__uint_as_float(w[0]), __uint_as_float(w[1]), __uint_as_float(w[2]), __uint_as_float(w[3]));
+  }
   __device__ static void unpack(const Raw& r, float (&o)[4]) { o[0] = r.x; o[1] = r.y; o[2] = r.z; o[3] = r.w; }
 };
 template <> struct BLoad<1, float> {
   using Raw = float;
   __device__ static Raw load(const float* p) { return *p; }
+  __device__ static Raw load_at(BufferOfB b, uint32_t offset) { return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(b, (int)offset, 0, 0)); }
   __device__ static void unpack(const Raw& r, float (&o)[1]) { o[0] = r; }
 };
 __device__ __forceinline__ void widen_pair(bf16_t, unsigned w, float& lo, float& hi) {
@@ -146,6 +165,10 @@ __device__ __forceinline__ void widen_pair(f16_t, unsigned w, float& lo, float& 
 template <class BT> struct BLoad<4, BT> {       // BT = bf16_t or f16_t: 8 bytes = 4 elements
   using Raw = uint2;
   __device__ static Raw load(const BT* p) { return *reinterpret_cast<const uint2*>(p); }
+  __device__ static Raw load_at(BufferOfB b, uint32_t offset) {
+    const auto w = __builtin_amdgcn_raw_buffer_load_b64(b, (int)offset, 0, 0);
+    return make_uint2(w[0], w[1]);
+  }
   __device__ static void unpack(const Raw& r, float (&o)[4]) {
     widen_pair(BT{}, r.x, o[0], o[1]);
     widen_pair(BT{}, r.y, o[2], o[3]);
@@ -154,11 +177,13 @@ template <class BT> struct BLoad<4, BT> {       // BT = bf16_t or f16_t: 8 bytes
 template <> struct BLoad<1, bf16_t> {
   using Raw = uint16_t;
   __device__ static Raw load(const bf16_t* p) { return p->bits; }
+  __device__ static Raw load_at(BufferOfB b, uint32_t offset) { return __builtin_amdgcn_raw_buffer_load_b16(b, (int)offset, 0, 0); }
   __device__ static void unpack(const Raw& r, float (&o)[1]) { o[0] = __uint_as_float((unsigned)r << 16); }
 };
 template <> struct BLoad<1, f16_t> {
   using Raw = uint16_t;
   __device__ static Raw load(const f16_t* p) { return p->bits; }
+  __device__ static Raw load_at(BufferOfB b, uint32_t offset) { return __builtin_amdgcn_raw_buffer_load_b16(b, (int)offset, 0, 0); }
   __device__ static void unpack(const Raw& r, float (&o)[1]) { o[0] = (float)__builtin_bit_cast(_Float16, r); }
 };
 
@@ -290,18 +315,29 @@ struct FoldRows {
     using Load = BLoad<V, BT>;
     int2 e2[U];
     typename Load::Raw b[U][T];
-    const BT* nothing = reinterpret_cast<const BT*>(kZeroLine);      // the same 16 bytes for every lane: a uniform address
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int uu = u < left ? u : (left > 0 ? left - 1 : 0);
       e2[u] = ka[first + uu * stride];
       if (F == kAdd && u >= left) e2[u].y = 0;
     }
+    if (a.b_row_bytes != 0) {
+      // the staged key is the byte offset of the entry's row of B; an entry that does not exist reads past the end (zeros)
+      const BufferOfB whole_b = buffer_of(a.B, a.b_bytes);
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const BT* brow = reinterpret_cast<const BT*>(a.B) + (int64_t)e2[u].x * a.N;
+      for (int u = 0; u < U; ++u) {
+        const uint32_t row_offset = F == kAdd && u >= left ? kPastTheEnd : (uint32_t)e2[u].x;
 #pragma unroll
-      for (int t = 0; t < T; ++t) b[u][t] = Load::load(F == kAdd && u >= left ? nothing : brow + colc[t]);
+        for (int t = 0; t < T; ++t) b[u][t] = Load::load_at(whole_b, row_offset + (uint32_t)colc[t] * (uint32_t)sizeof(BT));
+      }
+    } else {
+      const BT* nothing = reinterpret_cast<const BT*>(kZeroLine);      // the same 16 bytes for every lane: a uniform address
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const BT* brow = reinterpret_cast<const BT*>(a.B) + (int64_t)e2[u].x * a.N;
+#pragma unroll
+        for (int t = 0; t < T; ++t) b[u][t] = Load::load(F == kAdd && u >= left ? nothing : brow + colc[t]);
+      }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
@@ -963,6 +999,7 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
           const int idx = u0 + u * kWave + lane;
           k[u] = 0;
           if (u0 + u * kWave < count) k[u] = a.colind[from + (idx < count ? idx : count - 1)];
+          if (a.b_row_bytes != 0) k[u] *= (int)a.b_row_bytes;      // the row's byte offset in B (fits 31 bits on this path)
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -1031,6 +1068,7 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
                 if (row_info[pos + step].x <= xc) pos += step;
               const int p = xc + cs + row_info[pos].y;
               k[u] = a.colind[p];
+              if (a.b_row_bytes != 0) k[u] *= (int)a.b_row_bytes;
               v[u] = a.vals ? a.vals[p] : 1.0f;
             }
 #pragma unroll

@@ -319,6 +319,7 @@ inline int next_pow2(int64_t x) {
 struct Tuning {
   int g = -1, t = -1, remap = -1, shift = -1, short_len = -1, k_parts = -1;
   int longest_row = -1;       // the caller's upper bound on the stored entries of a row; -1 = not known
+  bool wide_addresses = false;   // 64-bit addresses for the gathers even where 32-bit offsets would do
 };
 
 inline int parse_tuning(const gespmm_tuning_t* in, Tuning* out) {
@@ -344,6 +345,7 @@ inline int parse_tuning(const gespmm_tuning_t* in, Tuning* out) {
   out->short_len = in->short_len >= 0 ? in->short_len : -1;
   out->k_parts = in->k_parts >= 0 ? (in->k_parts < 2 ? 1 : in->k_parts) : -1;
   out->longest_row = in->longest_row > 0 ? in->longest_row : -1;
+  out->wide_addresses = in->wide_addresses > 0;
   return GESPMM_OK;
 }
 
@@ -594,6 +596,20 @@ inline void launch_init_rows(int vec, int64_t M, int64_t N, const int32_t* rowpt
                        empty_value, split_value, shift, lanes_shift);
 }
 
+// Fold jobs gather through a buffer descriptor with 32-bit byte offsets when B is smaller than 2 GiB (and, for
+// the scalar kernels, holds 4-byte elements: a 2-byte buffer load would need a 2-byte aligned descriptor path
+// of its own); otherwise the kernels compute 64-bit addresses.
+inline void set_narrow_b(const ChunkLaunch& L, int vec, KernelArgs* a) {
+  const int64_t elem = L.b_dtype == GESPMM_F32 ? 4 : 2;
+  const int64_t bytes = L.K * L.N * elem;
+  a->b_row_bytes = 0;
+  a->b_bytes = 0;
+  if (bytes > 0 && bytes < (int64_t)0x7ff00000 && (vec == 4 || elem == 4) && !L.tuning.wide_addresses) {
+    a->b_row_bytes = (uint32_t)(L.N * elem);
+    a->b_bytes = (uint32_t)bytes;
+  }
+}
+
 // The K-phased path: C = A (x) B as plan.k_parts launches, part q of the column range after part q - 1.
 // Every launch gathers from K / k_parts rows of B only, which the L2s hold, instead of from all of B.
 //   1. every non-empty row of C is preset to the reduce identity (empty rows to 0);
@@ -642,6 +658,7 @@ inline int launch_phased(const ChunkLaunch& L, const gespmm_plan_t& plan, MainKe
   a.C = L.dense_out;
   a.accumulate = 1;
   a.taper_chunks = kTaperChunks;
+  set_narrow_b(L, plan.vec, &a);
   int status = GESPMM_OK;
   for (int q = 0; q < Q; ++q) {
     a.rowptr = virtual_start + (int64_t)q * (M + 1);
@@ -740,6 +757,7 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream, bool* took_wh
   a.packed_split = L.packed_split ? 1 : 0;
   a.accumulate = 0;
   a.row_window = plan.row_window;
+  if (fold_job) set_narrow_b(L, plan.vec, &a);
   if (plan.row_window > 0) a.packed_split = 0;    // no row is split
   else if (L.packed_split && (plan.vec != 4 || L.N > kWave * kFinishWords || !L.arg)) return GESPMM_ERR_BAD_ARG;
   int status = GESPMM_OK;

@@ -36,14 +36,14 @@ class gespmm_plan_t(ctypes.Structure):
 class gespmm_tuning_t(ctypes.Structure):
     _fields_ = [("lanes_per_row", ctypes.c_int32), ("tiles_per_lane", ctypes.c_int32),
                 ("xcd_remap", ctypes.c_int32), ("chunk_nnz", ctypes.c_int32),
-                ("short_len", ctypes.c_int32), ("k_parts", ctypes.c_int32), ("longest_row", ctypes.c_int32)]
+                ("short_len", ctypes.c_int32), ("k_parts", ctypes.c_int32), ("longest_row", ctypes.c_int32), ("wide_addresses", ctypes.c_int32)]
 
 
 def _tuning(t):
-    """None, a gespmm_tuning_t, a dict of field names, or up to seven numbers in field order (-1 = automatic)."""
+    """None, a gespmm_tuning_t, a dict of field names, or up to eight numbers in field order (-1 = automatic)."""
     if t is None or isinstance(t, gespmm_tuning_t):
         return t
-    out = gespmm_tuning_t(-1, -1, -1, -1, -1, -1, -1)
+    out = gespmm_tuning_t(-1, -1, -1, -1, -1, -1, -1, -1)
     if isinstance(t, dict):
         for name, value in t.items():
             if name not in dict(gespmm_tuning_t._fields_):

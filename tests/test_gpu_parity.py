@@ -215,7 +215,11 @@ def test_seeded_random_shapes(gs, seed):
             v = None
         B = graphgen.random_dense(K, N, int(rng.integers(1 << 30)))
         op = str(rng.choice(OPS))
-        check(gs, rp, ci, v, B, op, label=f"random seed={seed}")
+        C_narrow = check(gs, rp, ci, v, B, op, label=f"random seed={seed}")
+        # the same call with 64-bit addresses for its gathers instead of buffer offsets: max / min the same bits
+        C_wide = check(gs, rp, ci, v, B, op, label=f"random seed={seed} wide", tuning=dict(wide_addresses=1))
+        if op in ("max", "min"):
+            assert np.array_equal(C_narrow.view(np.uint32), C_wide.view(np.uint32))
         if op in ("max", "min"):
             C, arg = gs.gespmm_csr_arg(dev(rp), dev(ci), dev(v), dev(B), op)
             torch.cuda.synchronize()
@@ -593,6 +597,25 @@ def test_entry_count_near_the_32_bit_limit(gs):
     assert bool((C == 0.0).all())
     p = ctypes.c_void_p(0x1000)                         # beyond the limit: rejected on the host, nothing runs
     assert gs.lib().gespmm_csr(M, K, N, 2**31 - 1, p, p, None, p, p, 0, None) == 3
+
+
+@pytest.mark.parametrize("K", [670_000, 671_200])
+def test_feature_matrix_at_the_2_gib_border_of_the_buffer_offsets(gs, K):
+    """B of 800 columns: 670,000 rows are 2,144,000,000 bytes, just inside what the gathers address with 32-bit
+    buffer offsets (byte offsets up to the top of the signed range); 671,200 rows are beyond the border, where the
+    kernels compute 64-bit addresses.  Few rows of A, entries spread over all of B including its last row."""
+    N, M = 800, 300
+    say(f"  case 2 GiB border K={K} bytes={K * N * 4}")
+    rng = np.random.default_rng(K)
+    B = rng.standard_normal((K, N), dtype=np.float32)
+    rp, ci, v = graphgen.random_csr(M, K, 20.0, 77, empty_frac=0.1, long_rows=((5, 1500),))
+    ci[-1] = K - 1
+    ci[rp[5]:rp[5] + 3] = (0, K - 1, K - 2)
+    dB = dev(B)
+    for op in ("sum", "max"):
+        check(gs, rp, ci, v, B, op, dB=dB, label=f"2 GiB border K={K}")
+    del dB
+    torch.cuda.empty_cache()
 
 
 def test_zz_report_worst_error_ratio(gs):
