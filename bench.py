@@ -799,6 +799,8 @@ def main():
         out["measured_copy_GBps"] = copy
         out["roofline"]["frac_of_measured_copy"] = achieved / copy
         out["single_call"]["cold_model_GBps"] = r["model_bytes"] / (out["single_call"]["cold_mean_ms"] * 1e-3) / 1e9
+        # the same calls captured into one HIP graph and replayed (what a launch-bound inner loop would do)
+        out["single_call"]["hip_graph_ms_per_step"] = time_graph_replay(gs, torch, case, op, min(args.steps, 200))
     if not args.no_cpu:
         out["cpu_baseline"], out["parity"] = cpu_baseline(w, case.B_host, op, C_timed)
     if sweep_rows is not None:
