@@ -142,16 +142,39 @@ static __global__ void __launch_bounds__(kBlock) phase_pieces(int32_t M, int32_t
   const bool live = row < M && q < Q;
   const int r = (int)(row < M ? row : M - 1);
   const int s = rowptr[r], e = rowptr[r + 1];
-  // Binary search over the whole row.  For any data, sorted or not, the result is monotone in the
-  // column searched for as long as every search starts from the same interval, which is what makes
-  // the pieces a partition of the row: the end of piece q IS the start of piece q + 1.
-  int lo = s, hi = e;
+  // Eight-way search over the whole row: seven probes per round, all in flight together, three rounds
+  // for a row of 500 entries where a binary search makes nine dependent loads.  The interval becomes the
+  // gap before the LEFTMOST probe whose column is >= the one searched for.  For any data, sorted or not,
+  // that choice is monotone in the column searched for as long as every search starts from the same
+  // interval (a larger column can only move the leftmost such probe to the right, and equal intervals
+  // are probed alike), which is what makes the pieces a partition of the row: the end of piece q IS the
+  // start of piece q + 1.
+  int lo = s, hi = e;                               // the answer lies in [lo, hi]
   const int64_t column = (int64_t)q * cols_per_part;
   if (q == 0 || !live) hi = lo;                     // piece 0 starts where the row starts
   while (lo < hi) {
-    const int mid = lo + ((hi - lo) >> 1);
-    if (colind[mid] < column) lo = mid + 1;
-    else hi = mid;
+    const int step = (hi - lo + 7) >> 3;
+    int seen[7];
+#pragma unroll
+    for (int i = 0; i < 7; ++i) {
+      const int p = lo + (i + 1) * step - 1;        // a probe at or beyond hi does not exist
+      seen[i] = colind[p < hi ? p : hi - 1];
+    }
+    int new_lo = lo, new_hi = hi;
+    bool found = false;
+#pragma unroll
+    for (int i = 0; i < 7; ++i) {
+      const int p = lo + (i + 1) * step - 1;
+      if (!found && p < hi) {
+        if (seen[i] < column) new_lo = p + 1;
+        else {
+          new_hi = p;
+          found = true;
+        }
+      }
+    }
+    lo = new_lo;
+    hi = new_hi;
   }
   const int begin = lo;
   const int next_begin = __shfl_down(begin, 1, kWave);    // the lane to the right holds part q + 1 of the same row
