@@ -227,8 +227,8 @@ int gespmm_pool_backward(int64_t M, int64_t K, int64_t N, int64_t nnz, const int
  * column range is cut into by the K-phased path of gespmm_csr_ex; 0 or 1 = off).  A value that
  * has no kernel makes the call return GESPMM_ERR_BAD_ARG.
  * longest_row is not an override but something the caller may know about the matrix: an upper
- * bound on the stored entries of any row (-1 or 0 = not known).  With it the forward call on fp32
- * features can take the WHOLE-ROW path when rows are short against a chunk (or the problem is
+ * bound on the stored entries of any row (-1 or 0 = not known).  With it the forward call (and the
+ * value+position call and user-defined reduces on fp32 features) can take the WHOLE-ROW path when rows are short against a chunk (or the problem is
  * small): every row is computed by one wavefront and written once, so the call is a single kernel
  * launch without presetting and without atomics, and sum / mean become independent of the order in
  * which wavefronts finish.  The bound only selects the path: the result is right whatever it says;
@@ -347,7 +347,8 @@ int gespmm_csr_arg_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_
  *
  * gespmm_csr_custom: C[i, j] = merge over the stored entries p of row i of step(identity(), vals[p],
  * B[colind[p], j]), 0 for a row that stores nothing.  Arguments, layout, ownership, stream semantics and
- * errors as gespmm_csr (fp32 features); tuning as in gespmm_csr_ex (longest_row and k_parts are ignored).
+ * errors as gespmm_csr (fp32 features); tuning as in gespmm_csr_ex (k_parts is ignored; longest_row selects the
+ * whole-row path as there, on which no compare-and-swap loop runs).
  * Rows that lie in several chunks are combined by a compare-and-swap loop around merge.
  */
 typedef struct gespmm_custom_op gespmm_custom_op_t;

@@ -859,6 +859,17 @@ struct CustomRows {
         for (int x = 0; x < V; ++x) s.acc[t].v[x] = R::merge(s.acc[t].v[x], __shfl_xor(s.acc[t].v[x], off, kWave));
   }
 
+  // A row without stored entries yields 0 (whole-row path).
+  __device__ static void store_empty(const KernelArgs& a, int64_t row, const int (&col)[T]) {
+    float* crow = a.C + row * (int64_t)a.N;
+    Vec<V> zero;
+#pragma unroll
+    for (int x = 0; x < V; ++x) zero.v[x] = 0.0f;
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+      if (col[t] < a.N) zero.store(crow + col[t]);
+  }
+
   __device__ static void end(State& s, const KernelArgs& a, int64_t row, bool whole, int, const int (&col)[T]) {
     float* crow = a.C + row * (int64_t)a.N;
 #pragma unroll

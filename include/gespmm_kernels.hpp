@@ -305,7 +305,7 @@ MainKernel pick_phased(int job, int vec, int G, int T) {
   return nullptr;
 }
 
-// Kernels of the whole-row path: the three folds and max / min with positions, on fp32 features, one tile per lane.
+// Kernels of the whole-row path, one tile per lane: the three folds and max / min with positions on fp32 features ...
 inline bool has_owned_kernel(int G, int T) { return T == 1 && G >= 1 && G <= kWave; }
 
 template <class P4, class P1>
@@ -316,6 +316,24 @@ MainKernel pick_owned_shapes(int vec, int G) {      // P4 / P1: the policy for 4
   GESPMM_CASE(1) GESPMM_CASE(2) GESPMM_CASE(4) GESPMM_CASE(8) GESPMM_CASE(16) GESPMM_CASE(32) GESPMM_CASE(64)
 #undef GESPMM_CASE
   return nullptr;
+}
+
+// ... and the three folds on 16-bit features (slots of up to 32 lanes with four columns per lane)
+template <int F, class BT>
+MainKernel pick_owned_b16_fold(int vec, int G) {
+  if (vec == 4 && G > 32) return nullptr;
+  return pick_owned_shapes<FoldRows<F, 4, 1, BT>, FoldRows<F, 1, 1, BT>>(vec, G);
+}
+
+template <class BT>
+MainKernel pick_owned_b16(int job, int vec, int G, int T) {
+  if (T != 1) return nullptr;
+  switch (job) {
+    case kJobAdd: return pick_owned_b16_fold<kAdd, BT>(vec, G);
+    case kJobMax: return pick_owned_b16_fold<kMax, BT>(vec, G);
+    case kJobMin: return pick_owned_b16_fold<kMin, BT>(vec, G);
+    default: return nullptr;
+  }
 }
 
 inline MainKernel pick_owned(int job, int vec, int G, int T) {
@@ -411,7 +429,8 @@ inline int choose_parts(int64_t M, int64_t K, int64_t nnz, int vec, int block_by
 
 // elem_bytes: size of one element of the dense input (4, or 2 for the 16-bit formats); a lane
 // loads four columns at once when the width and the alignment allow it, one otherwise.
-// whole_rows_allowed: the job has kernels of the whole-row path (the forward folds on fp32 features).
+// whole_rows_allowed: the job has kernels of the whole-row path (the forward folds; max / min with positions and
+// user-defined reduces on fp32 features).
 inline void make_plan(int64_t M, int64_t K, int64_t N, int64_t nnz, bool aligned16, int elem_bytes, const Tuning& tune,
                       size_t workspace_bytes, gespmm_plan_t* p, bool whole_rows_allowed = true) {
   int vec = 1;
@@ -575,6 +594,7 @@ struct ChunkLaunch {
   bool only_split = false;             // position job: leave rows that lie inside one chunk alone
   bool packed_split = false;           // fused value+position job: packed words for split rows, unpacked at the end
   MainKernel (*picker)(int vec, int G, int T) = nullptr;   // user-defined reduce: its own kernel table
+  MainKernel (*owned_picker)(int vec, int G, int T) = nullptr;   // ... and its kernels of the whole-row path
   // user-defined reduce compiled at run time: launches the chunk kernel of the planned shape itself
   int (*launcher)(void* context, const gespmm_plan_t& plan, const KernelArgs& args, hipStream_t stream) = nullptr;
   void* launcher_context = nullptr;
@@ -715,7 +735,8 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream, bool* took_wh
   }
   gespmm_plan_t plan;
   const bool arg_job = !L.picker && !L.launcher && (L.job == kJobMaxWithArg || L.job == kJobMinWithArg) && L.arg && !L.one_lane_per_entry;
-  const bool whole_rows_allowed = (fold_job || arg_job) && L.b_dtype == GESPMM_F32 && L.init_target == L.dense_out;
+  const bool custom_job = (L.picker && L.owned_picker) || L.launcher;
+  const bool whole_rows_allowed = (fold_job || ((arg_job || custom_job) && L.b_dtype == GESPMM_F32)) && L.init_target == L.dense_out;
   make_plan(L.M, L.K, L.N, L.nnz, aligned16, L.b_dtype == GESPMM_F32 ? 4 : 2, tune, L.workspace_bytes, &plan, whole_rows_allowed);
   if (L.one_lane_per_entry) {
     plan.vec = 1;
@@ -744,7 +765,15 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream, bool* took_wh
   else if (L.b_dtype == GESPMM_BF16) kernel = pick_b16<bf16_t>(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
   else if (L.b_dtype == GESPMM_F16) kernel = pick_b16<f16_t>(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
   else kernel = pick_kernel(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
-  if (plan.row_window > 0) kernel = pick_owned(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
+  if (plan.row_window > 0 && L.launcher) {
+    kernel = nullptr;
+  } else if (plan.row_window > 0 && L.picker) {
+    kernel = L.owned_picker(plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
+  } else if (plan.row_window > 0) {
+    if (L.b_dtype == GESPMM_BF16) kernel = pick_owned_b16<bf16_t>(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
+    else if (L.b_dtype == GESPMM_F16) kernel = pick_owned_b16<f16_t>(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
+    else kernel = pick_owned(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
+  }
   if (!kernel && !L.launcher) return GESPMM_ERR_BAD_ARG;
 
   // (a) empty rows and rows shared by several chunks are preset (the whole-row path writes every row itself)
@@ -825,6 +854,11 @@ struct CustomBind {
 };
 
 template <class R>
+MainKernel pick_custom_owned(int vec, int G, int T) {
+  return T == 1 ? pick_owned_shapes<CustomRows<R, 4, 1>, CustomRows<R, 1, 1>>(vec, G) : nullptr;
+}
+
+template <class R>
 MainKernel pick_custom(int vec, int G, int T) {
   return vec == 4 ? pick_gt<CustomBind<R>::template Rows, 4>(G, T) : pick_gt<CustomBind<R>::template Rows, 1>(G, T);
 }
@@ -846,6 +880,7 @@ int csr_custom(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowp
   const int parsed = parse_tuning(tuning, &L.tuning);
   if (parsed != GESPMM_OK) return parsed;
   L.picker = &pick_custom<R>;
+  L.owned_picker = &pick_custom_owned<R>;
   L.M = M; L.K = K; L.N = N; L.nnz = nnz;
   L.rowptr = rowptr; L.colind = colind; L.vals = vals;
   L.dense_in = B; L.dense_out = C;

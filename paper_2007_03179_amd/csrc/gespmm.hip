@@ -25,7 +25,7 @@ int gespmm_plan_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, int aligned16, 
   Tuning tune;
   const int parsed = parse_tuning(tuning, &tune);
   if (parsed != GESPMM_OK) return parsed;
-  make_plan(M, K, N, nnz, aligned16 != 0, element_bytes(b_dtype), tune, workspace_bytes, out, b_dtype == GESPMM_F32);
+  make_plan(M, K, N, nnz, aligned16 != 0, element_bytes(b_dtype), tune, workspace_bytes, out);
   return GESPMM_OK;
 }
 
@@ -527,7 +527,7 @@ int gespmm_custom_op_create(const char* source, const char* name, gespmm_custom_
   // step() and merge(): build the most common kernel shape now, so that a mistake in them is reported here
   if (status == GESPMM_OK) {
     hipFunction_t function = nullptr;
-    status = op->kernel_for(4, 8, 1, &function, &text);
+    status = op->kernel_for(4, 8, 1, false, &function, &text);
   }
   copy_log(text, log, log_bytes);
   if (status != GESPMM_OK) {

@@ -138,17 +138,17 @@ struct gespmm_custom_op {
     hipFunction_t function = nullptr;
   };
   std::mutex lock;          // guards `kernels`
-  std::map<std::tuple<int, int, int>, Built> kernels;   // (vec, G, T) -> loaded kernel
+  std::map<std::tuple<int, int, int, int>, Built> kernels;   // (vec, G, T, whole-row path) -> loaded kernel
 
   // The chunk kernel for CustomRows<name, vec, T> with slots of G lanes; compiled and loaded on first use.
-  int kernel_for(int vec, int G, int T, hipFunction_t* out, std::string* log) {
+  int kernel_for(int vec, int G, int T, bool whole_rows, hipFunction_t* out, std::string* log) {
     std::lock_guard<std::mutex> guard(lock);
-    const auto key = std::make_tuple(vec, G, T);
+    const auto key = std::make_tuple(vec, G, T, whole_rows ? 1 : 0);
     auto found = kernels.find(key);
     if (found == kernels.end()) {
       const std::string expression = "gespmm_detail::chunk_kernel<gespmm_detail::CustomRows<" + name + ", " + std::to_string(vec) +
                                      ", " + std::to_string(T) + ">, " + std::to_string(vec) + ", " + std::to_string(G) + ", " +
-                                     std::to_string(T) + ", false, false>";
+                                     std::to_string(T) + ", false, " + (whole_rows ? "true" : "false") + ">";
       std::vector<char> code;
       std::string symbol;
       const int compiled = gespmm_detail::rtc_compile(source, arch, expression, "", &code, &symbol, log);
@@ -171,7 +171,7 @@ namespace gespmm_detail {
 inline int rtc_launch(void* context, const gespmm_plan_t& plan, const KernelArgs& args, hipStream_t stream) {
   gespmm_custom_op* op = static_cast<gespmm_custom_op*>(context);
   hipFunction_t function = nullptr;
-  const int built = op->kernel_for(plan.vec, plan.lanes_per_row, plan.tiles_per_lane, &function, nullptr);
+  const int built = op->kernel_for(plan.vec, plan.lanes_per_row, plan.tiles_per_lane, plan.row_window > 0, &function, nullptr);
   if (built != GESPMM_OK) return built;
   KernelArgs copy = args;
   void* params[] = {&copy};

@@ -30,6 +30,13 @@ int custom_sum_of_squares(int64_t M, int64_t K, int64_t N, int64_t nnz, const in
   return gespmm::csr_custom<SumOfSquares>(M, K, N, nnz, rowptr, colind, vals, B, C, (hipStream_t)stream);
 }
 
+// the same with the caller's bound on the longest row: the whole-row path (one launch, no compare-and-swap combine)
+int custom_sum_of_squares_bounded(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+                                  const float* vals, const float* B, float* C, void* stream, int longest_row) {
+  gespmm_tuning_t tuning = {-1, -1, -1, -1, -1, -1, longest_row, -1};
+  return gespmm::csr_custom<SumOfSquares>(M, K, N, nnz, rowptr, colind, vals, B, C, (hipStream_t)stream, &tuning);
+}
+
 int custom_max_magnitude(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
                          const float* vals, const float* B, float* C, void* stream) {
   return gespmm::csr_custom<MaxMagnitude>(M, K, N, nnz, rowptr, colind, vals, B, C, (hipStream_t)stream);

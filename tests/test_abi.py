@@ -215,9 +215,9 @@ def test_whole_row_path_is_planned_only_from_a_bound_on_the_longest_row():
     assert plan(1_000_000, 1_000_000, 128, 10_000_000, tuning=dict(longest_row=256))["row_window"] == 512
     assert plan(1_000_000, 1_000_000, 128, 10_000_000, tuning=dict(longest_row=257))["row_window"] == 0
     assert plan(1_000_000, 1_000_000, 128, 5_000_000, tuning=dict(longest_row=5))["row_window"] == 0
-    # the K-phased path and 16-bit features keep their own kernels; LDS per workgroup stays within 64 KB
+    # the K-phased path keeps its own kernels; 16-bit features have whole-row kernels too; LDS per workgroup stays within 64 KB
     assert plan(232_965, 232_965, 64, 114_693_532, workspace_bytes=1 << 40, tuning=dict(longest_row=100))["row_window"] == 0
-    assert plan(19_717, 19_717, 128, 88_648, "bf16", tuning=dict(longest_row=173))["row_window"] == 0
+    assert plan(19_717, 19_717, 128, 88_648, "bf16", tuning=dict(longest_row=173))["row_window"] > 0
     assert plan(1000, 1000, 64, 10_000, tuning=dict(longest_row=1000, chunk_nnz=1024))["row_window"] == 0
     assert plan(1000, 1000, 64, 10_000, tuning=dict(longest_row=960, chunk_nnz=1024))["row_window"] == 1984
 

@@ -173,3 +173,20 @@ def test_value_and_position_b16_on_a_workload(gs):
         Cref, aref = oracle.spmm_arg(w.rowptr, w.colind, vals, Bw, op)
         assert np.array_equal(C.cpu().numpy().view(np.uint32), Cref.astype(np.float32).view(np.uint32))
         assert np.array_equal(arg.cpu().numpy(), aref)
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f16"])
+@pytest.mark.parametrize("N", [1, 4, 8, 37, 64, 136, 512])
+def test_whole_row_path_on_16_bit_features(gs, N, dt):
+    """The single-launch path (tuning.longest_row) with B stored in 16 bits: true and understated bounds, empty rows,
+    rows longer than a chunk, every slot width the kernels exist for."""
+    rp, ci, v = graphgen.random_csr(600, 400, 9.0, 900 + N, empty_frac=0.15, long_rows=((77, 900), (599, 0), (0, 0)))
+    B = graphgen.random_dense(400, N, N)
+    dA, dB = (dev(rp), dev(ci), dev(v)), narrow(B, dt)[0].cuda()
+    longest = int(np.diff(rp).max())
+    for hint, G, chunk in ((longest, -1, -1), (4, -1, 64), (longest, 32, 128), (100, 1, 1024), (longest, 2, 16)):
+        tuning = dict(longest_row=hint, lanes_per_row=G, chunk_nnz=chunk)
+        if G < 0:                                   # (a forced narrow slot can make the problem too large for a long bound)
+            assert gs.gespmm_plan_ex(600, 400, N, len(ci), dt, tuning=tuning)["row_window"] > 0
+        for op in OPS:
+            check(gs, rp, ci, v, B, dt, op, dA=dA, dB=dB, tuning=tuning, label=f"whole-row hint={hint} G={G} S={chunk}")
