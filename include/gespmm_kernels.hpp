@@ -410,16 +410,20 @@ inline size_t phased_workspace_bytes(int64_t M, int Q) {
 // the rows of A are long enough that a piece of a row still holds a few dozen entries.  A part is
 // sized to about 7.5 MB of B rows: measured on the 233k-vertex workload (60 MB of B), 8 parts beat
 // 6, 10, 14, 20 and 28; smaller parts raise the L2 hit rate further (65 % -> 84 %) but every phase
-// re-reads and re-writes C and walks all rows again, which costs more than the hits bring.  Needs
-// the vector kernels and, unless forced, a workspace that is large enough.
-inline int choose_parts(int64_t M, int64_t K, int64_t nnz, int vec, int block_bytes, const Tuning& tune,
+// re-reads and re-writes C and walks all rows again, which costs more than the hits bring.  The
+// phases start to pay where the rows the PLAIN path's own column block touches (plain_block_bytes per
+// row) reach about twice an L2: a 40k-row matrix of mean row 130 at N = 512 (10 MB per block of 256
+// bytes) is 15 % faster in two parts, the same matrix at N = 128 (5 MB per block of 128 bytes) is
+// slower.  Needs the vector kernels and, unless forced, a workspace that is large enough.
+inline int choose_parts(int64_t M, int64_t K, int64_t nnz, int vec, int block_bytes, int plain_block_bytes, const Tuning& tune,
                         size_t workspace_bytes) {
   if (vec != 4 || M <= 0 || K <= 0 || nnz <= 0) return 1;
   if (tune.k_parts >= 0) return tune.k_parts < 2 ? 1 : (int)(tune.k_parts < K ? tune.k_parts : (K < 2 ? 1 : K));
   const int64_t live = K * block_bytes;
   const int64_t mean_row = nnz / M;
-  if (live < (12ll << 20) || mean_row < 128) return 1;
+  if (K * plain_block_bytes < (8ll << 20) || mean_row < 128) return 1;
   int64_t q = (live + (15ll << 18)) / (15ll << 19);        // nearest multiple of 7.5 MB
+  if (q < 2) q = 2;
   while (q > 2 && mean_row / q < 32) --q;
   if (q > kMaxParts) q = kMaxParts;
   if (q < 2) return 1;
@@ -447,7 +451,8 @@ inline void make_plan(int64_t M, int64_t K, int64_t N, int64_t nnz, bool aligned
     const int line = 128 / (vec * elem_bytes);  // lanes that cover one 128-byte line of a row of B
     // the K-phased path keeps B in L2 by its own means and takes two lines per block
     const int wide = G > 2 * line ? 2 * line : G;
-    parts = choose_parts(M, K, nnz, vec, wide * vec * elem_bytes, tune, workspace_bytes);
+    const int plain = G > line ? (ncv <= 4 * line ? line : 2 * line) : G;      // what the plain path would take
+    parts = choose_parts(M, K, nnz, vec, wide * vec * elem_bytes, plain * vec * elem_bytes, tune, workspace_bytes);
     if (parts > 1) G = wide < 8 ? 8 : wide;
     else if (G > line) G = ncv <= 4 * line ? line : 2 * line;   // one line; two lines for wide N
   } else if (elem_bytes == 2) {

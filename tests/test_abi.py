@@ -200,6 +200,11 @@ def test_k_phased_path_is_planned_for_large_features_and_long_rows():
     assert gs.gespmm_plan_ex(1_000_000, 1_000_000, 32, 15_357_733, **big)["k_parts"] == 1
     assert gs.gespmm_plan_ex(20_000, 20_000, 64, 10_000_000, **big)["k_parts"] == 1
     assert gs.gespmm_csr_workspace_bytes(1_000_000, 1_000_000, 32, 15_357_733) == 0
+    # 40,000 rows of 130 entries: two parts where the plain path's column block (256 bytes at N = 512) sees 10 MB of B,
+    # none where it sees 5 MB (128-byte blocks at N = 128)
+    assert gs.gespmm_plan_ex(40_000, 40_000, 512, 5_165_394, **big)["k_parts"] == 2
+    assert gs.gespmm_plan_ex(40_000, 40_000, 256, 5_165_394, **big)["k_parts"] == 2
+    assert gs.gespmm_plan_ex(40_000, 40_000, 128, 5_165_394, **big)["k_parts"] == 1
 
 
 def test_whole_row_path_is_planned_only_from_a_bound_on_the_longest_row():
