@@ -341,7 +341,9 @@ int gespmm_csr_arg_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_
  * gespmm_custom_op_create compiles on the calling thread (about a second), runs a one-thread kernel on the
  * current device to read identity() and synchronises with it; kernels for further launch shapes are
  * compiled on first use inside gespmm_csr_custom (a fraction of a second each, once).  The operation is
- * bound to the device that was current at creation.  It may be used from several threads.
+ * bound to the device that was current at creation.  It may be used from several threads.  Creation
+ * allocates and synchronises, and so does the first call with a new launch shape (it loads a module): do
+ * both outside HIP graph capture; later calls only launch kernels and can be captured.
  * Errors: GESPMM_ERR_NULL, GESPMM_ERR_BAD_ARG (name is not an identifier; another device is current),
  * GESPMM_ERR_COMPILE (see log), GESPMM_ERR_NO_RTC, GESPMM_ERR_HIP.
  *
