@@ -499,7 +499,9 @@ inline void make_plan(int64_t M, int64_t K, int64_t N, int64_t nnz, bool aligned
   // row up to 32 entries avoids that combine for most rows (measured: up to 22 % on a
   // 27-point stencil, within 3 % either way on power-law graphs of the same mean).
   const int64_t mean_row = M > 0 ? nnz / M / parts : 0;
-  int auto_short = p->slots >= 4 ? 16 : 2 * p->slots;      // (four slots: 16 beats 8 by 0-5 % on twelve matrices at N = 256 / 512)
+  // (four slots: 16 beats 8 by 0-5 % on twelve matrices at N = 256 / 512; sixteen slots and more, N <= 16: 32 beats
+  //  16 by 5-15 % on a 170k-vertex power-law graph and by 2 % on the R-MAT workload, and is neutral on nine others)
+  int auto_short = p->slots >= 16 ? 32 : (p->slots >= 4 ? 16 : 2 * p->slots);
   if (mean_row > 16 && mean_row <= 48) auto_short = 32;
   p->short_len = tune.short_len >= 0 ? tune.short_len : auto_short;
   // The whole-row path (one launch, no presetting, no atomics) when the caller has said how long the

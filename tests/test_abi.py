@@ -231,7 +231,7 @@ def test_chunk_size_follows_width_and_problem_size():
     big = 100_000_000
     plans = [gs.gespmm_plan(10**6, N, big) for N in (8, 16, 32, 64, 128, 512)]
     assert [p["chunk_nnz"] for p in plans] == [512, 512, 256, 256, 256, 256]
-    assert [p["short_len"] for p in plans] == [16, 16, 16, 16, 16, 16]
+    assert [p["short_len"] for p in plans] == [32, 32, 16, 16, 16, 16]
     # long rows (mean length >= 128): larger chunks, fewer split rows
     assert gs.gespmm_plan(232_965, 64, 114_693_532)["chunk_nnz"] == 512
     assert all(p["lds_bytes"] == 4 * (p["chunk_nnz"] + 64) * 8 for p in plans)
