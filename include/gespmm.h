@@ -357,6 +357,9 @@ typedef struct gespmm_custom_op gespmm_custom_op_t;
 int gespmm_custom_op_create(const char* source, const char* name, gespmm_custom_op_t** out, char* log,
                             size_t log_bytes);
 int gespmm_custom_op_destroy(gespmm_custom_op_t* op);
+/* Compiles the same text for `arch` (NULL = "gfx950") without touching a device and without keeping anything:
+ * GESPMM_OK, or GESPMM_ERR_COMPILE with the compiler's messages in log.  A pure host function. */
+int gespmm_custom_op_check(const char* source, const char* name, const char* arch, char* log, size_t log_bytes);
 int gespmm_csr_custom(gespmm_custom_op_t* op, int64_t M, int64_t K, int64_t N, int64_t nnz,
                       const int32_t* rowptr, const int32_t* colind, const float* vals, const float* B,
                       float* C, const gespmm_tuning_t* tuning, void* stream);

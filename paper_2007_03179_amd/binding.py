@@ -127,6 +127,8 @@ def lib():
         L.gespmm_calibration_gather_shape.argtypes = [vp, i64, ci, vp, i64, ci, ci, ci, ci, vp, i64, vp]
         L.gespmm_custom_op_create.restype = ci
         L.gespmm_custom_op_create.argtypes = [ctypes.c_char_p, ctypes.c_char_p, ctypes.POINTER(vp), ctypes.c_char_p, ctypes.c_size_t]
+        L.gespmm_custom_op_check.restype = ci
+        L.gespmm_custom_op_check.argtypes = [ctypes.c_char_p, ctypes.c_char_p, ctypes.c_char_p, ctypes.c_char_p, ctypes.c_size_t]
         L.gespmm_custom_op_destroy.restype = ci
         L.gespmm_custom_op_destroy.argtypes = [vp]
         L.gespmm_csr_custom.restype = ci
@@ -432,6 +434,18 @@ def gespmm_custom_op_create(source: str, name: str):
         err.log = log.value.decode(errors="replace")
         raise err
     return handle
+
+
+def gespmm_custom_op_check(source: str, name: str, arch: str = "gfx950") -> str:
+    """Compile the text of a user-defined reduce without a GPU; returns the compiler's messages (warnings) or
+    raises GespmmError with them."""
+    log = ctypes.create_string_buffer(1 << 16)
+    status = lib().gespmm_custom_op_check(source.encode(), name.encode(), arch.encode(), log, len(log))
+    if status != GESPMM_OK:
+        err = GespmmError(status, gespmm_status_string(status) + "\n" + log.value.decode(errors="replace"))
+        err.log = log.value.decode(errors="replace")
+        raise err
+    return log.value.decode(errors="replace")
 
 
 def gespmm_custom_op_destroy(op):

@@ -538,6 +538,20 @@ int gespmm_custom_op_create(const char* source, const char* name, gespmm_custom_
   return GESPMM_OK;
 }
 
+int gespmm_custom_op_check(const char* source, const char* name, const char* arch, char* log, size_t log_bytes) {
+  if (log && log_bytes > 0) log[0] = '\0';
+  if (!source || !name) return GESPMM_ERR_NULL;
+  if (!is_identifier(name)) return GESPMM_ERR_BAD_ARG;
+  const std::string text = std::string("#include \"gespmm_device.hpp\"\n#line 1 \"user_reduce\"\n") + source + "\n" +
+                           "extern \"C\" __global__ void gespmm_identity_of(float* out) { *out = " + name + "::identity(); }\n";
+  const std::string expression = std::string("gespmm_detail::chunk_kernel<gespmm_detail::CustomRows<") + name + ", 4, 1>, 4, 8, 1, false, false>";
+  std::vector<char> code;
+  std::string symbol, messages;
+  const int status = rtc_compile(text, arch && *arch ? arch : "gfx950", expression, "", &code, &symbol, &messages);
+  copy_log(messages, log, log_bytes);
+  return status;
+}
+
 int gespmm_custom_op_destroy(gespmm_custom_op_t* op) {
   if (!op) return GESPMM_OK;
   int status = GESPMM_OK;

@@ -288,3 +288,28 @@ def test_embedded_device_header_is_the_header():
     device = open(os.path.join(ROOT, "include", "gespmm_device.hpp")).read()
     includes = re.findall(r"#include\s*[<\"]([^>\"]+)[>\"]", device)
     assert sorted(includes) == ["cstdint", "hip/hip_runtime.h"], includes
+
+
+def test_run_time_reduce_compiles_without_a_gpu():
+    """The text of a user-defined reduce goes through the run-time compiler together with the embedded kernel header,
+    for gfx950, on a machine without a GPU: a good text compiles, a broken one and one without step() are reported."""
+    good = """struct SumOfSquares {
+      static __device__ float identity() { return 0.0f; }
+      static __device__ float step(float acc, float a, float b) { const float x = a * b; return acc + x * x; }
+      static __device__ float merge(float x, float y) { return x + y; } };"""
+    try:
+        gs.gespmm_custom_op_check(good, "SumOfSquares")
+    except gs.GespmmError as e:
+        if e.status == 8:
+            pytest.skip("libhiprtc.so is not installed here")
+        raise
+    with pytest.raises(gs.GespmmError) as e:
+        gs.gespmm_custom_op_check("struct Broken { static __device__ float identity() { return 0.0f } };", "Broken")
+    assert e.value.status == 7 and "error" in e.value.log
+    with pytest.raises(gs.GespmmError) as e:
+        gs.gespmm_custom_op_check("""struct NoStep { static __device__ float identity() { return 0.0f; }
+                                     static __device__ float merge(float x, float y) { return x + y; } };""", "NoStep")
+    assert e.value.status == 7 and "step" in e.value.log
+    with pytest.raises(gs.GespmmError) as e:
+        gs.gespmm_custom_op_check(good, "Sum Of Squares")
+    assert e.value.status == 1
