@@ -167,7 +167,7 @@ class DeviceCase:
         self.C = torch.empty((w.M, N), dtype=torch.float32, device=dev)
         self.work = None                                 # workspace of the K-phased path, when the plan wants one
         import paper_2007_03179_amd as gs
-        self.tuning = case_tuning(w)
+        self.tuning = gs.make_tuning(case_tuning(w))      # built once: the calls of the timed loop pass the structure
         need = gs.gespmm_csr_workspace_bytes(w.M, w.K, N, w.nnz, B_DTYPE_NAME, tuning=self.tuning) if USE_WORKSPACE else 0
         if need:
             self.work = torch.empty(need // 4 + 1, dtype=torch.int32, device=dev)
@@ -179,14 +179,16 @@ class DeviceCase:
         roofline figure; the two extra event records per step cost a few microseconds, which
         only matters for microsecond-scale workloads)."""
         stream = torch.cuda.current_stream()
+        # the same call of gespmm_csr_ex every step, its arguments marshalled once (the binding's prepared form)
+        call = gs.gespmm_csr_prepared(self.rp, self.ci, self.v, self.B, op, C=self.C, workspace=self.work, tuning=self.tuning, stream=stream)
         for _ in range(warmup):
-            forward(gs, self.tuning)(self.rp, self.ci, self.v, self.B, op, C=self.C, stream=stream, workspace=self.work)
+            call()
         torch.cuda.synchronize()
         launches_per_call = self.plan["k_parts"]         # main-kernel launches one call makes
         prof = gs.gespmm_profiler_create(steps * launches_per_call) if bracket_kernel else None
         t0 = time.perf_counter()
         for _ in range(steps):
-            forward(gs, self.tuning)(self.rp, self.ci, self.v, self.B, op, C=self.C, stream=stream, workspace=self.work, profiler=prof)
+            call(prof)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         main_ms_sum, launches = gs.gespmm_profiler_finish(prof) if bracket_kernel else (float("nan"), 0)
@@ -383,6 +385,7 @@ def gcn_share(args, gs, torch, graphgen, dev):
 def sweep(args, gs, torch, graphgen, dev, evictor):
     """Every workload / width / op of the five configurations; table on stderr."""
     rows = []
+    rocsparse = Rocsparse(torch) if args.rocsparse and B_ELEM_BYTES == 4 else None
     for name in graphgen.WORKLOAD_NAMES + graphgen.EXTRA_WORKLOAD_NAMES:
         w = graphgen.workload(name, args.scale)
         print(f"# {w.describe()}", file=sys.stderr, flush=True)
@@ -395,13 +398,18 @@ def sweep(args, gs, torch, graphgen, dev, evictor):
                 r["main_kernel_ms"], r["model_GBps_kernel"] = k["main_kernel_ms"], k["model_GBps_kernel"]
                 r["graph_ms_per_step"] = time_graph_replay(gs, torch, case, op, steps) if w.nnz * N < 5e8 else None
                 r.update(warm_and_cold(gs, torch, case, op, evictor, calls=20))
+                r["rocsparse_ms"], r["rocsparse_alg"] = None, None
+                if rocsparse is not None and op == "sum":          # the vendor library has the plain product only
+                    case.time(gs, torch, op, 1, 0, bracket_kernel=False)          # case.C: this library's result, to check the vendor's call against
+                    r["rocsparse_ms"], r["rocsparse_alg"] = rocsparse.best_time(case, min(steps, 200), case.C)
                 rows.append(r)
                 print(f"{r['workload']:20s} N={N:4d} {op:5s} step {r['ms_per_step']*1e3:9.1f} us  kernel "
                       f"{r['main_kernel_ms']*1e3:9.1f} us  {r['gflops']:8.1f} GFLOP/s  model "
                       f"{r['model_GBps_step']:8.1f} GB/s ({r['model_GBps_step']/HBM_PEAK_GBPS*100:5.1f}% of HBM peak)"
                       f"  single call min {r['warm_min_ms']*1e3:8.1f} us, caches flushed {r['cold_mean_ms']*1e3:8.1f} us"
-                      + (f"  in a HIP graph {r['graph_ms_per_step']*1e3:7.1f} us" if r["graph_ms_per_step"] else ""),
-                      file=sys.stderr, flush=True)
+                      + (f"  in a HIP graph {r['graph_ms_per_step']*1e3:7.1f} us" if r["graph_ms_per_step"] else "")
+                      + (f"  rocsparse_spmm [{r['rocsparse_alg']}] {r['rocsparse_ms']*1e3:8.1f} us ({r['rocsparse_ms']/r['ms_per_step']:4.2f}x)"
+                         if r["rocsparse_ms"] else ""), file=sys.stderr, flush=True)
             del case
             torch.cuda.empty_cache()
     return rows
@@ -591,11 +599,83 @@ def geomean(xs):
     return math.exp(sum(math.log(x) for x in xs) / len(xs)) if xs else None
 
 
+class Rocsparse:
+    """The vendor's own CSR x dense product (rocsparse_spmm on librocsparse.so, fp32, row-major B and C), called
+    directly.  It plays the part cuSPARSE plays in the paper's Table VII; timed: the compute stage only (buffer
+    query and the preprocess stage are done once, outside the timed region)."""
+    ALGS = {"default": 0, "csr": 1, "csr_row_split": 4, "csr_nnz_split": 5, "csr_merge_path": 9}
+
+    def __init__(self, torch):
+        import ctypes
+        self.ct, self.torch = ctypes, torch
+        self.lib = ctypes.CDLL("librocsparse.so")
+        self.handle = ctypes.c_void_p()
+        self.check(self.lib.rocsparse_create_handle(ctypes.byref(self.handle)))
+        self.check(self.lib.rocsparse_set_stream(self.handle, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)))
+        self.one, self.zero = ctypes.c_float(1.0), ctypes.c_float(0.0)
+
+    def check(self, status):
+        if status != 0:
+            raise RuntimeError(f"rocsparse status {status}")
+
+    def prepare(self, case, alg):
+        """Descriptors, buffer and preprocess stage for one case; returns a function that runs the compute stage."""
+        ct, vp = self.ct, self.ct.c_void_p
+        w, N = case.w, case.N
+        A, B, C = vp(), vp(), vp()
+        i32, f32, base0, row_major, csr_op = 2, 151, 0, 0, 111
+        out = self.torch.empty((w.M, N), dtype=self.torch.float32, device=case.B.device)
+        self.check(self.lib.rocsparse_create_csr_descr(ct.byref(A), ct.c_int64(w.M), ct.c_int64(w.K), ct.c_int64(w.nnz), vp(case.rp.data_ptr()),
+                                                       vp(case.ci.data_ptr()), vp(case.v.data_ptr()), i32, i32, base0, f32))
+        self.check(self.lib.rocsparse_create_dnmat_descr(ct.byref(B), ct.c_int64(w.K), ct.c_int64(N), ct.c_int64(N), vp(case.B.data_ptr()), f32, row_major))
+        self.check(self.lib.rocsparse_create_dnmat_descr(ct.byref(C), ct.c_int64(w.M), ct.c_int64(N), ct.c_int64(N), vp(out.data_ptr()), f32, row_major))
+        size = ct.c_size_t(0)
+
+        def stage(which, buffer):
+            return self.lib.rocsparse_spmm(self.handle, csr_op, csr_op, ct.byref(self.one), A, B, ct.byref(self.zero), C, f32,
+                                           self.ALGS[alg], which, ct.byref(size), buffer)
+        self.check(stage(1, None))
+        work = self.torch.empty(max(int(size.value), 16), dtype=self.torch.uint8, device=case.B.device)
+        self.check(stage(2, vp(work.data_ptr())))
+        keep = (A, B, C, work)
+
+        def compute():
+            self.check(stage(3, vp(work.data_ptr())))
+            return out
+        compute.keep = keep
+        return compute
+
+    def best_time(self, case, steps, reference):
+        """Milliseconds per call of the fastest of the library's CSR algorithms on this case (each checked against
+        `reference`, the result of this library, to make sure the call computes the same product)."""
+        best, best_alg = None, None
+        for alg in self.ALGS:
+            try:
+                run = self.prepare(case, alg)
+                got = run()
+                self.torch.cuda.synchronize()
+            except RuntimeError:
+                continue
+            scale = float(reference.abs().max()) + 1e-30
+            if float((got - reference).abs().max()) > 1e-3 * scale:
+                print(f"# rocsparse {alg}: result differs from this library's, not counted", file=sys.stderr)
+                continue
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                run()
+            self.torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / steps
+            if best is None or ms < best:
+                best, best_alg = ms, alg
+        return best, best_alg
+
+
 def shape_suite(args, gs, torch, graphgen, dev):
     """The shape suite at N = 128 / 256 / 512, geometric means per width as in the paper's
     Table VII.  With --vendor the same product through torch's CSR matmul (the vendor sparse
     library underneath) is timed beside it, as context."""
     rows = []
+    rocsparse = Rocsparse(torch) if args.rocsparse and B_ELEM_BYTES == 4 else None
     for name in graphgen.SUITE_NAMES:
         w = graphgen.suite_matrix(name)
         d = w.describe()
@@ -610,6 +690,9 @@ def shape_suite(args, gs, torch, graphgen, dev):
             steps = max(20, min(args.steps, int(2e11 / (w.nnz * N))))
             r = case.time(gs, torch, "sum", steps, 3, bracket_kernel=False)
             r["vendor_ms"] = None
+            r["rocsparse_ms"], r["rocsparse_alg"] = None, None
+            if rocsparse is not None:
+                r["rocsparse_ms"], r["rocsparse_alg"] = rocsparse.best_time(case, steps, case.C)
             if A is not None:
                 for _ in range(2):
                     torch.sparse.mm(A, case.B)
@@ -623,7 +706,9 @@ def shape_suite(args, gs, torch, graphgen, dev):
             print(f"{name:22s} N={N:4d} {r['ms_per_step']*1e3:9.1f} us {r['gflops']:8.1f} GFLOP/s  model "
                   f"{r['model_GBps_step']:8.1f} GB/s ({r['model_GBps_step']/HBM_PEAK_GBPS*100:5.1f}% of HBM peak)"
                   + (f"  vendor CSR matmul {r['vendor_ms']*1e3:9.1f} us ({r['vendor_ms']/r['ms_per_step']:5.2f}x)"
-                     if r["vendor_ms"] else ""), file=sys.stderr, flush=True)
+                     if r["vendor_ms"] else "")
+                  + (f"  rocsparse_spmm [{r['rocsparse_alg']}] {r['rocsparse_ms']*1e3:9.1f} us ({r['rocsparse_ms']/r['ms_per_step']:5.2f}x)"
+                     if r["rocsparse_ms"] else ""), file=sys.stderr, flush=True)
             del case
             torch.cuda.empty_cache()
     summary = []
@@ -631,12 +716,14 @@ def shape_suite(args, gs, torch, graphgen, dev):
         sel = [r for r in rows if r["N"] == N]
         g = {"N": N, "matrices": len(sel), "geomean_gflops": geomean([r["gflops"] for r in sel]),
              "geomean_model_GBps": geomean([r["model_GBps_step"] for r in sel]),
-             "geomean_speedup_over_vendor": geomean([r["vendor_ms"] / r["ms_per_step"] for r in sel if r["vendor_ms"]])}
+             "geomean_speedup_over_vendor": geomean([r["vendor_ms"] / r["ms_per_step"] for r in sel if r["vendor_ms"]]),
+             "geomean_speedup_over_rocsparse": geomean([r["rocsparse_ms"] / r["ms_per_step"] for r in sel if r["rocsparse_ms"]])}
         summary.append(g)
         print(f"geometric mean N={N:4d}: {g['geomean_gflops']:8.1f} GFLOP/s, model {g['geomean_model_GBps']:8.1f} GB/s"
-              + (f", {g['geomean_speedup_over_vendor']:.2f}x the vendor CSR matmul" if g["geomean_speedup_over_vendor"] else ""),
+              + (f", {g['geomean_speedup_over_vendor']:.2f}x the vendor CSR matmul" if g["geomean_speedup_over_vendor"] else "")
+              + (f", {g['geomean_speedup_over_rocsparse']:.2f}x rocsparse_spmm" if g["geomean_speedup_over_rocsparse"] else ""),
               file=sys.stderr, flush=True)
-    return {"rows": [{k: r[k] for k in ("workload", "N", "ms_per_step", "gflops", "model_GBps_step", "vendor_ms")}
+    return {"rows": [{k: r[k] for k in ("workload", "N", "ms_per_step", "gflops", "model_GBps_step", "vendor_ms", "rocsparse_ms", "rocsparse_alg")}
                      for r in rows], "summary": summary}
 
 
@@ -659,6 +746,8 @@ def main():
                     help="also time a 2-layer GCN training step and the share of the aggregation in it")
     ap.add_argument("--suite", action="store_true",
                     help="also run the shape suite at N = 128/256/512 and print geometric means (Table VII's layout)")
+    ap.add_argument("--rocsparse", action="store_true",
+                    help="with --suite or --sweep: time rocsparse_spmm (the fastest of its CSR algorithms per case) beside each case")
     ap.add_argument("--vendor", action="store_true",
                     help="with --suite: time torch's CSR matmul (vendor sparse library) beside each case")
     ap.add_argument("--tile-study", action="store_true",
@@ -805,7 +894,7 @@ def main():
         out["cpu_baseline"], out["parity"] = cpu_baseline(w, case.B_host, op, C_timed)
     if sweep_rows is not None:
         out["sweep"] = [{k: row[k] for k in ("workload", "N", "op", "ms_per_step", "gflops", "model_GBps_step",
-                                             "warm_min_ms", "cold_mean_ms")}
+                                             "warm_min_ms", "cold_mean_ms", "graph_ms_per_step", "rocsparse_ms", "rocsparse_alg")}
                         for row in sweep_rows]
     if grad_rows is not None:
         out["gradients"] = grad_rows

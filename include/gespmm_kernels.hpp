@@ -451,10 +451,15 @@ inline void make_plan(int64_t M, int64_t K, int64_t N, int64_t nnz, bool aligned
     const int line = 128 / (vec * elem_bytes);  // lanes that cover one 128-byte line of a row of B
     // the K-phased path keeps B in L2 by its own means and takes two lines per block
     const int wide = G > 2 * line ? 2 * line : G;
-    const int plain = G > line ? (ncv <= 4 * line ? line : 2 * line) : G;      // what the plain path would take
+    // One line per block up to four lines of columns, two beyond.  Exactly four lines (N = 128 in fp32) go either
+    // way: with short rows the per-row work of a column block weighs more than the L2 residency of a narrower
+    // slice of B, and two blocks of two lines beat four blocks of one (13 of 16 suite matrices, by up to 31 % on
+    // 27-point stencils; the three that lose, by 1-7 %, have mean rows of 30 and more).
+    const bool two_lines = ncv > 4 * line || (elem_bytes == 4 && ncv == 4 * line && M > 0 && nnz / M < 28);
+    const int plain = G > line ? (two_lines ? 2 * line : line) : G;            // what the plain path would take
     parts = choose_parts(M, K, nnz, vec, wide * vec * elem_bytes, plain * vec * elem_bytes, tune, workspace_bytes);
     if (parts > 1) G = wide < 8 ? 8 : wide;
-    else if (G > line) G = ncv <= 4 * line ? line : 2 * line;   // one line; two lines for wide N
+    else G = plain;
   } else if (elem_bytes == 2) {
     if (G > 64) G = 64;                         // one column per lane, one tile: up to 64 columns per block
   } else if (G > 16) {

@@ -8,7 +8,7 @@ from .binding import (GespmmError, OPS, gespmm_custom_op_create, gespmm_custom_o
                       gespmm_csr_simple, gespmm_csr_transpose, gespmm_csr_transpose_noalloc, gespmm_csr_transpose_workspace_bytes,
                       gespmm_csr_transposed, gespmm_plan, gespmm_pool_backward,
                       gespmm_csr_ex, gespmm_csr_arg_ex, gespmm_csr_workspace_bytes, gespmm_plan_ex,
-                      gespmm_profiler_create, gespmm_profiler_finish, gespmm_tuning_t,
+                      gespmm_profiler_create, gespmm_profiler_finish, gespmm_tuning_t, make_tuning, gespmm_csr_prepared,
                       gespmm_status_string, gespmm_version, lib)
 
 __all__ = ["GespmmError", "OPS", "gespmm_custom_op_create", "gespmm_custom_op_check", "gespmm_custom_op_destroy", "gespmm_csr_custom", "gespmm_calibration_copy", "gespmm_calibration_gather", "gespmm_calibration_gather_shape", "gespmm_csr", "gespmm_csr_arg", "gespmm_csr_b16",
@@ -16,5 +16,5 @@ __all__ = ["GespmmError", "OPS", "gespmm_custom_op_create", "gespmm_custom_op_ch
            "gespmm_csr_simple", "gespmm_csr_transpose", "gespmm_csr_transpose_noalloc", "gespmm_csr_transpose_workspace_bytes",
            "gespmm_csr_transposed", "gespmm_plan", "gespmm_pool_backward",
            "gespmm_csr_ex", "gespmm_csr_arg_ex", "gespmm_csr_workspace_bytes", "gespmm_plan_ex",
-           "gespmm_profiler_create", "gespmm_profiler_finish", "gespmm_tuning_t",
+           "gespmm_profiler_create", "gespmm_profiler_finish", "gespmm_tuning_t", "make_tuning", "gespmm_csr_prepared",
            "gespmm_status_string", "gespmm_version", "lib"]

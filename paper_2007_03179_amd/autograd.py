@@ -46,7 +46,9 @@ class CsrGraph:
         rows, cols = (self.K, self.M) if transposed else (self.M, self.K)
         if transposed not in self._longest:            # one read-back per orientation
             self._longest[transposed] = int((rowptr[1:] - rowptr[:-1]).max().item()) if rows else 0
-        tuning = {"longest_row": self._longest[transposed]}
+        if ("tuning", transposed) not in self._longest:
+            self._longest[("tuning", transposed)] = _b.make_tuning({"longest_row": self._longest[transposed]})
+        tuning = self._longest[("tuning", transposed)]
         if op in ("max", "min"):                       # value and position (forward pass of the pooling aggregation)
             return _b.gespmm_csr_arg_ex(rowptr, colind, vals, B, op, tuning=tuning)
         dtype = {torch.float32: "f32", torch.bfloat16: "bf16", torch.float16: "f16"}[B.dtype]

@@ -55,6 +55,12 @@ def _tuning(t):
     return out
 
 
+def make_tuning(t):
+    """A gespmm_tuning_t built once from a dict of field names (or a sequence in field order), for callers that
+    make many calls with the same overrides: passing the structure skips the conversion on every call."""
+    return _tuning(t)
+
+
 def _tuning_ref(t):
     t = _tuning(t)
     return None if t is None else ctypes.byref(t)
@@ -404,6 +410,34 @@ def gespmm_csr_ex(rowptr, colind, vals, B, op, C=None, workspace=None, tuning=No
                                0 if workspace is None else workspace.numel() * workspace.element_size(),
                                _tuning_ref(tuning), profiler, _stream(stream)))
     return C
+
+
+class gespmm_csr_prepared:
+    """gespmm_csr_ex with its arguments checked and marshalled once, for loops that repeat one call (same tensors,
+    same stream): calling the object issues the C call and returns C.  The tensors must stay alive and in place."""
+
+    def __init__(self, rowptr, colind, vals, B, op, C=None, workspace=None, tuning=None, stream=None):
+        import torch
+        M, (K, N) = rowptr.numel() - 1, B.shape
+        if C is None:
+            C = torch.empty((M, N), dtype=torch.float32, device=B.device)
+        code_b = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}[B.dtype]
+        _check_tensors(rowptr, colind, vals, B, C, b_dtype=B.dtype)
+        assert workspace is None or (workspace.is_cuda and workspace.is_contiguous())
+        code = OPS[op] if isinstance(op, str) else int(op)
+        self.C = C
+        self._keep = (rowptr, colind, vals, B, C, workspace, _tuning(tuning))
+        self._fn = lib().gespmm_csr_ex
+        self._head = (M, K, N, colind.numel(), _ptr(rowptr), _ptr(colind), _ptr(vals), _ptr(B), code_b, _ptr(C), code,
+                      _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+                      None if self._keep[6] is None else ctypes.byref(self._keep[6]))
+        self._stream = _stream(stream)
+
+    def __call__(self, profiler=None):
+        status = self._fn(*self._head, profiler, self._stream)
+        if status != GESPMM_OK:
+            _check(status)
+        return self.C
 
 
 def gespmm_csr_arg_ex(rowptr, colind, vals, B, op, C=None, arg=None, tuning=None, stream=None):

@@ -228,6 +228,29 @@ def test_seeded_random_shapes(gs, seed):
             assert np.array_equal(arg.cpu().numpy(), aref)
 
 
+def test_prepared_call_is_the_same_call(gs):
+    """gespmm_csr_prepared marshals the arguments of gespmm_csr_ex once; every call of the object is that C call."""
+    rp, ci, v = graphgen.random_csr(800, 600, 9.0, 12, empty_frac=0.1, long_rows=((3, 900),))
+    B = graphgen.random_dense(600, 40, 12)
+    d = dev(rp), dev(ci), dev(v), dev(B)
+    for op in OPS:
+        for tuning in (None, dict(longest_row=int(np.diff(rp).max())), gs.make_tuning(dict(chunk_nnz=64))):
+            C = torch.full((800, 40), float("nan"), dtype=torch.float32, device="cuda")
+            call = gs.gespmm_csr_prepared(*d, op, C=C, tuning=tuning)
+            for _ in range(3):
+                out = call()
+            torch.cuda.synchronize()
+            assert out is C
+            ok, worst = oracle.compare(op, C.cpu().numpy(), *oracle.spmm(rp, ci, v, B, op))
+            assert ok, (op, worst)
+    prof = gs.gespmm_profiler_create(2)
+    call = gs.gespmm_csr_prepared(*d, "sum")
+    call(prof)
+    call(prof)
+    ms, launches = gs.gespmm_profiler_finish(prof)
+    assert launches == 2 and ms > 0
+
+
 def test_calls_on_two_streams_at_once_do_not_disturb_each_other(gs):
     """The library keeps no state between calls and owns no scratch memory: calls in flight on two streams
     (different matrices, different ops, enqueued alternately) both give the oracle's result."""
