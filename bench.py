@@ -890,6 +890,16 @@ def main():
         out["single_call"]["cold_model_GBps"] = r["model_bytes"] / (out["single_call"]["cold_mean_ms"] * 1e-3) / 1e9
         # the same calls captured into one HIP graph and replayed (what a launch-bound inner loop would do)
         out["single_call"]["hip_graph_ms_per_step"] = time_graph_replay(gs, torch, case, op, min(args.steps, 200))
+    if evictor is not None and args.b_dtype == "f32" and op == "sum":
+        # context, outside the timed region: the vendor library's CSR x dense product on the same operands
+        try:
+            ms, alg = Rocsparse(torch).best_time(case, min(args.steps, 50), case.C)
+            if ms:
+                out["vendor_baseline"] = {"library": "rocsparse_spmm", "algorithm": alg, "ms_per_call": ms,
+                                          "this_library_speedup": ms / r["ms_per_step"],
+                                          "note": "fastest of rocSPARSE's CSR algorithms, compute stage only, result checked against this library's"}
+        except (OSError, RuntimeError, AttributeError) as exc:
+            print(f"bench.py: no rocSPARSE baseline ({exc})", file=sys.stderr)
     if not args.no_cpu:
         out["cpu_baseline"], out["parity"] = cpu_baseline(w, case.B_host, op, C_timed)
     if sweep_rows is not None:
