@@ -642,7 +642,12 @@ class Rocsparse:
         def compute():
             self.check(stage(3, vp(work.data_ptr())))
             return out
+        def release():
+            self.lib.rocsparse_destroy_spmat_descr(A)
+            self.lib.rocsparse_destroy_dnmat_descr(B)
+            self.lib.rocsparse_destroy_dnmat_descr(C)
         compute.keep = keep
+        compute.release = release
         return compute
 
     def best_time(self, case, steps, reference):
@@ -659,12 +664,14 @@ class Rocsparse:
             scale = float(reference.abs().max()) + 1e-30
             if float((got - reference).abs().max()) > 1e-3 * scale:
                 print(f"# rocsparse {alg}: result differs from this library's, not counted", file=sys.stderr)
+                run.release()
                 continue
             t0 = time.perf_counter()
             for _ in range(steps):
                 run()
             self.torch.cuda.synchronize()
             ms = (time.perf_counter() - t0) * 1e3 / steps
+            run.release()
             if best is None or ms < best:
                 best, best_alg = ms, alg
         return best, best_alg
