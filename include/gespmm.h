@@ -228,10 +228,11 @@ int gespmm_pool_backward(int64_t M, int64_t K, int64_t N, int64_t nnz, const int
  * has no kernel makes the call return GESPMM_ERR_BAD_ARG.
  * longest_row is not an override but something the caller may know about the matrix: an upper
  * bound on the stored entries of any row (-1 or 0 = not known).  With it the forward call (and the
- * value+position call and user-defined reduces on fp32 features) can take the WHOLE-ROW path when rows are short against a chunk (or the problem is
- * small): every row is computed by one wavefront and written once, so the call is a single kernel
- * launch without presetting and without atomics, and sum / mean become independent of the order in
- * which wavefronts finish.  The bound only selects the path: the result is right whatever it says;
+ * value+position call and user-defined reduces on fp32 features) can take the WHOLE-ROW path when
+ * rows are short against a chunk (or the problem is small): every row is computed by one wavefront
+ * and written once, so the call is a single kernel launch without presetting and without atomics,
+ * and sum / mean become independent of the order in which wavefronts finish.  A structure that a C
+ * caller initialises with fewer fields leaves the later ones 0, which means "not known" / automatic.  The bound only selects the path: the result is right whatever it says;
  * a row much longer than stated is walked by one wavefront alone and is slow.
  * wide_addresses = 1 makes the forward kernels compute 64-bit addresses for their gathers also when B
  * is smaller than 2 GiB, where they otherwise gather through a buffer descriptor with 32-bit offsets
