@@ -291,10 +291,15 @@ def time_gradients(args, gs, torch, graphgen, dev):
             "transposed": lambda: gs.gespmm_csr_transposed(case.rp, case.ci, case.v, dC, "sum", w.K, dB=dB),
             "pool_backward": lambda: gs.gespmm_pool_backward(case.ci, case.v, arg, dC, w.K, dB=dB),
         }
-        rpT, ciT, vT = gs.gespmm_csr_transpose(case.rp, case.ci, case.v, w.K)
+        # (the sorted transpose keeps the columns of a transposed row in order, which the K-phased path wants)
+        rpT, ciT, vT = gs.gespmm_csr_transpose_sorted(case.rp, case.ci, case.v, w.K)
         calls["csr_transpose"] = lambda: gs.gespmm_csr_transpose(case.rp, case.ci, case.v, w.K)
         calls["csr_transpose_sorted"] = lambda: gs.gespmm_csr_transpose_sorted(case.rp, case.ci, case.v, w.K)
-        calls["forward_on_transposed"] = lambda: gs.gespmm_csr(rpT, ciT, vT, dC, "sum", C=dB)
+        # the gradient of sum / mean as the autograd wrapper issues it: the forward call on the transposed arrays, with
+        # a workspace (the K-phased path where it applies)
+        need = gs.gespmm_csr_workspace_bytes(w.K, w.M, N, w.nnz)
+        workT = torch.empty(need // 4 + 1, dtype=torch.int32, device=dev) if need else None
+        calls["forward_on_transposed"] = lambda: gs.gespmm_csr_ex(rpT, ciT, vT, dC, "sum", C=dB, workspace=workT)
         for kind, call in calls.items():                # "arg" runs first and leaves valid positions behind
             steps = max(10, args.steps // (10 if w.nnz > 5e7 else 1))
             for _ in range(3):
