@@ -296,6 +296,7 @@ __device__ __forceinline__ void wave_lds_fence() {
 template <int F, int V, int T, class BT = float>
 struct FoldRows {
   static constexpr bool kCanSkipWholeRows = false;
+  static constexpr bool kHasFullPass = true;
   struct State { Vec<V> acc[T]; };
 
   __device__ static void begin(State& s, const KernelArgs&, int64_t, int, const int (&)[T]) {
@@ -337,6 +338,40 @@ struct FoldRows {
         const BT* brow = reinterpret_cast<const BT*>(a.B) + (int64_t)e2[u].x * a.N;
 #pragma unroll
         for (int t = 0; t < T; ++t) b[u][t] = Load::load(F == kAdd && u >= left ? nothing : brow + colc[t]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int t = 0; t < T; ++t) {
+        float bx[V];
+        Load::unpack(b[u][t], bx);
+#pragma unroll
+        for (int x = 0; x < V; ++x) s.acc[t].v[x] = fold<F>(s.acc[t].v[x], __int_as_float(e2[u].y), bx[x]);
+      }
+  }
+
+  // The same for a pass in which every lane has all U entries (the usual case inside a long row): the
+  // entries sit at fixed distances from `first`, nothing is clamped, masked or replaced.
+  template <int U>
+  __device__ static void pass_full(State& s, const KernelArgs& a, const int2* ka, int first, int stride, const int (&colc)[T]) {
+    using Load = BLoad<V, BT>;
+    int2 e2[U];
+    typename Load::Raw b[U][T];
+#pragma unroll
+    for (int u = 0; u < U; ++u) e2[u] = ka[first + u * stride];
+    if (a.b_row_bytes != 0) {
+      const BufferOfB whole_b = buffer_of(a.B, a.b_bytes);
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int t = 0; t < T; ++t) b[u][t] = Load::load_at(whole_b, (uint32_t)e2[u].x + (uint32_t)colc[t] * (uint32_t)sizeof(BT));
+    } else {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const BT* brow = reinterpret_cast<const BT*>(a.B) + (int64_t)e2[u].x * a.N;
+#pragma unroll
+        for (int t = 0; t < T; ++t) b[u][t] = Load::load(brow + colc[t]);
       }
     }
 #pragma unroll
@@ -897,6 +932,12 @@ struct CustomRows {
 
 // The value+position fold carries twice the state per column; with half as many gathers in flight it
 // fits 76 registers (6 waves per SIMD instead of 4) and is 3-9 % faster.
+// Policies that have a pass_full<U>() say so with a member `kHasFullPass = true`.
+template <bool B> struct enable_if_true {};
+template <> struct enable_if_true<true> { using type = void; };
+template <class P, class = void> struct has_full_pass { static constexpr bool value = false; };
+template <class P> struct has_full_pass<P, typename enable_if_true<P::kHasFullPass>::type> { static constexpr bool value = true; };
+
 template <class P> struct FlightDivisor { static constexpr int value = 1; };
 template <int F, int V, int T, class BT> struct FlightDivisor<FoldArgRows<F, V, T, BT>> { static constexpr int value = 2; };
 
@@ -1159,6 +1200,12 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
               stage(w, wn);
               for (int base = 0; base < wn; base += U * NS) {
                 const int first = base + slot;
+                if constexpr (has_full_pass<P>::value) {
+                  if (base + U * NS <= wn) {
+                    P::template pass_full<U>(st, a, ka, first, NS, colc);
+                    continue;
+                  }
+                }
                 const int left = (wn - first + NS - 1) / NS;
                 P::template pass<U>(st, a, ka, w, left > 0 ? first : wn - 1, NS, left, col, colc);
               }
@@ -1171,6 +1218,12 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
         P::begin(st, a, rbase + i, e - s, colc);
         for (int base = ps; base < pe; base += U * NS) {
           const int first = base + slot;
+          if constexpr (has_full_pass<P>::value) {
+            if (base + U * NS <= pe) {                       // (wave-uniform) every lane has all its U entries
+              P::template pass_full<U>(st, a, ka, first, NS, colc);
+              continue;
+            }
+          }
           const int left = (pe - first + NS - 1) / NS;       // entries first, first+NS, ... below pe
           P::template pass<U>(st, a, ka, cs, left > 0 ? first : pe - 1, NS, left, col, colc);
         }
