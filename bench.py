@@ -286,8 +286,11 @@ def time_gradients(args, gs, torch, graphgen, dev):
         dC = torch.from_numpy(graphgen.uniform_pm1((w.M, N), 99, stream=N)).to(dev)
         arg = torch.empty((w.M, N), dtype=torch.int32, device=dev)
         dB = torch.empty((w.K, N), dtype=torch.float32, device=dev)
+        need_a = gs.gespmm_csr_workspace_bytes(w.M, w.K, N, w.nnz)
+        work_a = torch.empty(need_a // 4 + 1, dtype=torch.int32, device=dev) if need_a else None
         calls = {
-            "arg": lambda: gs.gespmm_csr_arg(case.rp, case.ci, case.v, case.B, "max", C=case.C, arg=arg),
+            # max with positions as the autograd wrapper issues it: with a workspace (the K-phased path where it applies)
+            "arg": lambda: gs.gespmm_csr_arg_ex(case.rp, case.ci, case.v, case.B, "max", C=case.C, arg=arg, workspace=work_a),
             "transposed": lambda: gs.gespmm_csr_transposed(case.rp, case.ci, case.v, dC, "sum", w.K, dB=dB),
             "pool_backward": lambda: gs.gespmm_pool_backward(case.ci, case.v, arg, dC, w.K, dB=dB),
         }

@@ -318,11 +318,29 @@ int gespmm_csr_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* r
                   void* workspace, size_t workspace_bytes, const gespmm_tuning_t* tuning,
                   gespmm_profiler_t* profiler, void* stream);
 
-/* gespmm_csr_arg_b16 with tuning overrides (NULL = automatic; k_parts is ignored; with longest_row and fp32
+/* gespmm_csr_arg_b16 with tuning overrides (NULL = automatic; k_parts is ignored: no workspace; with longest_row and fp32
  * features the call can take the whole-row path: one launch instead of four). */
 int gespmm_csr_arg_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
                       const int32_t* colind, const float* vals, const void* B, int b_dtype, float* C,
                       int32_t* arg, int op, const gespmm_tuning_t* tuning, void* stream);
+
+/*
+ * gespmm_csr_arg_ex with a workspace, which lets max / min with positions (Section V-E's pooling aggregation)
+ * take the K-phased path of gespmm_csr_ex under the same rule (B several times larger than the L2 caches, mean
+ * row >= 128 entries) when the features are fp32, N is a multiple of 4 and at most 1024, and B, C and arg are
+ * 16-byte aligned; otherwise the call is gespmm_csr_arg_ex.  On that path every output carries (value, position)
+ * as one 64-bit word, held in the row's own C and arg storage through all phases and unpacked by one kernel after
+ * the last; values and positions are exactly those of gespmm_csr_arg (measured: 2.7 instead of 3.4 ms on a
+ * 233k-vertex graph of mean degree 492 at N = 64).
+ *   workspace        device, gespmm_csr_workspace_bytes(M, K, N, nnz, GESPMM_F32, tuning) bytes, 4-byte aligned,
+ *                    or NULL (no phases); contents need not be initialised, nothing survives the call.
+ *   tuning           k_parts >= 2 forces the phases (GESPMM_ERR_WORKSPACE without a large enough workspace,
+ *                    GESPMM_ERR_BAD_ARG if the call cannot take them), 0 or 1 forbids them.
+ */
+int gespmm_csr_arg_ws(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                      const int32_t* colind, const float* vals, const void* B, int b_dtype, float* C,
+                      int32_t* arg, int op, void* workspace, size_t workspace_bytes,
+                      const gespmm_tuning_t* tuning, void* stream);
 
 /*
  * User-defined reduce operations compiled at run time (Eq. 1; Section IV-A: the user supplies an

@@ -354,7 +354,7 @@ struct FoldRows {
   // The same for a pass in which every lane has all U entries (the usual case inside a long row): the
   // entries sit at fixed distances from `first`, nothing is clamped, masked or replaced.
   template <int U>
-  __device__ static void pass_full(State& s, const KernelArgs& a, const int2* ka, int first, int stride, const int (&colc)[T]) {
+  __device__ static void pass_full(State& s, const KernelArgs& a, const int2* ka, int, int first, int stride, const int (&colc)[T]) {
     using Load = BLoad<V, BT>;
     int2 e2[U];
     typename Load::Raw b[U][T];
@@ -485,30 +485,62 @@ struct FoldArgRows {
       const int uu = u < left ? u : (left > 0 ? left - 1 : 0);
       e2[u] = ka[first + uu * stride];
     }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const BT* brow = reinterpret_cast<const BT*>(a.B) + (int64_t)e2[u].x * a.N;
-#pragma unroll
-      for (int t = 0; t < T; ++t) b[u][t] = Load::load(brow + colc[t]);
-    }
+    gather<U>(a, e2, colc, b);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int uu = u < left ? u : (left > 0 ? left - 1 : 0);
-      const int where_u = cs + first + uu * stride;      // recomputed here rather than kept in registers across the loads
+      fold_entry(s, e2[u], b[u], cs + first + uu * stride);      // (the index is recomputed here rather than kept in registers across the loads)
+    }
+  }
+
+  // A pass in which every lane has all U entries: fixed distances from `first`, nothing clamped.
+  static constexpr bool kHasFullPass = true;
+  template <int U>
+  __device__ static void pass_full(State& s, const KernelArgs& a, const int2* ka, int cs, int first, int stride, const int (&colc)[T]) {
+    int2 e2[U];
+    typename BLoad<V, BT>::Raw b[U][T];
 #pragma unroll
-      for (int t = 0; t < T; ++t) {
-        float bx[V];
-        Load::unpack(b[u][t], bx);
+    for (int u = 0; u < U; ++u) e2[u] = ka[first + u * stride];
+    gather<U>(a, e2, colc, b);
 #pragma unroll
-        for (int x = 0; x < V; ++x) {
-          // A lane meets its entries in increasing index order, so "first among equals" is
-          // "replace on strict improvement only".  The hardware max / min orders the zeros
-          // (+0 above -0), so the running value changes its bits exactly when the entry improves it.
-          const float product = __int_as_float(e2[u].y) * bx[x];
-          const float next = F == kMax ? __builtin_fmaxf(s.best[t][x], product) : __builtin_fminf(s.best[t][x], product);
-          s.where[t][x] = __float_as_int(next) != __float_as_int(s.best[t][x]) ? where_u : s.where[t][x];
-          s.best[t][x] = next;
-        }
+    for (int u = 0; u < U; ++u) fold_entry(s, e2[u], b[u], cs + first + u * stride);
+  }
+
+  // The rows of B of U staged entries (the staged key is the row's byte offset when B is gathered through a buffer
+  // descriptor, the column index otherwise).
+  template <int U>
+  __device__ static void gather(const KernelArgs& a, const int2 (&e2)[U], const int (&colc)[T], typename BLoad<V, BT>::Raw (&b)[U][T]) {
+    using Load = BLoad<V, BT>;
+    if (a.b_row_bytes != 0) {
+      const BufferOfB whole_b = buffer_of(a.B, a.b_bytes);
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int t = 0; t < T; ++t) b[u][t] = Load::load_at(whole_b, (uint32_t)e2[u].x + (uint32_t)colc[t] * (uint32_t)sizeof(BT));
+    } else {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const BT* brow = reinterpret_cast<const BT*>(a.B) + (int64_t)e2[u].x * a.N;
+#pragma unroll
+        for (int t = 0; t < T; ++t) b[u][t] = Load::load(brow + colc[t]);
+      }
+    }
+  }
+
+  __device__ static void fold_entry(State& s, const int2 entry, const typename BLoad<V, BT>::Raw (&b)[T], int where_u) {
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+      float bx[V];
+      BLoad<V, BT>::unpack(b[t], bx);
+#pragma unroll
+      for (int x = 0; x < V; ++x) {
+        // A lane meets its entries in increasing index order, so "first among equals" is
+        // "replace on strict improvement only".  The hardware max / min orders the zeros
+        // (+0 above -0), so the running value changes its bits exactly when the entry improves it.
+        const float product = __int_as_float(entry.y) * bx[x];
+        const float next = F == kMax ? __builtin_fmaxf(s.best[t][x], product) : __builtin_fminf(s.best[t][x], product);
+        s.where[t][x] = __float_as_int(next) != __float_as_int(s.best[t][x]) ? where_u : s.where[t][x];
+        s.best[t][x] = next;
       }
     }
   }
@@ -554,7 +586,42 @@ struct FoldArgRows {
 #pragma unroll
     for (int t = 0; t < T; ++t) {
       if (col[t] < a.N) {
-        if (whole) {
+        if (whole && a.accumulate) {
+          // A phase of the K-phased path: during all phases every row holds packed words (zero: nothing yet).
+          // This wavefront alone touches the row in this launch, so the better of (what the earlier phases
+          // left, this phase's piece) goes back with plain loads and stores.
+          const int half = a.N >> 1;
+          if (V == 4 && (half & 3) == 0) {
+            // the lane's four words lie side by side in one of the two arrays: two 16-byte loads and stores
+            const int j = col[t];
+            ulonglong2* words = reinterpret_cast<ulonglong2*>(j < half ? reinterpret_cast<unsigned long long*>(crow) + j
+                                                                       : reinterpret_cast<unsigned long long*>(arow) + (j - half));
+            ulonglong2 lo = words[0], hi = words[1];
+            const unsigned long long m0 = pack(key_of(s.best[t][0]), s.where[t][0]), m1 = pack(key_of(s.best[t][1 % V]), s.where[t][1 % V]);
+            const unsigned long long m2 = pack(key_of(s.best[t][2 % V]), s.where[t][2 % V]), m3 = pack(key_of(s.best[t][3 % V]), s.where[t][3 % V]);
+            lo.x = m0 > lo.x ? m0 : lo.x;
+            lo.y = m1 > lo.y ? m1 : lo.y;
+            hi.x = m2 > hi.x ? m2 : hi.x;
+            hi.y = m3 > hi.y ? m3 : hi.y;
+            words[0] = lo;
+            words[1] = hi;
+            continue;
+          }
+          unsigned long long* slot[V];
+          unsigned long long before[V];
+#pragma unroll
+          for (int x = 0; x < V; ++x) {
+            const int j = col[t] + x;
+            slot[x] = j < half ? reinterpret_cast<unsigned long long*>(crow) + j
+                               : reinterpret_cast<unsigned long long*>(arow) + (j - half);
+            before[x] = *slot[x];
+          }
+#pragma unroll
+          for (int x = 0; x < V; ++x) {
+            const unsigned long long mine = pack(key_of(s.best[t][x]), s.where[t][x]);
+            if (mine > before[x]) *slot[x] = mine;
+          }
+        } else if (whole) {
           Vec<V> value, place;
 #pragma unroll
           for (int x = 0; x < V; ++x) {
@@ -613,7 +680,7 @@ __global__ void __launch_bounds__(kBlock) finish_split_rows(int32_t M, int32_t N
   bool split = false;
   if (r < M) {
     const int s = rowptr[r], e = rowptr[r + 1];
-    split = e > s && row_is_shared(s, e, r, chunk_shift);
+    split = chunk_shift < 0 || (e > s && row_is_shared(s, e, r, chunk_shift));   // (chunk_shift < 0: every row holds packed words)
   }
   unsigned long long todo = __ballot(split);
   const int half = N >> 1;
@@ -657,6 +724,10 @@ __global__ void __launch_bounds__(kBlock) finish_split_rows(int32_t M, int32_t N
           float value;
           int where;
           Rows::unpack(word[q][k], value, where);
+          if (word[q][k] == 0ull) {          // below every word of a real entry: the row stores nothing
+            value = 0.0f;
+            where = -1;
+          }
           crow[j] = value;
           arow[j] = where;
         }
@@ -1150,16 +1221,18 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
             const int r_ps = (d.x >> 6) & 4095;
             const int r_len = have ? (d.x >> 18) & 4095 : 0;
             const int64_t row = rbase + (d.x & 63);
+            // (stored position of a slice entry = cs + its offset, in a phase plus the row's delta)
+            const int r_cs = kPhased ? cs + row_info[d.x & 63].y : cs;
             typename P::State st;
             P::begin(st, a, row, d.y, colc);
             // U entries per step; a last step with at most U / 2 entries left in every slot takes
             // the half-size pass (fewer padded gathers: up to 7 % on matrices of short rows)
             for (int it = 0; __ballot(it < r_len) != 0ull;) {
               if (U >= 4 && __ballot(r_len - it > U / 2) == 0ull) {
-                P::template pass<(U >= 4 ? U / 2 : U)>(st, a, ka, cs, r_ps + (it < r_len ? it : 0), 1, r_len - it, col, colc);
+                P::template pass<(U >= 4 ? U / 2 : U)>(st, a, ka, r_cs, r_ps + (it < r_len ? it : 0), 1, r_len - it, col, colc);
                 it += U / 2;
               } else {
-                P::template pass<U>(st, a, ka, cs, r_ps + (it < r_len ? it : 0), 1, r_len - it, col, colc);
+                P::template pass<U>(st, a, ka, r_cs, r_ps + (it < r_len ? it : 0), 1, r_len - it, col, colc);
                 it += U;
               }
             }
@@ -1202,7 +1275,7 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
                 const int first = base + slot;
                 if constexpr (has_full_pass<P>::value) {
                   if (base + U * NS <= wn) {
-                    P::template pass_full<U>(st, a, ka, first, NS, colc);
+                    P::template pass_full<U>(st, a, ka, w, first, NS, colc);
                     continue;
                   }
                 }
@@ -1216,16 +1289,18 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
           }
         }
         P::begin(st, a, rbase + i, e - s, colc);
+        // (stored position of a slice entry = cs + its offset, in a phase plus the row's delta)
+        const int row_cs = kPhased ? cs + __builtin_amdgcn_readlane(my_delta, i) : cs;
         for (int base = ps; base < pe; base += U * NS) {
           const int first = base + slot;
           if constexpr (has_full_pass<P>::value) {
             if (base + U * NS <= pe) {                       // (wave-uniform) every lane has all its U entries
-              P::template pass_full<U>(st, a, ka, first, NS, colc);
+              P::template pass_full<U>(st, a, ka, row_cs, first, NS, colc);
               continue;
             }
           }
           const int left = (pe - first + NS - 1) / NS;       // entries first, first+NS, ... below pe
-          P::template pass<U>(st, a, ka, cs, left > 0 ? first : pe - 1, NS, left, col, colc);
+          P::template pass<U>(st, a, ka, row_cs, left > 0 ? first : pe - 1, NS, left, col, colc);
         }
         P::template combine<G>(st);
         if (slot == 0) P::end(st, a, rbase + i, whole, e - s, col);

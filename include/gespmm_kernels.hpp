@@ -305,6 +305,18 @@ MainKernel pick_phased(int job, int vec, int G, int T) {
   return nullptr;
 }
 
+// max / min with positions on the K-phased path (fp32 features, four columns per lane)
+inline MainKernel pick_phased_arg(int job, int vec, int G, int T) {
+  if (vec != 4) return nullptr;
+#define GESPMM_CASE(JOB, FF, GG, TT) if (job == JOB && G == GG && T == TT) return chunk_kernel<FoldArgRows<FF, 4, TT>, 4, GG, TT, true>;
+  GESPMM_CASE(kJobMaxWithArg, kMax, 8, 1) GESPMM_CASE(kJobMaxWithArg, kMax, 16, 1) GESPMM_CASE(kJobMaxWithArg, kMax, 32, 1)
+  GESPMM_CASE(kJobMaxWithArg, kMax, 8, 2) GESPMM_CASE(kJobMaxWithArg, kMax, 16, 2)
+  GESPMM_CASE(kJobMinWithArg, kMin, 8, 1) GESPMM_CASE(kJobMinWithArg, kMin, 16, 1) GESPMM_CASE(kJobMinWithArg, kMin, 32, 1)
+  GESPMM_CASE(kJobMinWithArg, kMin, 8, 2) GESPMM_CASE(kJobMinWithArg, kMin, 16, 2)
+#undef GESPMM_CASE
+  return nullptr;
+}
+
 // Kernels of the whole-row path, one tile per lane: the three folds and max / min with positions on fp32 features ...
 inline bool has_owned_kernel(int G, int T) { return T == 1 && G >= 1 && G <= kWave; }
 
@@ -416,13 +428,13 @@ inline size_t phased_workspace_bytes(int64_t M, int Q) {
 // bytes) is 15 % faster in two parts, the same matrix at N = 128 (5 MB per block of 128 bytes) is
 // slower.  Needs the vector kernels and, unless forced, a workspace that is large enough.
 inline int choose_parts(int64_t M, int64_t K, int64_t nnz, int vec, int block_bytes, int plain_block_bytes, const Tuning& tune,
-                        size_t workspace_bytes) {
+                        size_t workspace_bytes, int64_t part_bytes = 15ll << 19) {
   if (vec != 4 || M <= 0 || K <= 0 || nnz <= 0) return 1;
   if (tune.k_parts >= 0) return tune.k_parts < 2 ? 1 : (int)(tune.k_parts < K ? tune.k_parts : (K < 2 ? 1 : K));
   const int64_t live = K * block_bytes;
   const int64_t mean_row = nnz / M;
   if (K * plain_block_bytes < (8ll << 20) || mean_row < 128) return 1;
-  int64_t q = (live + (15ll << 18)) / (15ll << 19);        // nearest multiple of 7.5 MB
+  int64_t q = (live + part_bytes / 2) / part_bytes;        // nearest multiple of 7.5 MB (10 MB with positions)
   if (q < 2) q = 2;
   while (q > 2 && mean_row / q < 32) --q;
   if (q > kMaxParts) q = kMaxParts;
@@ -435,8 +447,10 @@ inline int choose_parts(int64_t M, int64_t K, int64_t nnz, int vec, int block_by
 // loads four columns at once when the width and the alignment allow it, one otherwise.
 // whole_rows_allowed: the job has kernels of the whole-row path (the forward folds; max / min with positions and
 // user-defined reduces on fp32 features).
+// with_positions: max / min that also record positions; their phases move twice the bytes per output, so the
+// parts are a third larger (measured on the 233k-vertex workload: 2.86 / 2.77 / 2.91 ms with 4 / 6 / 8 parts).
 inline void make_plan(int64_t M, int64_t K, int64_t N, int64_t nnz, bool aligned16, int elem_bytes, const Tuning& tune,
-                      size_t workspace_bytes, gespmm_plan_t* p, bool whole_rows_allowed = true) {
+                      size_t workspace_bytes, gespmm_plan_t* p, bool whole_rows_allowed = true, bool with_positions = false) {
   int vec = 1;
   if (aligned16 && N > 0) vec = N % 4 == 0 ? 4 : 1;        // 16-byte loads of fp32, 8-byte loads of 16-bit elements
   const int64_t ncv = N > 0 ? (N + vec - 1) / vec : 1;     // vector columns to cover
@@ -457,7 +471,8 @@ inline void make_plan(int64_t M, int64_t K, int64_t N, int64_t nnz, bool aligned
     // 27-point stencils; the three that lose, by 1-7 %, have mean rows of 30 and more).
     const bool two_lines = ncv > 4 * line || (elem_bytes == 4 && ncv == 4 * line && M > 0 && nnz / M < 28);
     const int plain = G > line ? (two_lines ? 2 * line : line) : G;            // what the plain path would take
-    parts = choose_parts(M, K, nnz, vec, wide * vec * elem_bytes, plain * vec * elem_bytes, tune, workspace_bytes);
+    parts = choose_parts(M, K, nnz, vec, wide * vec * elem_bytes, plain * vec * elem_bytes, tune, workspace_bytes,
+                         with_positions ? (10ll << 20) : (15ll << 19));
     if (parts > 1) G = wide < 8 ? 8 : wide;
     else G = plain;
   } else if (elem_bytes == 2) {
@@ -665,6 +680,27 @@ inline void set_narrow_b(const ChunkLaunch& L, int vec, KernelArgs* a) {
   }
 }
 
+// Unpacks the (value, position) words that rows hold after a fused pass: the rows shared by several chunks of
+// 2^shift items, or every row (shift < 0).
+inline int launch_finish_rows(bool is_max, int64_t M, int64_t N, const int32_t* rowptr, float* C, int32_t* arg, int shift,
+                              hipStream_t stream) {
+  const unsigned blocks = (unsigned)((M + kBlock - 1) / kBlock);
+  int words = 1;
+  while (words * kWave < N) words *= 2;
+#define GESPMM_FINISH(WW)                                                                                                \
+  if (words == WW) {                                                                                                     \
+    if (is_max)                                                                                                          \
+      hipLaunchKernelGGL((finish_split_rows<kMax, WW>), dim3(blocks), dim3(kBlock), 0, stream, (int32_t)M, (int32_t)N, rowptr, \
+                         C, arg, shift);                                                                                 \
+    else                                                                                                                 \
+      hipLaunchKernelGGL((finish_split_rows<kMin, WW>), dim3(blocks), dim3(kBlock), 0, stream, (int32_t)M, (int32_t)N, rowptr, \
+                         C, arg, shift);                                                                                 \
+  }
+  GESPMM_FINISH(1) GESPMM_FINISH(2) GESPMM_FINISH(4) GESPMM_FINISH(8) GESPMM_FINISH(16)
+#undef GESPMM_FINISH
+  return hipGetLastError() == hipSuccess ? GESPMM_OK : GESPMM_ERR_HIP;
+}
+
 // The K-phased path: C = A (x) B as plan.k_parts launches, part q of the column range after part q - 1.
 // Every launch gathers from K / k_parts rows of B only, which the L2s hold, instead of from all of B.
 //   1. every non-empty row of C is preset to the reduce identity (empty rows to 0);
@@ -684,7 +720,17 @@ inline int launch_phased(const ChunkLaunch& L, const gespmm_plan_t& plan, MainKe
   int32_t* sums = delta + (int64_t)Q * M;
   const int cols_per_part = (int)((L.K + Q - 1) / Q);
 
-  launch_init_rows(plan.vec, M, L.N, L.rowptr, L.dense_out, L.empty_value, L.split_value, -1, stream);
+  const bool with_positions = L.job == kJobMaxWithArg || L.job == kJobMinWithArg;
+  if (with_positions) {
+    // value and position travel as one 64-bit word per output, kept in the row's own C and arg storage through
+    // all phases (zero: no entry yet) and unpacked by one kernel after the last phase
+    if (!L.arg || L.N > kWave * kFinishWords || plan.vec != 4) return GESPMM_ERR_BAD_ARG;
+    int filled = launch_fill(L.dense_out, M * L.N, 0.0f, stream);
+    if (filled == GESPMM_OK) filled = launch_fill(reinterpret_cast<float*>(L.arg), M * L.N, 0.0f, stream);
+    if (filled != GESPMM_OK) return filled;
+  } else {
+    launch_init_rows(plan.vec, M, L.N, L.rowptr, L.dense_out, L.empty_value, L.split_value, -1, stream);
+  }
   const unsigned piece_blocks = (unsigned)(((int64_t)Q * M + kBlock - 1) / kBlock);
   int lanes_shift = 0;                              // lanes that share a row in phase_pieces
   while ((1 << lanes_shift) < Q) ++lanes_shift;
@@ -713,6 +759,10 @@ inline int launch_phased(const ChunkLaunch& L, const gespmm_plan_t& plan, MainKe
   a.C = L.dense_out;
   a.accumulate = 1;
   a.taper_chunks = kTaperChunks;
+  if (with_positions) {
+    a.arg = L.arg;
+    a.packed_split = 1;
+  }
   set_narrow_b(L, plan.vec, &a);
   int status = GESPMM_OK;
   for (int q = 0; q < Q; ++q) {
@@ -724,6 +774,7 @@ inline int launch_phased(const ChunkLaunch& L, const gespmm_plan_t& plan, MainKe
     if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
     if (!record_stop(L.profiler, stream, timed, &status)) return status;
   }
+  if (with_positions) return launch_finish_rows(L.job == kJobMaxWithArg, M, L.N, L.rowptr, L.dense_out, L.arg, -1, stream);
   if (L.is_mean) {
     int64_t blocks = (M * L.N + kBlock - 1) / kBlock;
     if (blocks > 256 * 32) blocks = 256 * 32;
@@ -740,16 +791,18 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream, bool* took_wh
   const bool aligned16 = (((uintptr_t)L.dense_in | (uintptr_t)L.dense_out | (uintptr_t)L.result_in |
                            (uintptr_t)L.also_aligned) & 15u) == 0;
   const bool fold_job = !L.picker && !L.launcher && (L.job == kJobAdd || L.job == kJobMax || L.job == kJobMin) && !L.one_lane_per_entry;
+  const bool arg_job = !L.picker && !L.launcher && (L.job == kJobMaxWithArg || L.job == kJobMinWithArg) && L.arg && !L.one_lane_per_entry;
+  // jobs that have kernels of the K-phased path: the folds, and max / min with positions on fp32 features of up to 1024 columns
+  const bool phases_possible = fold_job || (arg_job && L.b_dtype == GESPMM_F32 && L.N <= kWave * kFinishWords);
   Tuning tune = L.tuning;
-  if (!fold_job || !L.workspace) {
-    if (tune.k_parts > 1 && fold_job) return GESPMM_ERR_WORKSPACE;   // phases were asked for but there is nowhere to put their row starts
+  if (!phases_possible || !L.workspace) {
+    if (tune.k_parts > 1 && phases_possible) return GESPMM_ERR_WORKSPACE;   // phases were asked for but there is nowhere to put their row starts
     tune.k_parts = 1;
   }
   gespmm_plan_t plan;
-  const bool arg_job = !L.picker && !L.launcher && (L.job == kJobMaxWithArg || L.job == kJobMinWithArg) && L.arg && !L.one_lane_per_entry;
   const bool custom_job = (L.picker && L.owned_picker) || L.launcher;
   const bool whole_rows_allowed = (fold_job || ((arg_job || custom_job) && L.b_dtype == GESPMM_F32)) && L.init_target == L.dense_out;
-  make_plan(L.M, L.K, L.N, L.nnz, aligned16, L.b_dtype == GESPMM_F32 ? 4 : 2, tune, L.workspace_bytes, &plan, whole_rows_allowed);
+  make_plan(L.M, L.K, L.N, L.nnz, aligned16, L.b_dtype == GESPMM_F32 ? 4 : 2, tune, L.workspace_bytes, &plan, whole_rows_allowed, arg_job);
   if (L.one_lane_per_entry) {
     plan.vec = 1;
     plan.lanes_per_row = 1;
@@ -764,7 +817,8 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream, bool* took_wh
 
   if (plan.k_parts > 1 && L.nnz > 0) {
     MainKernel phased = nullptr;
-    if (L.b_dtype == GESPMM_BF16) phased = pick_phased<bf16_t>(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
+    if (arg_job) phased = pick_phased_arg(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
+    else if (L.b_dtype == GESPMM_BF16) phased = pick_phased<bf16_t>(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
     else if (L.b_dtype == GESPMM_F16) phased = pick_phased<f16_t>(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
     else phased = pick_phased<float>(L.job, plan.vec, plan.lanes_per_row, plan.tiles_per_lane);
     if (!phased) return GESPMM_ERR_BAD_ARG;
@@ -821,7 +875,7 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream, bool* took_wh
   a.packed_split = L.packed_split ? 1 : 0;
   a.accumulate = 0;
   a.row_window = plan.row_window;
-  if (fold_job) set_narrow_b(L, plan.vec, &a);
+  if (fold_job || arg_job) set_narrow_b(L, plan.vec, &a);
   if (plan.row_window > 0) a.packed_split = 0;    // no row is split
   else if (L.packed_split && (plan.vec != 4 || L.N > kWave * kFinishWords || !L.arg)) return GESPMM_ERR_BAD_ARG;
   int status = GESPMM_OK;
@@ -839,24 +893,7 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream, bool* took_wh
     if (took_whole_rows) *took_whole_rows = true;
     return GESPMM_OK;
   }
-  if (L.packed_split) {
-    const unsigned blocks = (unsigned)((L.M + kBlock - 1) / kBlock);
-    int words = 1;
-    while (words * kWave < L.N) words *= 2;
-    const bool is_max = L.job == kJobMaxWithArg;
-#define GESPMM_FINISH(WW)                                                                                             \
-  if (words == WW) {                                                                                                  \
-    if (is_max)                                                                                                       \
-      hipLaunchKernelGGL((finish_split_rows<kMax, WW>), dim3(blocks), dim3(kBlock), 0, stream, (int32_t)L.M, (int32_t)L.N, \
-                         L.rowptr, L.dense_out, L.arg, shift);                                                        \
-    else                                                                                                              \
-      hipLaunchKernelGGL((finish_split_rows<kMin, WW>), dim3(blocks), dim3(kBlock), 0, stream, (int32_t)L.M, (int32_t)L.N, \
-                         L.rowptr, L.dense_out, L.arg, shift);                                                        \
-  }
-    GESPMM_FINISH(1) GESPMM_FINISH(2) GESPMM_FINISH(4) GESPMM_FINISH(8) GESPMM_FINISH(16)
-#undef GESPMM_FINISH
-    if (hipGetLastError() != hipSuccess) return GESPMM_ERR_HIP;
-  }
+  if (L.packed_split) return launch_finish_rows(L.job == kJobMaxWithArg, L.M, L.N, L.rowptr, L.dense_out, L.arg, shift, stream);
   return GESPMM_OK;
 }
 

@@ -49,13 +49,13 @@ class CsrGraph:
         if ("tuning", transposed) not in self._longest:
             self._longest[("tuning", transposed)] = _b.make_tuning({"longest_row": self._longest[transposed]})
         tuning = self._longest[("tuning", transposed)]
-        if op in ("max", "min"):                       # value and position (forward pass of the pooling aggregation)
-            return _b.gespmm_csr_arg_ex(rowptr, colind, vals, B, op, tuning=tuning)
         dtype = {torch.float32: "f32", torch.bfloat16: "bf16", torch.float16: "f16"}[B.dtype]
         key = (transposed, B.shape[1], dtype)
         if key not in self._workspaces:
             need = _b.gespmm_csr_workspace_bytes(rows, cols, B.shape[1], colind.numel(), dtype, tuning=tuning)
             self._workspaces[key] = torch.empty(need // 4 + 1, dtype=torch.int32, device=B.device) if need else None
+        if op in ("max", "min"):                       # value and position (forward pass of the pooling aggregation)
+            return _b.gespmm_csr_arg_ex(rowptr, colind, vals, B, op, tuning=tuning, workspace=self._workspaces[key])
         return _b.gespmm_csr_ex(rowptr, colind, vals, B, "sum" if transposed else op, workspace=self._workspaces[key],
                                 tuning=tuning)
 

@@ -121,6 +121,8 @@ def lib():
         L.gespmm_csr_ex.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, ci, vp, ci, vp, ctypes.c_size_t, tp, vp, vp]
         L.gespmm_csr_arg_ex.restype = ci
         L.gespmm_csr_arg_ex.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, ci, vp, vp, ci, tp, vp]
+        L.gespmm_csr_arg_ws.restype = ci
+        L.gespmm_csr_arg_ws.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, ci, vp, vp, ci, vp, ctypes.c_size_t, tp, vp]
         L.gespmm_profiler_create.restype = ci
         L.gespmm_profiler_create.argtypes = [ci, ctypes.POINTER(vp)]
         L.gespmm_profiler_finish.restype = ci
@@ -440,8 +442,10 @@ class gespmm_csr_prepared:
         return self.C
 
 
-def gespmm_csr_arg_ex(rowptr, colind, vals, B, op, C=None, arg=None, tuning=None, stream=None):
-    """gespmm_csr_arg / gespmm_csr_arg_b16 with tuning overrides; returns (C fp32, arg int32)."""
+def gespmm_csr_arg_ex(rowptr, colind, vals, B, op, C=None, arg=None, tuning=None, stream=None, workspace=None):
+    """gespmm_csr_arg / gespmm_csr_arg_b16 with tuning overrides; returns (C fp32, arg int32).  With `workspace`
+    (a device tensor of gespmm_csr_workspace_bytes(...) bytes) the call is gespmm_csr_arg_ws, which may take the
+    K-phased path."""
     import torch
     M, (K, N) = rowptr.numel() - 1, B.shape
     if C is None:
@@ -452,6 +456,12 @@ def gespmm_csr_arg_ex(rowptr, colind, vals, B, op, C=None, arg=None, tuning=None
     _check_tensors(rowptr, colind, vals, B, C, b_dtype=B.dtype)
     assert arg.is_cuda and arg.dtype == torch.int32 and arg.is_contiguous() and arg.shape == C.shape
     code = OPS[op] if isinstance(op, str) else int(op)
+    if workspace is not None:
+        assert workspace.is_cuda and workspace.is_contiguous()
+        _check(lib().gespmm_csr_arg_ws(M, K, N, colind.numel(), _ptr(rowptr), _ptr(colind), _ptr(vals), _ptr(B), code_b,
+                                       _ptr(C), _ptr(arg), code, _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                       _tuning_ref(tuning), _stream(stream)))
+        return C, arg
     _check(lib().gespmm_csr_arg_ex(M, K, N, colind.numel(), _ptr(rowptr), _ptr(colind), _ptr(vals), _ptr(B), code_b,
                                    _ptr(C), _ptr(arg), code, _tuning_ref(tuning), _stream(stream)))
     return C, arg

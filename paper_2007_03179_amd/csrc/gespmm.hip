@@ -135,8 +135,20 @@ int gespmm_csr_arg_b16(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32
 }
 
 int gespmm_csr_arg_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
+                      const int32_t* colind, const float* vals, const void* B, int b_dtype, float* C,
+                      int32_t* arg, int op, const gespmm_tuning_t* tuning, void* stream) {
+  gespmm_tuning_t no_phases;
+  if (tuning) {
+    no_phases = *tuning;
+    no_phases.k_parts = 1;
+  }
+  return gespmm_csr_arg_ws(M, K, N, nnz, rowptr, colind, vals, B, b_dtype, C, arg, op, nullptr, 0, tuning ? &no_phases : nullptr, stream);
+}
+
+int gespmm_csr_arg_ws(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* rowptr,
                       const int32_t* colind, const float* vals, const void* B_, int b_dtype, float* C,
-                      int32_t* arg, int op, const gespmm_tuning_t* tuning, void* stream_) {
+                      int32_t* arg, int op, void* workspace, size_t workspace_bytes,
+                      const gespmm_tuning_t* tuning, void* stream_) {
   if (!known_dtype(b_dtype)) return GESPMM_ERR_BAD_ARG;
   const float* B = static_cast<const float*>(B_);
   if (op != GESPMM_MAX && op != GESPMM_MIN) return GESPMM_ERR_BAD_ARG;
@@ -148,7 +160,6 @@ int gespmm_csr_arg_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_
   ChunkLaunch L;
   const int parsed = parse_tuning(tuning, &L.tuning);
   if (parsed != GESPMM_OK) return parsed;
-  L.tuning.k_parts = 1;
   L.job = op == GESPMM_MAX ? kJobMaxWithArg : kJobMinWithArg;
   L.M = M; L.K = K; L.N = N; L.nnz = nnz;
   L.rowptr = rowptr; L.colind = colind; L.vals = vals;
@@ -165,9 +176,19 @@ int gespmm_csr_arg_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_
   // (rows preset to the reduce identity / INT_MAX), positions by a second pass over the matrix.
   const bool vector = N % 4 == 0 && (((uintptr_t)B | (uintptr_t)C | (uintptr_t)arg) & 15u) == 0;
   L.packed_split = vector && N <= kWave * kFinishWords && nnz > 0;
+  const bool phases_possible = L.packed_split && b_dtype == GESPMM_F32;
+  if (L.tuning.k_parts > 1 && nnz > 0) {            // phases were asked for
+    if (!phases_possible) return GESPMM_ERR_BAD_ARG;
+    if (!workspace) return GESPMM_ERR_WORKSPACE;
+  }
+  if (!phases_possible || !workspace) L.tuning.k_parts = 1;
   if (L.packed_split) {
     L.split_value = 0.0f;
     L.split2_value = 0.0f;
+    if (phases_possible && workspace) {
+      L.workspace = workspace;
+      L.workspace_bytes = workspace_bytes;
+    }
     return launch_chunks(L, stream);
   }
   L.split_value = op == GESPMM_MAX ? -__builtin_inff() : __builtin_inff();

@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported(L):
             "gespmm_calibration_copy", "gespmm_calibration_gather", "gespmm_csr_arg", "gespmm_csr_transposed", "gespmm_pool_backward",
             "gespmm_csr_transpose", "gespmm_csr_transpose_workspace_bytes", "gespmm_csr_transpose_noalloc",
             "gespmm_csr_b16", "gespmm_plan_b16", "gespmm_csr_arg_b16", "gespmm_csr_transpose_sorted",
-            "gespmm_csr_transpose_sorted_workspace_bytes", "gespmm_version"} <= set(names)
+            "gespmm_csr_transpose_sorted_workspace_bytes", "gespmm_version", "gespmm_csr_arg_ws"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 

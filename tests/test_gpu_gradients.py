@@ -33,13 +33,14 @@ def dev(x):
     return None if x is None else torch.from_numpy(np.ascontiguousarray(x)).cuda()
 
 
-def check_arg(gs, rp, ci, v, B, op, rows=None, label="", dA=None, dB=None, tuning=None):
+def check_arg(gs, rp, ci, v, B, op, rows=None, label="", dA=None, dB=None, tuning=None, workspace=None):
     say(f"  case arg {label} op={op} M={len(rp) - 1} N={B.shape[1]} nnz={len(ci)}")
     d_rp, d_ci, d_v = dA if dA is not None else (dev(rp), dev(ci), dev(v))
-    if tuning is None:
+    if tuning is None and workspace is None:
         C, arg = gs.gespmm_csr_arg(d_rp, d_ci, d_v, dB if dB is not None else dev(B), op)
     else:
-        C, arg = gs.gespmm_csr_arg_ex(d_rp, d_ci, d_v, dB if dB is not None else dev(B), op, tuning=tuning)
+        C, arg = gs.gespmm_csr_arg_ex(d_rp, d_ci, d_v, dB if dB is not None else dev(B), op, tuning=tuning,
+                                      workspace=workspace)
     torch.cuda.synchronize()
     C, arg = C.cpu().numpy(), arg.cpu().numpy()
     Cref, aref = oracle.spmm_arg(rp, ci, v, B, op, rows=rows)
@@ -105,6 +106,74 @@ def test_positions_whole_row_path(gs, N):
     C, arg = check_arg(gs, rp0, np.zeros(0, np.int32), np.zeros(0, np.float32), B, "max", tuning=dict(longest_row=3),
                        label="whole-row nnz=0")
     assert not C.any() and (arg == -1).all()
+
+
+@pytest.mark.parametrize("N", [4, 12, 64, 128, 520, 1024])
+def test_positions_k_phased_path(gs, N):
+    """Value and position through the phases of the column range (gespmm_csr_arg_ws with forced parts): ties within and
+    across parts, repeated and unsorted columns, empty rows, rows split among chunks, every kernel shape of the path."""
+    rp, ci, v = graphgen.random_csr(500, 400, 30.0, 900 + N, empty_frac=0.1, long_rows=((77, 2500), (499, 0), (0, 700)),
+                                    duplicates=True, sort_cols=False)
+    B = np.round(graphgen.random_dense(400, N, N) * 4.0).astype(np.float32)
+    v = np.round(v * 2.0).astype(np.float32)
+    v[v == 0] = 1.0
+    B[5] = -0.0
+    B[6] = 0.0
+    dA, dB = (dev(rp), dev(ci), dev(v)), dev(B)
+    sorted_rows = graphgen.random_csr(500, 400, 30.0, 901 + N, empty_frac=0.1, long_rows=((3, 1500),))
+    shapes = ((-1, -1, -1), (8, 1, 64), (16, 1, 512), (32, 1, 128), (8, 2, 256), (16, 2, 1024))
+    for parts in (2, 3, 8):
+        for G, T, chunk in shapes:
+            if G > 0 and G * T * 4 > max(N, 32) * 2:
+                continue                                       # (shapes far wider than the matrix add nothing)
+            tuning = dict(k_parts=parts, lanes_per_row=G, tiles_per_lane=T, chunk_nnz=chunk)
+            need = gs.gespmm_csr_workspace_bytes(len(rp) - 1, 400, N, len(ci), "f32", tuning=tuning)
+            assert need > 0
+            ws = torch.empty(need // 4 + 1, dtype=torch.int32, device="cuda")
+            for op in ("max", "min"):
+                check_arg(gs, rp, ci, v, B, op, dA=dA, dB=dB, tuning=tuning, workspace=ws,
+                          label=f"phased parts={parts} G={G} T={T} S={chunk}")
+        check_arg(gs, *sorted_rows, B, "max", tuning=dict(k_parts=parts), workspace=ws, label=f"phased sorted parts={parts}")
+    # all-ones weights (vals == NULL) and nothing stored at all
+    check_arg(gs, rp, ci, None, B, "min", tuning=dict(k_parts=3), workspace=ws, label="phased no vals")
+    rp0 = np.zeros(6, dtype=np.int32)
+    C, arg = check_arg(gs, rp0, np.zeros(0, np.int32), np.zeros(0, np.float32), B, "max", tuning=dict(k_parts=2),
+                       workspace=ws, label="phased nnz=0")
+    assert not C.any() and (arg == -1).all()
+
+
+def test_positions_k_phased_path_chosen_by_the_rule(gs):
+    """Long rows and a B that is many times an L2: with a workspace the call takes the phases by itself (and says so
+    in the plan); values and positions equal the oracle's and the plain call's."""
+    M, K, N = 1500, 90000, 64
+    rp, ci, v = graphgen.random_csr(M, K, 150.0, 77, empty_frac=0.02, long_rows=((9, 6000),))
+    B = np.round(graphgen.random_dense(K, N, 78) * 16.0).astype(np.float32)
+    plan = gs.gespmm_plan_ex(M, K, N, len(ci), workspace_bytes=1 << 30)
+    assert plan["k_parts"] > 1, plan
+    need = gs.gespmm_csr_workspace_bytes(M, K, N, len(ci))
+    ws = torch.empty(need // 4 + 1, dtype=torch.int32, device="cuda")
+    dA, dB = (dev(rp), dev(ci), dev(v)), dev(B)
+    for op in ("max", "min"):
+        C, arg = check_arg(gs, rp, ci, v, B, op, dA=dA, dB=dB, workspace=ws, label="phased by rule")
+        C0, arg0 = gs.gespmm_csr_arg(*dA, dB, op)
+        assert np.array_equal(C0.cpu().numpy().view(np.uint32), C.view(np.uint32)) and np.array_equal(arg0.cpu().numpy(), arg)
+
+
+def test_positions_k_phased_argument_errors(gs):
+    rp, ci, v = graphgen.random_csr(64, 64, 5.0, 5)
+    B = graphgen.random_dense(64, 8, 6)
+    dA, dB = (dev(rp), dev(ci), dev(v)), dev(B)
+    ws = torch.empty(1 << 16, dtype=torch.int32, device="cuda")
+    gs.gespmm_csr_arg_ex(*dA, dB, "max", tuning=dict(k_parts=2))   # the call without a workspace ignores k_parts
+    with pytest.raises(gs.GespmmError) as e:                    # too small a workspace
+        gs.gespmm_csr_arg_ex(*dA, dB, "max", tuning=dict(k_parts=2), workspace=ws[:4])
+    assert e.value.status == 4
+    with pytest.raises(gs.GespmmError) as e:                    # 16-bit features have no phased kernels with positions
+        gs.gespmm_csr_arg_ex(*dA, dB.to(torch.bfloat16), "max", tuning=dict(k_parts=2), workspace=ws)
+    assert e.value.status == 1
+    with pytest.raises(gs.GespmmError) as e:                    # nor do widths that are not a multiple of four
+        gs.gespmm_csr_arg_ex(*dA, dev(graphgen.random_dense(64, 7, 6)), "max", tuning=dict(k_parts=2), workspace=ws)
+    assert e.value.status == 1
 
 
 def test_positions_every_launch_shape(gs):
