@@ -94,6 +94,7 @@ struct KernelArgs {
   uint32_t b_row_bytes;   // fold jobs on a B below 2 GiB: bytes of one row of B (the staged key of an entry is then
                           // the byte offset of its row of B, and the gathers are buffer loads); 0 = 64-bit addresses
   uint32_t b_bytes;       // ... and the size of B in bytes
+  int32_t stream_stores;  // finished rows of C are written with streaming stores (whole 128-byte lines, written once)
 };
 
 // Entry p of row r is item p + r of the merged sequence of entries and row ends; chunk c owns the
@@ -112,11 +113,18 @@ template <> struct Vec<4> {
     return Vec{{t.x, t.y, t.z, t.w}};
   }
   __device__ void store(float* p) const { *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]); }
+  // a store that tells the caches the line will not be read again soon (results that are written once)
+  __device__ void store_streaming(float* p) const {
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    f4 t = {v[0], v[1], v[2], v[3]};
+    __builtin_nontemporal_store(t, reinterpret_cast<f4*>(p));
+  }
 };
 template <> struct Vec<1> {
   float v[1];
   __device__ static Vec load(const float* p) { return Vec{{*p}}; }
   __device__ void store(float* p) const { *p = v[0]; }
+  __device__ void store_streaming(float* p) const { __builtin_nontemporal_store(v[0], p); }
 };
 // Element types of the dense input.  The 16-bit types are storage formats only: every
 // value is widened to fp32 (exactly) before the multiply, and products and sums are fp32.
@@ -425,7 +433,8 @@ struct FoldRows {
 #pragma unroll
             for (int x = 0; x < V; ++x) s.acc[t].v[x] = s.acc[t].v[x] / len;
           }
-          s.acc[t].store(crow + col[t]);
+          if (a.stream_stores) s.acc[t].store_streaming(crow + col[t]);
+          else s.acc[t].store(crow + col[t]);
         } else {
           const float w = a.is_mean ? 1.0f / len : 1.0f;
 #pragma unroll
