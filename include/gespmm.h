@@ -116,7 +116,7 @@ int gespmm_csr_b16(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_t* 
  *         smallest p (first in storage order); -1 for an empty row.
  * One fused pass carries (value, position) pairs through the reduction; rows that several
  * wavefronts share combine their pairs as packed 64-bit words held, during the call, in the
- * row's own C and arg storage, and a small kernel unpacks them at the end (1.1 to 1.45 times
+ * row's own C and arg storage, and a small kernel unpacks them at the end (1.1 to 1.4 times
  * the cost of gespmm_csr).  That route needs the vector kernels (N a multiple of 4; B, C and
  * arg 16-byte aligned) and N <= 1024; otherwise split rows get their positions from a second
  * pass over the matrix (up to 1.9 times the cost of gespmm_csr).  Same errors as gespmm_csr;
@@ -330,7 +330,7 @@ int gespmm_csr_arg_ex(int64_t M, int64_t K, int64_t N, int64_t nnz, const int32_
  * row >= 128 entries) when the features are fp32, N is a multiple of 4 and at most 1024, and B, C and arg are
  * 16-byte aligned; otherwise the call is gespmm_csr_arg_ex.  On that path every output carries (value, position)
  * as one 64-bit word, held in the row's own C and arg storage through all phases and unpacked by one kernel after
- * the last; values and positions are exactly those of gespmm_csr_arg (measured: 2.7 instead of 3.4 ms on a
+ * the last; values and positions are exactly those of gespmm_csr_arg (measured: 2.6 instead of 3.4 ms on a
  * 233k-vertex graph of mean degree 492 at N = 64).
  *   workspace        device, gespmm_csr_workspace_bytes(M, K, N, nnz, GESPMM_F32, tuning) bytes, 4-byte aligned,
  *                    or NULL (no phases); contents need not be initialised, nothing survives the call.

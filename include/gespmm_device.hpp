@@ -683,7 +683,8 @@ __global__ void __launch_bounds__(kBlock) finish_split_rows(int32_t M, int32_t N
   using Rows = FoldArgRows<F, 4, 1>;
   constexpr int BATCH = kFinishWords / WORDS;
   const int lane = threadIdx.x & (kWave - 1);
-  const int64_t base = ((int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6)) * kWave;
+  // (the wavefront's number as a scalar: everything derived from it and from the ballot below stays in scalar registers)
+  const int64_t base = (int64_t)__builtin_amdgcn_readfirstlane((int)(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6))) * kWave;
   if (base >= M) return;
   const int64_t r = base + lane;
   bool split = false;
@@ -693,26 +694,41 @@ __global__ void __launch_bounds__(kBlock) finish_split_rows(int32_t M, int32_t N
   }
   unsigned long long todo = __ballot(split);
   const int half = N >> 1;
-  while (todo) {
-    int64_t row[BATCH];
+  // where this lane's words sit inside a row: 8-byte word `place[k]` of the row's C storage, or of its arg storage
+  bool in_c[WORDS];
+  int place[WORDS];
 #pragma unroll
-    for (int q = 0; q < BATCH; ++q) {                  // the next BATCH split rows (-1: none left)
-      row[q] = -1;
+  for (int k = 0; k < WORDS; ++k) {
+    const int j = lane + k * kWave;
+    const int jj = j < N ? j : N - 1;                  // lanes beyond the row re-read its last word (and store nothing)
+    in_c[k] = jj < half;
+    place[k] = jj < half ? jj : jj - half;
+  }
+  while (todo) {
+    // the next BATCH rows; when fewer are left the last one is repeated (its loads are harmless, its stores skipped).
+    // All loads are unconditional, so that they are in flight together: one round trip per batch.
+    int pick[BATCH];
+    int rows_here = 0;
+    const int first = __builtin_ctzll(todo);
+#pragma unroll
+    for (int q = 0; q < BATCH; ++q) {
+      pick[q] = first;
       if (todo) {
-        row[q] = base + __builtin_ctzll(todo);
+        pick[q] = __builtin_ctzll(todo);
         todo &= todo - 1;
+        ++rows_here;
       }
     }
     unsigned long long word[BATCH][WORDS];
 #pragma unroll
     for (int q = 0; q < BATCH; ++q) {
-      if (row[q] < 0) continue;
-      const unsigned long long* cslots = reinterpret_cast<const unsigned long long*>(C + row[q] * (int64_t)N);
-      const unsigned long long* aslots = reinterpret_cast<const unsigned long long*>(arg + row[q] * (int64_t)N);
+      const int64_t at = (base + pick[q]) * (int64_t)N;
+      const unsigned long long* cwords = reinterpret_cast<const unsigned long long*>(C + at);
+      const unsigned long long* awords = reinterpret_cast<const unsigned long long*>(arg + at);
 #pragma unroll
       for (int k = 0; k < WORDS; ++k) {
-        const int j = lane + k * kWave;
-        word[q][k] = j < N ? (j < half ? cslots[j] : aslots[j - half]) : 0ull;
+        const unsigned long long* src = (in_c[k] ? cwords : awords) + place[k];
+        word[q][k] = *src;
       }
     }
     // every word of these rows has been read (by all lanes) before any lane overwrites a row:
@@ -723,9 +739,9 @@ __global__ void __launch_bounds__(kBlock) finish_split_rows(int32_t M, int32_t N
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int q = 0; q < BATCH; ++q) {
-      if (row[q] < 0) continue;
-      float* crow = C + row[q] * (int64_t)N;
-      int32_t* arow = arg + row[q] * (int64_t)N;
+      if (q >= rows_here) break;                        // (wave-uniform)
+      float* crow = C + (base + pick[q]) * (int64_t)N;
+      int32_t* arow = arg + (base + pick[q]) * (int64_t)N;
 #pragma unroll
       for (int k = 0; k < WORDS; ++k) {
         const int j = lane + k * kWave;
