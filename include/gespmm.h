@@ -222,7 +222,7 @@ int gespmm_pool_backward(int64_t M, int64_t K, int64_t N, int64_t nnz, const int
 /*
  * Per-call overrides of the automatic launch shape, for tests, benchmarks and callers who know
  * their matrix.  Every field: -1 = automatic.  lanes_per_row in {1,2,4,...,64}, tiles_per_lane
- * in {1,2,4}, xcd_remap in {0,1}, chunk_nnz a power of two in [16, 1024], short_len in
+ * in {1,2,4}, xcd_remap in [0, 4096] (see gespmm_plan_t), chunk_nnz a power of two in [16, 1024], short_len in
  * [0, 1024] (0 = every row is handled by all slots together), k_parts in [0, 64] (parts the
  * column range is cut into by the K-phased path of gespmm_csr_ex; 0 or 1 = off).  A value that
  * has no kernel makes the call return GESPMM_ERR_BAD_ARG.
@@ -264,7 +264,8 @@ typedef struct {
   int64_t chunks;         /* ceil((nnz + M) / S)                                          */
   int64_t grid_x;         /* workgroups along x of one main-kernel launch                 */
   int32_t block_threads;  /* threads per workgroup                                        */
-  int32_t xcd_remap;      /* 1: consecutive chunks are kept on one XCD                    */
+  int32_t xcd_remap;      /* workgroups -> XCDs: 0 round-robin as dispatched, 1 one contiguous range per XCD,
+                             r > 1 runs of r consecutive workgroups per XCD, the runs round-robin */
   int32_t short_len;      /* row segments up to this length are handled one per slot      */
   int32_t lds_bytes;      /* dynamic LDS per workgroup                                    */
   int32_t k_parts;        /* main-kernel launches per call: 1, or the parts of the K-phased path */

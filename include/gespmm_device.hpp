@@ -234,6 +234,14 @@ template <int F> __device__ __forceinline__ void atomic_fold(float* ptr, float x
 // chunks then meets its atomics in one L2, and neighbouring rows of C stay together.
 __device__ __forceinline__ int64_t logical_block(int64_t b, int64_t nb, int remap) {
   if (!remap) return b;
+  if (remap > 1) {
+    // runs of `remap` consecutive workgroups per XCD, the runs dealt round-robin: neighbours share an L2 and
+    // every XCD still gets an even share of every stretch of 8 * remap workgroups
+    const int64_t period = (int64_t)kXcds * remap;
+    if (b >= nb / period * period) return b;          // (the last, incomplete period stays as dispatched)
+    const int64_t w = b % period;
+    return b - w + (w % kXcds) * remap + w / kXcds;
+  }
   const int64_t xcd = b % kXcds, within = b / kXcds;
   const int64_t q = nb / kXcds, r = nb % kXcds;
   return xcd * q + (xcd < r ? xcd : r) + within;

@@ -154,7 +154,7 @@ def test_plan_scalar_path(N, aligned):
 def test_tuning_override_is_validated():
     plan = lambda **t: gs.gespmm_plan_ex(1000, 1000, 64, 10_000, tuning=t)
     for bad in (dict(lanes_per_row=3), dict(tiles_per_lane=3), dict(lanes_per_row=2, tiles_per_lane=4),   # no such kernel
-                dict(chunk_nnz=100), dict(chunk_nnz=2048), dict(chunk_nnz=8), dict(short_len=5000), dict(xcd_remap=2),
+                dict(chunk_nnz=100), dict(chunk_nnz=2048), dict(chunk_nnz=8), dict(short_len=5000), dict(xcd_remap=5000),
                 dict(k_parts=65)):
         with pytest.raises(gs.GespmmError):
             plan(**bad)
@@ -164,6 +164,18 @@ def test_tuning_override_is_validated():
     assert (p["lanes_per_row"], p["chunk_nnz"], p["short_len"], p["chunks"]) == (8, 1024, 5, 11)
     assert p["lds_bytes"] == 4 * (1024 + 64) * 8
     assert gs.gespmm_plan(1000, 64, 10_000)["lanes_per_row"] == 8           # nothing sticks between calls
+    assert plan(xcd_remap=16)["xcd_remap"] == 16                            # runs of 16 workgroups per XCD
+
+
+def test_plan_xcd_mapping_rule():
+    """Round-robin runs of workgroups per XCD on the plain path (shorter runs for small grids), one contiguous range
+    per XCD for long rows, as dispatched on the K-phased path."""
+    assert gs.gespmm_plan(1_000_000, 128, 6_000_000)["xcd_remap"] == 32
+    assert gs.gespmm_plan(20_000, 128, 90_000)["xcd_remap"] in (2, 4, 8, 16)
+    assert gs.gespmm_plan(100, 128, 400)["xcd_remap"] == 0
+    assert gs.gespmm_plan(40_000, 128, 40_000 * 600)["xcd_remap"] == 1
+    p = gs.gespmm_plan_ex(232_965, 232_965, 64, 114_000_000, workspace_bytes=1 << 30)
+    assert p["k_parts"] > 1 and p["xcd_remap"] == 0
 
 
 def test_two_threads_with_different_tunings_get_their_own_plans():
@@ -251,7 +263,7 @@ def test_chunk_size_follows_width_and_problem_size():
     assert gs.gespmm_plan(100_000, 128, 1_600_000)["short_len"] == 16
     assert gs.gespmm_plan(100_000, 128, 4_900_000)["short_len"] == 16
     p = gs.gespmm_plan(169_343, 128, 2_330_033)
-    assert p["chunk_nnz"] == 256 and p["xcd_remap"] == 0
+    assert p["chunk_nnz"] == 256 and p["xcd_remap"] == 32        # runs of 32 workgroups per XCD
     # rows much longer than a chunk: consecutive chunks stay on one XCD
     assert gs.gespmm_plan(232_965, 64, 114_693_532)["xcd_remap"] == 1
 
