@@ -645,8 +645,13 @@ struct FoldArgRows {
             value.v[x] = s.best[t][x];
             place.v[x] = __int_as_float(s.where[t][x]);
           }
-          value.store(crow + col[t]);
-          place.store(reinterpret_cast<float*>(arow + col[t]));
+          if (a.stream_stores) {
+            value.store_streaming(crow + col[t]);
+            place.store_streaming(reinterpret_cast<float*>(arow + col[t]));
+          } else {
+            value.store(crow + col[t]);
+            place.store(reinterpret_cast<float*>(arow + col[t]));
+          }
         } else if (a.packed_split) {
           const int half = a.N >> 1;         // N is even; a lane's V words can straddle the two halves
 #pragma unroll

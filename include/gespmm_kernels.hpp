@@ -888,7 +888,7 @@ inline int launch_chunks(const ChunkLaunch& L, hipStream_t stream, bool* took_wh
   if (fold_job || arg_job) set_narrow_b(L, plan.vec, &a);
   // Rows of C written once, in whole 128-byte lines per slot: streaming stores leave more of the L2s to B (2-5 %
   // on matrices of short rows at N >= 128; narrower slots write part of a line and lose 2 % with them).
-  a.stream_stores = fold_job && plan.vec == 4 && plan.lanes_per_row * 16 >= 128 ? 1 : 0;
+  a.stream_stores = (fold_job || arg_job) && plan.vec == 4 && plan.lanes_per_row * 16 >= 128 ? 1 : 0;
   if (plan.row_window > 0) a.packed_split = 0;    // no row is split
   else if (L.packed_split && (plan.vec != 4 || L.N > kWave * kFinishWords || !L.arg)) return GESPMM_ERR_BAD_ARG;
   int status = GESPMM_OK;
