@@ -95,6 +95,7 @@ struct KernelArgs {
                           // the byte offset of its row of B, and the gathers are buffer loads); 0 = 64-bit addresses
   uint32_t b_bytes;       // ... and the size of B in bytes
   int32_t stream_stores;  // finished rows of C are written with streaming stores (whole 128-byte lines, written once)
+  int32_t stream_entries; // K-phased path: colind / vals are loaded with the streaming hint (one column block: read once)
 };
 
 // Entry p of row r is item p + r of the merged sequence of entries and row ends; chunk c owns the
@@ -302,6 +303,14 @@ __global__ void __launch_bounds__(kBlock) init_rows(int32_t M, int32_t N, const 
 // end (write the row).  In `pass`, `first` is the LDS index of the lane's first entry,
 // `stride` the distance to its next one, `left` how many of the U entries exist (<= 0:
 // none); `first` itself always is a valid index.
+
+template <bool B> struct BoolTag { static constexpr bool value = B; };
+
+// The same address as a pointer into global memory (which is what the arrays of this library are).
+template <class T>
+__device__ __forceinline__ const __attribute__((address_space(1))) T* global_pointer(const T* p) {
+  return (const __attribute__((address_space(1))) T*)p;
+}
 
 __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -1216,28 +1225,40 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
           const int be = __builtin_amdgcn_readlane(my_pe, 63 - __builtin_clzll(vmask));
           row_info[lane] = make_int2(rr < a.M ? my_s - cs : INT32_MAX, my_delta);
           wave_lds_fence();
-          for (int x0 = bs; x0 < be; x0 += 4 * kWave) {
-            int k[4];
-            float v[4];
+          // Entries that the call reads exactly once (one column block) are loaded with the streaming hint: they
+          // then take less of the L2s away from the part of B the phase gathers from.  Two copies of the loop, so
+          // that neither carries a branch per load.
+          auto stage_batch = [&](auto streaming) {
+            for (int x0 = bs; x0 < be; x0 += 4 * kWave) {
+              int k[4];
+              float v[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-              const int x = x0 + u * kWave + lane;
-              const int xc = x < be ? x : be - 1;
-              int pos = 0;                                 // last row of the batch that starts at or before xc
+              for (int u = 0; u < 4; ++u) {
+                const int x = x0 + u * kWave + lane;
+                const int xc = x < be ? x : be - 1;
+                int pos = 0;                                 // last row of the batch that starts at or before xc
 #pragma unroll
-              for (int step = kWave / 2; step > 0; step >>= 1)
-                if (row_info[pos + step].x <= xc) pos += step;
-              const int p = xc + cs + row_info[pos].y;
-              k[u] = a.colind[p];
-              if (a.b_row_bytes != 0) k[u] *= (int)a.b_row_bytes;
-              v[u] = a.vals ? a.vals[p] : 1.0f;
+                for (int step = kWave / 2; step > 0; step >>= 1)
+                  if (row_info[pos + step].x <= xc) pos += step;
+                const int p = xc + cs + row_info[pos].y;
+                if constexpr (decltype(streaming)::value) {
+                  k[u] = __builtin_nontemporal_load(global_pointer(a.colind + p));
+                  v[u] = a.vals ? __builtin_nontemporal_load(global_pointer(a.vals + p)) : 1.0f;
+                } else {
+                  k[u] = a.colind[p];
+                  v[u] = a.vals ? a.vals[p] : 1.0f;
+                }
+                if (a.b_row_bytes != 0) k[u] *= (int)a.b_row_bytes;
+              }
+#pragma unroll
+              for (int u = 0; u < 4; ++u) {
+                const int x = x0 + u * kWave + lane;
+                if (x < be) ka[x] = make_int2(k[u], __float_as_int(v[u]));
+              }
             }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-              const int x = x0 + u * kWave + lane;
-              if (x < be) ka[x] = make_int2(k[u], __float_as_int(v[u]));
-            }
-          }
+          };
+          if (a.stream_entries) stage_batch(BoolTag<true>{});
+          else stage_batch(BoolTag<false>{});
           wave_lds_fence();
         }
       }

@@ -774,6 +774,9 @@ inline int launch_phased(const ChunkLaunch& L, const gespmm_plan_t& plan, MainKe
     a.packed_split = 1;
   }
   set_narrow_b(L, plan.vec, &a);
+  // with one column block every stored entry is read once per call (measured: 1.3 % faster on the 233k-vertex workload;
+  // with several blocks the re-reads of the entries would miss: 6 % slower on a 40k-row matrix at N = 512)
+  a.stream_entries = plan.col_blocks == 1 ? 1 : 0;
   int status = GESPMM_OK;
   for (int q = 0; q < Q; ++q) {
     a.rowptr = virtual_start + (int64_t)q * (M + 1);
