@@ -167,6 +167,23 @@ def test_every_kernel_shape(gs, vec_n):
                       label=f"G={G} T={T} remap={remap} S={chunk} short={short}")
 
 
+@pytest.mark.parametrize("whole_rows", [False, True])
+def test_xcd_runs_cover_every_chunk(gs, whole_rows):
+    """Workgroups are dealt to the XCDs in runs (plan.xcd_remap > 1): every run length, on grids that are a multiple
+    of eight runs, one short of it, one beyond it and shorter than one period, must still visit every chunk once."""
+    rp, ci, v = graphgen.random_csr(4000, 900, 9.0, 61, empty_frac=0.05, long_rows=((17, 700),))
+    B = graphgen.random_dense(900, 32, 61)
+    dA, dB = (dev(rp), dev(ci), dev(v)), dev(B)
+    longest = int(np.diff(rp).max())
+    for chunk in (16, 64, 256):                       # about 2500, 630 and 160 workgroups
+        for runs in (2, 3, 5, 16, 32, 79, 4096):
+            tuning = dict(xcd_remap=runs, chunk_nnz=chunk, longest_row=longest if whole_rows else -1)
+            plan = gs.gespmm_plan_ex(4000, 900, 32, len(ci), tuning=tuning)
+            assert plan["xcd_remap"] == runs and (plan["row_window"] > 0) == (whole_rows and chunk + longest <= 1984)
+            for op in ("sum", "max"):
+                check(gs, rp, ci, v, B, op, dA=dA, dB=dB, tuning=tuning, label=f"runs={runs} S={chunk} whole={whole_rows}")
+
+
 def test_unaligned_buffers_take_scalar_path(gs):
     rp, ci, v = graphgen.random_csr(200, 150, 8.0, 9)
     B = graphgen.random_dense(150, 64, 9)
