@@ -1169,7 +1169,6 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
           const int idx = u0 + u * kWave + lane;
           k[u] = 0;
           if (u0 + u * kWave < count) k[u] = a.colind[from + (idx < count ? idx : count - 1)];
-          if (a.b_row_bytes != 0) k[u] *= (int)a.b_row_bytes;      // the row's byte offset in B (fits 31 bits on this path)
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -1180,7 +1179,9 @@ __global__ void __launch_bounds__(kBlock) chunk_kernel(const KernelArgs a) {
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
           const int idx = u0 + u * kWave + lane;
-          if (idx < count) ka[idx] = make_int2(k[u], __float_as_int(v[u]));
+          // (the key becomes the row's byte offset in B, which fits 31 bits on this path, only here: used right
+          //  after its load it would make every load wait for the one before)
+          if (idx < count) ka[idx] = make_int2(a.b_row_bytes != 0 ? k[u] * (int)a.b_row_bytes : k[u], __float_as_int(v[u]));
         }
       }
       wave_lds_fence();
