@@ -38,17 +38,17 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 # null: the number would describe another kernel.
 MEASURED_TRAFFIC_BYTES = {
     "large_dense_degree/N64/sum": [
-        (12.0889e9, "vec=4 G=16 T=1 S=512 col_blocks=1 k_parts=8", "chunk_kernel_large_dense_degree_N64_sum.md"),
-        (23.0985e9, "vec=4 G=8 T=1 S=512 col_blocks=2 k_parts=1", "chunk_kernel_large_dense_degree_N64_sum_plain_path.md")],
-    "general_ops/N128/sum": [(1.05786e9, "vec=4 G=16 T=1 S=256 col_blocks=2 k_parts=1", "chunk_kernel_general_ops_N128_sum.md")],
-    "skew_narrow/N8/sum": [(0.627129e9, "vec=4 G=2 T=1 S=512 col_blocks=1 k_parts=1", "chunk_kernel_skew_narrow_N8_sum.md")],
-    "skew_narrow/N32/sum": [(1.18438e9, "vec=4 G=8 T=1 S=256 col_blocks=1 k_parts=1", "chunk_kernel_skew_narrow_N32_sum.md")],
-    "width_sweep/N512/sum": [(0.184103e9, "vec=4 G=16 T=1 S=256 col_blocks=8 k_parts=1 row_window=429", "chunk_kernel_width_sweep_N512_sum.md")],
-    "uniform_512k_d4/N128/sum": [(1.37122e9, "vec=4 G=16 T=1 S=256 col_blocks=2 k_parts=1", "chunk_kernel_uniform_512k_d4_N128_sum.md")],
+        (11.6001e9, "vec=4 G=16 T=1 S=512 col_blocks=1 k_parts=8", "chunk_kernel_large_dense_degree_N64_sum.md"),
+        (23.0278e9, "vec=4 G=8 T=1 S=512 col_blocks=2 k_parts=1", "chunk_kernel_large_dense_degree_N64_sum_plain_path.md")],
+    "general_ops/N128/sum": [(1.05873e9, "vec=4 G=16 T=1 S=256 col_blocks=2 k_parts=1", "chunk_kernel_general_ops_N128_sum.md")],
+    "skew_narrow/N8/sum": [(0.624357e9, "vec=4 G=2 T=1 S=512 col_blocks=1 k_parts=1", "chunk_kernel_skew_narrow_N8_sum.md")],
+    "skew_narrow/N32/sum": [(1.18322e9, "vec=4 G=8 T=1 S=256 col_blocks=1 k_parts=1", "chunk_kernel_skew_narrow_N32_sum.md")],
+    "width_sweep/N512/sum": [(0.184119e9, "vec=4 G=16 T=1 S=256 col_blocks=8 k_parts=1 row_window=429", "chunk_kernel_width_sweep_N512_sum.md")],
+    "uniform_512k_d4/N128/sum": [(1.37096e9, "vec=4 G=16 T=1 S=256 col_blocks=2 k_parts=1", "chunk_kernel_uniform_512k_d4_N128_sum.md")],
 }
 MEASURED_TRAFFIC_BYTES_BF16 = {
     "large_dense_degree/N64/sum": [
-        (6.98880e9, "vec=4 G=16 T=1 S=512 col_blocks=1 k_parts=4", "chunk_kernel_large_dense_degree_N64_bf16_sum.md")],
+        (6.58541e9, "vec=4 G=16 T=1 S=512 col_blocks=1 k_parts=4", "chunk_kernel_large_dense_degree_N64_bf16_sum.md")],
 }
 
 
