@@ -245,7 +245,11 @@ def test_whole_row_path_is_planned_only_from_a_bound_on_the_longest_row():
 def test_chunk_size_follows_width_and_problem_size():
     big = 100_000_000
     plans = [gs.gespmm_plan(10**6, N, big) for N in (8, 16, 32, 64, 128, 512)]
-    assert [p["chunk_nnz"] for p in plans] == [512, 512, 256, 256, 256, 256]
+    assert [p["chunk_nnz"] for p in plans] == [1024, 512, 256, 256, 256, 256]
+    # ... 1024 only while thousands of chunks remain, and up to N = 32 when the caller bounds the rows by 64 entries
+    assert gs.gespmm_plan(169_343, 8, 2_330_033)["chunk_nnz"] == 512
+    bounded = lambda N, L: gs.gespmm_plan_ex(524_288, 524_288, N, 2_099_988, tuning=dict(longest_row=L))["chunk_nnz"]
+    assert [bounded(N, 16) for N in (8, 16, 32, 64)] == [1024, 1024, 1024, 256] and bounded(32, 65) == 256
     assert [p["short_len"] for p in plans] == [32, 32, 16, 16, 16, 16]
     # long rows (mean length >= 128): larger chunks, fewer split rows
     assert gs.gespmm_plan(232_965, 64, 114_693_532)["chunk_nnz"] == 512
