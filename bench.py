@@ -41,7 +41,7 @@ MEASURED_TRAFFIC_BYTES = {
         (11.6001e9, "vec=4 G=16 T=1 S=512 col_blocks=1 k_parts=8", "chunk_kernel_large_dense_degree_N64_sum.md"),
         (23.0278e9, "vec=4 G=8 T=1 S=512 col_blocks=2 k_parts=1", "chunk_kernel_large_dense_degree_N64_sum_plain_path.md")],
     "general_ops/N128/sum": [(1.05873e9, "vec=4 G=16 T=1 S=256 col_blocks=2 k_parts=1", "chunk_kernel_general_ops_N128_sum.md")],
-    "skew_narrow/N8/sum": [(0.624357e9, "vec=4 G=2 T=1 S=512 col_blocks=1 k_parts=1", "chunk_kernel_skew_narrow_N8_sum.md")],
+    "skew_narrow/N8/sum": [(0.618235e9, "vec=4 G=2 T=1 S=1024 col_blocks=1 k_parts=1", "chunk_kernel_skew_narrow_N8_sum.md")],
     "skew_narrow/N32/sum": [(1.18322e9, "vec=4 G=8 T=1 S=256 col_blocks=1 k_parts=1", "chunk_kernel_skew_narrow_N32_sum.md")],
     "width_sweep/N512/sum": [(0.184119e9, "vec=4 G=16 T=1 S=256 col_blocks=8 k_parts=1 row_window=429", "chunk_kernel_width_sweep_N512_sum.md")],
     "uniform_512k_d4/N128/sum": [(1.37096e9, "vec=4 G=16 T=1 S=256 col_blocks=2 k_parts=1", "chunk_kernel_uniform_512k_d4_N128_sum.md")],
