@@ -184,8 +184,9 @@ def test_xcd_runs_cover_every_chunk(gs, whole_rows):
                 check(gs, rp, ci, v, B, op, dA=dA, dB=dB, tuning=tuning, label=f"runs={runs} S={chunk} whole={whole_rows}")
 
 
-def test_unaligned_buffers_take_scalar_path(gs):
-    rp, ci, v = graphgen.random_csr(200, 150, 8.0, 9)
+def test_unaligned_buffers(gs):
+    """B (and, below, C) at addresses that are only 4-byte aligned take one column per lane; guard values around C."""
+    rp, ci, v = graphgen.random_csr(200, 150, 8.0, 9, empty_frac=0.1, long_rows=((5, 700),))
     B = graphgen.random_dense(150, 64, 9)
     d_rp, d_ci, d_v = dev(rp), dev(ci), dev(v)
     raw = torch.empty(150 * 64 + 1, dtype=torch.float32, device="cuda")
@@ -198,6 +199,40 @@ def test_unaligned_buffers_take_scalar_path(gs):
         torch.cuda.synchronize()
         ok, worst = oracle.compare(op, C.cpu().numpy(), *oracle.spmm(rp, ci, v, B, op))
         assert ok, worst
+        raw_c = torch.full((200 * 64 + 3,), 7.0, dtype=torch.float32, device="cuda")      # C two floats off, guards around it
+        d_C = raw_c[2:-1].view(200, 64)
+        for tuning in (None, dict(longest_row=700, chunk_nnz=1024), dict(chunk_nnz=16)):
+            gs.gespmm_csr_ex(d_rp, d_ci, d_v, d_B, op, C=d_C, tuning=tuning)
+            torch.cuda.synchronize()
+            ok, worst = oracle.compare(op, d_C.cpu().numpy(), *oracle.spmm(rp, ci, v, B, op))
+            assert ok, worst
+            assert raw_c[0].item() == 7.0 and raw_c[1].item() == 7.0 and raw_c[-1].item() == 7.0
+
+
+@pytest.mark.parametrize("N", [5, 6, 7, 9, 33, 65, 127, 130, 250, 1001])
+def test_widths_that_are_no_multiple_of_four(gs, N):
+    """One column per lane: all four reductions, rows split among chunks, the whole-row path, forced shapes (a forced
+    number of parts is ignored: no phased kernel for these widths), guard values around an unaligned C."""
+    rp, ci, v = graphgen.random_csr(700, 500, 12.0, 400 + N, empty_frac=0.1, long_rows=((3, 3000), (699, 1500), (350, 0)),
+                                    duplicates=True, sort_cols=False)
+    B = graphgen.random_dense(500, N, 400 + N)
+    dA, dB = (dev(rp), dev(ci), dev(v)), dev(B)
+    raw_c = torch.full((700 * N + 8,), -3.0, dtype=torch.float32, device="cuda")
+    d_C = raw_c[3:-5].view(700, N)                    # (and only 4-byte aligned)
+    ws = torch.empty(1 << 20, dtype=torch.int32, device="cuda")
+    variants = [dict(), dict(chunk_nnz=16), dict(chunk_nnz=1024, short_len=0), dict(longest_row=100, chunk_nnz=256),
+                dict(k_parts=3), dict(k_parts=2, lanes_per_row=8, tiles_per_lane=2), dict(k_parts=5, lanes_per_row=16, tiles_per_lane=2, chunk_nnz=64),
+                dict(lanes_per_row=4, tiles_per_lane=2), dict(lanes_per_row=64, tiles_per_lane=4)]
+    for tuning in variants:
+        for op in OPS:
+            say(f"  case ragged N={N} {tuning} op={op}")
+            gs.gespmm_csr_ex(*dA, dB, op, C=d_C, tuning=tuning, workspace=ws if "k_parts" in tuning else None)
+            torch.cuda.synchronize()
+            ok, worst = oracle.compare(op, d_C.cpu().numpy(), *oracle.spmm(rp, ci, v, B, op))
+            assert ok, (tuning, op, worst)
+            assert (raw_c[:3] == -3.0).all().item() and (raw_c[-5:] == -3.0).all().item()
+            if op in ("max", "min"):
+                assert np.array_equal(d_C.cpu().numpy().view(np.uint32), oracle.spmm(rp, ci, v, B, op)[0].astype(np.float32).view(np.uint32))
 
 
 def test_simple_entry_point_and_side_stream(gs):
