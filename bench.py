@@ -38,7 +38,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
 # null: the number would describe another kernel.
 MEASURED_TRAFFIC_BYTES = {
     "large_dense_degree/N64/sum": [
-        (11.6001e9, "vec=4 G=16 T=1 S=512 col_blocks=1 k_parts=8", "chunk_kernel_large_dense_degree_N64_sum.md"),
+        (11.2728e9, "vec=4 G=16 T=1 S=1024 col_blocks=1 k_parts=8", "chunk_kernel_large_dense_degree_N64_sum.md"),
         (23.0278e9, "vec=4 G=8 T=1 S=512 col_blocks=2 k_parts=1", "chunk_kernel_large_dense_degree_N64_sum_plain_path.md")],
     "general_ops/N128/sum": [(1.05873e9, "vec=4 G=16 T=1 S=256 col_blocks=2 k_parts=1", "chunk_kernel_general_ops_N128_sum.md")],
     "skew_narrow/N8/sum": [(0.618235e9, "vec=4 G=2 T=1 S=1024 col_blocks=1 k_parts=1", "chunk_kernel_skew_narrow_N8_sum.md")],
@@ -48,7 +48,7 @@ MEASURED_TRAFFIC_BYTES = {
 }
 MEASURED_TRAFFIC_BYTES_BF16 = {
     "large_dense_degree/N64/sum": [
-        (6.58541e9, "vec=4 G=16 T=1 S=512 col_blocks=1 k_parts=4", "chunk_kernel_large_dense_degree_N64_bf16_sum.md")],
+        (6.27652e9, "vec=4 G=16 T=1 S=1024 col_blocks=1 k_parts=4", "chunk_kernel_large_dense_degree_N64_bf16_sum.md")],
 }
 
 

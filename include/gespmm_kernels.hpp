@@ -491,7 +491,10 @@ inline void make_plan(int64_t M, int64_t K, int64_t N, int64_t nnz, bool aligned
   const int64_t col_blocks = (ncv + (int64_t)G * T - 1) / ((int64_t)G * T);
   const int64_t items = nnz + M;
   int shift = ((int64_t)vec * G * T * elem_bytes <= 64 || (M > 0 && nnz / M >= 128)) ? 9 : 8;
-  if (parts > 1) shift = 9;                     // measured: 512 and 1024 within 1 %, 256 is 10 % slower
+  // (the phases: 256 is 10 % slower than 512; 1024 is 3 % faster than 512 on the 233k-vertex workload, whose phases
+  //  hold 14,000 chunks of that size, and 5 % slower on a 40k-row matrix whose phases are left with 2,500)
+  //  (max / min with positions: 2 % slower with 1024, they keep 512)
+  if (parts > 1) shift = (!with_positions && ((nnz / parts + M) >> 10) >= 8192) ? 10 : 9;
   // Narrow column blocks gather so little per entry that the fixed work of a chunk (row search, first row bounds)
   // weighs most: chunks of 1024 items where the problem still has thousands of them.  Up to 32 bytes per row of B
   // (N <= 8 in fp32): 4-7 % faster on R-MAT and power-law graphs of 10^6 rows, 15-27 % on a 27-point stencil and a

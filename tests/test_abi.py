@@ -253,6 +253,9 @@ def test_chunk_size_follows_width_and_problem_size():
     assert [p["short_len"] for p in plans] == [32, 32, 16, 16, 16, 16]
     # long rows (mean length >= 128): larger chunks, fewer split rows
     assert gs.gespmm_plan(232_965, 64, 114_693_532)["chunk_nnz"] == 512
+    # the phases of the K-phased path: 1024 while a phase still has thousands of chunks
+    assert gs.gespmm_plan_ex(232_965, 232_965, 64, 114_693_532, workspace_bytes=1 << 30)["chunk_nnz"] == 1024
+    assert gs.gespmm_plan_ex(40_000, 40_000, 512, 5_165_394, workspace_bytes=1 << 30)["chunk_nnz"] == 512
     assert all(p["lds_bytes"] == 4 * (p["chunk_nnz"] + 64) * 8 for p in plans)
     assert all(p["chunks"] == -(-(big + 10**6) // p["chunk_nnz"]) for p in plans)
     # small problems: smaller chunks, so the rows spread over more wavefronts
