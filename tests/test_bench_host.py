@@ -48,7 +48,7 @@ def test_every_profile_names_its_command_and_measured_traffic_agrees():
 
 def test_traffic_is_null_for_a_launch_shape_without_a_profile():
     import bench
-    plan = dict(vec=4, lanes_per_row=16, tiles_per_lane=1, chunk_nnz=512, col_blocks=1, k_parts=8)
+    plan = dict(vec=4, lanes_per_row=16, tiles_per_lane=1, chunk_nnz=1024, col_blocks=1, k_parts=8)
     assert bench.measured_traffic(bench.MEASURED_TRAFFIC_BYTES, "large_dense_degree/N64/sum", plan) == bench.MEASURED_TRAFFIC_BYTES["large_dense_degree/N64/sum"][0][0]
     plan["k_parts"] = 9
     assert bench.measured_traffic(bench.MEASURED_TRAFFIC_BYTES, "large_dense_degree/N64/sum", plan) is None
